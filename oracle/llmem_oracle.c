@@ -1,0 +1,307 @@
+/* CPU oracle B: the peak-GPU-memory estimator in plain C, int64 with 128-bit
+ * overflow checks.
+ *
+ * TEST INFRASTRUCTURE ONLY: the parity tests, the smoke check and the benchmark's
+ * CPU-baseline leg call this; the product never does, and this file shares no
+ * code, header or table with the HIP path.  It restates oracle A
+ * (llmem_oracle.py) for speed; the two are compared on whole grids by the tests,
+ * and oracle A carries the pins against the paper.
+ *
+ * Passages followed (same as oracle A):
+ *   Sec. 4.2  m_peak^s, m_p, m_os, m_out, m_lm
+ *   Sec. 5    m_peak^dp (ZeRO-3), m_peak^tp, m_back^tp
+ *   Sec. 4.1  chunk size chosen to minimise waste (search over 2^k MiB, k = 2..10)
+ *   Sec. 2.1 / Sec. 3.1  timeline traversal with live tensors, 512-byte blocks
+ *
+ * The timeline is walked event by event, block by block; no closed form over the
+ * L equal blocks is used here.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <stdlib.h>
+
+typedef __int128 i128;
+
+enum { B16 = 2, B32 = 4 };
+enum { NDIM = 15 };
+enum { DIM_ONE, DIM_BS, DIM_SL, DIM_SLM1, DIM_H, DIM_FFN, DIM_NHEADS, DIM_NKV, DIM_HEADDIM,
+       DIM_KVDIM, DIM_V, DIM_P, DIM_L, DIM_BLOGITS, DIM_D };
+enum { CLS_E, CLS_L, CLS_B, CLS_N };
+enum { ROLE_EMBED_TOK, ROLE_LM_HEAD, ROLE_OTHER };
+enum { SEG_A, SEG_F, SEG_H, SEG_B, SEG_Z, NSEG };
+enum { NDETAIL = 12 };
+enum { D_PEAK, D_PARAM, D_GRAD, D_OS, D_OUT, D_LM, D_BACK, D_K, D_LIVE, D_NPARAMS, D_TMAX, D_FLAGS };
+enum { ERR_ARCH = 1, ERR_METHOD = 2, ERR_D = 4, ERR_HEADS = 8, ERR_CHUNK = 16, CHUNK_INFEASIBLE = 32 };
+enum { CFG_LOGITS_FP32 = 1, CFG_TIED = 2, CFG_GRAD_ALIAS = 4 };
+enum { K_MIN = 2, K_MAX = 10, K_FIXED_MAX = 16 };
+
+typedef struct {
+    int64_t coef;
+    int32_t ndims, dims[4];
+    int32_t cls, role, per_layer;
+} o_param;
+
+typedef struct {
+    int64_t coef;
+    int32_t ndims, dims[4];
+    int32_t elem_bytes, seg, sign, method_mask, scale, times_L;
+} o_event;
+
+typedef struct {
+    int32_t n_params, n_events;
+    const o_param *params;
+    const o_event *events;
+} o_table;
+
+typedef struct {
+    const uint8_t *arch_id; const uint32_t *h; const uint16_t *L; const uint16_t *n_heads;
+    const uint16_t *n_kv; const uint32_t *ffn; const uint32_t *V; const uint32_t *P;
+    const uint16_t *bs; const uint16_t *sl; const uint8_t *method; const uint8_t *d;
+    const int8_t *chunk_k; const uint8_t *flags;
+} o_configs;
+
+/* every intermediate goes through fit(): overflow of int64 is recorded, not ignored */
+static int64_t fit(i128 v, int *ovf)
+{
+    if (v > (i128)INT64_MAX || v < (i128)INT64_MIN) { *ovf = 1; return 0; }
+    return (int64_t)v;
+}
+static int64_t cdiv(int64_t a, int64_t b) { return (int64_t)(((i128)a + b - 1) / b); }
+static int64_t up(int64_t a, int64_t unit, int *ovf) { return fit((i128)cdiv(a, unit) * unit, ovf); }
+
+static int64_t monomial(int64_t coef, int ndims, const int32_t *dims, const int64_t *D, int *ovf)
+{
+    int64_t x = coef;
+    for (int j = 0; j < ndims; ++j) x = fit((i128)x * D[dims[j]], ovf);
+    return x;
+}
+
+static int64_t chunk_elems(int k) { return ((int64_t)1 << k) * 1024 * 1024 / B16; }
+
+static void param_memory(int64_t embed_p, int64_t other_p, int64_t cs, int64_t cu_p,
+                         int64_t *m_p, int64_t *m_p16, int64_t *m_p32, int *ovf)
+{
+    int64_t chunked = fit((i128)embed_p + (i128)cdiv(other_p, cs) * cs, ovf);
+    *m_p = up(fit((i128)chunked * (B16 + B32), ovf), cu_p, ovf);
+    *m_p16 = up(fit((i128)chunked * B16, ovf), cu_p, ovf);
+    *m_p32 = up(fit((i128)chunked * B32, ovf), cu_p, ovf);
+}
+
+static int64_t compose(int method, int64_t d, int64_t m_base, int64_t m_p, int64_t m_p16,
+                       int64_t m_p32, int64_t m_os, int64_t m_out, int64_t m_lm, int64_t m_back,
+                       int64_t align, int *ovf)
+{
+    if (method == 0) return fit((i128)m_base + m_p + m_os + m_out + m_lm, ovf);
+    if (method == 1)
+        return fit((i128)m_base + m_p16 + up(cdiv(fit((i128)m_p32 + m_os, ovf), d), align, ovf)
+                   + m_out + m_lm, ovf);
+    return fit((i128)m_base + up(cdiv(fit((i128)m_p + m_os, ovf), d), align, ovf)
+               + m_out + m_lm + m_back, ovf);
+}
+
+static void estimate_one(const o_configs *c, int64_t i, const o_table *tables, int n_tables,
+                         int64_t m_base, int64_t cu_p, int64_t align, int want_timeline,
+                         int64_t *out, int64_t *scratch, int *ovf)
+{
+    for (int j = 0; j < NDETAIL; ++j) out[j] = 0;
+    int err = 0;
+    int method = c->method[i], k_in = c->chunk_k[i], cflags = c->flags[i];
+    int64_t d = c->d[i];
+    if (c->arch_id[i] >= n_tables) err |= ERR_ARCH;
+    if (method > 2) err |= ERR_METHOD;
+    if (d == 0) err |= ERR_D;
+    if (c->n_heads[i] == 0) err |= ERR_HEADS;
+    if (!(k_in == -1 || (k_in >= 0 && k_in <= K_FIXED_MAX))) err |= ERR_CHUNK;
+    if (err) { out[D_PEAK] = -1; out[D_FLAGS] = err; return; }
+
+    const o_table *t = &tables[c->arch_id[i]];
+    int64_t D[NDIM];
+    int64_t L = c->L[i], bs = c->bs[i], sl = c->sl[i], h = c->h[i], V = c->V[i];
+    int64_t head_dim = h / c->n_heads[i];
+    D[DIM_ONE] = 1; D[DIM_BS] = bs; D[DIM_SL] = sl; D[DIM_SLM1] = sl > 0 ? sl - 1 : 0;
+    D[DIM_H] = h; D[DIM_FFN] = c->ffn[i]; D[DIM_NHEADS] = c->n_heads[i]; D[DIM_NKV] = c->n_kv[i];
+    D[DIM_HEADDIM] = head_dim; D[DIM_KVDIM] = (int64_t)c->n_kv[i] * head_dim; D[DIM_V] = V;
+    D[DIM_P] = c->P[i]; D[DIM_L] = L; D[DIM_BLOGITS] = (cflags & CFG_LOGITS_FP32) ? B32 : B16;
+    D[DIM_D] = d;
+
+    /* Notation table: embed_p, lm_p, other_p; Sec. 4.2: m_os summed tensor by tensor */
+    int64_t embed_p = 0, lm_p = 0, other_p = 0, t_max = 0, e_n = 0, m_os = 0;
+    for (int j = 0; j < t->n_params; ++j) {
+        const o_param *p = &t->params[j];
+        int64_t t_p = monomial(p->coef, p->ndims, p->dims, D, ovf);
+        int64_t count = p->per_layer ? L : 1;
+        if (p->role == ROLE_EMBED_TOK) embed_p = fit((i128)embed_p + (i128)t_p * count, ovf);
+        else if (p->role == ROLE_LM_HEAD) lm_p = fit((i128)lm_p + (i128)t_p * count, ovf);
+        else {
+            other_p = fit((i128)other_p + (i128)t_p * count, ovf);
+            if (t_p > t_max) t_max = t_p;
+        }
+        if (p->cls == CLS_E && p->role != ROLE_LM_HEAD) e_n += 1;
+        if ((p->cls == CLS_E || p->cls == CLS_L) && p->role != ROLE_LM_HEAD) {
+            int64_t one = up(fit((i128)t_p * (B32 + B32), ovf), cu_p, ovf);
+            for (int64_t l = 0; l < count; ++l) m_os = fit((i128)m_os + one, ovf);
+        }
+    }
+    int64_t n_params = fit((i128)embed_p + other_p + ((cflags & CFG_TIED) ? 0 : lm_p), ovf);
+
+    /* Sec. 4.2: m_out, m_lm; Sec. 5: m_back^tp */
+    int64_t A = fit((i128)bs * sl * h, ovf);
+    int64_t m_out = up(fit((i128)(e_n + L) * A * B16, ovf), cu_p, ovf);
+    int64_t B = D[DIM_BLOGITS];
+    int64_t m_lm = fit((i128)up(fit((i128)bs * sl * V * B, ovf), cu_p, ovf)
+                       + 2 * (i128)up(fit((i128)bs * D[DIM_SLM1] * V * B, ovf), cu_p, ovf)
+                       + (i128)lm_p * B16, ovf);
+    int64_t m_back = 0;
+    if (method == 2)
+        m_back = fit((i128)cdiv(fit((i128)L * A * (d - 1) * B16, ovf), d * cu_p) * cu_p, ovf);
+
+    /* Sec. 4.1: gradient fp16 aliases param fp16 unless switched off */
+    int64_t trainable = fit((i128)embed_p + other_p, ovf);
+    int64_t grad_bytes = fit((i128)trainable * B16, ovf);
+    int64_t grad_logical = method == 0 ? grad_bytes : cdiv(grad_bytes, d);
+    int64_t grad_extra = 0;
+    if (!(cflags & CFG_GRAD_ALIAS))
+        grad_extra = method == 0 ? up(grad_bytes, cu_p, ovf)
+                                 : up(cdiv(up(grad_bytes, cu_p, ovf), d), align, ovf);
+
+    /* chunk size: given, or searched over 2^k MiB (every candidate is estimated) */
+    int k = k_in;
+    int64_t m_p = 0, m_p16 = 0, m_p32 = 0, m_peak = 0;
+    if (k_in == -1) {
+        int best_k = -1; int64_t best_waste = 0;
+        int64_t cand_peak[K_MAX + 1], cand_p[K_MAX + 1], cand_p16[K_MAX + 1], cand_p32[K_MAX + 1];
+        for (int kk = K_MIN; kk <= K_MAX; ++kk) {
+            int64_t cs = chunk_elems(kk);
+            param_memory(embed_p, other_p, cs, cu_p, &cand_p[kk], &cand_p16[kk], &cand_p32[kk], ovf);
+            cand_peak[kk] = fit((i128)compose(method, d, m_base, cand_p[kk], cand_p16[kk], cand_p32[kk],
+                                              m_os, m_out, m_lm, m_back, align, ovf) + grad_extra, ovf);
+            if (t_max > cs) continue;
+            int64_t waste = fit((i128)cdiv(other_p, cs) * cs - other_p, ovf);
+            if (best_k < 0 || waste < best_waste) { best_k = kk; best_waste = waste; }
+        }
+        k = best_k < 0 ? K_MAX : best_k;
+        m_peak = cand_peak[k]; m_p = cand_p[k]; m_p16 = cand_p16[k]; m_p32 = cand_p32[k];
+    } else {
+        param_memory(embed_p, other_p, chunk_elems(k), cu_p, &m_p, &m_p16, &m_p32, ovf);
+        m_peak = fit((i128)compose(method, d, m_base, m_p, m_p16, m_p32, m_os, m_out, m_lm, m_back,
+                                   align, ovf) + grad_extra, ovf);
+    }
+    int flags = t_max > chunk_elems(k) ? CHUNK_INFEASIBLE : 0;
+
+    int64_t param_gpu, os_gpu;
+    if (method == 0) { param_gpu = m_p; os_gpu = m_os; }
+    else if (method == 1) {
+        param_gpu = fit((i128)m_p16 + up(cdiv(m_p32, d), align, ovf), ovf);
+        os_gpu = up(cdiv(m_os, d), align, ovf);
+    } else {
+        param_gpu = up(cdiv(m_p, d), align, ovf);
+        os_gpu = up(cdiv(m_os, d), align, ovf);
+    }
+
+    int64_t peak_live = 0;
+    if (want_timeline) {
+        /* value of every table event under this configuration ... */
+        int seg_first[NSEG + 1];
+        for (int s = 0, j = 0; s < NSEG; ++s) {          /* table events are grouped by segment */
+            while (j < t->n_events && t->events[j].seg < s) ++j;
+            seg_first[s] = j;
+        }
+        seg_first[NSEG] = t->n_events;
+        for (int j = 0; j < t->n_events; ++j) {
+            const o_event *e = &t->events[j];
+            int64_t v = 0;
+            if (e->method_mask & (1 << method)) {
+                int64_t raw = fit((i128)monomial(e->coef, e->ndims, e->dims, D, ovf) * e->elem_bytes, ovf);
+                if (e->scale == 1) raw = cdiv(fit((i128)raw * (d - 1), ovf), d);
+                v = up(raw, align, ovf);
+                if (e->times_L) v = fit((i128)v * L, ovf);
+                v *= e->sign;
+            }
+            scratch[j] = v;
+        }
+        /* ... then the walk: resident state, A, F x L, H, B x L, Z */
+        int64_t live = fit((i128)m_base + param_gpu + os_gpu + (i128)lm_p * B16 + grad_extra, ovf);
+        int64_t peak = live;
+        for (int s = 0; s < NSEG; ++s) {
+            int64_t reps = (s == SEG_F || s == SEG_B) ? L : 1;
+            for (int64_t r = 0; r < reps; ++r)
+                for (int j = seg_first[s]; j < seg_first[s + 1]; ++j) {
+                    live = fit((i128)live + scratch[j], ovf);
+                    if (live > peak) peak = live;
+                }
+        }
+        peak_live = peak;
+    }
+
+    out[D_PEAK] = m_peak; out[D_PARAM] = param_gpu; out[D_GRAD] = grad_logical; out[D_OS] = os_gpu;
+    out[D_OUT] = m_out; out[D_LM] = m_lm; out[D_BACK] = m_back; out[D_K] = k; out[D_LIVE] = peak_live;
+    out[D_NPARAMS] = n_params; out[D_TMAX] = t_max; out[D_FLAGS] = flags;
+}
+
+/* detail: n rows of NDETAIL int64 (row-major), may be NULL; peaks: n int64, may be NULL.
+ * Returns 0, or 1 if any intermediate overflowed int64 (results then meaningless),
+ * or 2 on a malformed table (segments out of order, selector out of range). */
+int llmem_oracle_estimate(const o_configs *cfg, int64_t n, const o_table *tables, int n_tables,
+                          int64_t m_base, int64_t cu_p, int64_t align, int want_timeline,
+                          int64_t *peaks, int64_t *detail, int threads)
+{
+    int max_events = 0;
+    for (int a = 0; a < n_tables; ++a) {
+        const o_table *t = &tables[a];
+        if (t->n_events > max_events) max_events = t->n_events;
+        for (int j = 0; j < t->n_events; ++j) {
+            const o_event *e = &t->events[j];
+            if (e->seg < 0 || e->seg >= NSEG || (j > 0 && e->seg < t->events[j - 1].seg)) return 2;
+            for (int q = 0; q < e->ndims; ++q) if (e->dims[q] < 0 || e->dims[q] >= NDIM) return 2;
+        }
+        for (int j = 0; j < t->n_params; ++j)
+            for (int q = 0; q < t->params[j].ndims; ++q)
+                if (t->params[j].dims[q] < 0 || t->params[j].dims[q] >= NDIM) return 2;
+    }
+    int any_ovf = 0;
+    #pragma omp parallel num_threads(threads > 0 ? threads : 1) reduction(|:any_ovf)
+    {
+        int64_t *scratch = (int64_t *)malloc(sizeof(int64_t) * (size_t)(max_events + 1));
+        int ovf = 0;
+        #pragma omp for schedule(dynamic, 256)
+        for (int64_t i = 0; i < n; ++i) {
+            int64_t row[NDETAIL];
+            estimate_one(cfg, i, tables, n_tables, m_base, cu_p, align, want_timeline, row, scratch, &ovf);
+            if (peaks) peaks[i] = row[D_PEAK];
+            if (detail) for (int j = 0; j < NDETAIL; ++j) detail[i * NDETAIL + j] = row[j];
+        }
+        free(scratch);
+        any_ovf |= ovf;
+    }
+    return any_ovf;
+}
+
+/* Explicit event lists: signed raw sizes, CSR offsets.  512-byte blocks; two
+ * pools split at 2 MiB of rounded size; reserved memory in 2 MiB segments. */
+int llmem_oracle_event_lists(const int64_t *events, const int64_t *offsets, int64_t n,
+                             int64_t *allocated, int64_t *reserved, int threads)
+{
+    const int64_t ALIGN = 512, SPLIT = 2 * 1024 * 1024, SEGMENT = 2 * 1024 * 1024;
+    int any_ovf = 0;
+    #pragma omp parallel for schedule(dynamic, 64) num_threads(threads > 0 ? threads : 1) reduction(|:any_ovf)
+    for (int64_t i = 0; i < n; ++i) {
+        int ovf = 0;
+        int64_t live_s = 0, live_l = 0, peak_s = 0, peak_l = 0, peak_t = 0;
+        for (int64_t e = offsets[i]; e < offsets[i + 1]; ++e) {
+            int64_t raw = events[e];
+            int64_t mag = raw >= 0 ? raw : fit(-(i128)raw, &ovf);
+            int64_t r = up(mag, ALIGN, &ovf);
+            int64_t delta = raw >= 0 ? r : -r;
+            if (r < SPLIT) live_s = fit((i128)live_s + delta, &ovf);
+            else live_l = fit((i128)live_l + delta, &ovf);
+            if (live_s > peak_s) peak_s = live_s;
+            if (live_l > peak_l) peak_l = live_l;
+            int64_t tot = fit((i128)live_s + live_l, &ovf);
+            if (tot > peak_t) peak_t = tot;
+        }
+        allocated[i] = peak_t;
+        reserved[i] = fit((i128)up(peak_s, SEGMENT, &ovf) + up(peak_l, SEGMENT, &ovf), &ovf);
+        any_ovf |= ovf;
+    }
+    return any_ovf;
+}

@@ -1,0 +1,64 @@
+"""Oracle B (C, int64 with overflow checks) restates oracle A (Python, unbounded
+integers): the two must agree on every detail column, on whole grid 1, on seeded
+samples of grids 2-4, on random tables with wild configurations and on explicit
+event lists.  Oracle A carries the pins; this extends them to B."""
+import numpy as np
+import pytest
+
+from oracle import llmem_oracle as A
+from oracle import oracle_c as B
+from workloads import events as E
+from workloads import grids as G
+from workloads import tables as T
+
+CONST = T.Constants(m_base=256 << 20)
+
+
+def _same(cfg, tables, const=CONST):
+    rows = np.asarray(A.estimate(cfg, tables, const), dtype=np.int64)
+    peaks, detail = B.estimate(cfg, tables, const, threads=4)
+    assert (rows == detail).all()
+    assert (peaks == detail[:, 0]).all()
+    p2, _ = B.estimate(cfg, tables, const, timeline=False, want_detail=False)
+    assert (p2 == peaks).all()
+
+
+def test_grid1_all_configs():
+    g = G.grid1()
+    assert len(g["h"]) == 432
+    _same(g, [T.gpt_table()])
+
+
+@pytest.mark.parametrize("name,n", [("g2", 120), ("g3", 60), ("g4", 60)])
+def test_grid_samples(name, n):
+    spec = G.GRIDS[name]
+    first = 12345 if name != "g1" else 0
+    _same(spec["make"](n=n, seed=0, first=first), [T.FAMILIES[spec["family"]]()])
+
+
+def test_random_tables_wild_configs():
+    rng = np.random.default_rng(7)
+    tabs = [T.random_table(rng, 9, 150, "r0"), T.llama_table(), T.random_table(rng, 0, 0, "empty"),
+            T.random_table(rng, 64, 700, "r3")]
+    cfg = G.random_configs(rng, 300, n_arch=len(tabs), wild=True)
+    _same(cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512))
+    _same(cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512))
+
+
+def test_event_lists():
+    ev, off = E.generate(40, seed=3, first=7)
+    a1, r1 = A.event_lists_peaks(ev, off)
+    a2, r2 = B.event_lists_peaks(ev, off, threads=3)
+    assert (np.asarray(a1) == a2).all() and (np.asarray(r1) == r2).all()
+    ev, off = E.from_lists([[], [5], [-5, 5], [2097152, 1, -2097152], []])
+    a1, r1 = A.event_lists_peaks(ev, off)
+    a2, r2 = B.event_lists_peaks(ev, off)
+    assert list(a2) == a1 and list(r2) == r1
+
+
+def test_oracle_b_reports_overflow():
+    t = T.ArchTable("big", (), (T.EventEntry("x", "A", +1, 2**31, ("V", "V", "V", "V"), 8),))
+    cfg = G.random_configs(np.random.default_rng(0), 4)
+    cfg["V"][:] = 200000
+    with pytest.raises(OverflowError):
+        B.estimate(cfg, [t], CONST)
