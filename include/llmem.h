@@ -1,0 +1,258 @@
+/* llmem.h - C ABI of the batched peak-GPU-memory estimator (gfx950).
+ *
+ * The library evaluates, for n independent fine-tuning configurations, the
+ * estimator of "LLMem: Estimating GPU Memory Usage for Fine-Tuning Pre-Trained
+ * LLMs" (arXiv 2404.10933): the closed-form peak of Sec. 4.2 (single GPU /
+ * conventional data parallelism) and Sec. 5 (ZeRO-3 "advanced DP", 1-D tensor
+ * parallelism), the chunk-size choice of Sec. 4.1, and a traversal of the
+ * operator timeline with live tensors and 512-byte allocator blocks (Sec. 2.1,
+ * Sec. 3.1).  All arithmetic is exact int64 byte arithmetic.
+ *
+ * Conventions
+ *   DEV   pointer to device memory, owned by the caller; the library never
+ *         allocates, frees or retains it.
+ *   HOST  pointer to host memory, read during the call only.
+ *   Every call enqueues its kernels on `hip_stream` (a hipStream_t passed as
+ *   void*; NULL = the default stream) and returns without synchronising.
+ *   Return value: LLMEM_OK or a negative error code; on an error nothing has been
+ *   enqueued and no output is written.
+ */
+#ifndef LLMEM_H
+#define LLMEM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LLMEM_ABI_VERSION 1
+
+/* ---- error codes --------------------------------------------------------- */
+#define LLMEM_OK            0
+#define LLMEM_EINVAL_NULL  (-1)   /* a required pointer is NULL                          */
+#define LLMEM_EINVAL_N     (-2)   /* n < 0 (n == 0 is a valid no-op)                     */
+#define LLMEM_EINVAL_TABLE (-3)   /* malformed tables / constants (see llmem_tables)     */
+#define LLMEM_EHIP         (-4)   /* a HIP call failed; llmem_strerror gives the text    */
+#define LLMEM_EINVAL_ARG   (-5)   /* any other bad argument (unknown grid id, ...)       */
+
+/* ---- limits --------------------------------------------------------------- */
+#define LLMEM_MAX_ARCH          8     /* architecture tables per call                   */
+#define LLMEM_MAX_PARAM_ENTRIES 64    /* parameter-table entries per architecture       */
+#define LLMEM_MAX_EVENT_ENTRIES 1024  /* timeline events per architecture               */
+#define LLMEM_MAX_EVENT_SLOTS   3072  /* LDS slots for all architectures of one call    */
+
+/* ---- configurations (structure of arrays) --------------------------------- */
+/* One fine-tuning configuration = the inputs of the paper's problem statement
+ * (Notation table; Algorithm 1 inputs): decoder shape, bs, sl, method, gpu_n (d),
+ * chunk size.  Each member is a DEV array of n values.                         */
+typedef struct llmem_configs {
+    uint8_t  *arch_id;   /* index into llmem_tables.arch                                   */
+    uint32_t *h;         /* hidden width (o_n)                                             */
+    uint16_t *L;         /* number of transformer blocks (l_n)                             */
+    uint16_t *n_heads;   /* attention heads; head_dim = h / n_heads                        */
+    uint16_t *n_kv;      /* key/value heads; kv_dim = n_kv * head_dim                      */
+    uint32_t *ffn;       /* feed-forward width                                             */
+    uint32_t *V;         /* dictionary size (dict_n)                                       */
+    uint32_t *P;         /* rows of a learned position table (0 if none)                   */
+    uint16_t *bs;        /* batch size                                                     */
+    uint16_t *sl;        /* sequence length                                                */
+    uint8_t  *method;    /* LLMEM_METHOD_*                                                 */
+    uint8_t  *d;         /* partition degree gpu_n, >= 1 (ignored by conventional DP)      */
+    int8_t   *chunk_k;   /* chunk of 2^k MiB of fp16 values, 0..16; LLMEM_CHUNK_SEARCH     */
+    uint8_t  *flags;     /* LLMEM_CFG_* bits                                               */
+} llmem_configs;
+
+#define LLMEM_METHOD_CDP   0   /* conventional data parallelism = single-GPU peak (Sec. 5) */
+#define LLMEM_METHOD_ZERO3 1   /* advanced data parallelism, ZeRO-3 (Sec. 5)              */
+#define LLMEM_METHOD_TP    2   /* 1-D tensor parallelism (Sec. 5)                         */
+
+#define LLMEM_CHUNK_SEARCH (-1) /* search k = 2..10: least padding waste among the chunk
+                                   sizes that hold the largest tensor, ties to the smaller */
+
+#define LLMEM_CFG_LOGITS_FP32 1 /* B = 4 bytes per logit in m_lm, else 2 (Sec. 4.2)        */
+#define LLMEM_CFG_TIED_LM_HEAD 2 /* lm_head shares the input embedding: n_params only      */
+#define LLMEM_CFG_GRAD_ALIAS  4 /* gradient fp16 shares the param fp16 space (Sec. 4.1);
+                                   when clear a gradient term is added to the peak         */
+
+/* ---- architecture tables --------------------------------------------------- */
+/* Every size is  coef * D[dim[0]] * D[dim[1]] * D[dim[2]] * D[dim[3]]  over the
+ * per-configuration dimension vector D; unused selectors are LLMEM_DIM_ONE.   */
+enum llmem_dim {
+    LLMEM_DIM_ONE = 0, LLMEM_DIM_BS, LLMEM_DIM_SL, LLMEM_DIM_SL_M1 /* max(sl-1,0) */, LLMEM_DIM_H,
+    LLMEM_DIM_FFN, LLMEM_DIM_N_HEADS, LLMEM_DIM_N_KV, LLMEM_DIM_HEAD_DIM, LLMEM_DIM_KV_DIM,
+    LLMEM_DIM_V, LLMEM_DIM_P, LLMEM_DIM_L, LLMEM_DIM_B_LOGITS /* 2 or 4 */, LLMEM_DIM_D,
+    LLMEM_NDIM
+};
+
+/* A parameter tensor (element count).  Classes and roles follow Sec. 4.2: only
+ * Embedding and Linear tensors carry optimizer-state pages (m_os); the token
+ * embedding is embed_p, the lm_head is lm_p, everything else other_p.          */
+typedef struct llmem_param_entry {
+    uint32_t coef;
+    uint8_t  dim[4];
+    uint8_t  cls;        /* LLMEM_CLS_*                                                   */
+    uint8_t  role;       /* LLMEM_ROLE_*                                                  */
+    uint8_t  per_layer;  /* 1: one such tensor in each of the L blocks                    */
+    uint8_t  reserved[5];
+} llmem_param_entry;     /* 16 bytes */
+
+#define LLMEM_CLS_EMBEDDING 0
+#define LLMEM_CLS_LINEAR    1
+#define LLMEM_CLS_BIAS      2
+#define LLMEM_CLS_NORM      3
+#define LLMEM_ROLE_EMBED_TOK 0
+#define LLMEM_ROLE_LM_HEAD   1
+#define LLMEM_ROLE_OTHER     2
+
+/* One allocator event of the fine-tuning iteration (bytes = monomial * elem_bytes,
+ * optionally scaled, rounded up to the allocator block, optionally times L).
+ * Events of one architecture must be grouped by segment in the order A F H B Z:
+ * A once, F once per block, H once, B once per block, Z once.                  */
+typedef struct llmem_event_entry {
+    uint32_t coef;
+    uint8_t  dim[4];
+    uint8_t  elem_bytes;
+    uint8_t  seg;          /* LLMEM_SEG_*                                                 */
+    uint8_t  flags;        /* LLMEM_EV_* bits                                             */
+    uint8_t  method_mask;  /* bit m set: the event exists under method m                  */
+    uint32_t reserved;
+} llmem_event_entry;       /* 16 bytes */
+
+#define LLMEM_SEG_A 0
+#define LLMEM_SEG_F 1
+#define LLMEM_SEG_H 2
+#define LLMEM_SEG_B 3
+#define LLMEM_SEG_Z 4
+#define LLMEM_NSEG  5
+#define LLMEM_EV_FREE      1   /* release (negative) instead of allocation                 */
+#define LLMEM_EV_TIMES_L   2   /* rounded size multiplied by L (L equal tensors at once)   */
+#define LLMEM_EV_TP_GATHER 4   /* raw bytes -> ceil(raw * (d-1) / d): the backward
+                                  all-gather buffer of Sec. 5 (m_back^tp)                  */
+
+typedef struct llmem_arch_desc {
+    int32_t param_first, n_param;   /* range in params_host / params_dev                   */
+    int32_t event_first, n_event;   /* range in events_host / events_dev                   */
+} llmem_arch_desc;
+
+/* HOST struct.  The entry arrays are given twice with identical contents: a HOST
+ * copy, validated on every call, and a DEV copy the kernels read.
+ * LLMEM_EINVAL_TABLE is returned when: n_arch is outside 1..LLMEM_MAX_ARCH; a
+ * range is negative, exceeds the limits above or the array lengths; a selector
+ * is >= LLMEM_NDIM; cls / role / seg are out of range; events are not grouped
+ * A F H B Z; cu_p or align is not a power of two, align > cu_p, align < 1,
+ * or m_base < 0.                                                               */
+typedef struct llmem_tables {
+    int64_t m_base;     /* initially used GPU memory (Notation table), bytes               */
+    int64_t cu_p;       /* CUDA page size of Sec. 4.2, typically 2 MiB; power of two       */
+    int64_t align;      /* allocator block, 512 bytes (Sec. 3.1); power of two             */
+    int32_t n_arch;
+    int32_t n_param_total, n_event_total;   /* lengths of the entry arrays                 */
+    int32_t reserved;
+    llmem_arch_desc arch[LLMEM_MAX_ARCH];
+    const llmem_param_entry *params_host;   /* HOST */
+    const llmem_event_entry *events_host;   /* HOST */
+    const llmem_param_entry *params_dev;    /* DEV  */
+    const llmem_event_entry *events_dev;    /* DEV  */
+} llmem_tables;
+
+/* ---- outputs --------------------------------------------------------------- */
+/* Detail columns: out_detail is DEV, LLMEM_NDETAIL columns of n int64 each
+ * (column c of configuration i at out_detail[c * n + i]).                      */
+enum llmem_detail {
+    LLMEM_D_PEAK = 0,     /* m_peak of the configuration's method (Sec. 4.2 / Sec. 5)      */
+    LLMEM_D_PARAM_GPU,    /* parameter bytes resident per GPU                              */
+    LLMEM_D_GRAD_GPU,     /* logical fp16 gradient bytes per GPU                           */
+    LLMEM_D_OS_GPU,       /* momentum + variance bytes per GPU                             */
+    LLMEM_D_OUT,          /* m_out                                                         */
+    LLMEM_D_LM,           /* m_lm                                                          */
+    LLMEM_D_BACK,         /* m_back^tp (0 unless TP)                                       */
+    LLMEM_D_K,            /* chunk exponent used                                           */
+    LLMEM_D_PEAK_LIVE,    /* largest live bytes over the event timeline                    */
+    LLMEM_D_NPARAMS,      /* parameter count                                               */
+    LLMEM_D_TMAX,         /* largest single tensor outside embedding / lm_head (elements)  */
+    LLMEM_D_FLAGS,        /* LLMEM_F_* bits                                                */
+    LLMEM_NDETAIL
+};
+
+/* Per-configuration data errors are reported in band: m_peak = -1, every other
+ * detail column 0 except the flags.                                            */
+#define LLMEM_F_ERR_ARCH    1   /* arch_id >= n_arch                                       */
+#define LLMEM_F_ERR_METHOD  2   /* method > 2                                              */
+#define LLMEM_F_ERR_D       4   /* d == 0                                                  */
+#define LLMEM_F_ERR_HEADS   8   /* n_heads == 0                                            */
+#define LLMEM_F_ERR_CHUNK   16  /* chunk_k outside {-1} U [0, 16]                          */
+#define LLMEM_F_CHUNK_INFEASIBLE 32 /* the largest tensor exceeds the chunk used (a search
+                                       without a feasible candidate falls back to k = 10) */
+
+/* ---- entry points ---------------------------------------------------------- */
+
+/* m_peak of n configurations (Sec. 4.2 equation for m_peak^s; Sec. 5 equations
+ * for m_peak^dp and m_peak^tp; chunk search per Sec. 4.1).
+ *   cfg            HOST struct of DEV columns, n values each
+ *   method_tables  HOST struct (see llmem_tables)
+ *   out_peaks      DEV, n int64
+ * Runs on the default stream.  Intermediate values must fit int64 (they do for
+ * any decoder up to ~10^12 parameters at bs*sl <= 2^20); overflow wraps.      */
+int llmem_estimate(const llmem_configs *cfg, int64_t n, const llmem_tables *method_tables,
+                   int64_t *out_peaks);
+
+/* As llmem_estimate, plus the detail columns (component sizes of the same
+ * sections, and the timeline peak of Sec. 2.1 / Sec. 3.1) when out_detail is not
+ * NULL; out_peaks may be NULL when out_detail is given.                        */
+int llmem_estimate_ex(const llmem_configs *cfg, int64_t n, const llmem_tables *method_tables,
+                      int64_t *out_peaks, int64_t *out_detail, void *hip_stream);
+
+/* Peaks of explicit allocator timelines (Sec. 2.1 / Sec. 3.1: sequential
+ * traversal with live tensors, sizes rounded to 512-byte blocks).
+ *   events   DEV, signed raw byte counts: > 0 allocation, < 0 release, 0 no-op
+ *   offsets  DEV, n + 1 ascending offsets; list i is events[offsets[i] .. offsets[i+1])
+ *   out_allocated DEV n int64: max over prefixes of the live rounded bytes
+ *   out_reserved  DEV n int64: two pools split at LLMEM_POOL_SPLIT of rounded size
+ *                 (a release goes to the pool of its own size); each pool's largest
+ *                 live total rounded up to LLMEM_SEGMENT, summed
+ * The empty prefix counts, so both outputs are >= 0.                          */
+int llmem_timeline_peaks(const int64_t *events, const int64_t *offsets, int64_t n,
+                         int64_t *out_allocated, int64_t *out_reserved, void *hip_stream);
+
+#define LLMEM_BLOCK      512
+#define LLMEM_POOL_SPLIT (2 * 1024 * 1024)
+#define LLMEM_SEGMENT    (2 * 1024 * 1024)
+
+/* Seeded synthetic inputs, generated on the device.  Every draw is
+ * lo + mix64(seed, index, field) mod span with splitmix64's finaliser over
+ * seed + 0x9E3779B97F4A7C15*(index+1) + 0xD1B54A32D192ED03*(field+1).
+ * grid_id 1..4: the tiny Cartesian grid (432 configurations), the OPT/GPT-style
+ * grid, the Llama-style grid, and the Llama-style grid with chunk search.
+ * cfg_out columns are DEV arrays of n values receiving configurations
+ * first .. first+n-1 (grid 1: first + n <= 432, else LLMEM_EINVAL_ARG).       */
+int llmem_grid_generate(int grid_id, uint64_t seed, int64_t first, int64_t n,
+                        const llmem_configs *cfg_out, void *hip_stream);
+
+/* Event lists of configurations first .. first+n-1 of the explicit-timeline
+ * grid.  Two steps, both asynchronous: llmem_events_count writes the n list
+ * lengths (DEV int64); the caller turns them into n + 1 offsets (exclusive
+ * prefix sum) and passes those to llmem_events_generate, which fills
+ * events[offsets[i] .. offsets[i+1]).                                         */
+int llmem_events_count(uint64_t seed, int64_t first, int64_t n, int64_t *counts, void *hip_stream);
+int llmem_events_generate(uint64_t seed, int64_t first, int64_t n, const int64_t *offsets,
+                          int64_t *events, void *hip_stream);
+
+/* Bytes of device memory n configurations occupy over all 14 columns. */
+size_t llmem_config_bytes(int64_t n);
+/* Upper bound of the bytes of n event lists (events only, not the offsets). */
+size_t llmem_events_bytes(int64_t n);
+
+/* Host-only self-test hook: floor(x / d) computed by the multiply-high constants
+ * the kernels use for their divisions by the partition degree (0 <= x < 2^63,
+ * 1 <= d <= 255; returns 0 for d outside that range).                          */
+uint64_t llmem_selftest_divide(uint64_t x, uint32_t d);
+
+const char *llmem_strerror(int code);
+int llmem_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LLMEM_H */

@@ -1,0 +1,9 @@
+"""MI355X-native batched evaluation of the LLMem peak-GPU-memory estimator
+(arXiv 2404.10933).  The work is done by hand-written gfx950 kernels behind a C
+ABI (include/llmem.h); `binding` marshals arguments to it."""
+from .binding import (  # noqa: F401
+    LlmemError, Tables, DeviceConfigs, load_library, library_path,
+    llmem_estimate, llmem_estimate_ex, llmem_timeline_peaks, llmem_grid_generate,
+    llmem_events_count, llmem_events_generate, llmem_config_bytes, llmem_events_bytes,
+    llmem_strerror, llmem_abi_version, NDETAIL, DETAIL_COLUMNS,
+)

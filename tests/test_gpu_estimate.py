@@ -1,0 +1,111 @@
+"""Parity of the HIP estimator with the CPU oracle, element by element and bit
+exact (all integer byte arithmetic), through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import llmem_oracle as A
+from oracle import oracle_c as B
+from workloads import grids as G
+from workloads import tables as T
+
+pytestmark = pytest.mark.gpu
+
+CONST = T.Constants(m_base=256 << 20)
+
+
+@pytest.fixture(scope="module")
+def U():
+    import gpu_util
+    return gpu_util
+
+
+def _check(U, cfg, tables, const=CONST, threads=8):
+    want_p, want_d = B.estimate(cfg, tables, const, threads=threads)
+    got_p, got_d = U.hip_estimate(cfg, tables, const)
+    U.assert_same("detail", got_d, want_d)
+    U.assert_same("peaks", got_p, want_p)
+    got_p2, _ = U.hip_estimate(cfg, tables, const, detail=False)
+    U.assert_same("peaks (no detail)", got_p2, want_p)
+
+
+def test_grid1_all(U):
+    cfg = G.grid1()
+    _check(U, cfg, [T.gpt_table()])
+    # and directly against the Python oracle that carries the pins
+    rows = np.asarray(A.estimate(cfg, [T.gpt_table()], CONST), dtype=np.int64)
+    _, got = U.hip_estimate(cfg, [T.gpt_table()], CONST)
+    U.assert_same("detail vs oracle A", got, rows)
+
+
+@pytest.mark.parametrize("name,n,first", [("g2", 100_000, 0), ("g3", 64 * 300 + 37, 500_000),
+                                          ("g4", 64 * 300 + 1, 9_000_000)])
+def test_grid_slices(U, name, n, first):
+    spec = G.GRIDS[name]
+    _check(U, spec["make"](n=n, seed=0, first=first), [T.FAMILIES[spec["family"]]()])
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 127, 128, 129, 1000])
+def test_ragged_sizes(U, n):
+    cfg = G.grid4(n=n, seed=3)
+    _check(U, cfg, [T.llama_table()])
+
+
+def test_random_tables_wild_configs(U):
+    rng = np.random.default_rng(11)
+    tabs = [T.random_table(rng, 9, 150, "r0"), T.llama_table(), T.random_table(rng, 0, 0, "empty"),
+            T.random_table(rng, 64, 700, "r3"), T.gpt_table(), T.random_table(rng, 1, 1, "one"),
+            T.random_table(rng, 30, 1024, "max")]
+    cfg = G.random_configs(rng, 64 * 40 + 5, n_arch=len(tabs), wild=True)
+    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512))
+    _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512))
+    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1))
+
+
+def test_degenerate_and_flag_cases(U):
+    rng = np.random.default_rng(12)
+    tabs = [T.degenerate_table(T.llama_table()), T.opt_table()]
+    cfg = G.random_configs(rng, 3000, n_arch=2)
+    cfg["flags"][:] = rng.integers(0, 8, size=3000)       # tied / untied, aliasing on and off, both logit widths
+    cfg["L"][:100] = 0
+    cfg["sl"][100:200] = 1
+    cfg["chunk_k"][200:300] = -1
+    cfg["h"][200:260] = 40000                              # no feasible chunk candidate
+    cfg["n_heads"][200:260] = 8
+    cfg["ffn"][200:260] = 60000
+    _check(U, cfg, tabs)
+
+
+def test_determinism_and_stream(U):
+    cfg = G.grid3(n=20_000, seed=5)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        a = U.hip_estimate(cfg, [T.llama_table()], CONST, stream=s)
+    b = U.hip_estimate(cfg, [T.llama_table()], CONST)
+    U.assert_same("detail twice", a[1], b[1])
+
+
+def test_full_size_grid4(U):
+    """10^7 configurations, in the launch configuration the benchmark times:
+    m_peak of every configuration against the oracle, and all detail columns
+    (including the timeline walk) on the first and last batches plus a seeded sample."""
+    import paper_2404_10933_amd as M
+    n = 10_000_000
+    cfg = G.grid4(n=n, seed=0)
+    tables = [T.llama_table()]
+    dev = M.DeviceConfigs.from_numpy(cfg)
+    tab = M.Tables(tables, m_base=CONST.m_base, cu_p=CONST.cu_p, align=CONST.align)
+    peaks = torch.empty(n, dtype=torch.int64, device="cuda")
+    det = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
+    M.llmem_estimate_ex(dev, tab, peaks, det)
+    torch.cuda.synchronize()
+    got_p = peaks.cpu().numpy()
+    want_p, _ = B.estimate(cfg, tables, CONST, timeline=False, want_detail=False, threads=16)
+    U.assert_same("m_peak, all 10^7", got_p, want_p)
+    rng = np.random.default_rng(0)
+    idx = np.unique(np.concatenate([np.arange(2048), np.arange(n - 2048, n), rng.integers(0, n, size=30_000)]))
+    sub = G.slice_configs(cfg, idx)
+    _, want_d = B.estimate(sub, tables, CONST, threads=16)
+    got_d = det[:, torch.from_numpy(idx).cuda()].cpu().numpy().T
+    U.assert_same("detail, sampled", got_d, want_d)
+    assert (got_p[idx] == want_d[:, 0]).all()

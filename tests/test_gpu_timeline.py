@@ -1,0 +1,60 @@
+"""Parity of the explicit-timeline kernel with the CPU oracle (bit exact)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import llmem_oracle as A
+from oracle import oracle_c as B
+from workloads import events as E
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def U():
+    import gpu_util
+    return gpu_util
+
+
+def _check(U, ev, off):
+    want_a, want_r = B.event_lists_peaks(ev, off, threads=8)
+    got_a, got_r = U.hip_timeline(ev, off)
+    U.assert_same("allocated", got_a, want_a)
+    U.assert_same("reserved", got_r, want_r)
+
+
+def test_handwritten_lists(U):
+    M2 = 2 * 1024 * 1024
+    lists = [[], [1], [-1, 1], [511, 512, 513, -511, -512, -513], [M2 - 513, M2 - 512, M2 - 511, M2, M2 + 1],
+             [3_000_000, 100, -3_000_000, 100], [0, 0, 0], [5, -5] * 700, [M2] * 1500 + [-M2] * 1500,
+             list(range(1, 1024)), list(range(1, 1025)), list(range(1, 1026)), list(range(1, 2050)), []]
+    ev, off = E.from_lists(lists)
+    _check(U, ev, off)
+    a, r = A.event_lists_peaks(ev, off)                  # the pinned Python oracle agrees too
+    got_a, got_r = U.hip_timeline(ev, off)
+    assert list(got_a) == a and list(got_r) == r
+
+
+def test_random_ragged_lists(U):
+    rng = np.random.default_rng(21)
+    lists = []
+    for _ in range(300):
+        n = int(rng.integers(0, 5000))
+        mag = (2.0 ** rng.uniform(0, 24, size=n)).astype(np.int64)
+        lists.append(list(np.where(rng.random(n) < 0.5, mag, -mag)))   # arbitrary signs: prefixes go negative
+    ev, off = E.from_lists(lists)
+    _check(U, ev, off)
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 257])
+def test_generated_lists_small(U, n):
+    ev, off = E.generate(n, seed=2, first=11, threads=8)
+    _check(U, ev, off)
+
+
+def test_full_size_event_grid(U):
+    """10^5 lists of about 10^4 events (8 GB), every list against the oracle."""
+    n = 100_000
+    ev, off = E.generate(n, seed=0, threads=16)
+    assert len(ev) > 9 * 10 ** 8
+    _check(U, ev, off)

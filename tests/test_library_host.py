@@ -1,0 +1,132 @@
+"""Host-side behaviour of the C-ABI library that needs no GPU: it loads, exports
+every declared symbol, validates arguments before touching the device, and its
+multiply-high division constants are exact."""
+import ctypes
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2404_10933_amd as M
+    if not os.path.exists(M.library_path()):
+        from paper_2404_10933_amd import build
+        build.build()
+    return M.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "llmem.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(llmem_[a-z_]+)\s*\(", header))
+    assert {"llmem_estimate", "llmem_estimate_ex", "llmem_timeline_peaks", "llmem_grid_generate",
+            "llmem_events_count", "llmem_events_generate", "llmem_config_bytes", "llmem_events_bytes",
+            "llmem_strerror", "llmem_abi_version", "llmem_selftest_divide"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_abi_and_sizes(lib):
+    import paper_2404_10933_amd as M
+    assert M.llmem_abi_version() == 1
+    assert M.llmem_config_bytes(10) == 10 * 31 and M.llmem_config_bytes(-1) == 0
+    assert M.llmem_events_bytes(2) == 2 * 6 * 3450 * 8
+    assert "NULL" in M.llmem_strerror(-1) and "unknown" in M.llmem_strerror(-99)
+
+
+def test_division_constants_are_exact(lib):
+    rng = random.Random(0)
+    for d in range(1, 256):
+        xs = [0, 1, d - 1, d, d + 1, 2 ** 63 - 1, 2 ** 63 - d, 2 ** 62, 2 ** 32 - 1, 2 ** 32, 2 ** 32 + 1]
+        xs += [rng.randrange(2 ** 63) for _ in range(300)]
+        xs += [min(d * rng.randrange(2 ** 55) + e, 2 ** 63 - 1) for e in (-1, 0, 1) for _ in range(30)]
+        for x in xs:
+            x = max(x, 0)
+            assert lib.llmem_selftest_divide(x, d) == x // d, (x, d)
+    assert lib.llmem_selftest_divide(5, 0) == 0 and lib.llmem_selftest_divide(5, 256) == 0
+
+
+def _structs():
+    from paper_2404_10933_amd import binding as Bd
+    return Bd
+
+
+def _host_tables(Bd, params, events, n_arch=1, cu_p=2 << 20, align=512, m_base=0, arch=None):
+    t = Bd._Tables()
+    t.m_base, t.cu_p, t.align, t.n_arch = m_base, cu_p, align, n_arch
+    t.n_param_total, t.n_event_total = len(params), len(events)
+    a = arch or [(0, len(params), 0, len(events))]
+    for i, d in enumerate(a):
+        t.arch[i] = Bd._ArchDesc(*d)
+    fake_dev = 0x1000                                       # never dereferenced: validation fails first / n == 0
+    t.params_host = params.ctypes.data if len(params) else None
+    t.events_host = events.ctypes.data if len(events) else None
+    t.params_dev = fake_dev if len(params) else None
+    t.events_dev = fake_dev if len(events) else None
+    return t
+
+
+def test_argument_validation_without_gpu(lib):
+    Bd = _structs()
+    params = np.zeros(2, dtype=Bd.PARAM_DTYPE)
+    events = np.zeros(3, dtype=Bd.EVENT_DTYPE)
+    events["seg"] = [0, 1, 4]
+    cfg = Bd._Configs()
+    out = ctypes.c_void_p(0x2000)
+    ok = _host_tables(Bd, params, events)
+    est = lib.llmem_estimate_ex
+    assert est(ctypes.byref(cfg), 0, ctypes.byref(ok), out, None, None) == 0          # n == 0: no-op
+    assert est(ctypes.byref(cfg), -1, ctypes.byref(ok), out, None, None) == -2
+    assert est(None, 0, ctypes.byref(ok), out, None, None) == -1
+    assert est(ctypes.byref(cfg), 0, None, out, None, None) == -1
+    assert est(ctypes.byref(cfg), 0, ctypes.byref(ok), None, None, None) == -1
+    assert est(ctypes.byref(cfg), 5, ctypes.byref(ok), out, None, None) == -1          # NULL columns
+    assert lib.llmem_estimate(ctypes.byref(cfg), 0, ctypes.byref(ok), None) == -1
+
+    def bad(**kw):
+        p, e = params.copy(), events.copy()
+        mut = kw.pop("mut", None)
+        if mut:
+            mut(p, e)
+        t = _host_tables(Bd, p, e, **kw)
+        return est(ctypes.byref(cfg), 0, ctypes.byref(t), out, None, None)
+
+    assert bad(n_arch=0) == -3 and bad(n_arch=9) == -3
+    assert bad(cu_p=3 << 20) == -3 and bad(align=500) == -3 and bad(align=4 << 20) == -3 and bad(m_base=-1) == -3
+    assert bad(arch=[(0, 3, 0, 3)]) == -3 and bad(arch=[(0, 2, 1, 3)]) == -3 and bad(arch=[(-1, 2, 0, 3)]) == -3
+    assert bad(mut=lambda p, e: p["dim"].__setitem__((0, 1), 15)) == -3               # selector out of range
+    assert bad(mut=lambda p, e: p["cls"].__setitem__(0, 4)) == -3
+    assert bad(mut=lambda p, e: p["role"].__setitem__(1, 3)) == -3
+    assert bad(mut=lambda p, e: e["seg"].__setitem__(1, 5)) == -3
+    assert bad(mut=lambda p, e: e["seg"].__setitem__(2, 0)) == -3                      # segments out of order
+    assert bad(mut=lambda p, e: e["flags"].__setitem__(0, 8)) == -3
+    assert bad(mut=lambda p, e: e["method_mask"].__setitem__(0, 8)) == -3
+    too_many = np.zeros(1025, dtype=Bd.EVENT_DTYPE)
+    t = _host_tables(Bd, params, too_many)
+    assert est(ctypes.byref(cfg), 0, ctypes.byref(t), out, None, None) == -3
+
+    tl = lib.llmem_timeline_peaks
+    assert tl(None, None, -1, None, None, None) == -2 and tl(None, None, 0, None, None, None) == 0
+    assert tl(None, None, 3, None, None, None) == -1
+    assert lib.llmem_grid_generate(5, 0, 0, 0, ctypes.byref(cfg), None) == -5
+    assert lib.llmem_grid_generate(1, 0, 400, 33, ctypes.byref(cfg), None) == -5
+    assert lib.llmem_grid_generate(2, 0, 0, -1, ctypes.byref(cfg), None) == -2
+    assert lib.llmem_grid_generate(2, 0, 0, 4, ctypes.byref(cfg), None) == -1
+    assert lib.llmem_events_count(0, 0, 4, None, None) == -1
+    assert lib.llmem_events_generate(0, 0, 4, None, None, None) == -1
+
+
+def test_table_packing_layout():
+    """The binding's 16-byte records match the C structs field by field."""
+    Bd = _structs()
+    assert [Bd.PARAM_DTYPE.fields[k][1] for k in ("coef", "dim", "cls", "role", "per_layer")] == [0, 4, 8, 9, 10]
+    assert [Bd.EVENT_DTYPE.fields[k][1] for k in ("coef", "dim", "elem_bytes", "seg", "flags", "method_mask")] \
+        == [0, 4, 8, 9, 10, 11]
+    assert ctypes.sizeof(Bd._ArchDesc) == 16
+    assert Bd._Tables.arch.offset == 40 and Bd._Tables.params_host.offset == 40 + 8 * 16
