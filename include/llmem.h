@@ -139,7 +139,8 @@ typedef struct llmem_arch_desc {
 /* HOST struct.  The entry arrays are given twice with identical contents: a HOST
  * copy, validated on every call, and a DEV copy the kernels read.
  * LLMEM_EINVAL_TABLE is returned when: n_arch is outside 1..LLMEM_MAX_ARCH; a
- * range is negative, exceeds the limits above or the array lengths; a selector
+ * range is negative, exceeds the limits above or the array lengths (the slot limit
+ * only binds the kernel that uses slots, see LLMEM_KERNEL_*); a selector
  * is >= LLMEM_NDIM; cls / role / seg are out of range; events are not grouped
  * A F H B Z; cu_p or align is not a power of two, align > cu_p, align < 1,
  * or m_base < 0.                                                               */
@@ -149,13 +150,25 @@ typedef struct llmem_tables {
     int64_t align;      /* allocator block, 512 bytes (Sec. 3.1); power of two             */
     int32_t n_arch;
     int32_t n_param_total, n_event_total;   /* lengths of the entry arrays                 */
-    int32_t reserved;
+    int32_t kernel;                         /* LLMEM_KERNEL_*; 0 lets the library choose   */
     llmem_arch_desc arch[LLMEM_MAX_ARCH];
     const llmem_param_entry *params_host;   /* HOST */
     const llmem_event_entry *events_host;   /* HOST */
     const llmem_param_entry *params_dev;    /* DEV  */
     const llmem_event_entry *events_dev;    /* DEV  */
 } llmem_tables;
+
+/* Two kernels compute the same results.  LLMEM_KERNEL_LANE holds one configuration
+ * per lane (64 per wavefront) and walks the tables entry by entry; it needs at most
+ * 32 distinct size expressions among the events of each architecture.
+ * LLMEM_KERNEL_WAVE gives a whole wavefront to each configuration with the lanes
+ * spread over table entries; it needs the events of all architectures, dealt to
+ * lanes, to fit LLMEM_MAX_EVENT_SLOTS.  LLMEM_KERNEL_AUTO takes the first where the
+ * tables allow it, else the second; a forced choice the tables do not allow is
+ * LLMEM_EINVAL_TABLE.                                                          */
+#define LLMEM_KERNEL_AUTO 0
+#define LLMEM_KERNEL_WAVE 1
+#define LLMEM_KERNEL_LANE 2
 
 /* ---- outputs --------------------------------------------------------------- */
 /* Detail columns: out_detail is DEV, LLMEM_NDETAIL columns of n int64 each

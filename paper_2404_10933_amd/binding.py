@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libllmem.so")
 _lib = None
 
 MAX_ARCH = 8
+KERNEL_AUTO, KERNEL_WAVE, KERNEL_LANE = 0, 1, 2
 NDETAIL = 12
 DETAIL_COLUMNS = ("m_peak", "param_bytes_gpu", "grad_bytes_gpu", "os_bytes_gpu", "m_out", "m_lm",
                   "m_back", "k_chosen", "peak_live", "n_params", "t_max", "flags")
@@ -63,7 +64,7 @@ class _ArchDesc(ctypes.Structure):
 class _Tables(ctypes.Structure):
     _fields_ = [("m_base", ctypes.c_int64), ("cu_p", ctypes.c_int64), ("align", ctypes.c_int64),
                 ("n_arch", ctypes.c_int32), ("n_param_total", ctypes.c_int32),
-                ("n_event_total", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("n_event_total", ctypes.c_int32), ("kernel", ctypes.c_int32),
                 ("arch", _ArchDesc * MAX_ARCH),
                 ("params_host", ctypes.c_void_p), ("events_host", ctypes.c_void_p),
                 ("params_dev", ctypes.c_void_p), ("events_dev", ctypes.c_void_p)]
@@ -152,13 +153,14 @@ class Tables:
     (validated by the library on every call) and the same bytes on the device."""
 
     def __init__(self, tables: Sequence, m_base: int = 0, cu_p: int = 2 * 1024 * 1024, align: int = 512,
-                 device="cuda"):
+                 device="cuda", kernel: int = 0):
         if len(tables) > MAX_ARCH:
             raise ValueError("too many architecture tables")
         params, events = [], []
         self.struct = _Tables()
         self.struct.m_base, self.struct.cu_p, self.struct.align = m_base, cu_p, align
         self.struct.n_arch = len(tables)
+        self.struct.kernel = kernel
         for a, t in enumerate(tables):
             self.struct.arch[a] = _ArchDesc(len(params), len(t.params), len(events), len(t.events))
             for p in t.params:

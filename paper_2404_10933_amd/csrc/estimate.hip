@@ -17,41 +17,13 @@
 #include <string.h>
 
 #include "../../include/llmem.h"
+#include "estimate_args.h"
 #include "wave.h"
 
 namespace llmem {
 
-__constant__ DivMagicTable c_div = DivMagicTable();
-
 constexpr int WAVES_PER_BLOCK = 4;
 constexpr int BLOCK = 64 * WAVES_PER_BLOCK;
-constexpr int K_SEARCH_MIN = 2, K_SEARCH_MAX = 10, K_FIXED_MAX = 16;
-constexpr int B16 = 2, B32 = 4;
-
-// How the events of one architecture are dealt to the 64 lanes: every lane owns
-// `per_lane` consecutive events of a single segment; segment s occupies lanes
-// lane0[s] .. lane0[s+1]-1.  LDS slot j*64 + lane holds the lane's j-th event.
-struct ArchLayout {
-    int param_first, n_param;
-    int event_first;            // first entry of the architecture in events_dev
-    int seg_first[LLMEM_NSEG + 1];  // segment boundaries relative to event_first
-    int per_lane;
-    int lane0[LLMEM_NSEG + 1];
-    int slot_first;             // first LDS slot
-};
-
-struct EstimateArgs {
-    llmem_configs cfg;
-    long long n;
-    long long m_base;
-    int cu_shift, align_shift;
-    int n_arch, n_param_total, n_slot_total;
-    ArchLayout arch[LLMEM_MAX_ARCH];
-    const uint4 *params_dev;
-    const uint4 *events_dev;
-    long long *out_peaks;
-    long long *out_detail;
-};
 
 // x / d and ceil(x / d) for wave-uniform or per-lane x, 1 <= d <= 255, x < 2^63
 __device__ __forceinline__ u64 div_small(u64 x, u32 d, u64 mul, u32 shift)
@@ -376,8 +348,10 @@ static int log2_exact(int64_t v)
 
 // Checks the host copy of the tables and derives the lane layout of every
 // architecture's events.  Returns LLMEM_OK or LLMEM_EINVAL_*.
-static int plan_tables(const llmem_tables *t, EstimateArgs *out)
+static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, bool *batch_ok)
 {
+    *wave_ok = true;
+    *batch_ok = true;
     if (!t->params_host && t->n_param_total > 0) return LLMEM_EINVAL_NULL;
     if (!t->events_host && t->n_event_total > 0) return LLMEM_EINVAL_NULL;
     if (!t->params_dev && t->n_param_total > 0) return LLMEM_EINVAL_NULL;
@@ -393,7 +367,7 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out)
     out->m_base = t->m_base;
     out->n_arch = t->n_arch;
     out->n_param_total = t->n_param_total;
-    int slot = 0;
+    int slot = 0, code = 0;
     for (int ar = 0; ar < t->n_arch; ++ar) {
         const llmem_arch_desc &d = t->arch[ar];
         ArchLayout &al = out->arch[ar];
@@ -436,9 +410,27 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out)
             al.lane0[s + 1] = al.lane0[s] + (per_lane ? (seg_count[s] + per_lane - 1) / per_lane : 0);
         al.slot_first = slot;
         slot += per_lane * 64;
+        // lane-per-configuration kernel: event codes of the architecture, number of size classes
+        al.code_first = code;
+        code += (d.n_event + 15) & ~15;
+        if (d.n_event > out->max_events) out->max_events = d.n_event;
+        int n_class = 0;
+        for (int j = 0; j < d.n_event && n_class <= NC_MAX; ++j) {
+            const uint32_t *w = reinterpret_cast<const uint32_t *>(&t->events_host[d.event_first + j]);
+            const ClassKey kj = make_class_key(w[0], w[1], w[2]);
+            bool seen = false;
+            for (int q = 0; q < j && !seen; ++q) {
+                const uint32_t *v = reinterpret_cast<const uint32_t *>(&t->events_host[d.event_first + q]);
+                const ClassKey kq = make_class_key(v[0], v[1], v[2]);
+                seen = kq.coef == kj.coef && kq.dims == kj.dims && kq.meta == kj.meta;
+            }
+            if (!seen) ++n_class;
+        }
+        if (n_class > NC_MAX) *batch_ok = false;
     }
-    if (slot > LLMEM_MAX_EVENT_SLOTS) return LLMEM_EINVAL_TABLE;
     out->n_slot_total = slot;
+    out->code_bytes = code;
+    *wave_ok = slot <= LLMEM_MAX_EVENT_SLOTS;
     return LLMEM_OK;
 }
 
@@ -450,8 +442,17 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     if (n < 0) return LLMEM_EINVAL_N;
     EstimateArgs args;
     memset(&args, 0, sizeof(args));
-    int rc = plan_tables(tables, &args);
+    bool wave_ok, batch_ok;
+    int rc = plan_tables(tables, &args, &wave_ok, &batch_ok);
     if (rc != LLMEM_OK) return rc;
+    // which kernel: the lane-per-configuration kernel needs every architecture's timeline to
+    // have at most NC_MAX size classes; the wavefront-per-configuration kernel needs the dealt
+    // events of all architectures to fit its LDS slots
+    const int hint = tables->kernel;
+    if (hint < LLMEM_KERNEL_AUTO || hint > LLMEM_KERNEL_LANE) return LLMEM_EINVAL_TABLE;
+    if ((hint == LLMEM_KERNEL_WAVE && !wave_ok) || (hint == LLMEM_KERNEL_LANE && !batch_ok)
+        || (!wave_ok && !batch_ok)) return LLMEM_EINVAL_TABLE;
+    const bool use_batch = hint == LLMEM_KERNEL_LANE || (hint == LLMEM_KERNEL_AUTO && batch_ok);
     if (n == 0) return LLMEM_OK;
     if (!cfg->arch_id || !cfg->h || !cfg->L || !cfg->n_heads || !cfg->n_kv || !cfg->ffn || !cfg->V
         || !cfg->P || !cfg->bs || !cfg->sl || !cfg->method || !cfg->d || !cfg->chunk_k || !cfg->flags)
@@ -463,8 +464,19 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     args.out_peaks = reinterpret_cast<long long *>(out_peaks);
     args.out_detail = reinterpret_cast<long long *>(out_detail);
 
-    const size_t lds_bytes = sizeof(uint4) * (size_t)(args.n_param_total + args.n_slot_total);
     const int64_t n_batch = (n + 63) / 64;
+    if (use_batch) {
+        int64_t blocks = (n_batch + 3) / 4;
+        if (blocks > 256 * 4) blocks = 256 * 4;
+        launch_batch_kernel(args, out_detail != nullptr, (unsigned)blocks, stream);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) {
+            snprintf(g_hip_error, sizeof(g_hip_error), "HIP error: %s", hipGetErrorString(e));
+            return LLMEM_EHIP;
+        }
+        return LLMEM_OK;
+    }
+    const size_t lds_bytes = sizeof(uint4) * (size_t)(args.n_param_total + args.n_slot_total);
     int64_t blocks = (n_batch + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     const int64_t max_blocks = 256 * 16;          // 256 CUs, a few resident workgroups each
     if (blocks > max_blocks) blocks = max_blocks;

@@ -1,0 +1,69 @@
+// Kernel arguments and table planning shared by the two estimator kernels
+// (one wavefront per configuration; one lane per configuration).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/llmem.h"
+
+namespace llmem {
+
+constexpr int K_SEARCH_MIN = 2, K_SEARCH_MAX = 10, K_FIXED_MAX = 16;
+constexpr int B16 = 2, B32 = 4;
+
+// lane-per-configuration kernel: size classes per architecture, event code bits
+constexpr int NC_MAX = 32;
+constexpr unsigned CODE_FREE = 32, CODE_CHECK = 64;
+
+struct ArchLayout {
+    int param_first, n_param;
+    int event_first;                 // first entry of the architecture in events_dev
+    int seg_first[LLMEM_NSEG + 1];   // segment boundaries relative to event_first
+    // wavefront-per-configuration kernel: every lane owns `per_lane` consecutive events of a
+    // single segment; segment s occupies lanes lane0[s] .. lane0[s+1]-1; LDS slot
+    // slot_first + j*64 + lane holds the lane's j-th event
+    int per_lane;
+    int lane0[LLMEM_NSEG + 1];
+    int slot_first;
+    // lane-per-configuration kernel: first byte of the architecture's event codes in LDS
+    int code_first;
+};
+
+struct EstimateArgs {
+    llmem_configs cfg;
+    long long n;
+    long long m_base;
+    int cu_shift, align_shift;
+    int n_arch, n_param_total, n_slot_total;
+    int code_bytes, max_events;
+    ArchLayout arch[LLMEM_MAX_ARCH];
+    const uint4 *params_dev;
+    const uint4 *events_dev;
+    long long *out_peaks;
+    long long *out_detail;
+};
+
+// Events with equal keys have equal byte sizes for every configuration: same
+// coefficient, same multiset of dimensions, same element width, scaling flags
+// and method mask.  x, y, z are the first three dwords of an llmem_event_entry.
+struct ClassKey { uint32_t coef, dims, meta; };
+
+__host__ __device__ inline ClassKey make_class_key(uint32_t x, uint32_t y, uint32_t z)
+{
+    uint32_t d0 = y & 15u, d1 = (y >> 8) & 15u, d2 = (y >> 16) & 15u, d3 = (y >> 24) & 15u, t;
+#define LLMEM_CSWAP(p, q) if (p > q) { t = p; p = q; q = t; }
+    LLMEM_CSWAP(d0, d1) LLMEM_CSWAP(d2, d3) LLMEM_CSWAP(d0, d2) LLMEM_CSWAP(d1, d3) LLMEM_CSWAP(d1, d2)
+#undef LLMEM_CSWAP
+    const uint32_t elem_bytes = z & 255u, flags = (z >> 16) & 255u, mask = (z >> 24) & 7u;
+    ClassKey k;
+    k.coef = x;
+    k.dims = d0 | (d1 << 8) | (d2 << 16) | (d3 << 24);
+    k.meta = elem_bytes | ((flags & (LLMEM_EV_TIMES_L | LLMEM_EV_TP_GATHER)) << 8) | (mask << 16);
+    return k;
+}
+
+size_t batch_kernel_lds_bytes(const EstimateArgs &a);
+void launch_batch_kernel(const EstimateArgs &args, bool detail, unsigned blocks, hipStream_t stream);
+
+}  // namespace llmem

@@ -1,0 +1,350 @@
+// Batched peak-GPU-memory estimator, throughput kernel: one lane per
+// configuration, 64 configurations per wavefront.
+//
+// The lanes of a wave hold 64 consecutive configurations (coalesced column
+// loads).  Table entries are wave-uniform, so the wave walks the parameter table
+// and the timeline of the architecture entry by entry while every lane evaluates
+// the entry for its own configuration: no cross-lane reduction is needed, the
+// prefix sum and running maximum of the timeline live in registers, and results
+// are already one per lane for a coalesced store.
+//
+// Workgroup set-up (once, in LDS): the timeline events of each architecture are
+// grouped into size classes - events whose byte size is the same expression
+// (coefficient, dimensions, element width, scaling, method mask).  A lane
+// evaluates each class once per configuration and keeps the rounded sizes in
+// registers; an event is then one signed add of its class, and the running
+// maximum is taken where the live total can peak (an allocation followed by a
+// release or by the end of its segment).
+//
+// Closed form: Sec. 4.2 (m_p, m_os, m_out, m_lm, m_peak^s) and Sec. 5 (m_peak^dp,
+// m_peak^tp, m_back^tp) of arXiv 2404.10933; chunk size per Sec. 4.1; timeline
+// traversal per Sec. 2.1 / Sec. 3.1.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/llmem.h"
+#include "estimate_args.h"
+#include "wave.h"
+
+namespace llmem {
+
+namespace {
+
+constexpr int BB_WAVES = 4;
+constexpr int BB_BLOCK = 64 * BB_WAVES;
+constexpr i64 LOWEST = (i64)0x8000000000000000ull;
+
+__device__ __forceinline__ u64 b_div(u64 x, u32 d, u64 mul, u32 shift)
+{
+    return d == 1 ? x : (__umul64hi(x, mul) >> shift);
+}
+__device__ __forceinline__ u64 b_cdiv(u64 x, u32 d, u64 mul, u32 shift) { return b_div(x + (d - 1), d, mul, shift); }
+__device__ __forceinline__ u64 b_up(u64 x, int shift) { return ((x + ((1ull << shift) - 1)) >> shift) << shift; }
+__device__ __forceinline__ u32 uni(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
+
+}  // namespace
+
+template <bool DETAIL>
+__global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const EstimateArgs a)
+{
+    extern __shared__ uint4 lds[];
+    // LDS: class table | event codes | class counts | scratch of the set-up
+    uint4 *cls_tab = lds;                                              // n_arch * NC_MAX
+    uint8_t *codes = reinterpret_cast<uint8_t *>(lds + a.n_arch * NC_MAX);
+    int *n_class = reinterpret_cast<int *>(codes + a.code_bytes);       // LLMEM_MAX_ARCH ints
+    uint4 *tmp_key = reinterpret_cast<uint4 *>(n_class + LLMEM_MAX_ARCH);
+    unsigned short *tmp_rep = reinterpret_cast<unsigned short *>(tmp_key + a.max_events);
+    unsigned short *tmp_cid = tmp_rep + a.max_events;
+
+    // ---- set-up: size classes and event codes of every architecture ----------------
+    if (threadIdx.x < LLMEM_MAX_ARCH) n_class[threadIdx.x] = 0;
+    __syncthreads();
+    if (DETAIL) {
+        for (int ar = 0; ar < a.n_arch; ++ar) {
+            const ArchLayout &al = a.arch[ar];
+            const int n = al.seg_first[LLMEM_NSEG];
+            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {
+                const uint4 raw = a.events_dev[al.event_first + e];
+                const ClassKey k = make_class_key(raw.x, raw.y, raw.z);
+                tmp_key[e] = make_uint4(k.coef, k.dims, k.meta, raw.z);
+            }
+            __syncthreads();
+            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {
+                const uint4 me = tmp_key[e];
+                int rep = e;
+                for (int j = 0; j < e; ++j) {
+                    const uint4 o = tmp_key[j];
+                    if (o.x == me.x && o.y == me.y && o.z == me.z) { rep = j; break; }
+                }
+                tmp_rep[e] = (unsigned short)rep;
+            }
+            __syncthreads();
+            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {
+                if (tmp_rep[e] != e) continue;
+                int cid = 0;
+                for (int j = 0; j < e; ++j) cid += tmp_rep[j] == j ? 1 : 0;
+                tmp_cid[e] = (unsigned short)cid;
+                if (cid < NC_MAX) cls_tab[ar * NC_MAX + cid] = tmp_key[e];
+                atomicMax(&n_class[ar], cid + 1);
+            }
+            __syncthreads();
+            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {
+                const u32 z = tmp_key[e].w;
+                const u32 seg = (z >> 8) & 255u, fl = (z >> 16) & 255u;
+                const bool is_free = fl & LLMEM_EV_FREE;
+                bool check = !is_free;
+                if (check && e + 1 < n) {
+                    const u32 zn = tmp_key[e + 1].w;
+                    check = (((zn >> 8) & 255u) != seg) || (((zn >> 16) & 255u) & LLMEM_EV_FREE);
+                }
+                codes[al.code_first + e] = (uint8_t)((tmp_cid[tmp_rep[e]] & (NC_MAX - 1)) | (is_free ? CODE_FREE : 0)
+                                                     | (check ? CODE_CHECK : 0));
+            }
+            __syncthreads();
+        }
+    }
+
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const long long n = a.n;
+    const long long n_batch = (n + 63) >> 6;
+    const int cu_shift = a.cu_shift, align_shift = a.align_shift;
+    const u64 m_base = (u64)a.m_base;
+
+    for (long long b = (long long)blockIdx.x * BB_WAVES + wave; b < n_batch;
+         b += (long long)gridDim.x * BB_WAVES) {
+        const long long i = (b << 6) + lane;
+        const bool in_range = i < n;
+        u32 h = 1, ffn = 0, V = 0, P = 0, arch_id = 0, method = 0, d = 1, cflags = 0, L = 0, n_heads = 1,
+            n_kv = 0, bs = 0, sl = 0;
+        int chunk_k = 0;
+        if (in_range) {
+            h = a.cfg.h[i]; ffn = a.cfg.ffn[i]; V = a.cfg.V[i]; P = a.cfg.P[i];
+            arch_id = a.cfg.arch_id[i]; method = a.cfg.method[i]; d = a.cfg.d[i]; cflags = a.cfg.flags[i];
+            L = a.cfg.L[i]; n_heads = a.cfg.n_heads[i]; n_kv = a.cfg.n_kv[i];
+            chunk_k = a.cfg.chunk_k[i]; bs = a.cfg.bs[i]; sl = a.cfg.sl[i];
+        }
+        u32 err = 0;
+        if (arch_id >= (u32)a.n_arch) err |= LLMEM_F_ERR_ARCH;
+        if (method > 2) err |= LLMEM_F_ERR_METHOD;
+        if (d == 0) err |= LLMEM_F_ERR_D;
+        if (n_heads == 0) err |= LLMEM_F_ERR_HEADS;
+        if (!(chunk_k == -1 || (chunk_k >= 0 && chunk_k <= K_FIXED_MAX))) err |= LLMEM_F_ERR_CHUNK;
+        const bool valid = in_range && err == 0;
+
+        // dimension vector of this lane's configuration
+        const u32 head_dim = h / (n_heads ? n_heads : 1u);
+        u32 D[16];
+        D[LLMEM_DIM_ONE] = 1; D[LLMEM_DIM_BS] = bs; D[LLMEM_DIM_SL] = sl; D[LLMEM_DIM_SL_M1] = sl ? sl - 1 : 0;
+        D[LLMEM_DIM_H] = h; D[LLMEM_DIM_FFN] = ffn; D[LLMEM_DIM_N_HEADS] = n_heads; D[LLMEM_DIM_N_KV] = n_kv;
+        D[LLMEM_DIM_HEAD_DIM] = head_dim; D[LLMEM_DIM_KV_DIM] = n_kv * head_dim; D[LLMEM_DIM_V] = V;
+        D[LLMEM_DIM_P] = P; D[LLMEM_DIM_L] = L;
+        const u32 Blog = (cflags & LLMEM_CFG_LOGITS_FP32) ? B32 : B16;
+        D[LLMEM_DIM_B_LOGITS] = Blog; D[LLMEM_DIM_D] = d; D[15] = 0;
+        const DivMagic mg = c_div.t[d & 255u];
+        const u64 div_mul = mg.mul;
+        const u32 div_shift = mg.shift;
+
+        i64 r_peak = err ? -1 : 0, r_param = 0, r_grad = 0, r_os = 0, r_out = 0, r_lm = 0, r_back = 0, r_k = 0,
+            r_live = 0, r_np = 0, r_tmax = 0, r_flags = err;
+
+        unsigned long long todo = __builtin_amdgcn_ballot_w64(valid);
+        while (todo) {
+            const int first = __builtin_ctzll(todo);
+            const u32 ar = read_lane(arch_id, first);
+            const bool mine = valid && arch_id == ar;
+            todo &= ~__builtin_amdgcn_ballot_w64(mine);
+            if (!mine) continue;
+            const ArchLayout &al = a.arch[ar];
+            const int n_param = (int)uni((u32)al.n_param), param_first = (int)uni((u32)al.param_first);
+
+            // ---- parameter table (Notation table; Sec. 4.2, equation for m_os) ---------
+            u64 embed_p = 0, lm_p = 0, other_p = 0, t_max = 0, m_os = 0;
+            u32 e_n = 0;
+            for (int j = 0; j < n_param; ++j) {
+                const uint4 pe = a.params_dev[param_first + j];           // wave-uniform
+                const u32 cls = pe.z & 255u, role = (pe.z >> 8) & 255u, per_layer = (pe.z >> 16) & 255u;
+                u64 t_p = (u64)pe.x * D[pe.y & 15u];
+                t_p *= D[(pe.y >> 8) & 15u];
+                t_p *= D[(pe.y >> 16) & 15u];
+                t_p *= D[(pe.y >> 24) & 15u];
+                const u64 copies = per_layer ? (u64)L : 1ull;
+                const u64 tot = t_p * copies;
+                if (role == LLMEM_ROLE_EMBED_TOK) embed_p += tot;
+                else if (role == LLMEM_ROLE_LM_HEAD) lm_p += tot;
+                else { other_p += tot; t_max = t_p > t_max ? t_p : t_max; }
+                if (cls <= LLMEM_CLS_LINEAR && role != LLMEM_ROLE_LM_HEAD)
+                    m_os += b_up(t_p * (u64)(B32 + B32), cu_shift) * copies;
+                if (cls == LLMEM_CLS_EMBEDDING && role != LLMEM_ROLE_LM_HEAD) ++e_n;
+            }
+            const u64 n_params = embed_p + other_p + ((cflags & LLMEM_CFG_TIED_LM_HEAD) ? 0ull : lm_p);
+
+            // ---- Sec. 4.2: m_out, m_lm; Sec. 5: m_back^tp -----------------------------------
+            const u64 A = (u64)bs * sl * h;
+            const u64 m_out = b_up(((u64)e_n + L) * A * B16, cu_shift);
+            const u64 row = (u64)bs * V * Blog;
+            const u64 m_lm = b_up(row * sl, cu_shift) + 2 * b_up(row * D[LLMEM_DIM_SL_M1], cu_shift) + lm_p * B16;
+            u64 m_back = 0;
+            if (method == LLMEM_METHOD_TP) {
+                const u64 pages = ((u64)L * A * (d - 1) * B16 + ((1ull << cu_shift) - 1)) >> cu_shift;
+                m_back = b_cdiv(pages, d, div_mul, div_shift) << cu_shift;
+            }
+            // ---- Sec. 4.1: gradients alias param fp16 unless switched off -------------------
+            const u64 grad_bytes = (embed_p + other_p) * B16;
+            const u64 grad_logical = method == LLMEM_METHOD_CDP ? grad_bytes : b_cdiv(grad_bytes, d, div_mul, div_shift);
+            u64 grad_extra = 0;
+            if (!(cflags & LLMEM_CFG_GRAD_ALIAS)) {
+                const u64 g = b_up(grad_bytes, cu_shift);
+                grad_extra = method == LLMEM_METHOD_CDP ? g : b_up(b_cdiv(g, d, div_mul, div_shift), align_shift);
+            }
+
+            // ---- chunk size (Sec. 4.1), m_p and the method's peak ----------------------------
+            // Every candidate k = 2..10 is estimated; the feasible one with the least padding
+            // waste wins, ties to the smaller chunk.  A lane with a given chunk size estimates
+            // that one.
+            const bool search = chunk_k == -1;
+            const bool any_search = __builtin_amdgcn_ballot_w64(search) != 0;
+            u64 m_peak = 0, mp = 0, mp16 = 0, mp32 = 0, best_waste = ~0ull;
+            int k_used = search ? K_SEARCH_MAX : chunk_k;
+            bool found = !search;
+            for (int j = 0; j <= K_SEARCH_MAX - K_SEARCH_MIN; ++j) {
+                if (j > 0 && !any_search) break;
+                const int k = search ? K_SEARCH_MIN + j : chunk_k;
+                const int cs_shift = k + 19;                                  // 2^k MiB of fp16 values
+                const u64 cs_mask = (1ull << cs_shift) - 1;
+                const u64 other_chunked = (other_p + cs_mask) & ~cs_mask;     // ceil(other_p / cs) * cs
+                const u64 chunked = embed_p + other_chunked;
+                const u64 c_p = b_up(chunked * (B16 + B32), cu_shift);
+                const u64 c_p16 = b_up(chunked * B16, cu_shift);
+                const u64 c_p32 = b_up(chunked * B32, cu_shift);
+                const u64 to_shard = method == LLMEM_METHOD_ZERO3 ? c_p32 + m_os : c_p + m_os;
+                const u64 shard = b_up(b_cdiv(to_shard, d, div_mul, div_shift), align_shift);
+                u64 states;
+                if (method == LLMEM_METHOD_CDP) states = c_p + m_os;
+                else if (method == LLMEM_METHOD_ZERO3) states = c_p16 + shard;
+                else states = shard + m_back;
+                const u64 c_peak = m_base + states + m_out + m_lm + grad_extra;
+                const u64 waste = other_chunked - other_p;
+                const bool feasible = t_max <= (1ull << cs_shift);
+                // search lanes: strictly smaller waste among feasible candidates; the last candidate
+                // stands in when none is feasible.  Other lanes: iteration 0 is their estimate.
+                const bool take = search ? ((feasible && waste < best_waste) || (!found && j == K_SEARCH_MAX - K_SEARCH_MIN))
+                                         : j == 0;
+                if (take) {
+                    m_peak = c_peak; mp = c_p; mp16 = c_p16; mp32 = c_p32; k_used = k;
+                    if (feasible) { best_waste = waste; found = true; }
+                }
+            }
+            const u32 flags = t_max > (1ull << (k_used + 19)) ? LLMEM_F_CHUNK_INFEASIBLE : 0;
+            r_peak = (i64)m_peak;
+
+            if (DETAIL) {
+                u64 param_gpu, os_gpu;
+                if (method == LLMEM_METHOD_CDP) {
+                    param_gpu = mp; os_gpu = m_os;
+                } else {
+                    const u64 os_sh = b_up(b_cdiv(m_os, d, div_mul, div_shift), align_shift);
+                    const u64 p_sh = b_up(b_cdiv(method == LLMEM_METHOD_ZERO3 ? mp32 : mp, d, div_mul, div_shift), align_shift);
+                    param_gpu = method == LLMEM_METHOD_ZERO3 ? mp16 + p_sh : p_sh;
+                    os_gpu = os_sh;
+                }
+
+                // ---- size classes of the timeline: rounded bytes per class, in registers ------
+                u32 s_lo[NC_MAX], s_hi[NC_MAX];
+#pragma unroll
+                for (int c = 0; c < NC_MAX; ++c) { s_lo[c] = 0; s_hi[c] = 0; }
+                const int nc_raw = (int)uni((u32)n_class[ar]);
+                const int nc = nc_raw < NC_MAX ? nc_raw : NC_MAX;
+                for (int c = 0; c < nc; ++c) {
+                    const uint4 ce = cls_tab[ar * NC_MAX + c];                // wave-uniform
+                    const u32 coef = uni(ce.x), dims = uni(ce.y), meta = uni(ce.z);
+                    u64 x = (u64)coef * (meta & 255u);
+                    x *= D[dims & 15u];
+                    x *= D[(dims >> 8) & 15u];
+                    x *= D[(dims >> 16) & 15u];
+                    x *= D[(dims >> 24) & 15u];
+                    const u32 fl = (meta >> 8) & 255u, mask = (meta >> 16) & 7u;
+                    if (fl & LLMEM_EV_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
+                    u64 r = b_up(x, align_shift);
+                    if (fl & LLMEM_EV_TIMES_L) r *= (u64)L;
+                    if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
+                    s_lo[c] = (u32)r;
+                    s_hi[c] = (u32)(r >> 32);
+                }
+
+                // ---- timeline (Sec. 2.1 / Sec. 3.1): A, F x L, H, B x L, Z ---------------------
+                // `at` is the live total at the start of the segment relative to the resident
+                // state; the L equal blocks shift the prefix linearly, so the maximum over the
+                // repetitions of F (or B) is taken at the first or the last one.
+                i64 at = 0, best = 0;                                         // the empty prefix counts
+                const uint8_t *cd = codes + (int)uni((u32)al.code_first);
+                for (int s = 0; s < LLMEM_NSEG; ++s) {
+                    i64 run = 0, top = LOWEST;
+                    const int e_begin = (int)uni((u32)al.seg_first[s]), e_end = (int)uni((u32)al.seg_first[s + 1]);
+                    for (int e = e_begin; e < e_end; ++e) {
+                        const u32 code = uni((u32)cd[e]);
+                        const u32 idx = code & (NC_MAX - 1);
+                        const i64 v = (i64)(((u64)s_hi[idx] << 32) | s_lo[idx]);
+                        if (code & CODE_FREE) run -= v; else run += v;
+                        if (code & CODE_CHECK) top = run > top ? run : top;
+                    }
+                    const bool repeated = s == LLMEM_SEG_F || s == LLMEM_SEG_B;
+                    if (repeated) {
+                        const i64 shift = ((i64)L - 1) * run;
+                        const i64 cand = at + top + (shift > 0 ? shift : 0);
+                        if (top != LOWEST && L != 0) best = cand > best ? cand : best;
+                        at += (i64)L * run;
+                    } else {
+                        const i64 cand = at + top;
+                        if (top != LOWEST) best = cand > best ? cand : best;
+                        at += run;
+                    }
+                }
+                const i64 prelude = (i64)(m_base + param_gpu + os_gpu + lm_p * B16 + grad_extra);
+                r_param = (i64)param_gpu; r_grad = (i64)grad_logical; r_os = (i64)os_gpu; r_out = (i64)m_out;
+                r_lm = (i64)m_lm; r_back = (i64)m_back; r_k = (i64)k_used; r_live = prelude + best;
+                r_np = (i64)n_params; r_tmax = (i64)t_max; r_flags = (i64)flags;
+            }
+        }
+
+        if (in_range) {
+            if (a.out_peaks) a.out_peaks[i] = r_peak;
+            if (DETAIL) {
+                long long *o = a.out_detail + i;
+                o[(long long)LLMEM_D_PEAK * n] = r_peak;
+                o[(long long)LLMEM_D_PARAM_GPU * n] = r_param;
+                o[(long long)LLMEM_D_GRAD_GPU * n] = r_grad;
+                o[(long long)LLMEM_D_OS_GPU * n] = r_os;
+                o[(long long)LLMEM_D_OUT * n] = r_out;
+                o[(long long)LLMEM_D_LM * n] = r_lm;
+                o[(long long)LLMEM_D_BACK * n] = r_back;
+                o[(long long)LLMEM_D_K * n] = r_k;
+                o[(long long)LLMEM_D_PEAK_LIVE * n] = r_live;
+                o[(long long)LLMEM_D_NPARAMS * n] = r_np;
+                o[(long long)LLMEM_D_TMAX * n] = r_tmax;
+                o[(long long)LLMEM_D_FLAGS * n] = r_flags;
+            }
+        }
+    }
+}
+
+size_t batch_kernel_lds_bytes(const EstimateArgs &a)
+{
+    size_t bytes = sizeof(uint4) * (size_t)a.n_arch * NC_MAX;       // class table
+    bytes += (size_t)a.code_bytes;                                   // event codes
+    bytes += sizeof(int) * LLMEM_MAX_ARCH;                           // class counts
+    bytes += sizeof(uint4) * (size_t)a.max_events;                   // set-up scratch: keys
+    bytes += 2 * sizeof(unsigned short) * (size_t)a.max_events;      // set-up scratch: representatives, ids
+    return (bytes + 15) & ~(size_t)15;
+}
+
+void launch_batch_kernel(const EstimateArgs &args, bool detail, unsigned blocks, hipStream_t stream)
+{
+    const size_t lds_bytes = batch_kernel_lds_bytes(args);
+    if (detail)
+        hipLaunchKernelGGL(estimate_batch_kernel<true>, dim3(blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
+    else
+        hipLaunchKernelGGL(estimate_batch_kernel<false>, dim3(blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
+}
+
+}  // namespace llmem

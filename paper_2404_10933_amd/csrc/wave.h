@@ -102,4 +102,7 @@ struct DivMagicTable {
     constexpr DivMagicTable() : t{} { for (unsigned d = 0; d < 256; ++d) t[d] = make_magic(d); }
 };
 
+// one copy per translation unit (device symbols are not shared across them)
+static __constant__ DivMagicTable c_div = DivMagicTable();
+
 }  // namespace llmem

@@ -6,10 +6,10 @@ import torch
 import paper_2404_10933_amd as M
 
 
-def hip_estimate(cfg_np, tables, const, detail=True, stream=None):
+def hip_estimate(cfg_np, tables, const, detail=True, stream=None, kernel=0):
     """Returns (peaks[n], detail[n, 12] or None) computed by the HIP kernels."""
     dev = M.DeviceConfigs.from_numpy(cfg_np)
-    tab = M.Tables(tables, m_base=const.m_base, cu_p=const.cu_p, align=const.align)
+    tab = M.Tables(tables, m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=kernel)
     n = dev.n
     peaks = torch.full((max(n, 1),), -7, dtype=torch.int64, device="cuda")
     det = torch.full((M.NDETAIL, max(n, 1)), -7, dtype=torch.int64, device="cuda") if detail else None

@@ -20,13 +20,20 @@ def U():
     return gpu_util
 
 
-def _check(U, cfg, tables, const=CONST, threads=8):
+WAVE, LANE = 1, 2       # LLMEM_KERNEL_WAVE, LLMEM_KERNEL_LANE
+BOTH = (WAVE, LANE)
+
+
+def _check(U, cfg, tables, const=CONST, threads=8, kernels=BOTH):
+    """Both kernels (one wavefront per configuration; one lane per configuration),
+    each forced, plus the library's own choice, against the oracle."""
     want_p, want_d = B.estimate(cfg, tables, const, threads=threads)
-    got_p, got_d = U.hip_estimate(cfg, tables, const)
-    U.assert_same("detail", got_d, want_d)
-    U.assert_same("peaks", got_p, want_p)
-    got_p2, _ = U.hip_estimate(cfg, tables, const, detail=False)
-    U.assert_same("peaks (no detail)", got_p2, want_p)
+    for kernel in tuple(kernels) + (0,):
+        got_p, got_d = U.hip_estimate(cfg, tables, const, kernel=kernel)
+        U.assert_same(f"detail (kernel {kernel})", got_d, want_d)
+        U.assert_same(f"peaks (kernel {kernel})", got_p, want_p)
+        got_p2, _ = U.hip_estimate(cfg, tables, const, detail=False, kernel=kernel)
+        U.assert_same(f"peaks, no detail (kernel {kernel})", got_p2, want_p)
 
 
 def test_grid1_all(U):
@@ -57,9 +64,27 @@ def test_random_tables_wild_configs(U):
             T.random_table(rng, 64, 700, "r3"), T.gpt_table(), T.random_table(rng, 1, 1, "one"),
             T.random_table(rng, 30, 1024, "max")]
     cfg = G.random_configs(rng, 64 * 40 + 5, n_arch=len(tabs), wild=True)
+    # more than 32 distinct sizes in one architecture: only the wavefront-per-configuration kernel applies
+    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), kernels=(WAVE,))
+    _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512), kernels=(WAVE,))
+    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), kernels=(WAVE,))
+    import paper_2404_10933_amd as M
+    with pytest.raises(M.LlmemError) as e:
+        U.hip_estimate(cfg, tabs, CONST, kernel=LANE)
+    assert e.value.code == -3
+
+
+def test_random_tables_few_sizes(U):
+    """Random tables whose events share at most 32 size expressions, several
+    architectures mixed inside each wavefront's 64 configurations."""
+    rng = np.random.default_rng(13)
+    tabs = [T.random_table(rng, 9, 150, "r0", n_sizes=32), T.llama_table(), T.random_table(rng, 0, 0, "empty"),
+            T.random_table(rng, 64, 1024, "r3", n_sizes=20), T.gpt_table(), T.random_table(rng, 1, 1, "one", n_sizes=1),
+            T.random_table(rng, 30, 600, "r6", n_sizes=7), T.opt_table()]
+    cfg = G.random_configs(rng, 64 * 40 + 5, n_arch=len(tabs), wild=True)
     _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512))
-    _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512))
     _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1))
+    _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512))
 
 
 def test_degenerate_and_flag_cases(U):
@@ -78,11 +103,12 @@ def test_degenerate_and_flag_cases(U):
 
 def test_determinism_and_stream(U):
     cfg = G.grid3(n=20_000, seed=5)
-    s = torch.cuda.Stream()
-    with torch.cuda.stream(s):
-        a = U.hip_estimate(cfg, [T.llama_table()], CONST, stream=s)
-    b = U.hip_estimate(cfg, [T.llama_table()], CONST)
-    U.assert_same("detail twice", a[1], b[1])
+    for kernel in BOTH:
+        s = torch.cuda.Stream()
+        with torch.cuda.stream(s):
+            a = U.hip_estimate(cfg, [T.llama_table()], CONST, stream=s, kernel=kernel)
+        b = U.hip_estimate(cfg, [T.llama_table()], CONST, kernel=kernel)
+        U.assert_same("detail twice", a[1], b[1])
 
 
 def test_full_size_grid4(U):

@@ -399,29 +399,39 @@ def degenerate_table(base: ArchTable) -> ArchTable:
     return ArchTable(base.name + "_degenerate", base.params, tuple(ev))
 
 
-def random_table(rng, n_param: int, n_event: int, name: str = "random") -> ArchTable:
+def random_table(rng, n_param: int, n_event: int, name: str = "random", n_sizes: int = 0) -> ArchTable:
     """A structurally valid but arbitrary table (for parity tests): random
     selectors, classes, roles, signs, method masks, scales and segment lengths.
+    With n_sizes > 0 the events draw their size expression (coefficient,
+    dimensions, element width, method mask, scaling) from a pool of that many.
     `rng` is a numpy Generator."""
-    small = ("one", "bs", "sl", "sl_m1", "h", "ffn", "n_heads", "n_kv", "head_dim", "kv_dim", "P", "L", "B_logits", "d")
+    large = ("sl", "sl_m1", "h", "ffn", "P", "kv_dim")          # at most two of these per size: no int64 overflow
+    tiny = ("one", "bs", "n_heads", "n_kv", "head_dim", "L", "B_logits", "d")
     params = []
     for i in range(n_param):
         nd = int(rng.integers(0, 3))
         dims = tuple(str(rng.choice(("h", "ffn", "V", "P", "kv_dim", "head_dim", "n_heads", "one"))) for _ in range(nd))
         params.append(ParamEntry(f"p{i}", int(rng.integers(1, 5)), dims,
                                  str(rng.choice(CLASSES)), str(rng.choice(ROLES)), bool(rng.integers(0, 2))))
+
+    def size_spec():
+        dims = tuple(str(rng.choice(large)) for _ in range(int(rng.integers(0, 3)))) \
+            + tuple(str(rng.choice(tiny)) for _ in range(int(rng.integers(0, 3))))
+        mask = frozenset(m for m in (0, 1, 2) if rng.integers(0, 4) > 0)
+        return (int(rng.integers(1, 9)), dims, int(rng.choice((1, 2, 4, 8))), mask,
+                "tp_gather" if rng.integers(0, 6) == 0 else "none", bool(rng.integers(0, 8) == 0))
+
+    pool = [size_spec() for _ in range(n_sizes)]
     cuts = sorted(int(x) for x in rng.integers(0, n_event + 1, size=4))
     bounds = [0] + cuts + [n_event]
     events = []
     for s, seg in enumerate(SEGMENTS):
         for i in range(bounds[s], bounds[s + 1]):
-            nd = int(rng.integers(0, 5))
-            dims = tuple(str(rng.choice(small)) for _ in range(nd))
-            mask = frozenset(m for m in (0, 1, 2) if rng.integers(0, 4) > 0)
-            events.append(EventEntry(
-                f"e{i}", seg, +1 if rng.integers(0, 5) > 1 else -1, int(rng.integers(1, 9)), dims,
-                int(rng.choice((1, 2, 4, 8))), mask,
-                "tp_gather" if rng.integers(0, 6) == 0 else "none", bool(rng.integers(0, 8) == 0)))
+            coef, dims, eb, mask, scale, times_l = pool[int(rng.integers(0, n_sizes))] if n_sizes else size_spec()
+            if n_sizes:
+                dims = tuple(rng.permutation(list(dims))) if dims else dims    # same product, other order
+            events.append(EventEntry(f"e{i}", seg, +1 if rng.integers(0, 5) > 1 else -1, coef,
+                                     tuple(str(x) for x in dims), eb, mask, scale, times_l))
     return ArchTable(name, tuple(params), tuple(events))
 
 
