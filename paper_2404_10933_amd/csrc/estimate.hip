@@ -410,26 +410,32 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, 
             al.lane0[s + 1] = al.lane0[s] + (per_lane ? (seg_count[s] + per_lane - 1) / per_lane : 0);
         al.slot_first = slot;
         slot += per_lane * 64;
-        // lane-per-configuration kernel: event codes of the architecture, number of size classes
+        // lane-per-configuration kernel: padded event codes, size classes and value slots
         al.code_first = code;
-        code += (d.n_event + 15) & ~15;
+        al.seg_code[0] = 0;
+        for (int s = 0; s < LLMEM_NSEG; ++s)
+            al.seg_code[s + 1] = al.seg_code[s] + (seg_count[s] + CODE_GROUP - 1) / CODE_GROUP * CODE_GROUP;
+        code += al.seg_code[LLMEM_NSEG];
         if (d.n_event > out->max_events) out->max_events = d.n_event;
         int n_class = 0;
-        for (int j = 0; j < d.n_event && n_class <= NC_MAX; ++j) {
+        for (int j = 0; j < d.n_event && n_class <= CLS_MAX; ++j) {
             const uint32_t *w = reinterpret_cast<const uint32_t *>(&t->events_host[d.event_first + j]);
             const ClassKey kj = make_class_key(w[0], w[1], w[2]);
-            bool seen = false;
-            for (int q = 0; q < j && !seen; ++q) {
+            bool first_of_class = true;
+            for (int q = 0; q < j && first_of_class; ++q) {
                 const uint32_t *v = reinterpret_cast<const uint32_t *>(&t->events_host[d.event_first + q]);
                 const ClassKey kq = make_class_key(v[0], v[1], v[2]);
-                seen = kq.coef == kj.coef && kq.dims == kj.dims && kq.meta == kj.meta;
+                first_of_class = !(kq.coef == kj.coef && kq.dims == kj.dims && kq.meta == kj.meta);
             }
-            if (!seen) ++n_class;
+            if (first_of_class) ++n_class;
         }
-        if (n_class > NC_MAX) *batch_ok = false;
+        if (n_class > CLS_MAX) *batch_ok = false;
+        if (n_class + 1 > out->s_slots) out->s_slots = n_class + 1;
     }
     out->n_slot_total = slot;
-    out->code_bytes = code;
+    out->code_count = code;
+    if (out->s_slots < 1) out->s_slots = 1;
+    if (*batch_ok && batch_kernel_lds_bytes(*out) > BATCH_LDS_LIMIT) *batch_ok = false;
     *wave_ok = slot <= LLMEM_MAX_EVENT_SLOTS;
     return LLMEM_OK;
 }
@@ -466,9 +472,7 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
 
     const int64_t n_batch = (n + 63) / 64;
     if (use_batch) {
-        int64_t blocks = (n_batch + 3) / 4;
-        if (blocks > 256 * 4) blocks = 256 * 4;
-        launch_batch_kernel(args, out_detail != nullptr, (unsigned)blocks, stream);
+        launch_batch_kernel(args, out_detail != nullptr, n_batch, stream);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) {
             snprintf(g_hip_error, sizeof(g_hip_error), "HIP error: %s", hipGetErrorString(e));

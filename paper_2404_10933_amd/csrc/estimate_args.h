@@ -12,9 +12,15 @@ namespace llmem {
 constexpr int K_SEARCH_MIN = 2, K_SEARCH_MAX = 10, K_FIXED_MAX = 16;
 constexpr int B16 = 2, B32 = 4;
 
-// lane-per-configuration kernel: size classes per architecture, event code bits
-constexpr int NC_MAX = 32;
-constexpr unsigned CODE_FREE = 32, CODE_CHECK = 64;
+// lane-per-configuration kernel: at most CLS_MAX size classes per architecture; class c
+// keeps its value in slot c + 1 of the wave's LDS array, slot 0 holds 0 (padding events).
+// An event code is the slot's byte offset (slot * 512) with two flags in the low bits;
+// codes are fetched CODE_GROUP at a time.
+constexpr int CLS_MAX = 48;
+constexpr int CODE_GROUP = 8;
+constexpr unsigned CODE_CHECK = 1, CODE_FREE = 2, CODE_OFFSET_MASK = 0xfe00;
+constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
+constexpr size_t BATCH_LDS_LIMIT = 64 * 1024;  // dynamic LDS a launch may ask for
 
 struct ArchLayout {
     int param_first, n_param;
@@ -26,8 +32,11 @@ struct ArchLayout {
     int per_lane;
     int lane0[LLMEM_NSEG + 1];
     int slot_first;
-    // lane-per-configuration kernel: first byte of the architecture's event codes in LDS
+    // lane-per-configuration kernel: the architecture's event codes start at code_first; the
+    // codes of segment s occupy [seg_code[s], seg_code[s+1]) relative to that, each segment
+    // padded to a multiple of CODE_GROUP
     int code_first;
+    int seg_code[LLMEM_NSEG + 1];
 };
 
 struct EstimateArgs {
@@ -36,7 +45,7 @@ struct EstimateArgs {
     long long m_base;
     int cu_shift, align_shift;
     int n_arch, n_param_total, n_slot_total;
-    int code_bytes, max_events;
+    int code_count, max_events, s_slots;
     ArchLayout arch[LLMEM_MAX_ARCH];
     const uint4 *params_dev;
     const uint4 *events_dev;
@@ -64,6 +73,6 @@ __host__ __device__ inline ClassKey make_class_key(uint32_t x, uint32_t y, uint3
 }
 
 size_t batch_kernel_lds_bytes(const EstimateArgs &a);
-void launch_batch_kernel(const EstimateArgs &args, bool detail, unsigned blocks, hipStream_t stream);
+void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream);
 
 }  // namespace llmem

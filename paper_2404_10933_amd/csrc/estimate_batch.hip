@@ -10,11 +10,12 @@
 //
 // Workgroup set-up (once, in LDS): the timeline events of each architecture are
 // grouped into size classes - events whose byte size is the same expression
-// (coefficient, dimensions, element width, scaling, method mask).  A lane
-// evaluates each class once per configuration and keeps the rounded sizes in
-// registers; an event is then one signed add of its class, and the running
-// maximum is taken where the live total can peak (an allocation followed by a
-// release or by the end of its segment).
+// (coefficient, dimensions, element width, scaling, method mask).  Every event
+// becomes a 16-bit code: the value slot of its class, whether it releases, and
+// whether the live total can peak there (an allocation followed by a release or
+// by the end of its segment).  Per batch a lane evaluates each class once and
+// stores the rounded size in a wave-private LDS array [slot][lane]; an event is
+// then one LDS read and one 64-bit add or subtract.
 //
 // Closed form: Sec. 4.2 (m_p, m_os, m_out, m_lm, m_peak^s) and Sec. 5 (m_peak^dp,
 // m_peak^tp, m_back^tp) of arXiv 2404.10933; chunk size per Sec. 4.1; timeline
@@ -30,7 +31,7 @@ namespace llmem {
 
 namespace {
 
-constexpr int BB_WAVES = 4;
+constexpr int BB_WAVES = BATCH_WAVES;
 constexpr int BB_BLOCK = 64 * BB_WAVES;
 constexpr i64 LOWEST = (i64)0x8000000000000000ull;
 
@@ -48,28 +49,30 @@ template <bool DETAIL>
 __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const EstimateArgs a)
 {
     extern __shared__ uint4 lds[];
-    // LDS: class table | event codes | class counts | scratch of the set-up
-    uint4 *cls_tab = lds;                                              // n_arch * NC_MAX
-    uint8_t *codes = reinterpret_cast<uint8_t *>(lds + a.n_arch * NC_MAX);
-    int *n_class = reinterpret_cast<int *>(codes + a.code_bytes);       // LLMEM_MAX_ARCH ints
-    uint4 *tmp_key = reinterpret_cast<uint4 *>(n_class + LLMEM_MAX_ARCH);
+    // LDS: class table | event codes | per-architecture counts | value slots of the waves
+    // (the set-up's scratch shares the space of the value slots)
+    uint4 *cls_tab = lds;                                                       // n_arch * CLS_MAX
+    unsigned short *codes = reinterpret_cast<unsigned short *>(lds + a.n_arch * CLS_MAX);
+    int *n_class = reinterpret_cast<int *>(codes + a.code_count);                // code_count is a multiple of 8
+    uint4 *dyn = reinterpret_cast<uint4 *>(n_class + LLMEM_MAX_ARCH);
+    uint4 *tmp_key = dyn;                                                        // max_events
     unsigned short *tmp_rep = reinterpret_cast<unsigned short *>(tmp_key + a.max_events);
     unsigned short *tmp_cid = tmp_rep + a.max_events;
 
-    // ---- set-up: size classes and event codes of every architecture ----------------
-    if (threadIdx.x < LLMEM_MAX_ARCH) n_class[threadIdx.x] = 0;
-    __syncthreads();
+    // ---- set-up: size classes, value slots and event codes of every architecture -----
     if (DETAIL) {
+        for (int t = threadIdx.x; t < a.code_count; t += BB_BLOCK) codes[t] = 0;  // padding: slot 0, no check
         for (int ar = 0; ar < a.n_arch; ++ar) {
             const ArchLayout &al = a.arch[ar];
             const int n = al.seg_first[LLMEM_NSEG];
+            if (threadIdx.x == 0) n_class[ar] = 0;
             for (int e = threadIdx.x; e < n; e += BB_BLOCK) {
                 const uint4 raw = a.events_dev[al.event_first + e];
                 const ClassKey k = make_class_key(raw.x, raw.y, raw.z);
                 tmp_key[e] = make_uint4(k.coef, k.dims, k.meta, raw.z);
             }
             __syncthreads();
-            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {
+            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {        // first event with the same key
                 const uint4 me = tmp_key[e];
                 int rep = e;
                 for (int j = 0; j < e; ++j) {
@@ -79,12 +82,12 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                 tmp_rep[e] = (unsigned short)rep;
             }
             __syncthreads();
-            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {
+            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {        // class id = rank of its first event
                 if (tmp_rep[e] != e) continue;
                 int cid = 0;
                 for (int j = 0; j < e; ++j) cid += tmp_rep[j] == j ? 1 : 0;
                 tmp_cid[e] = (unsigned short)cid;
-                if (cid < NC_MAX) cls_tab[ar * NC_MAX + cid] = tmp_key[e];
+                if (cid < CLS_MAX) cls_tab[ar * CLS_MAX + cid] = tmp_key[e];
                 atomicMax(&n_class[ar], cid + 1);
             }
             __syncthreads();
@@ -97,8 +100,11 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                     const u32 zn = tmp_key[e + 1].w;
                     check = (((zn >> 8) & 255u) != seg) || (((zn >> 16) & 255u) & LLMEM_EV_FREE);
                 }
-                codes[al.code_first + e] = (uint8_t)((tmp_cid[tmp_rep[e]] & (NC_MAX - 1)) | (is_free ? CODE_FREE : 0)
-                                                     | (check ? CODE_CHECK : 0));
+                const int cid = tmp_cid[tmp_rep[e]];
+                const u32 slot = cid + 1 < a.s_slots ? (u32)cid + 1u : 0u;
+                const u32 sg = seg < LLMEM_NSEG ? seg : LLMEM_NSEG - 1;
+                const int at = al.code_first + al.seg_code[sg] + (e - al.seg_first[sg]);
+                if (at >= 0 && at < a.code_count) codes[at] = (unsigned short)((slot << 9) | (is_free ? CODE_FREE : 0u) | (check ? CODE_CHECK : 0u));
             }
             __syncthreads();
         }
@@ -110,6 +116,10 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
     const long long n_batch = (n + 63) >> 6;
     const int cu_shift = a.cu_shift, align_shift = a.align_shift;
     const u64 m_base = (u64)a.m_base;
+    // value slots of this wave: slot s of lane l at byte s * 512 + l * 8; an event code is the
+    // slot's byte offset with the check flag in bit 0
+    char *vals = reinterpret_cast<char *>(dyn) + ((size_t)wave * a.s_slots * 64 + lane) * sizeof(i64);
+    if (DETAIL) *reinterpret_cast<i64 *>(vals) = 0;
 
     for (long long b = (long long)blockIdx.x * BB_WAVES + wave; b < n_batch;
          b += (long long)gridDim.x * BB_WAVES) {
@@ -249,14 +259,11 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                     os_gpu = os_sh;
                 }
 
-                // ---- size classes of the timeline: rounded bytes per class, in registers ------
-                u32 s_lo[NC_MAX], s_hi[NC_MAX];
-#pragma unroll
-                for (int c = 0; c < NC_MAX; ++c) { s_lo[c] = 0; s_hi[c] = 0; }
+                // ---- size classes of the timeline: signed rounded bytes into the value slots ----
                 const int nc_raw = (int)uni((u32)n_class[ar]);
-                const int nc = nc_raw < NC_MAX ? nc_raw : NC_MAX;
+                const int nc = nc_raw < CLS_MAX ? nc_raw : CLS_MAX;
                 for (int c = 0; c < nc; ++c) {
-                    const uint4 ce = cls_tab[ar * NC_MAX + c];                // wave-uniform
+                    const uint4 ce = cls_tab[ar * CLS_MAX + c];                // wave-uniform
                     const u32 coef = uni(ce.x), dims = uni(ce.y), meta = uni(ce.z);
                     u64 x = (u64)coef * (meta & 255u);
                     x *= D[dims & 15u];
@@ -268,8 +275,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                     u64 r = b_up(x, align_shift);
                     if (fl & LLMEM_EV_TIMES_L) r *= (u64)L;
                     if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
-                    s_lo[c] = (u32)r;
-                    s_hi[c] = (u32)(r >> 32);
+                    if (c + 1 < a.s_slots) *reinterpret_cast<i64 *>(vals + (c + 1) * 512) = (i64)r;
                 }
 
                 // ---- timeline (Sec. 2.1 / Sec. 3.1): A, F x L, H, B x L, Z ---------------------
@@ -277,16 +283,27 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                 // state; the L equal blocks shift the prefix linearly, so the maximum over the
                 // repetitions of F (or B) is taken at the first or the last one.
                 i64 at = 0, best = 0;                                         // the empty prefix counts
-                const uint8_t *cd = codes + (int)uni((u32)al.code_first);
+                const int code_first = (int)uni((u32)al.code_first);
                 for (int s = 0; s < LLMEM_NSEG; ++s) {
                     i64 run = 0, top = LOWEST;
-                    const int e_begin = (int)uni((u32)al.seg_first[s]), e_end = (int)uni((u32)al.seg_first[s + 1]);
-                    for (int e = e_begin; e < e_end; ++e) {
-                        const u32 code = uni((u32)cd[e]);
-                        const u32 idx = code & (NC_MAX - 1);
-                        const i64 v = (i64)(((u64)s_hi[idx] << 32) | s_lo[idx]);
-                        if (code & CODE_FREE) run -= v; else run += v;
-                        if (code & CODE_CHECK) top = run > top ? run : top;
+                    const int e_begin = code_first + (int)uni((u32)al.seg_code[s]);
+                    const int e_end = code_first + (int)uni((u32)al.seg_code[s + 1]);
+                    for (int e = e_begin; e < e_end; e += CODE_GROUP) {
+                        const uint4 cq = *reinterpret_cast<const uint4 *>(codes + e);   // 8 codes, wave-uniform
+                        const u32 w0 = uni(cq.x), w1 = uni(cq.y), w2 = uni(cq.z), w3 = uni(cq.w);
+                        const u32 c0 = w0 & 0xffffu, c1 = w0 >> 16, c2 = w1 & 0xffffu, c3 = w1 >> 16,
+                                  c4 = w2 & 0xffffu, c5 = w2 >> 16, c6 = w3 & 0xffffu, c7 = w3 >> 16;
+#define LLMEM_VAL(c) (*reinterpret_cast<const i64 *>(vals + (c & CODE_OFFSET_MASK)))
+                        const i64 v0 = LLMEM_VAL(c0), v1 = LLMEM_VAL(c1), v2 = LLMEM_VAL(c2), v3 = LLMEM_VAL(c3),
+                                  v4 = LLMEM_VAL(c4), v5 = LLMEM_VAL(c5), v6 = LLMEM_VAL(c6), v7 = LLMEM_VAL(c7);
+#undef LLMEM_VAL
+                        // the flags are wave-uniform: scalar branches pick add or subtract and skip the
+                        // compare and selects where the total cannot peak
+#define LLMEM_STEP(v, c) if (c & CODE_FREE) { asm volatile("" ::: "memory"); run -= v; } else { run += v; } \
+                         if (c & CODE_CHECK) { asm volatile("" ::: "memory"); top = run > top ? run : top; }
+                        LLMEM_STEP(v0, c0) LLMEM_STEP(v1, c1) LLMEM_STEP(v2, c2) LLMEM_STEP(v3, c3)
+                        LLMEM_STEP(v4, c4) LLMEM_STEP(v5, c5) LLMEM_STEP(v6, c6) LLMEM_STEP(v7, c7)
+#undef LLMEM_STEP
                     }
                     const bool repeated = s == LLMEM_SEG_F || s == LLMEM_SEG_B;
                     if (repeated) {
@@ -330,21 +347,40 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
 
 size_t batch_kernel_lds_bytes(const EstimateArgs &a)
 {
-    size_t bytes = sizeof(uint4) * (size_t)a.n_arch * NC_MAX;       // class table
-    bytes += (size_t)a.code_bytes;                                   // event codes
-    bytes += sizeof(int) * LLMEM_MAX_ARCH;                           // class counts
-    bytes += sizeof(uint4) * (size_t)a.max_events;                   // set-up scratch: keys
-    bytes += 2 * sizeof(unsigned short) * (size_t)a.max_events;      // set-up scratch: representatives, ids
-    return (bytes + 15) & ~(size_t)15;
+    size_t fixed = sizeof(uint4) * (size_t)a.n_arch * CLS_MAX;        // class table
+    fixed += sizeof(unsigned short) * (size_t)a.code_count;            // event codes
+    fixed += sizeof(int) * LLMEM_MAX_ARCH;                             // class counts
+    size_t scratch = sizeof(uint4) * (size_t)a.max_events;             // set-up scratch: keys
+    scratch += 2 * sizeof(unsigned short) * (size_t)(a.max_events + 1); // representatives, class ids
+    const size_t values = sizeof(long long) * 64 * (size_t)a.s_slots * BATCH_WAVES;
+    return ((fixed + (scratch > values ? scratch : values)) + 15) & ~(size_t)15;
 }
 
-void launch_batch_kernel(const EstimateArgs &args, bool detail, unsigned blocks, hipStream_t stream)
+void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream)
 {
     const size_t lds_bytes = batch_kernel_lds_bytes(args);
+    // as many workgroups as stay resident at once; each strides over the batches
+    static int cu_count = 0;
+    if (cu_count == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess
+            && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cu_count = v;
+        else
+            cu_count = 256;
+    }
+    int per_cu = 0;
+    const void *fn = detail ? reinterpret_cast<const void *>(&estimate_batch_kernel<true>)
+                            : reinterpret_cast<const void *>(&estimate_batch_kernel<false>);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, BB_BLOCK, lds_bytes) != hipSuccess || per_cu < 1)
+        per_cu = 1;
+    long long blocks = (n_batch + BB_WAVES - 1) / BB_WAVES;
+    const long long resident = (long long)per_cu * cu_count;
+    if (blocks > resident) blocks = resident;
     if (detail)
-        hipLaunchKernelGGL(estimate_batch_kernel<true>, dim3(blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
+        hipLaunchKernelGGL(estimate_batch_kernel<true>, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
     else
-        hipLaunchKernelGGL(estimate_batch_kernel<false>, dim3(blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
+        hipLaunchKernelGGL(estimate_batch_kernel<false>, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
 }
 
 }  // namespace llmem

@@ -78,7 +78,7 @@ def test_random_tables_few_sizes(U):
     """Random tables whose events share at most 32 size expressions, several
     architectures mixed inside each wavefront's 64 configurations."""
     rng = np.random.default_rng(13)
-    tabs = [T.random_table(rng, 9, 150, "r0", n_sizes=32), T.llama_table(), T.random_table(rng, 0, 0, "empty"),
+    tabs = [T.random_table(rng, 9, 150, "r0", n_sizes=22), T.llama_table(), T.random_table(rng, 0, 0, "empty"),
             T.random_table(rng, 64, 1024, "r3", n_sizes=20), T.gpt_table(), T.random_table(rng, 1, 1, "one", n_sizes=1),
             T.random_table(rng, 30, 600, "r6", n_sizes=7), T.opt_table()]
     cfg = G.random_configs(rng, 64 * 40 + 5, n_arch=len(tabs), wild=True)
