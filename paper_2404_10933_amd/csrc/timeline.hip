@@ -1,11 +1,17 @@
 // Peaks of explicit allocator timelines: one wavefront per event list.
 //
 // Sequential traversal with live tensors and 512-byte blocks (Sec. 2.1 / Sec. 3.1
-// of arXiv 2404.10933) as a scan: every lane walks a run of consecutive events
-// keeping running sums and running maxima of the two pools relative to the run's
-// start; a wave prefix sum over the runs' totals places each run on the list's
-// timeline; per-lane absolute maxima are carried from tile to tile and reduced
+// of arXiv 2404.10933) as a scan.  A wave streams its list in tiles of 1024
+// events: coalesced 16-byte loads, a transpose through wave-private LDS so that
+// every lane owns 16 consecutive events, a sequential walk of those 16 keeping
+// running sums and running maxima of the two pools relative to the run's start,
+// then a wave prefix sum over the runs' totals that places each run on the list's
+// timeline.  Per-lane absolute maxima are carried from tile to tile and reduced
 // once per list.
+//
+// While every event of a tile is below 2^35 bytes the walk is done in 32-bit
+// block counts (a run of 16 such events cannot overflow); otherwise the tile
+// takes the 64-bit path.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -17,10 +23,13 @@ namespace llmem {
 
 constexpr int TL_WAVES = 4;
 constexpr int TL_BLOCK = 64 * TL_WAVES;
-constexpr int TL_RUN = 16;                 // consecutive events per lane and tile
-constexpr int TL_TILE = 64 * TL_RUN;
+constexpr int TL_RUN = 16;                       // consecutive events per lane and tile
+constexpr int TL_TILE = 64 * TL_RUN;             // events per tile
+constexpr int TL_ROW = TL_RUN * 8 + 16;          // bytes of LDS per lane: 16 events + padding against bank conflicts
+constexpr int BLOCK_SHIFT = 9;                   // log2(LLMEM_BLOCK)
+constexpr int SPLIT_BLOCKS = LLMEM_POOL_SPLIT / LLMEM_BLOCK;
+static_assert((1 << BLOCK_SHIFT) == LLMEM_BLOCK, "block size");
 
-extern const char *last_hip_error();
 void set_hip_error(hipError_t e);
 
 __global__ __launch_bounds__(TL_BLOCK) void timeline_kernel(const long long *__restrict__ events,
@@ -28,30 +37,81 @@ __global__ __launch_bounds__(TL_BLOCK) void timeline_kernel(const long long *__r
                                                             long long n, long long *__restrict__ out_alloc,
                                                             long long *__restrict__ out_resv)
 {
+    __shared__ __attribute__((aligned(16))) char stage[TL_WAVES][64 * TL_ROW];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    char *mine = stage[wave];
+    // where this lane's pair of events of load j lands: tile index t = j*128 + 2*lane,
+    // owner lane t / 16, position t % 16
+    const int put0 = ((2 * lane) / TL_RUN) * TL_ROW + ((2 * lane) % TL_RUN) * 8;
+    const char *get = mine + lane * TL_ROW;
+
     for (long long li = (long long)blockIdx.x * TL_WAVES + wave; li < n;
          li += (long long)gridDim.x * TL_WAVES) {
         const long long first = offsets[li], last = offsets[li + 1];
         i64 carry_s = 0, carry_l = 0;                 // live bytes of the pools before the tile
         i64 best_s = 0, best_l = 0, best_t = 0;       // per-lane maxima; the empty prefix counts
-        for (long long base = first; base < last; base += TL_TILE) {
-            const long long e0 = base + (long long)lane * TL_RUN;
-            i64 run_s = 0, run_l = 0;
-            i64 top_s = 0, top_l = 0, top_t = 0;      // maxima relative to the run's start (>= 0: the start itself)
+        // tiles start at a 16-byte boundary of the event array; what lies before `first` or at
+        // and after `last` is read as 0 (an event of 0 bytes changes nothing)
+        const long long lead = (long long)((reinterpret_cast<uintptr_t>(events + first) >> 3) & 1);
+        for (long long base = first - lead; base < last; base += TL_TILE) {
+            // ---- coalesced loads: load j covers events base + j*128 .. +127, two per lane ----
+            u32 high_bits = 0;
 #pragma unroll
-            for (int j = 0; j < TL_RUN; ++j) {
-                const long long e = e0 + j;
-                const i64 raw = e < last ? events[e] : 0;
-                const u64 mag = raw < 0 ? (u64)0 - (u64)raw : (u64)raw;
-                const u64 r = (mag + (LLMEM_BLOCK - 1)) & ~(u64)(LLMEM_BLOCK - 1);
-                const i64 delta = raw < 0 ? -(i64)r : (i64)r;
-                const bool small = r < (u64)LLMEM_POOL_SPLIT;
-                run_s += small ? delta : 0;
-                run_l += small ? 0 : delta;
-                top_s = max64(top_s, run_s);
-                top_l = max64(top_l, run_l);
-                top_t = max64(top_t, run_s + run_l);
+            for (int j = 0; j < TL_TILE / 128; ++j) {
+                const long long e = base + j * 128 + 2 * lane;
+                i64 a0 = 0, a1 = 0;
+                if (e >= first && e + 1 < last) {
+                    const longlong2 p = *reinterpret_cast<const longlong2 *>(events + e);
+                    a0 = p.x; a1 = p.y;
+                } else {
+                    if (e >= first && e < last) a0 = events[e];
+                    if (e + 1 >= first && e + 1 < last) a1 = events[e + 1];
+                }
+                const u32 h0 = (u32)((u64)a0 >> 32), h1 = (u32)((u64)a1 >> 32);
+                high_bits |= (h0 ^ (u32)((int)h0 >> 31)) | (h1 ^ (u32)((int)h1 >> 31));
+                *reinterpret_cast<longlong2 *>(mine + put0 + j * (128 / TL_RUN) * TL_ROW) = make_longlong2(a0, a1);
+            }
+            const bool narrow = __builtin_amdgcn_ballot_w64(high_bits >= 8u) == 0;   // all |raw| < 2^35
+
+            i64 run_s, run_l, top_s, top_l, top_t;    // relative to the run's start; tops >= 0 (the start itself)
+            if (narrow) {
+                int rs = 0, rl = 0, ts = 0, tl = 0, tt = 0;          // in blocks
+#pragma unroll
+                for (int q = 0; q < TL_RUN / 2; ++q) {
+                    const longlong2 p = *reinterpret_cast<const longlong2 *>(get + q * 16);
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const i64 raw = u ? p.y : p.x;
+                        // signed block count: ceil(raw / 512) for raw >= 0, -ceil(-raw / 512) = floor(raw / 512) below
+                        const int sb = (int)((raw + (raw >= 0 ? (i64)(LLMEM_BLOCK - 1) : 0)) >> BLOCK_SHIFT);
+                        const int mag = sb < 0 ? -sb : sb;
+                        const int ds = mag < SPLIT_BLOCKS ? sb : 0;
+                        rs += ds;
+                        rl += sb - ds;
+                        ts = rs > ts ? rs : ts;
+                        tl = rl > tl ? rl : tl;
+                        const int t = rs + rl;
+                        tt = t > tt ? t : tt;
+                    }
+                }
+                run_s = (i64)rs << BLOCK_SHIFT; run_l = (i64)rl << BLOCK_SHIFT;
+                top_s = (i64)ts << BLOCK_SHIFT; top_l = (i64)tl << BLOCK_SHIFT; top_t = (i64)tt << BLOCK_SHIFT;
+            } else {
+                run_s = 0; run_l = 0; top_s = 0; top_l = 0; top_t = 0;
+#pragma unroll
+                for (int q = 0; q < TL_RUN; ++q) {
+                    const i64 raw = *reinterpret_cast<const i64 *>(get + q * 8);
+                    const u64 mag = raw < 0 ? (u64)0 - (u64)raw : (u64)raw;
+                    const u64 r = (mag + (LLMEM_BLOCK - 1)) & ~(u64)(LLMEM_BLOCK - 1);
+                    const i64 delta = raw < 0 ? -(i64)r : (i64)r;
+                    const bool small = r < (u64)LLMEM_POOL_SPLIT;
+                    run_s += small ? delta : 0;
+                    run_l += small ? 0 : delta;
+                    top_s = max64(top_s, run_s);
+                    top_l = max64(top_l, run_l);
+                    top_t = max64(top_t, run_s + run_l);
+                }
             }
             const i64 incl_s = wave_scan_add(run_s), incl_l = wave_scan_add(run_l);
             const i64 start_s = carry_s + incl_s - run_s, start_l = carry_l + incl_l - run_l;

@@ -46,6 +46,22 @@ def test_random_ragged_lists(U):
     _check(U, ev, off)
 
 
+def test_wide_events_take_the_64_bit_path(U):
+    """Events of 2^35 bytes and more leave the 32-bit block-count walk; mix both
+    kinds inside and across tiles, at both sides of the threshold."""
+    rng = np.random.default_rng(22)
+    T35 = 1 << 35
+    lists = [[T35 - 1, -(T35 - 1)], [T35, -T35], [T35 + 1, 5, -(T35 + 1)], [-T35, -(T35 - 1), T35 - 511, T35 - 512]]
+    for _ in range(120):
+        n = int(rng.integers(1, 4000))
+        mag = (2.0 ** rng.uniform(0, 30, size=n)).astype(np.int64)
+        wide = rng.random(n) < rng.choice((0.0, 0.001, 0.05, 1.0))
+        mag = np.where(wide, (2.0 ** rng.uniform(35, 50, size=n)).astype(np.int64), mag)
+        lists.append(list(np.where(rng.random(n) < 0.5, mag, -mag)))
+    ev, off = E.from_lists(lists)
+    _check(U, ev, off)
+
+
 @pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 257])
 def test_generated_lists_small(U, n):
     ev, off = E.generate(n, seed=2, first=11, threads=8)
