@@ -19,23 +19,45 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 # MI355X nominal peaks used for the roofline fractions
-PEAK_INT32_TOPS = 256 * 64 * 2.4e9 / 1e12      # 256 CUs x 64 lanes x 2.4 GHz simple int32 lane-ops
+PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12       # 256 CUs x one 64-lane vector instruction per clock x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs under profiles/, scaled by the
+# plain-copy reference; None while the kernel has changed since the counters were taken
+TRAFFIC_ESTIMATE = None
+TRAFFIC_TIMELINE = None
 
 
-def algorithmic_int32_ops(table, n_search_candidates):
-    """Integer work per configuration of the estimator itself, in 32-bit lane
-    operations (int64 add/compare/select/shift = 2, u64 x u32 multiply = 4,
-    division by d via multiply-high = 16).  Census of the method with the L equal
-    blocks collapsed; see the design doc for the derivation."""
-    ADD, MUL, DIV = 2, 4, 16
-    per_param = 4 * MUL + MUL + 3 * ADD + 2 * ADD + ADD          # monomial, x copies, page round-up, role sums, max
-    per_event = 5 * MUL + 3 * ADD + 2 * ADD + ADD + ADD          # monomial*bytes, block round-up, sign/mask, prefix add, max
-    fixed = 12 * MUL + 14 * ADD + 2 * DIV                        # m_out, m_lm (3 round-ups), m_back, gradient terms
-    per_candidate = 3 * (MUL + 3 * ADD) + 3 * ADD + DIV + 3 * ADD + 6 * ADD   # m_p, m_p16, m_p32, compose, waste, compare
-    tail = 3 * DIV + 10 * ADD + 2 * MUL + 12 * ADD                # resident bytes, layer closed form, prelude
-    return (len(table.params) * per_param + len(table.events) * per_event + fixed
-            + n_search_candidates * per_candidate + tail)
+def size_classes(table):
+    """Distinct size expressions among the timeline events (same coefficient,
+    dimensions, element width, scaling, method mask): evaluated once each."""
+    return len({(e.coef, tuple(sorted(d for d in e.dims if d != "one")), e.elem_bytes, e.scale, e.times_L,
+                 e.methods) for e in table.events})
+
+
+def peak_points(table):
+    """Events after which the live total can peak: an allocation followed by a
+    release or by the end of its segment."""
+    ev = table.events
+    return sum(1 for i, e in enumerate(ev)
+               if e.sign > 0 and (i + 1 == len(ev) or ev[i + 1].sign < 0 or ev[i + 1].seg != e.seg))
+
+
+def algorithmic_lane_ops(table, n_candidates):
+    """Integer work of one configuration in 64-bit lane operations of the method
+    itself (L equal blocks collapsed, equal sizes evaluated once), priced in gfx950
+    vector instructions: add/sub 1, multiply by a 32-bit dimension 2, round up to
+    a power of two 3, compare-and-select (max) 3, ceil-divide by d 12.
+    Derivation in the design doc, section 6."""
+    ADD, MUL, UP, MAX, DIV = 1, 2, 3, 3, 12
+    per_param = 4 * MUL + MUL + ADD + (8 * 0 + MUL + UP + MUL + ADD) / 2 + MAX / 2   # monomial, x L, role sum, m_os, t_max
+    per_class = 5 * MUL + UP + 1                                                     # monomial x bytes, block round-up, store
+    per_event = ADD
+    per_peak_point = MAX
+    fixed = (3 * MUL + MUL + UP) + (3 * MUL + 2 * (MUL + UP) + 3 * ADD) + (3 * MUL + UP + DIV) + 2 * MUL + DIV  # m_out, m_lm, m_back, grads
+    per_candidate = 2 * ADD + 3 * (MUL + UP) + DIV + UP + 5 * ADD + 2 * MAX          # chunking, m_p*, shard, compose, waste, pick
+    tail = 2 * (DIV + UP) + 5 * (MUL + MAX + 2 * ADD) + 4 * ADD                      # resident bytes, segments, prelude
+    return (len(table.params) * per_param + size_classes(table) * per_class + len(table.events) * per_event
+            + peak_points(table) * per_peak_point + fixed + n_candidates * per_candidate + tail)
 
 
 def main():
@@ -45,7 +67,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--n", type=int, default=10_000_000, help="configurations per step (default: the 10^7 grid)")
     ap.add_argument("--lists", type=int, default=100_000, help="event lists of the explicit-timeline grid (0: skip)")
-    ap.add_argument("--cpu-sample", type=int, default=200_000, help="configurations the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--cpu-sample", type=int, default=600_000, help="configurations the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--kernel", choices=("auto", "wave", "lane"), default="auto",
+                    help="estimator kernel: one wavefront or one lane per configuration (auto: the library chooses)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy ten times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; nothing is sharded and there are no collectives "
@@ -59,12 +85,22 @@ def main():
     from workloads import tables as T
 
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 27, dtype=torch.int64, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"bytes_read": src.numel() * 8, "bytes_written": src.numel() * 8,
+                                             "launches": 10}}))
+        return
     const = T.Constants(m_base=256 << 20)
     table = T.llama_table()
     n = args.n
     dev = M.DeviceConfigs.empty(n)
     M.llmem_grid_generate(4, 0, 0, n, dev)
-    tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align)
+    kernel = {"auto": 0, "wave": 1, "lane": 2}[args.kernel]
+    tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=kernel)
     peaks = torch.empty(n, dtype=torch.int64, device="cuda")
     detail = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
     torch.cuda.synchronize()
@@ -85,8 +121,9 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     value = n / (ms_per_step * 1e-3)
 
-    ops = algorithmic_int32_ops(table, 9)
+    ops = algorithmic_lane_ops(table, 9)
     achieved = ops * n / (kernel_ms * 1e-3) / 1e12
+    kernel_name = "estimate_kernel<true>" if args.kernel == "wave" else "estimate_batch_kernel<true>"
     bytes_per_cfg = M.llmem_config_bytes(1) + 8 + 8 * M.NDETAIL
     result = {
         "metric": "configs estimated/sec (bit-exact vs oracle)",
@@ -96,11 +133,11 @@ def main():
         "config": {"workload": "g4: Llama-style grid with ZeRO-3 chunk-size search (9 candidates), "
                                "m_peak + all detail columns incl. timeline peak",
                    "n_configs": n, "table_params": len(table.params), "table_events": len(table.events),
-                   "seed": 0},
-        "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_INT32_TOPS, "unit": "Tint32op/s",
-                     "frac": achieved / PEAK_INT32_TOPS, "traffic": None,
-                     "kernel": "estimate_kernel<true>", "kernel_ms": kernel_ms,
-                     "algorithmic_int32_ops_per_config": ops,
+                   "table_size_classes": size_classes(table), "kernel": args.kernel, "seed": 0},
+        "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
+                     "frac": achieved / PEAK_LANE_TOPS, "traffic": TRAFFIC_ESTIMATE,
+                     "kernel": kernel_name, "kernel_ms": kernel_ms,
+                     "algorithmic_lane_ops_per_config": ops,
                      "hbm_gbs_algorithmic": bytes_per_cfg * n / (kernel_ms * 1e-3) / 1e9},
     }
 
@@ -141,7 +178,7 @@ def main():
             "workload": "g5: explicit allocator event lists (~10^4 events each)", "n_lists": nl,
             "n_events": total, "ms_per_launch": ms, "lists_per_s": nl / (ms * 1e-3),
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": gbs / PEAK_HBM_GBS, "traffic": None, "kernel": "timeline_kernel"}}}
+                         "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_TIMELINE, "kernel": "timeline_kernel"}}}
         from workloads import events as E
         ev_c, off_c = E.generate(64, seed=0, first=0)
         wa, wr = B.event_lists_peaks(ev_c, off_c)

@@ -26,5 +26,20 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_calibrate() -> str:
+    """Compile the stand-alone calibration program (instruction issue rates, HBM read rate)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not os.path.exists(hipcc):
+        hipcc = "hipcc"
+    exe = os.path.join(HERE, "calibrate")
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-Xclang", "-target-feature", "-Xclang",
+                          "-packed-fp32-ops", "-o", exe, os.path.join(CSRC, "calibrate.hip")],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_calibrate())
