@@ -160,15 +160,21 @@ typedef struct llmem_tables {
 
 /* Two kernels compute the same results.  LLMEM_KERNEL_LANE holds one configuration
  * per lane (64 per wavefront) and walks the tables entry by entry; it needs at most
- * 32 distinct size expressions among the events of each architecture.
- * LLMEM_KERNEL_WAVE gives a whole wavefront to each configuration with the lanes
- * spread over table entries; it needs the events of all architectures, dealt to
- * lanes, to fit LLMEM_MAX_EVENT_SLOTS.  LLMEM_KERNEL_AUTO takes the first where the
- * tables allow it, else the second; a forced choice the tables do not allow is
- * LLMEM_EINVAL_TABLE.                                                          */
+ * 48 distinct size expressions among the events of each architecture.  Its timeline
+ * walk has two forms: the host reduces each segment to the peak points that no other
+ * point dominates and hands them to the kernel in its arguments
+ * (LLMEM_KERNEL_LANE_COMPILED, when that fits the argument space), or the kernel
+ * walks every event (LLMEM_KERNEL_LANE_EVENTS).  LLMEM_KERNEL_WAVE gives a whole
+ * wavefront to each configuration with the lanes spread over table entries; it needs
+ * the events of all architectures, dealt to lanes, to fit LLMEM_MAX_EVENT_SLOTS.
+ * LLMEM_KERNEL_AUTO takes the first of compiled, events, wave that the tables allow;
+ * LLMEM_KERNEL_LANE the first of compiled, events; a forced choice the tables do not
+ * allow is LLMEM_EINVAL_TABLE.                                                  */
 #define LLMEM_KERNEL_AUTO 0
 #define LLMEM_KERNEL_WAVE 1
 #define LLMEM_KERNEL_LANE 2
+#define LLMEM_KERNEL_LANE_EVENTS 3
+#define LLMEM_KERNEL_LANE_COMPILED 4
 
 /* ---- outputs --------------------------------------------------------------- */
 /* Detail columns: out_detail is DEV, LLMEM_NDETAIL columns of n int64 each

@@ -16,6 +16,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 #include "../../include/llmem.h"
 #include "estimate_args.h"
 #include "wave.h"
@@ -346,12 +348,77 @@ static int log2_exact(int64_t v)
     return s;
 }
 
+// Compiles the timeline of one architecture for the lane-per-configuration kernel: size classes,
+// then per segment the class-count vectors at the peak points (an allocation followed by a
+// release or by the end of the segment), minus those another point dominates component-wise
+// (class values are never negative, so a dominated point cannot hold the maximum), then the
+// segment's net change.  Appends 32-bit words to `prog`; returns false if the architecture does
+// not fit (too many classes or words).
+static bool compile_timeline(const llmem_event_entry *ev, int n_event, const int *seg_first, ArchLayout *al,
+                             std::vector<uint32_t> *prog)
+{
+    std::vector<ClassKey> classes;
+    std::vector<int> cls_of(n_event);
+    for (int j = 0; j < n_event; ++j) {
+        const uint32_t *w = reinterpret_cast<const uint32_t *>(&ev[j]);
+        const ClassKey k = make_class_key(w[0], w[1], w[2]);
+        int c = 0;
+        for (; c < (int)classes.size(); ++c)
+            if (classes[c].coef == k.coef && classes[c].dims == k.dims && classes[c].meta == k.meta) break;
+        if (c == (int)classes.size()) classes.push_back(k);
+        cls_of[j] = c;
+    }
+    const int nc = (int)classes.size();
+    if (nc > CLS_MAX) return false;
+    al->prog_first = (int)prog->size();
+    prog->push_back((uint32_t)nc);
+    for (const ClassKey &k : classes) { prog->push_back(k.coef); prog->push_back(k.dims); prog->push_back(k.meta); }
+    for (int s = 0; s < LLMEM_NSEG; ++s) {
+        std::vector<std::vector<int>> points;
+        std::vector<int> count(nc, 0);
+        for (int j = seg_first[s]; j < seg_first[s + 1]; ++j) {
+            const bool is_free = ev[j].flags & LLMEM_EV_FREE;
+            count[cls_of[j]] += is_free ? -1 : 1;
+            if (count[cls_of[j]] > 32767 || count[cls_of[j]] < -32767) return false;
+            if (!is_free && (j + 1 == seg_first[s + 1] || (ev[j + 1].flags & LLMEM_EV_FREE))) points.push_back(count);
+        }
+        std::vector<std::vector<int>> kept;
+        for (size_t j = 0; j < points.size(); ++j) {
+            bool dominated = false;
+            for (size_t k = 0; k < points.size() && !dominated; ++k) {
+                if (k == j) continue;
+                bool le = true, lt = false;
+                for (int c = 0; c < nc; ++c) { le = le && points[j][c] <= points[k][c]; lt = lt || points[j][c] < points[k][c]; }
+                dominated = le && (lt || k < j);
+            }
+            if (!dominated) kept.push_back(points[j]);
+        }
+        al->prog_seg[s] = (int)prog->size();
+        auto emit = [&](const std::vector<int> &v, uint32_t end_flag) {
+            int last = -1;
+            for (int c = 0; c < nc; ++c) if (v[c] != 0) last = c;
+            if (last < 0) { prog->push_back(end_flag); return; }          // empty sum: slot 0, count 0
+            for (int c = 0; c <= last; ++c) {
+                if (v[c] == 0) continue;
+                prog->push_back(((uint32_t)(c + 1) << 9) | (c == last ? end_flag : 0u) | ((uint32_t)v[c] << 16));
+            }
+        };
+        for (const auto &v : kept) emit(v, PROG_END_POINT);
+        emit(count, PROG_END_POINT | PROG_END_SEGMENT);
+        while ((prog->size() - (size_t)al->prog_seg[s]) % PROG_GROUP) prog->push_back(0u);
+    }
+    al->prog_seg[LLMEM_NSEG] = (int)prog->size();
+    return prog->size() <= (size_t)PROG_WORDS;
+}
+
 // Checks the host copy of the tables and derives the lane layout of every
 // architecture's events.  Returns LLMEM_OK or LLMEM_EINVAL_*.
-static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, bool *batch_ok)
+static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, bool *batch_ok, bool *prog_ok)
 {
     *wave_ok = true;
     *batch_ok = true;
+    *prog_ok = true;
+    std::vector<uint32_t> prog;
     if (!t->params_host && t->n_param_total > 0) return LLMEM_EINVAL_NULL;
     if (!t->events_host && t->n_event_total > 0) return LLMEM_EINVAL_NULL;
     if (!t->params_dev && t->n_param_total > 0) return LLMEM_EINVAL_NULL;
@@ -431,10 +498,16 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, 
         }
         if (n_class > CLS_MAX) *batch_ok = false;
         if (n_class + 1 > out->s_slots) out->s_slots = n_class + 1;
+        if (*prog_ok && !compile_timeline(t->events_host + d.event_first, d.n_event, al.seg_first, &al, &prog))
+            *prog_ok = false;
     }
+    if (*prog_ok) for (size_t q = 0; q < prog.size(); ++q) out->prog[q] = prog[q];
     out->n_slot_total = slot;
     out->code_count = code;
     if (out->s_slots < 1) out->s_slots = 1;
+    out->use_program = 1;                     // sizes the LDS of the compiled form
+    if (*prog_ok && batch_kernel_lds_bytes(*out) > BATCH_LDS_LIMIT) *prog_ok = false;
+    out->use_program = 0;
     if (*batch_ok && batch_kernel_lds_bytes(*out) > BATCH_LDS_LIMIT) *batch_ok = false;
     *wave_ok = slot <= LLMEM_MAX_EVENT_SLOTS;
     return LLMEM_OK;
@@ -448,17 +521,24 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     if (n < 0) return LLMEM_EINVAL_N;
     EstimateArgs args;
     memset(&args, 0, sizeof(args));
-    bool wave_ok, batch_ok;
-    int rc = plan_tables(tables, &args, &wave_ok, &batch_ok);
+    bool wave_ok, batch_ok, prog_ok;
+    int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok);
     if (rc != LLMEM_OK) return rc;
-    // which kernel: the lane-per-configuration kernel needs every architecture's timeline to
-    // have at most NC_MAX size classes; the wavefront-per-configuration kernel needs the dealt
-    // events of all architectures to fit its LDS slots
+    // which kernel (see LLMEM_KERNEL_* in the header)
     const int hint = tables->kernel;
-    if (hint < LLMEM_KERNEL_AUTO || hint > LLMEM_KERNEL_LANE) return LLMEM_EINVAL_TABLE;
-    if ((hint == LLMEM_KERNEL_WAVE && !wave_ok) || (hint == LLMEM_KERNEL_LANE && !batch_ok)
-        || (!wave_ok && !batch_ok)) return LLMEM_EINVAL_TABLE;
-    const bool use_batch = hint == LLMEM_KERNEL_LANE || (hint == LLMEM_KERNEL_AUTO && batch_ok);
+    int choice;
+    switch (hint) {
+    case LLMEM_KERNEL_AUTO: choice = prog_ok ? LLMEM_KERNEL_LANE_COMPILED : batch_ok ? LLMEM_KERNEL_LANE_EVENTS
+                                     : wave_ok ? LLMEM_KERNEL_WAVE : -1; break;
+    case LLMEM_KERNEL_LANE: choice = prog_ok ? LLMEM_KERNEL_LANE_COMPILED : batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1; break;
+    case LLMEM_KERNEL_WAVE: choice = wave_ok ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_EVENTS: choice = batch_ok ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_COMPILED: choice = prog_ok ? hint : -1; break;
+    default: choice = -1;
+    }
+    if (choice < 0) return LLMEM_EINVAL_TABLE;
+    const bool use_batch = choice != LLMEM_KERNEL_WAVE;
+    args.use_program = choice == LLMEM_KERNEL_LANE_COMPILED ? 1 : 0;
     if (n == 0) return LLMEM_OK;
     if (!cfg->arch_id || !cfg->h || !cfg->L || !cfg->n_heads || !cfg->n_kv || !cfg->ffn || !cfg->V
         || !cfg->P || !cfg->bs || !cfg->sl || !cfg->method || !cfg->d || !cfg->chunk_k || !cfg->flags)

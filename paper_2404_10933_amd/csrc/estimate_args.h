@@ -20,6 +20,17 @@ constexpr int CLS_MAX = 48;
 constexpr int CODE_GROUP = 8;
 constexpr unsigned CODE_CHECK = 1, CODE_FREE = 2, CODE_OFFSET_MASK = 0xfe00;
 constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
+// lane-per-configuration kernel, compiled form of the timeline: the host reduces the events of
+// every segment to the peak points no other point dominates (class-count vectors compared
+// component-wise) and passes the result in the kernel arguments.  Stream of 32-bit words per
+// architecture: n_class, then {coef, dims, meta} per class, then per segment A F H B Z its
+// terms in groups of PROG_GROUP.  A term is  slot * 512 | flags | count << 16  (count signed):
+// the partial sum gains count * value[slot]; PROG_END_POINT closes a peak point (its sum
+// competes for the segment's maximum and the partial sum restarts); with PROG_END_SEGMENT as
+// well it closes the segment's net change instead.  Padding terms are 0 (slot 0 holds 0).
+constexpr int PROG_WORDS = 704;
+constexpr int PROG_GROUP = 8;
+constexpr unsigned PROG_OFFSET_MASK = 0xfe00, PROG_END_POINT = 0x1, PROG_END_SEGMENT = 0x2;
 constexpr size_t BATCH_LDS_LIMIT = 64 * 1024;  // dynamic LDS a launch may ask for
 
 struct ArchLayout {
@@ -37,6 +48,10 @@ struct ArchLayout {
     // padded to a multiple of CODE_GROUP
     int code_first;
     int seg_code[LLMEM_NSEG + 1];
+    // compiled timeline: first word of the architecture in EstimateArgs::prog; the terms of
+    // segment s start at word prog_seg[s] (absolute) and end at prog_seg[s + 1]
+    int prog_first;
+    int prog_seg[LLMEM_NSEG + 1];
 };
 
 struct EstimateArgs {
@@ -51,6 +66,8 @@ struct EstimateArgs {
     const uint4 *events_dev;
     long long *out_peaks;
     long long *out_detail;
+    int use_program;                 // 1: the compiled timeline below is valid and used
+    uint32_t prog[PROG_WORDS];
 };
 
 // Events with equal keys have equal byte sizes for every configuration: same

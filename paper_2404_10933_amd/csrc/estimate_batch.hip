@@ -17,6 +17,12 @@
 // stores the rounded size in a wave-private LDS array [slot][lane]; an event is
 // then one LDS read and one 64-bit add or subtract.
 //
+// Compiled form (EstimateArgs::use_program): the host has already reduced every
+// segment to the peak points no other point dominates, each a short list of
+// (class, count) terms, and passes classes and terms in the kernel arguments;
+// they arrive through scalar loads and the set-up above is skipped.  A peak
+// point costs its terms (count * value) instead of every event before it.
+//
 // Closed form: Sec. 4.2 (m_p, m_os, m_out, m_lm, m_peak^s) and Sec. 5 (m_peak^dp,
 // m_peak^tp, m_back^tp) of arXiv 2404.10933; chunk size per Sec. 4.1; timeline
 // traversal per Sec. 2.1 / Sec. 3.1.
@@ -54,13 +60,13 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
     uint4 *cls_tab = lds;                                                       // n_arch * CLS_MAX
     unsigned short *codes = reinterpret_cast<unsigned short *>(lds + a.n_arch * CLS_MAX);
     int *n_class = reinterpret_cast<int *>(codes + a.code_count);                // code_count is a multiple of 8
-    uint4 *dyn = reinterpret_cast<uint4 *>(n_class + LLMEM_MAX_ARCH);
+    uint4 *dyn = a.use_program ? lds : reinterpret_cast<uint4 *>(n_class + LLMEM_MAX_ARCH);
     uint4 *tmp_key = dyn;                                                        // max_events
     unsigned short *tmp_rep = reinterpret_cast<unsigned short *>(tmp_key + a.max_events);
     unsigned short *tmp_cid = tmp_rep + a.max_events;
 
     // ---- set-up: size classes, value slots and event codes of every architecture -----
-    if (DETAIL) {
+    if (DETAIL && !a.use_program) {
         for (int t = threadIdx.x; t < a.code_count; t += BB_BLOCK) codes[t] = 0;  // padding: slot 0, no check
         for (int ar = 0; ar < a.n_arch; ++ar) {
             const ArchLayout &al = a.arch[ar];
@@ -259,12 +265,9 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                     os_gpu = os_sh;
                 }
 
-                // ---- size classes of the timeline: signed rounded bytes into the value slots ----
-                const int nc_raw = (int)uni((u32)n_class[ar]);
-                const int nc = nc_raw < CLS_MAX ? nc_raw : CLS_MAX;
-                for (int c = 0; c < nc; ++c) {
-                    const uint4 ce = cls_tab[ar * CLS_MAX + c];                // wave-uniform
-                    const u32 coef = uni(ce.x), dims = uni(ce.y), meta = uni(ce.z);
+                i64 at = 0, best = 0;                                         // the empty prefix counts
+                // value of one size class for this lane's configuration: rounded bytes
+                auto class_value = [&](u32 coef, u32 dims, u32 meta) -> u64 {
                     u64 x = (u64)coef * (meta & 255u);
                     x *= D[dims & 15u];
                     x *= D[(dims >> 8) & 15u];
@@ -275,14 +278,69 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                     u64 r = b_up(x, align_shift);
                     if (fl & LLMEM_EV_TIMES_L) r *= (u64)L;
                     if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
+                    return r;
+                };
+                // after a segment: `at` is the live total at its start relative to the resident state,
+                // `run` its net change, `top` its highest prefix.  The L equal blocks shift the prefix
+                // linearly, so the maximum over the repetitions of F (or B) is at the first or last one.
+                auto close_segment = [&](int s, i64 run, i64 top) {
+                    const bool repeated = s == LLMEM_SEG_F || s == LLMEM_SEG_B;
+                    if (repeated) {
+                        const i64 shift = ((i64)L - 1) * run;
+                        const i64 cand = at + top + (shift > 0 ? shift : 0);
+                        if (top != LOWEST && L != 0) best = cand > best ? cand : best;
+                        at += (i64)L * run;
+                    } else {
+                        const i64 cand = at + top;
+                        if (top != LOWEST) best = cand > best ? cand : best;
+                        at += run;
+                    }
+                };
+                if (a.use_program) {
+                    // ---- compiled timeline: classes and terms come from the kernel arguments ----
+                    int pc = (int)uni((u32)al.prog_first);
+                    const int nc_raw = (int)a.prog[pc];
+                    const int nc = nc_raw < a.s_slots - 1 ? nc_raw : a.s_slots - 1;
+                    ++pc;
+                    for (int c = 0; c < nc; ++c) {
+                        const u64 r = class_value(a.prog[pc + 3 * c], a.prog[pc + 3 * c + 1], a.prog[pc + 3 * c + 2]);
+                        *reinterpret_cast<i64 *>(vals + (c + 1) * 512) = (i64)r;
+                    }
+                    for (int s = 0; s < LLMEM_NSEG; ++s) {
+                        i64 acc = 0, top = LOWEST, run = 0;
+                        const int w_begin = (int)uni((u32)al.prog_seg[s]), w_end = (int)uni((u32)al.prog_seg[s + 1]);
+                        for (int w = w_begin; w < w_end; w += PROG_GROUP) {
+                            u32 t[PROG_GROUP];
+                            u64 v[PROG_GROUP];
+#pragma unroll
+                            for (int q = 0; q < PROG_GROUP; ++q) {
+                                t[q] = a.prog[w + q];                                    // scalar load
+                                v[q] = *reinterpret_cast<const u64 *>(vals + (t[q] & PROG_OFFSET_MASK));
+                            }
+#pragma unroll
+                            for (int q = 0; q < PROG_GROUP; ++q) {
+                                const int count = (int)t[q] >> 16;
+                                if (count >= 0) { acc += (i64)(v[q] * (u64)(u32)count); }
+                                else { asm volatile("" ::: "memory"); acc -= (i64)(v[q] * (u64)(u32)(-count)); }
+                                if (t[q] & PROG_END_POINT) {
+                                    asm volatile("" ::: "memory");
+                                    if (t[q] & PROG_END_SEGMENT) run = acc; else top = acc > top ? acc : top;
+                                    acc = 0;
+                                }
+                            }
+                        }
+                        close_segment(s, run, top);
+                    }
+                } else {
+                // ---- size classes of the timeline: rounded bytes into the value slots ----
+                const int nc_raw = (int)uni((u32)n_class[ar]);
+                const int nc = nc_raw < CLS_MAX ? nc_raw : CLS_MAX;
+                for (int c = 0; c < nc; ++c) {
+                    const uint4 ce = cls_tab[ar * CLS_MAX + c];                // wave-uniform
+                    const u64 r = class_value(uni(ce.x), uni(ce.y), uni(ce.z));
                     if (c + 1 < a.s_slots) *reinterpret_cast<i64 *>(vals + (c + 1) * 512) = (i64)r;
                 }
-
-                // ---- timeline (Sec. 2.1 / Sec. 3.1): A, F x L, H, B x L, Z ---------------------
-                // `at` is the live total at the start of the segment relative to the resident
-                // state; the L equal blocks shift the prefix linearly, so the maximum over the
-                // repetitions of F (or B) is taken at the first or the last one.
-                i64 at = 0, best = 0;                                         // the empty prefix counts
+                // ---- timeline (Sec. 2.1 / Sec. 3.1): A, F x L, H, B x L, Z, event by event ---------
                 const int code_first = (int)uni((u32)al.code_first);
                 for (int s = 0; s < LLMEM_NSEG; ++s) {
                     i64 run = 0, top = LOWEST;
@@ -305,17 +363,8 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                         LLMEM_STEP(v4, c4) LLMEM_STEP(v5, c5) LLMEM_STEP(v6, c6) LLMEM_STEP(v7, c7)
 #undef LLMEM_STEP
                     }
-                    const bool repeated = s == LLMEM_SEG_F || s == LLMEM_SEG_B;
-                    if (repeated) {
-                        const i64 shift = ((i64)L - 1) * run;
-                        const i64 cand = at + top + (shift > 0 ? shift : 0);
-                        if (top != LOWEST && L != 0) best = cand > best ? cand : best;
-                        at += (i64)L * run;
-                    } else {
-                        const i64 cand = at + top;
-                        if (top != LOWEST) best = cand > best ? cand : best;
-                        at += run;
-                    }
+                    close_segment(s, run, top);
+                }
                 }
                 const i64 prelude = (i64)(m_base + param_gpu + os_gpu + lm_p * B16 + grad_extra);
                 r_param = (i64)param_gpu; r_grad = (i64)grad_logical; r_os = (i64)os_gpu; r_out = (i64)m_out;
@@ -347,12 +396,13 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
 
 size_t batch_kernel_lds_bytes(const EstimateArgs &a)
 {
+    const size_t values = sizeof(long long) * 64 * (size_t)a.s_slots * BATCH_WAVES;
+    if (a.use_program) return (values + 15) & ~(size_t)15;             // compiled form: value slots only
     size_t fixed = sizeof(uint4) * (size_t)a.n_arch * CLS_MAX;        // class table
     fixed += sizeof(unsigned short) * (size_t)a.code_count;            // event codes
     fixed += sizeof(int) * LLMEM_MAX_ARCH;                             // class counts
     size_t scratch = sizeof(uint4) * (size_t)a.max_events;             // set-up scratch: keys
     scratch += 2 * sizeof(unsigned short) * (size_t)(a.max_events + 1); // representatives, class ids
-    const size_t values = sizeof(long long) * 64 * (size_t)a.s_slots * BATCH_WAVES;
     return ((fixed + (scratch > values ? scratch : values)) + 15) & ~(size_t)15;
 }
 

@@ -20,13 +20,14 @@ def U():
     return gpu_util
 
 
-WAVE, LANE = 1, 2       # LLMEM_KERNEL_WAVE, LLMEM_KERNEL_LANE
-BOTH = (WAVE, LANE)
+WAVE, LANE, LANE_EVENTS, LANE_COMPILED = 1, 2, 3, 4       # LLMEM_KERNEL_*
+BOTH = (WAVE, LANE_EVENTS, LANE_COMPILED)
 
 
 def _check(U, cfg, tables, const=CONST, threads=8, kernels=BOTH):
-    """Both kernels (one wavefront per configuration; one lane per configuration),
-    each forced, plus the library's own choice, against the oracle."""
+    """Every kernel form (one wavefront per configuration; one lane per configuration walking
+    all events; the same with the host-compiled timeline), each forced, plus the library's own
+    choice, against the oracle."""
     want_p, want_d = B.estimate(cfg, tables, const, threads=threads)
     for kernel in tuple(kernels) + (0,):
         got_p, got_d = U.hip_estimate(cfg, tables, const, kernel=kernel)
@@ -69,9 +70,10 @@ def test_random_tables_wild_configs(U):
     _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512), kernels=(WAVE,))
     _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), kernels=(WAVE,))
     import paper_2404_10933_amd as M
-    with pytest.raises(M.LlmemError) as e:
-        U.hip_estimate(cfg, tabs, CONST, kernel=LANE)
-    assert e.value.code == -3
+    for forced in (LANE, LANE_EVENTS, LANE_COMPILED):
+        with pytest.raises(M.LlmemError) as e:
+            U.hip_estimate(cfg, tabs, CONST, kernel=forced)
+        assert e.value.code == -3
 
 
 def test_random_tables_few_sizes(U):
@@ -82,9 +84,14 @@ def test_random_tables_few_sizes(U):
             T.random_table(rng, 64, 1024, "r3", n_sizes=20), T.gpt_table(), T.random_table(rng, 1, 1, "one", n_sizes=1),
             T.random_table(rng, 30, 600, "r6", n_sizes=7), T.opt_table()]
     cfg = G.random_configs(rng, 64 * 40 + 5, n_arch=len(tabs), wild=True)
-    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512))
-    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1))
-    _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512))
+    # all eight together do not fit the kernel arguments in compiled form
+    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), kernels=(WAVE, LANE_EVENTS))
+    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), kernels=(WAVE, LANE_EVENTS))
+    # subsets that do fit: every form
+    for subset in ([tabs[0], tabs[2], tabs[5]], [tabs[6], tabs[1]], [tabs[4], tabs[7]]):
+        sub = G.random_configs(rng, 64 * 20 + 3, n_arch=len(subset), wild=True)
+        _check(U, sub, subset, T.Constants(m_base=0, cu_p=2 << 20, align=512))
+        _check(U, sub, subset, T.Constants(m_base=7, cu_p=4096, align=512))
 
 
 def test_degenerate_and_flag_cases(U):
