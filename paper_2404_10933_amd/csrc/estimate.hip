@@ -348,15 +348,46 @@ static int log2_exact(int64_t v)
     return s;
 }
 
-// Compiles the timeline of one architecture for the lane-per-configuration kernel: size classes,
-// then per segment the class-count vectors at the peak points (an allocation followed by a
-// release or by the end of the segment), minus those another point dominates component-wise
-// (class values are never negative, so a dominated point cannot hold the maximum), then the
-// segment's net change.  Appends 32-bit words to `prog`; returns false if the architecture does
-// not fit (too many classes or words).
-static bool compile_timeline(const llmem_event_entry *ev, int n_event, const int *seg_first, ArchLayout *al,
-                             std::vector<uint32_t> *prog)
+// Size expression as the compiled tables carry it: the selectors that are not LLMEM_DIM_ONE and
+// their number.  `sorted_dims` holds four selectors in ascending order, one per byte.
+static uint32_t descriptor_of(uint32_t sorted_dims)
 {
+    uint32_t desc = 0, n = 0;
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t sel = (sorted_dims >> (8 * q)) & 15u;
+        if (sel == LLMEM_DIM_ONE) continue;
+        desc |= sel << (4 + 4 * n);
+        ++n;
+    }
+    return desc | n;
+}
+
+// Compiles the tables of one architecture for the lane-per-configuration kernel: parameter
+// entries grouped by size expression; size classes of the events; then per segment the
+// class-count vectors at the peak points (an allocation followed by a release or by the end of the
+// segment), minus those another point dominates component-wise (class values are never negative,
+// so a dominated point cannot hold the maximum), then the segment's net change.  Appends 32-bit
+// words to `prog`; returns false if the architecture does not fit.
+static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem_event_entry *ev, int n_event,
+                           const int *seg_first, ArchLayout *al, std::vector<uint32_t> *prog)
+{
+    // ---- parameter groups ----
+    struct Group { uint32_t coef, dims; uint32_t cnt[8]; };      // E, LM, OTHER, OS x once, per block
+    std::vector<Group> groups;
+    uint32_t e_n = 0;
+    for (int j = 0; j < n_param; ++j) {
+        const uint32_t *w = reinterpret_cast<const uint32_t *>(&pe[j]);
+        const ClassKey k = make_class_key(w[0], w[1], 0u);         // sorts the selectors
+        size_t g = 0;
+        for (; g < groups.size(); ++g) if (groups[g].coef == k.coef && groups[g].dims == k.dims) break;
+        if (g == groups.size()) groups.push_back(Group{k.coef, k.dims, {0, 0, 0, 0, 0, 0, 0, 0}});
+        const int layer = pe[j].per_layer ? 1 : 0;
+        const int role = pe[j].role == LLMEM_ROLE_EMBED_TOK ? 0 : pe[j].role == LLMEM_ROLE_LM_HEAD ? 1 : 2;
+        ++groups[g].cnt[2 * role + layer];
+        if (pe[j].cls <= LLMEM_CLS_LINEAR && pe[j].role != LLMEM_ROLE_LM_HEAD) ++groups[g].cnt[6 + layer];
+        if (pe[j].cls == LLMEM_CLS_EMBEDDING && pe[j].role != LLMEM_ROLE_LM_HEAD) ++e_n;
+    }
+    // ---- size classes ----
     std::vector<ClassKey> classes;
     std::vector<int> cls_of(n_event);
     for (int j = 0; j < n_event; ++j) {
@@ -369,10 +400,23 @@ static bool compile_timeline(const llmem_event_entry *ev, int n_event, const int
         cls_of[j] = c;
     }
     const int nc = (int)classes.size();
-    if (nc > CLS_MAX) return false;
+    if (nc > CLS_MAX || groups.size() > 255 || e_n > 255) return false;
     al->prog_first = (int)prog->size();
-    prog->push_back((uint32_t)nc);
-    for (const ClassKey &k : classes) { prog->push_back(k.coef); prog->push_back(k.dims); prog->push_back(k.meta); }
+    prog->push_back((uint32_t)groups.size() | (e_n << 8) | ((uint32_t)nc << 16));
+    for (const Group &g : groups) {
+        prog->push_back(g.coef);
+        prog->push_back(descriptor_of(g.dims));
+        prog->push_back(g.cnt[0] | (g.cnt[1] << 8) | (g.cnt[2] << 16) | (g.cnt[3] << 24));
+        prog->push_back(g.cnt[4] | (g.cnt[5] << 8) | (g.cnt[6] << 16) | (g.cnt[7] << 24));
+    }
+    for (const ClassKey &k : classes) {
+        const uint64_t c64 = (uint64_t)k.coef * (k.meta & 255u);   // coefficient * element bytes
+        if (c64 >> 32) return false;
+        const uint32_t flags = (k.meta >> 8) & 255u, mask = (k.meta >> 16) & 7u;
+        prog->push_back((uint32_t)c64);
+        prog->push_back(descriptor_of(k.dims) | ((flags & LLMEM_EV_TP_GATHER) ? DESC_TP_GATHER : 0u)
+                        | ((flags & LLMEM_EV_TIMES_L) ? DESC_TIMES_L : 0u) | (mask << 24));
+    }
     for (int s = 0; s < LLMEM_NSEG; ++s) {
         std::vector<std::vector<int>> points;
         std::vector<int> count(nc, 0);
@@ -498,7 +542,8 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, 
         }
         if (n_class > CLS_MAX) *batch_ok = false;
         if (n_class + 1 > out->s_slots) out->s_slots = n_class + 1;
-        if (*prog_ok && !compile_timeline(t->events_host + d.event_first, d.n_event, al.seg_first, &al, &prog))
+        if (*prog_ok && !compile_tables(t->params_host + d.param_first, d.n_param, t->events_host + d.event_first, d.n_event,
+                                        al.seg_first, &al, &prog))
             *prog_ok = false;
     }
     if (*prog_ok) for (size_t q = 0; q < prog.size(); ++q) out->prog[q] = prog[q];

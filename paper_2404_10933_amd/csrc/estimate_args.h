@@ -20,14 +20,25 @@ constexpr int CLS_MAX = 48;
 constexpr int CODE_GROUP = 8;
 constexpr unsigned CODE_CHECK = 1, CODE_FREE = 2, CODE_OFFSET_MASK = 0xfe00;
 constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
-// lane-per-configuration kernel, compiled form of the timeline: the host reduces the events of
-// every segment to the peak points no other point dominates (class-count vectors compared
+// lane-per-configuration kernel, compiled form of the tables: the host groups parameter entries
+// with the same size expression, groups events into size classes, reduces the events of every
+// segment to the peak points no other point dominates (class-count vectors compared
 // component-wise) and passes the result in the kernel arguments.  Stream of 32-bit words per
-// architecture: n_class, then {coef, dims, meta} per class, then per segment A F H B Z its
-// terms in groups of PROG_GROUP.  A term is  slot * 512 | flags | count << 16  (count signed):
-// the partial sum gains count * value[slot]; PROG_END_POINT closes a peak point (its sum
-// competes for the segment's maximum and the partial sum restarts); with PROG_END_SEGMENT as
-// well it closes the segment's net change instead.  Padding terms are 0 (slot 0 holds 0).
+// architecture:
+//   header     n_groups | e_n << 8 | n_class << 16
+//   per group  coefficient; descriptor; E_once | E_layer << 8 | LM_once << 16 | LM_layer << 24;
+//              OTHER_once | OTHER_layer << 8 | OS_once << 16 | OS_layer << 24
+//              (how many entries of the group count towards embed_p, lm_p, other_p, m_os, once or
+//              once per block)
+//   per class  coefficient * element bytes; descriptor
+//   per segment A F H B Z its terms in groups of PROG_GROUP.  A term is
+//              slot * 512 | flags | count << 16  (count signed): the partial sum gains
+//              count * value[slot]; PROG_END_POINT closes a peak point (its sum competes for the
+//              segment's maximum and the partial sum restarts); with PROG_END_SEGMENT as well it
+//              closes the segment's net change instead.  Padding terms are 0 (slot 0 holds 0).
+// Descriptor: number of dimensions (bits 0-2), their selectors (4 bits each from bit 4),
+// DESC_TP_GATHER, DESC_TIMES_L, method mask (bits 24-26).
+constexpr unsigned DESC_TP_GATHER = 1u << 20, DESC_TIMES_L = 1u << 21;
 constexpr int PROG_WORDS = 704;
 constexpr int PROG_GROUP = 8;
 constexpr unsigned PROG_OFFSET_MASK = 0xfe00, PROG_END_POINT = 0x1, PROG_END_SEGMENT = 0x2;

@@ -174,24 +174,55 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
             const ArchLayout &al = a.arch[ar];
             const int n_param = (int)uni((u32)al.n_param), param_first = (int)uni((u32)al.param_first);
 
+            // size of a compiled expression for this lane's configuration (descriptor: see estimate_args.h)
+            auto expression = [&](u32 coef, u32 desc) -> u64 {
+                const u32 nd = desc & 7u;
+                u64 x = coef;
+                if (nd > 0) x = (u64)coef * D[(desc >> 4) & 15u];
+                if (nd > 1) x *= D[(desc >> 8) & 15u];
+                if (nd > 2) x *= D[(desc >> 12) & 15u];
+                if (nd > 3) x *= D[(desc >> 16) & 15u];
+                return x;
+            };
             // ---- parameter table (Notation table; Sec. 4.2, equation for m_os) ---------
             u64 embed_p = 0, lm_p = 0, other_p = 0, t_max = 0, m_os = 0;
             u32 e_n = 0;
-            for (int j = 0; j < n_param; ++j) {
-                const uint4 pe = a.params_dev[param_first + j];           // wave-uniform
-                const u32 cls = pe.z & 255u, role = (pe.z >> 8) & 255u, per_layer = (pe.z >> 16) & 255u;
-                u64 t_p = (u64)pe.x * D[pe.y & 15u];
-                t_p *= D[(pe.y >> 8) & 15u];
-                t_p *= D[(pe.y >> 16) & 15u];
-                t_p *= D[(pe.y >> 24) & 15u];
-                const u64 copies = per_layer ? (u64)L : 1ull;
-                const u64 tot = t_p * copies;
-                if (role == LLMEM_ROLE_EMBED_TOK) embed_p += tot;
-                else if (role == LLMEM_ROLE_LM_HEAD) lm_p += tot;
-                else { other_p += tot; t_max = t_p > t_max ? t_p : t_max; }
-                if (cls <= LLMEM_CLS_LINEAR && role != LLMEM_ROLE_LM_HEAD)
-                    m_os += b_up(t_p * (u64)(B32 + B32), cu_shift) * copies;
-                if (cls == LLMEM_CLS_EMBEDDING && role != LLMEM_ROLE_LM_HEAD) ++e_n;
+            int pc = 0;                                                    // read position in the compiled tables
+            if (a.use_program) {
+                // entries with the same size expression arrive as one group with the number of
+                // entries that count towards each sum, once and once per block
+                pc = (int)uni((u32)al.prog_first);
+                const u32 head = a.prog[pc++];
+                e_n = (head >> 8) & 255u;
+                const int n_groups = (int)(head & 255u);
+                for (int g = 0; g < n_groups; ++g, pc += 4) {
+                    const u32 w2 = a.prog[pc + 2], w3 = a.prog[pc + 3];
+                    const u64 t_p = expression(a.prog[pc], a.prog[pc + 1]);
+                    if (w2 & 0xffffu) embed_p += t_p * (u64)((w2 & 255u) + ((w2 >> 8) & 255u) * L);
+                    if (w2 >> 16) lm_p += t_p * (u64)(((w2 >> 16) & 255u) + (w2 >> 24) * L);
+                    if (w3 & 0xffffu) {
+                        other_p += t_p * (u64)((w3 & 255u) + ((w3 >> 8) & 255u) * L);
+                        t_max = t_p > t_max ? t_p : t_max;
+                    }
+                    if (w3 >> 16) m_os += b_up(t_p * (u64)(B32 + B32), cu_shift) * (u64)(((w3 >> 16) & 255u) + (w3 >> 24) * L);
+                }
+            } else {
+                for (int j = 0; j < n_param; ++j) {
+                    const uint4 pe = a.params_dev[param_first + j];           // wave-uniform
+                    const u32 cls = pe.z & 255u, role = (pe.z >> 8) & 255u, per_layer = (pe.z >> 16) & 255u;
+                    u64 t_p = (u64)pe.x * D[pe.y & 15u];
+                    t_p *= D[(pe.y >> 8) & 15u];
+                    t_p *= D[(pe.y >> 16) & 15u];
+                    t_p *= D[(pe.y >> 24) & 15u];
+                    const u64 copies = per_layer ? (u64)L : 1ull;
+                    const u64 tot = t_p * copies;
+                    if (role == LLMEM_ROLE_EMBED_TOK) embed_p += tot;
+                    else if (role == LLMEM_ROLE_LM_HEAD) lm_p += tot;
+                    else { other_p += tot; t_max = t_p > t_max ? t_p : t_max; }
+                    if (cls <= LLMEM_CLS_LINEAR && role != LLMEM_ROLE_LM_HEAD)
+                        m_os += b_up(t_p * (u64)(B32 + B32), cu_shift) * copies;
+                    if (cls == LLMEM_CLS_EMBEDDING && role != LLMEM_ROLE_LM_HEAD) ++e_n;
+                }
             }
             const u64 n_params = embed_p + other_p + ((cflags & LLMEM_CFG_TIED_LM_HEAD) ? 0ull : lm_p);
 
@@ -298,12 +329,16 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                 };
                 if (a.use_program) {
                     // ---- compiled timeline: classes and terms come from the kernel arguments ----
-                    int pc = (int)uni((u32)al.prog_first);
-                    const int nc_raw = (int)a.prog[pc];
+                    const int nc_raw = (int)((a.prog[(int)uni((u32)al.prog_first)] >> 16) & 255u);
                     const int nc = nc_raw < a.s_slots - 1 ? nc_raw : a.s_slots - 1;
-                    ++pc;
-                    for (int c = 0; c < nc; ++c) {
-                        const u64 r = class_value(a.prog[pc + 3 * c], a.prog[pc + 3 * c + 1], a.prog[pc + 3 * c + 2]);
+                    for (int c = 0; c < nc; ++c, pc += 2) {
+                        const u32 desc = a.prog[pc + 1];
+                        u64 x = expression(a.prog[pc], desc);
+                        if (desc & DESC_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
+                        u64 r = b_up(x, align_shift);
+                        if (desc & DESC_TIMES_L) r *= (u64)L;
+                        const u32 mask = (desc >> 24) & 7u;
+                        if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
                         *reinterpret_cast<i64 *>(vals + (c + 1) * 512) = (i64)r;
                     }
                     for (int s = 0; s < LLMEM_NSEG; ++s) {

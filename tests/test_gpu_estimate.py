@@ -88,7 +88,7 @@ def test_random_tables_few_sizes(U):
     _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), kernels=(WAVE, LANE_EVENTS))
     _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), kernels=(WAVE, LANE_EVENTS))
     # subsets that do fit: every form
-    for subset in ([tabs[0], tabs[2], tabs[5]], [tabs[6], tabs[1]], [tabs[4], tabs[7]]):
+    for subset in ([tabs[0], tabs[2], tabs[5]], [tabs[6], tabs[5]], [tabs[1], tabs[4], tabs[7]]):
         sub = G.random_configs(rng, 64 * 20 + 3, n_arch=len(subset), wild=True)
         _check(U, sub, subset, T.Constants(m_base=0, cu_p=2 << 20, align=512))
         _check(U, sub, subset, T.Constants(m_base=7, cu_p=4096, align=512))
