@@ -263,6 +263,15 @@ size_t llmem_config_bytes(int64_t n);
 /* Upper bound of the bytes of n event lists (events only, not the offsets). */
 size_t llmem_events_bytes(int64_t n);
 
+/* Host-only: which kernel forms these tables allow and what they cost.  info[0] = bit mask
+ * (bit k set: LLMEM_KERNEL_k is allowed, k = 1..4), info[1] = 32-bit words of the compiled
+ * tables (of LLMEM_PROGRAM_WORDS available), info[2] = value slots per wavefront in the
+ * compiled form, info[3] = value slots per wavefront in the events form, info[4] = LDS slots
+ * of the wavefront-per-configuration form, info[5..7] = 0.  Returns LLMEM_OK or the error
+ * the estimator would return for these tables.                                           */
+#define LLMEM_PROGRAM_WORDS 704
+int llmem_kernel_forms(const llmem_tables *method_tables, int32_t info[8]);
+
 /* Host-only self-test hook: floor(x / d) computed by the multiply-high constants
  * the kernels use for their divisions by the partition degree (0 <= x < 2^63,
  * 1 <= d <= 255; returns 0 for d outside that range).                          */

@@ -100,6 +100,8 @@ def load_library():
     lib.llmem_events_bytes.restype = ctypes.c_size_t
     lib.llmem_strerror.argtypes = [ci]
     lib.llmem_strerror.restype = ctypes.c_char_p
+    lib.llmem_kernel_forms.argtypes = [ctypes.POINTER(_Tables), ctypes.POINTER(ctypes.c_int32)]
+    lib.llmem_kernel_forms.restype = ci
     lib.llmem_selftest_divide.argtypes = [u64, ctypes.c_uint32]
     lib.llmem_selftest_divide.restype = u64
     _lib = lib
@@ -170,12 +172,19 @@ class Tables:
         self.params_host = np.array(params, dtype=PARAM_DTYPE) if params else np.zeros(0, dtype=PARAM_DTYPE)
         self.events_host = np.array(events, dtype=EVENT_DTYPE) if events else np.zeros(0, dtype=EVENT_DTYPE)
         self.struct.n_param_total, self.struct.n_event_total = len(params), len(events)
-        self.params_dev = torch.from_numpy(self.params_host.view(np.uint8).reshape(-1).copy()).to(device)
-        self.events_dev = torch.from_numpy(self.events_host.view(np.uint8).reshape(-1).copy()).to(device)
         self.struct.params_host = self.params_host.ctypes.data if len(params) else None
         self.struct.events_host = self.events_host.ctypes.data if len(events) else None
-        self.struct.params_dev = self.params_dev.data_ptr() if len(params) else None
-        self.struct.events_dev = self.events_dev.data_ptr() if len(events) else None
+        if device is None:
+            # host-only tables: good for llmem_kernel_forms, not for launching (the device
+            # pointers are placeholders that are never dereferenced on the host)
+            self.params_dev = self.events_dev = None
+            self.struct.params_dev = 16 if len(params) else None
+            self.struct.events_dev = 16 if len(events) else None
+        else:
+            self.params_dev = torch.from_numpy(self.params_host.view(np.uint8).reshape(-1).copy()).to(device)
+            self.events_dev = torch.from_numpy(self.events_host.view(np.uint8).reshape(-1).copy()).to(device)
+            self.struct.params_dev = self.params_dev.data_ptr() if len(params) else None
+            self.struct.events_dev = self.events_dev.data_ptr() if len(events) else None
 
     @staticmethod
     def _dims(names):
@@ -251,6 +260,13 @@ def llmem_events_generate(seed: int, first: int, n: int, offsets: torch.Tensor, 
         raise ValueError("offsets: need int64 of n + 1 values; events int64")
     _check(load_library().llmem_events_generate(seed, first, n, _ptr(offsets), _ptr(events),
                                                 _stream_handle(stream)))
+
+
+def llmem_kernel_forms(tables: "Tables") -> Dict[str, int]:
+    info = (ctypes.c_int32 * 8)()
+    _check(load_library().llmem_kernel_forms(ctypes.byref(tables.struct), info))
+    return {"allowed": [k for k in range(1, 5) if info[0] >> k & 1], "program_words": info[1],
+            "compiled_slots": info[2], "event_slots": info[3], "wave_slots": info[4]}
 
 
 def llmem_config_bytes(n: int) -> int:

@@ -369,7 +369,7 @@ static uint32_t descriptor_of(uint32_t sorted_dims)
 // so a dominated point cannot hold the maximum), then the segment's net change.  Appends 32-bit
 // words to `prog`; returns false if the architecture does not fit.
 static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem_event_entry *ev, int n_event,
-                           const int *seg_first, ArchLayout *al, std::vector<uint32_t> *prog)
+                           const int *seg_first, ArchLayout *al, std::vector<uint32_t> *prog, int *p_slots)
 {
     // ---- parameter groups ----
     struct Group { uint32_t coef, dims; uint32_t cnt[8]; };      // E, LM, OTHER, OS x once, per block
@@ -409,24 +409,18 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
         prog->push_back(g.cnt[0] | (g.cnt[1] << 8) | (g.cnt[2] << 16) | (g.cnt[3] << 24));
         prog->push_back(g.cnt[4] | (g.cnt[5] << 8) | (g.cnt[6] << 16) | (g.cnt[7] << 24));
     }
-    for (const ClassKey &k : classes) {
-        const uint64_t c64 = (uint64_t)k.coef * (k.meta & 255u);   // coefficient * element bytes
-        if (c64 >> 32) return false;
-        const uint32_t flags = (k.meta >> 8) & 255u, mask = (k.meta >> 16) & 7u;
-        prog->push_back((uint32_t)c64);
-        prog->push_back(descriptor_of(k.dims) | ((flags & LLMEM_EV_TP_GATHER) ? DESC_TP_GATHER : 0u)
-                        | ((flags & LLMEM_EV_TIMES_L) ? DESC_TIMES_L : 0u) | (mask << 24));
-    }
+    // ---- peak points and net change of every segment ----
+    std::vector<std::vector<int>> seg_sums[LLMEM_NSEG];           // kept points, then the net change last
+    std::vector<int> neg_slot(nc, 0);                             // extra slot holding -value, if a count is negative
+    int n_slots = nc + 1;
     for (int s = 0; s < LLMEM_NSEG; ++s) {
         std::vector<std::vector<int>> points;
         std::vector<int> count(nc, 0);
         for (int j = seg_first[s]; j < seg_first[s + 1]; ++j) {
             const bool is_free = ev[j].flags & LLMEM_EV_FREE;
             count[cls_of[j]] += is_free ? -1 : 1;
-            if (count[cls_of[j]] > 32767 || count[cls_of[j]] < -32767) return false;
             if (!is_free && (j + 1 == seg_first[s + 1] || (ev[j + 1].flags & LLMEM_EV_FREE))) points.push_back(count);
         }
-        std::vector<std::vector<int>> kept;
         for (size_t j = 0; j < points.size(); ++j) {
             bool dominated = false;
             for (size_t k = 0; k < points.size() && !dominated; ++k) {
@@ -435,21 +429,43 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
                 for (int c = 0; c < nc; ++c) { le = le && points[j][c] <= points[k][c]; lt = lt || points[j][c] < points[k][c]; }
                 dominated = le && (lt || k < j);
             }
-            if (!dominated) kept.push_back(points[j]);
+            if (!dominated) seg_sums[s].push_back(points[j]);
         }
+        seg_sums[s].push_back(count);
+        for (const auto &v : seg_sums[s])
+            for (int c = 0; c < nc; ++c) if (v[c] < 0 && neg_slot[c] == 0) neg_slot[c] = n_slots++;
+    }
+    if (n_slots > PROG_SLOT_MAX) return false;
+    if (n_slots > *p_slots) *p_slots = n_slots;
+    // ---- emit: classes, then the terms of every segment ----
+    for (int c = 0; c < nc; ++c) {
+        const ClassKey &k = classes[c];
+        const uint64_t c64 = (uint64_t)k.coef * (k.meta & 255u);   // coefficient * element bytes
+        if (c64 >> 32) return false;
+        const uint32_t flags = (k.meta >> 8) & 255u, mask = (k.meta >> 16) & 7u;
+        prog->push_back((uint32_t)c64);
+        prog->push_back(descriptor_of(k.dims) | ((flags & LLMEM_EV_TP_GATHER) ? DESC_TP_GATHER : 0u)
+                        | ((flags & LLMEM_EV_TIMES_L) ? DESC_TIMES_L : 0u) | (mask << DESC_MASK_SHIFT)
+                        | ((uint32_t)neg_slot[c] << DESC_NEG_SLOT_SHIFT));
+    }
+    for (int s = 0; s < LLMEM_NSEG; ++s) {
         al->prog_seg[s] = (int)prog->size();
-        auto emit = [&](const std::vector<int> &v, uint32_t end_flag) {
-            int last = -1;
-            for (int c = 0; c < nc; ++c) if (v[c] != 0) last = c;
-            if (last < 0) { prog->push_back(end_flag); return; }          // empty sum: slot 0, count 0
-            for (int c = 0; c <= last; ++c) {
+        for (size_t j = 0; j < seg_sums[s].size(); ++j) {
+            const std::vector<int> &v = seg_sums[s][j];
+            const bool is_point = j + 1 < seg_sums[s].size();     // the last sum is the net change: stays open
+            const size_t group_first = prog->size();
+            for (int c = 0; c < nc; ++c) {
                 if (v[c] == 0) continue;
-                prog->push_back(((uint32_t)(c + 1) << 9) | (c == last ? end_flag : 0u) | ((uint32_t)v[c] << 16));
+                const int mag = v[c] < 0 ? -v[c] : v[c];
+                if (mag > 65535) return false;
+                const int slot = v[c] < 0 ? neg_slot[c] : c + 1;
+                prog->push_back(((uint32_t)slot << 9) | ((uint32_t)mag << 16));
             }
-        };
-        for (const auto &v : kept) emit(v, PROG_END_POINT);
-        emit(count, PROG_END_POINT | PROG_END_SEGMENT);
-        while ((prog->size() - (size_t)al->prog_seg[s]) % PROG_GROUP) prog->push_back(0u);
+            if (prog->size() == group_first && is_point) prog->push_back(0u);      // a point with an empty sum
+            while ((prog->size() - group_first) % PROG_GROUP) prog->push_back(0u);
+            // the flag sits in the first word of the sum's last group
+            if (is_point) (*prog)[prog->size() - PROG_GROUP] |= PROG_END_POINT;
+        }
     }
     al->prog_seg[LLMEM_NSEG] = (int)prog->size();
     return prog->size() <= (size_t)PROG_WORDS;
@@ -457,7 +473,8 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
 
 // Checks the host copy of the tables and derives the lane layout of every
 // architecture's events.  Returns LLMEM_OK or LLMEM_EINVAL_*.
-static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, bool *batch_ok, bool *prog_ok)
+static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, bool *batch_ok, bool *prog_ok,
+                       int *prog_words = nullptr)
 {
     *wave_ok = true;
     *batch_ok = true;
@@ -543,13 +560,15 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, 
         if (n_class > CLS_MAX) *batch_ok = false;
         if (n_class + 1 > out->s_slots) out->s_slots = n_class + 1;
         if (*prog_ok && !compile_tables(t->params_host + d.param_first, d.n_param, t->events_host + d.event_first, d.n_event,
-                                        al.seg_first, &al, &prog))
+                                        al.seg_first, &al, &prog, &out->p_slots))
             *prog_ok = false;
     }
     if (*prog_ok) for (size_t q = 0; q < prog.size(); ++q) out->prog[q] = prog[q];
+    if (prog_words) *prog_words = (int)prog.size();
     out->n_slot_total = slot;
     out->code_count = code;
     if (out->s_slots < 1) out->s_slots = 1;
+    if (out->p_slots < 1) out->p_slots = 1;
     out->use_program = 1;                     // sizes the LDS of the compiled form
     if (*prog_ok && batch_kernel_lds_bytes(*out) > BATCH_LDS_LIMIT) *prog_ok = false;
     out->use_program = 0;
@@ -624,6 +643,27 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
 const char *last_hip_error() { return g_hip_error; }
 
 }  // namespace llmem
+
+extern "C" int llmem_kernel_forms(const llmem_tables *tables, int32_t info[8])
+{
+    using namespace llmem;
+    if (!tables || !info) return LLMEM_EINVAL_NULL;
+    static_assert(LLMEM_PROGRAM_WORDS == PROG_WORDS, "header and kernel arguments disagree");
+    EstimateArgs args;
+    memset(&args, 0, sizeof(args));
+    bool wave_ok, batch_ok, prog_ok;
+    int words = 0;
+    const int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok, &words);
+    if (rc != LLMEM_OK) return rc;
+    for (int q = 0; q < 8; ++q) info[q] = 0;
+    info[0] = (wave_ok ? 1 << LLMEM_KERNEL_WAVE : 0) | (batch_ok ? 1 << LLMEM_KERNEL_LANE_EVENTS : 0)
+              | (prog_ok ? 1 << LLMEM_KERNEL_LANE_COMPILED : 0) | ((batch_ok || prog_ok) ? 1 << LLMEM_KERNEL_LANE : 0);
+    info[1] = words;
+    info[2] = args.p_slots;
+    info[3] = args.s_slots;
+    info[4] = args.n_slot_total;
+    return LLMEM_OK;
+}
 
 extern "C" uint64_t llmem_selftest_divide(uint64_t x, uint32_t d)
 {

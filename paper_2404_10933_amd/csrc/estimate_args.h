@@ -31,17 +31,22 @@ constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
 //              (how many entries of the group count towards embed_p, lm_p, other_p, m_os, once or
 //              once per block)
 //   per class  coefficient * element bytes; descriptor
-//   per segment A F H B Z its terms in groups of PROG_GROUP.  A term is
-//              slot * 512 | flags | count << 16  (count signed): the partial sum gains
-//              count * value[slot]; PROG_END_POINT closes a peak point (its sum competes for the
-//              segment's maximum and the partial sum restarts); with PROG_END_SEGMENT as well it
-//              closes the segment's net change instead.  Padding terms are 0 (slot 0 holds 0).
+//   per segment A F H B Z its sums, each in groups of PROG_GROUP terms: the peak points, then
+//              the segment's net change.  A term is  slot * 512 | count << 16: the partial sum
+//              gains count * value[slot].  PROG_END_POINT in the first term of a group closes a
+//              peak point after that group (its sum competes for the segment's maximum and the
+//              partial sum restarts); the net change comes last and stays open.  Padding terms
+//              are 0 (slot 0 holds 0).  Slot c + 1 holds the value of class c; a class that some
+//              sum counts negatively has a second slot holding minus its value.
 // Descriptor: number of dimensions (bits 0-2), their selectors (4 bits each from bit 4),
-// DESC_TP_GATHER, DESC_TIMES_L, method mask (bits 24-26).
+// DESC_TP_GATHER, DESC_TIMES_L, method mask (3 bits from DESC_MASK_SHIFT), slot of the negated
+// value (from DESC_NEG_SLOT_SHIFT, 0 = none).
 constexpr unsigned DESC_TP_GATHER = 1u << 20, DESC_TIMES_L = 1u << 21;
+constexpr int DESC_MASK_SHIFT = 22, DESC_NEG_SLOT_SHIFT = 25;
+constexpr int PROG_SLOT_MAX = 100;
 constexpr int PROG_WORDS = 704;
-constexpr int PROG_GROUP = 8;
-constexpr unsigned PROG_OFFSET_MASK = 0xfe00, PROG_END_POINT = 0x1, PROG_END_SEGMENT = 0x2;
+constexpr int PROG_GROUP = 4;
+constexpr unsigned PROG_OFFSET_MASK = 0xfe00, PROG_END_POINT = 0x1;
 constexpr size_t BATCH_LDS_LIMIT = 64 * 1024;  // dynamic LDS a launch may ask for
 
 struct ArchLayout {
@@ -72,6 +77,7 @@ struct EstimateArgs {
     int cu_shift, align_shift;
     int n_arch, n_param_total, n_slot_total;
     int code_count, max_events, s_slots;
+    int p_slots;                     // value slots per wave in the compiled form
     ArchLayout arch[LLMEM_MAX_ARCH];
     const uint4 *params_dev;
     const uint4 *events_dev;

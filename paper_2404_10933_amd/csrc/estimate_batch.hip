@@ -124,7 +124,8 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
     const u64 m_base = (u64)a.m_base;
     // value slots of this wave: slot s of lane l at byte s * 512 + l * 8; an event code is the
     // slot's byte offset with the check flag in bit 0
-    char *vals = reinterpret_cast<char *>(dyn) + ((size_t)wave * a.s_slots * 64 + lane) * sizeof(i64);
+    char *vals = reinterpret_cast<char *>(dyn)
+                 + ((size_t)wave * (a.use_program ? a.p_slots : a.s_slots) * 64 + lane) * sizeof(i64);
     if (DETAIL) *reinterpret_cast<i64 *>(vals) = 0;
 
     for (long long b = (long long)blockIdx.x * BB_WAVES + wave; b < n_batch;
@@ -329,41 +330,41 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                 };
                 if (a.use_program) {
                     // ---- compiled timeline: classes and terms come from the kernel arguments ----
-                    const int nc_raw = (int)((a.prog[(int)uni((u32)al.prog_first)] >> 16) & 255u);
-                    const int nc = nc_raw < a.s_slots - 1 ? nc_raw : a.s_slots - 1;
+                    const int nc = (int)((a.prog[(int)uni((u32)al.prog_first)] >> 16) & 255u);
                     for (int c = 0; c < nc; ++c, pc += 2) {
                         const u32 desc = a.prog[pc + 1];
                         u64 x = expression(a.prog[pc], desc);
                         if (desc & DESC_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
                         u64 r = b_up(x, align_shift);
                         if (desc & DESC_TIMES_L) r *= (u64)L;
-                        const u32 mask = (desc >> 24) & 7u;
+                        const u32 mask = (desc >> DESC_MASK_SHIFT) & 7u;
                         if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
-                        *reinterpret_cast<i64 *>(vals + (c + 1) * 512) = (i64)r;
+                        *reinterpret_cast<u64 *>(vals + (c + 1) * 512) = r;
+                        const u32 neg = desc >> DESC_NEG_SLOT_SHIFT;
+                        if (neg) *reinterpret_cast<u64 *>(vals + neg * 512) = 0ull - r;
                     }
                     for (int s = 0; s < LLMEM_NSEG; ++s) {
-                        i64 acc = 0, top = LOWEST, run = 0;
+                        // sums of count * value, four terms at a time, no branches: a flagged group
+                        // ends a peak point; what is left open at the end is the net change
+                        u64 acc = 0;
+                        i64 top = LOWEST;
                         const int w_begin = (int)uni((u32)al.prog_seg[s]), w_end = (int)uni((u32)al.prog_seg[s + 1]);
                         for (int w = w_begin; w < w_end; w += PROG_GROUP) {
-                            u32 t[PROG_GROUP];
-                            u64 v[PROG_GROUP];
-#pragma unroll
-                            for (int q = 0; q < PROG_GROUP; ++q) {
-                                t[q] = a.prog[w + q];                                    // scalar load
-                                v[q] = *reinterpret_cast<const u64 *>(vals + (t[q] & PROG_OFFSET_MASK));
-                            }
-#pragma unroll
-                            for (int q = 0; q < PROG_GROUP; ++q) {
-                                const int count = (int)t[q] >> 16;
-                                if (count >= 0) { acc += (i64)(v[q] * (u64)(u32)count); }
-                                else { asm volatile("" ::: "memory"); acc -= (i64)(v[q] * (u64)(u32)(-count)); }
-                                if (t[q] & PROG_END_POINT) {
-                                    asm volatile("" ::: "memory");
-                                    if (t[q] & PROG_END_SEGMENT) run = acc; else top = acc > top ? acc : top;
-                                    acc = 0;
-                                }
-                            }
+                            const u32 t0 = a.prog[w], t1 = a.prog[w + 1], t2 = a.prog[w + 2], t3 = a.prog[w + 3];
+                            const u64 v0 = *reinterpret_cast<const u64 *>(vals + (t0 & PROG_OFFSET_MASK));
+                            const u64 v1 = *reinterpret_cast<const u64 *>(vals + (t1 & PROG_OFFSET_MASK));
+                            const u64 v2 = *reinterpret_cast<const u64 *>(vals + (t2 & PROG_OFFSET_MASK));
+                            const u64 v3 = *reinterpret_cast<const u64 *>(vals + (t3 & PROG_OFFSET_MASK));
+                            acc += v0 * (u64)(t0 >> 16);
+                            acc += v1 * (u64)(t1 >> 16);
+                            acc += v2 * (u64)(t2 >> 16);
+                            acc += v3 * (u64)(t3 >> 16);
+                            const bool end = t0 & PROG_END_POINT;
+                            const bool up = end & ((i64)acc > top);
+                            top = up ? (i64)acc : top;
+                            acc = end ? 0ull : acc;
                         }
+                        const i64 run = (i64)acc;
                         close_segment(s, run, top);
                     }
                 } else {
@@ -431,8 +432,9 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
 
 size_t batch_kernel_lds_bytes(const EstimateArgs &a)
 {
+    if (a.use_program)                                                // compiled form: value slots only
+        return (sizeof(long long) * 64 * (size_t)a.p_slots * BATCH_WAVES + 15) & ~(size_t)15;
     const size_t values = sizeof(long long) * 64 * (size_t)a.s_slots * BATCH_WAVES;
-    if (a.use_program) return (values + 15) & ~(size_t)15;             // compiled form: value slots only
     size_t fixed = sizeof(uint4) * (size_t)a.n_arch * CLS_MAX;        // class table
     fixed += sizeof(unsigned short) * (size_t)a.code_count;            // event codes
     fixed += sizeof(int) * LLMEM_MAX_ARCH;                             // class counts

@@ -24,22 +24,32 @@ WAVE, LANE, LANE_EVENTS, LANE_COMPILED = 1, 2, 3, 4       # LLMEM_KERNEL_*
 BOTH = (WAVE, LANE_EVENTS, LANE_COMPILED)
 
 
-def _check(U, cfg, tables, const=CONST, threads=8, kernels=BOTH):
-    """Every kernel form (one wavefront per configuration; one lane per configuration walking
-    all events; the same with the host-compiled timeline), each forced, plus the library's own
-    choice, against the oracle."""
+def _check(U, cfg, tables, const=CONST, threads=8, expect=None):
+    """Every kernel form the tables allow (one wavefront per configuration; one lane per
+    configuration walking all events; the same with the host-compiled tables), each forced,
+    plus the library's own choice, against the oracle.  `expect`: forms that must be allowed."""
+    import paper_2404_10933_amd as M
+    allowed = M.llmem_kernel_forms(M.Tables(tables, m_base=const.m_base, cu_p=const.cu_p, align=const.align,
+                                            device=None))["allowed"]
+    if expect is not None:
+        assert sorted(k for k in allowed if k != LANE) == sorted(expect), allowed
     want_p, want_d = B.estimate(cfg, tables, const, threads=threads)
-    for kernel in tuple(kernels) + (0,):
+    for kernel in [0] + allowed:
         got_p, got_d = U.hip_estimate(cfg, tables, const, kernel=kernel)
         U.assert_same(f"detail (kernel {kernel})", got_d, want_d)
         U.assert_same(f"peaks (kernel {kernel})", got_p, want_p)
         got_p2, _ = U.hip_estimate(cfg, tables, const, detail=False, kernel=kernel)
         U.assert_same(f"peaks, no detail (kernel {kernel})", got_p2, want_p)
+    for kernel in (WAVE, LANE, LANE_EVENTS, LANE_COMPILED):
+        if kernel not in allowed:
+            with pytest.raises(M.LlmemError) as e:
+                U.hip_estimate(cfg, tables, const, kernel=kernel)
+            assert e.value.code == -3
 
 
 def test_grid1_all(U):
     cfg = G.grid1()
-    _check(U, cfg, [T.gpt_table()])
+    _check(U, cfg, [T.gpt_table()], expect=BOTH)
     # and directly against the Python oracle that carries the pins
     rows = np.asarray(A.estimate(cfg, [T.gpt_table()], CONST), dtype=np.int64)
     _, got = U.hip_estimate(cfg, [T.gpt_table()], CONST)
@@ -50,7 +60,7 @@ def test_grid1_all(U):
                                           ("g4", 64 * 300 + 1, 9_000_000)])
 def test_grid_slices(U, name, n, first):
     spec = G.GRIDS[name]
-    _check(U, spec["make"](n=n, seed=0, first=first), [T.FAMILIES[spec["family"]]()])
+    _check(U, spec["make"](n=n, seed=0, first=first), [T.FAMILIES[spec["family"]]()], expect=BOTH)
 
 
 @pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 127, 128, 129, 1000])
@@ -65,15 +75,10 @@ def test_random_tables_wild_configs(U):
             T.random_table(rng, 64, 700, "r3"), T.gpt_table(), T.random_table(rng, 1, 1, "one"),
             T.random_table(rng, 30, 1024, "max")]
     cfg = G.random_configs(rng, 64 * 40 + 5, n_arch=len(tabs), wild=True)
-    # more than 32 distinct sizes in one architecture: only the wavefront-per-configuration kernel applies
-    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), kernels=(WAVE,))
-    _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512), kernels=(WAVE,))
-    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), kernels=(WAVE,))
-    import paper_2404_10933_amd as M
-    for forced in (LANE, LANE_EVENTS, LANE_COMPILED):
-        with pytest.raises(M.LlmemError) as e:
-            U.hip_estimate(cfg, tabs, CONST, kernel=forced)
-        assert e.value.code == -3
+    # more than 48 distinct sizes in one architecture: only the wavefront-per-configuration kernel applies
+    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), expect=(WAVE,))
+    _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512), expect=(WAVE,))
+    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), expect=(WAVE,))
 
 
 def test_random_tables_few_sizes(U):
@@ -85,13 +90,14 @@ def test_random_tables_few_sizes(U):
             T.random_table(rng, 30, 600, "r6", n_sizes=7), T.opt_table()]
     cfg = G.random_configs(rng, 64 * 40 + 5, n_arch=len(tabs), wild=True)
     # all eight together do not fit the kernel arguments in compiled form
-    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), kernels=(WAVE, LANE_EVENTS))
-    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), kernels=(WAVE, LANE_EVENTS))
+    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), expect=(WAVE, LANE_EVENTS))
+    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), expect=(WAVE, LANE_EVENTS))
     # subsets that do fit: every form
-    for subset in ([tabs[0], tabs[2], tabs[5]], [tabs[6], tabs[5]], [tabs[1], tabs[4], tabs[7]]):
+    small = T.random_table(rng, 12, 140, "r8", n_sizes=9)
+    for subset in ([tabs[6], tabs[5]], [tabs[1], tabs[4], tabs[7]], [small, tabs[2], tabs[5], tabs[1]]):
         sub = G.random_configs(rng, 64 * 20 + 3, n_arch=len(subset), wild=True)
-        _check(U, sub, subset, T.Constants(m_base=0, cu_p=2 << 20, align=512))
-        _check(U, sub, subset, T.Constants(m_base=7, cu_p=4096, align=512))
+        _check(U, sub, subset, T.Constants(m_base=0, cu_p=2 << 20, align=512), expect=BOTH)
+        _check(U, sub, subset, T.Constants(m_base=7, cu_p=4096, align=512), expect=BOTH)
 
 
 def test_degenerate_and_flag_cases(U):
