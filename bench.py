@@ -23,41 +23,27 @@ PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12       # 256 CUs x one 64-lane vector in
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs under profiles/, scaled by the
 # plain-copy reference; None while the kernel has changed since the counters were taken
-TRAFFIC_ESTIMATE = None
-TRAFFIC_TIMELINE = None
+TRAFFIC_ESTIMATE = 1.3502e9     # 10^7 configurations, all detail columns
+TRAFFIC_TIMELINE = 8.0201e9     # 100 000 event lists, 1 000 110 810 events
 
 
-def size_classes(table):
-    """Distinct size expressions among the timeline events (same coefficient,
-    dimensions, element width, scaling, method mask): evaluated once each."""
-    return len({(e.coef, tuple(sorted(d for d in e.dims if d != "one")), e.elem_bytes, e.scale, e.times_L,
-                 e.methods) for e in table.events})
-
-
-def peak_points(table):
-    """Events after which the live total can peak: an allocation followed by a
-    release or by the end of its segment."""
-    ev = table.events
-    return sum(1 for i, e in enumerate(ev)
-               if e.sign > 0 and (i + 1 == len(ev) or ev[i + 1].sign < 0 or ev[i + 1].seg != e.seg))
-
-
-def algorithmic_lane_ops(table, n_candidates):
-    """Integer work of one configuration in 64-bit lane operations of the method
-    itself (L equal blocks collapsed, equal sizes evaluated once), priced in gfx950
-    vector instructions: add/sub 1, multiply by a 32-bit dimension 2, round up to
-    a power of two 3, compare-and-select (max) 3, ceil-divide by d 12.
-    Derivation in the design doc, section 6."""
-    ADD, MUL, UP, MAX, DIV = 1, 2, 3, 3, 12
-    per_param = 4 * MUL + MUL + ADD + (8 * 0 + MUL + UP + MUL + ADD) / 2 + MAX / 2   # monomial, x L, role sum, m_os, t_max
-    per_class = 5 * MUL + UP + 1                                                     # monomial x bytes, block round-up, store
-    per_event = ADD
-    per_peak_point = MAX
-    fixed = (3 * MUL + MUL + UP) + (3 * MUL + 2 * (MUL + UP) + 3 * ADD) + (3 * MUL + UP + DIV) + 2 * MUL + DIV  # m_out, m_lm, m_back, grads
-    per_candidate = 2 * ADD + 3 * (MUL + UP) + DIV + UP + 5 * ADD + 2 * MAX          # chunking, m_p*, shard, compose, waste, pick
-    tail = 2 * (DIV + UP) + 5 * (MUL + MAX + 2 * ADD) + 4 * ADD                      # resident bytes, segments, prelude
-    return (len(table.params) * per_param + size_classes(table) * per_class + len(table.events) * per_event
-            + peak_points(table) * per_peak_point + fixed + n_candidates * per_candidate + tail)
+def algorithmic_lane_ops(forms, n_candidates):
+    """Integer work of one configuration in 64-bit lane operations of the method itself, in its
+    leanest known form (equal size expressions evaluated once, the L equal blocks collapsed, the
+    timeline reduced to the peak points no other point dominates), priced in gfx950 vector
+    instructions: add/sub 1, 32x32->64 multiply 1, multiply of a 64-bit value by a 32-bit one 3,
+    round up to a power of two 3, compare-and-select (max) 3, ceil-divide by d 12.
+    `forms` = llmem_kernel_forms of the tables.  Derivation in the design doc, section 6."""
+    ADD, MUL32, MUL, UP, MAX, DIV = 1, 1, 3, 3, 3, 12
+    per_group = MUL32 + MUL + (MUL32 + MUL + ADD) + (ADD + UP + MUL32 + MUL + ADD) + MAX   # expression, role sum, m_os, t_max
+    per_class = MUL32 + 2 * MUL + UP + ADD                                                 # expression, block round-up, store
+    per_term = MUL + ADD
+    per_point = MAX
+    fixed = (2 * MUL + MUL + UP) + (2 * MUL + 2 * (MUL + UP) + 3 * ADD) + (3 * MUL + UP + DIV) + 2 * MUL + DIV
+    per_candidate = 2 * ADD + 3 * (MUL + UP) + DIV + UP + 5 * ADD + 2 * MAX
+    tail = 2 * (DIV + UP) + 5 * (MUL + MAX + 2 * ADD) + 4 * ADD
+    return (forms["param_groups"] * per_group + forms["size_classes"] * per_class + forms["terms"] * per_term
+            + forms["peak_points"] * per_point + fixed + n_candidates * per_candidate + tail)
 
 
 def main():
@@ -121,7 +107,8 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     value = n / (ms_per_step * 1e-3)
 
-    ops = algorithmic_lane_ops(table, 9)
+    forms = M.llmem_kernel_forms(tab)
+    ops = algorithmic_lane_ops(forms, 9)
     achieved = ops * n / (kernel_ms * 1e-3) / 1e12
     kernel_name = "estimate_kernel<true>" if args.kernel == "wave" else "estimate_batch_kernel<true>"
     bytes_per_cfg = M.llmem_config_bytes(1) + 8 + 8 * M.NDETAIL
@@ -133,9 +120,11 @@ def main():
         "config": {"workload": "g4: Llama-style grid with ZeRO-3 chunk-size search (9 candidates), "
                                "m_peak + all detail columns incl. timeline peak",
                    "n_configs": n, "table_params": len(table.params), "table_events": len(table.events),
-                   "table_size_classes": size_classes(table), "kernel": args.kernel, "seed": 0},
+                   "table_size_classes": forms["size_classes"], "table_peak_points": forms["peak_points"],
+                   "table_terms": forms["terms"], "kernel": args.kernel, "seed": 0},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
-                     "frac": achieved / PEAK_LANE_TOPS, "traffic": TRAFFIC_ESTIMATE,
+                     "frac": achieved / PEAK_LANE_TOPS,
+                     "traffic": TRAFFIC_ESTIMATE if (n == 10_000_000 and args.kernel == "auto") else None,
                      "kernel": kernel_name, "kernel_ms": kernel_ms,
                      "algorithmic_lane_ops_per_config": ops,
                      "hbm_gbs_algorithmic": bytes_per_cfg * n / (kernel_ms * 1e-3) / 1e9},
@@ -178,7 +167,8 @@ def main():
             "workload": "g5: explicit allocator event lists (~10^4 events each)", "n_lists": nl,
             "n_events": total, "ms_per_launch": ms, "lists_per_s": nl / (ms * 1e-3),
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_TIMELINE, "kernel": "timeline_kernel"}}}
+                         "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_TIMELINE if nl == 100_000 else None,
+                         "kernel": "timeline_kernel"}}}
         from workloads import events as E
         ev_c, off_c = E.generate(64, seed=0, first=0)
         wa, wr = B.event_lists_peaks(ev_c, off_c)

@@ -267,8 +267,10 @@ size_t llmem_events_bytes(int64_t n);
  * (bit k set: LLMEM_KERNEL_k is allowed, k = 1..4), info[1] = 32-bit words of the compiled
  * tables (of LLMEM_PROGRAM_WORDS available), info[2] = value slots per wavefront in the
  * compiled form, info[3] = value slots per wavefront in the events form, info[4] = LDS slots
- * of the wavefront-per-configuration form, info[5..7] = 0.  Returns LLMEM_OK or the error
- * the estimator would return for these tables.                                           */
+ * of the wavefront-per-configuration form; when the compiled form is allowed also info[5] =
+ * parameter groups | size classes << 16, info[6] = (class, count) terms, info[7] = peak points
+ * kept, summed over the architectures (else 0).  Returns LLMEM_OK or the error the estimator
+ * would return for these tables.                                                          */
 #define LLMEM_PROGRAM_WORDS 704
 int llmem_kernel_forms(const llmem_tables *method_tables, int32_t info[8]);
 

@@ -266,7 +266,9 @@ def llmem_kernel_forms(tables: "Tables") -> Dict[str, int]:
     info = (ctypes.c_int32 * 8)()
     _check(load_library().llmem_kernel_forms(ctypes.byref(tables.struct), info))
     return {"allowed": [k for k in range(1, 5) if info[0] >> k & 1], "program_words": info[1],
-            "compiled_slots": info[2], "event_slots": info[3], "wave_slots": info[4]}
+            "compiled_slots": info[2], "event_slots": info[3], "wave_slots": info[4],
+            "param_groups": info[5] & 0xffff, "size_classes": info[5] >> 16, "terms": info[6],
+            "peak_points": info[7]}
 
 
 def llmem_config_bytes(n: int) -> int:

@@ -369,7 +369,8 @@ static uint32_t descriptor_of(uint32_t sorted_dims)
 // so a dominated point cannot hold the maximum), then the segment's net change.  Appends 32-bit
 // words to `prog`; returns false if the architecture does not fit.
 static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem_event_entry *ev, int n_event,
-                           const int *seg_first, ArchLayout *al, std::vector<uint32_t> *prog, int *p_slots)
+                           const int *seg_first, ArchLayout *al, std::vector<uint32_t> *prog, int *p_slots,
+                           int *stats)
 {
     // ---- parameter groups ----
     struct Group { uint32_t coef, dims; uint32_t cnt[8]; };      // E, LM, OTHER, OS x once, per block
@@ -436,6 +437,8 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
             for (int c = 0; c < nc; ++c) if (v[c] < 0 && neg_slot[c] == 0) neg_slot[c] = n_slots++;
     }
     if (n_slots > PROG_SLOT_MAX) return false;
+    stats[0] += (int)groups.size();
+    stats[1] += nc;
     if (n_slots > *p_slots) *p_slots = n_slots;
     // ---- emit: classes, then the terms of every segment ----
     for (int c = 0; c < nc; ++c) {
@@ -460,7 +463,9 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
                 if (mag > 65535) return false;
                 const int slot = v[c] < 0 ? neg_slot[c] : c + 1;
                 prog->push_back(((uint32_t)slot << 9) | ((uint32_t)mag << 16));
+                ++stats[2];                                                         // (class, count) terms
             }
+            stats[3] += is_point ? 1 : 0;                                           // peak points
             if (prog->size() == group_first && is_point) prog->push_back(0u);      // a point with an empty sum
             while ((prog->size() - group_first) % PROG_GROUP) prog->push_back(0u);
             // the flag sits in the first word of the sum's last group
@@ -474,8 +479,10 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
 // Checks the host copy of the tables and derives the lane layout of every
 // architecture's events.  Returns LLMEM_OK or LLMEM_EINVAL_*.
 static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, bool *batch_ok, bool *prog_ok,
-                       int *prog_words = nullptr)
+                       int *prog_words = nullptr, int *prog_stats = nullptr)
 {
+    int stats_local[4] = {0, 0, 0, 0};
+    int *stats = prog_stats ? prog_stats : stats_local;
     *wave_ok = true;
     *batch_ok = true;
     *prog_ok = true;
@@ -560,7 +567,7 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, 
         if (n_class > CLS_MAX) *batch_ok = false;
         if (n_class + 1 > out->s_slots) out->s_slots = n_class + 1;
         if (*prog_ok && !compile_tables(t->params_host + d.param_first, d.n_param, t->events_host + d.event_first, d.n_event,
-                                        al.seg_first, &al, &prog, &out->p_slots))
+                                        al.seg_first, &al, &prog, &out->p_slots, stats))
             *prog_ok = false;
     }
     if (*prog_ok) for (size_t q = 0; q < prog.size(); ++q) out->prog[q] = prog[q];
@@ -653,7 +660,8 @@ extern "C" int llmem_kernel_forms(const llmem_tables *tables, int32_t info[8])
     memset(&args, 0, sizeof(args));
     bool wave_ok, batch_ok, prog_ok;
     int words = 0;
-    const int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok, &words);
+    int stats[4] = {0, 0, 0, 0};
+    const int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok, &words, stats);
     if (rc != LLMEM_OK) return rc;
     for (int q = 0; q < 8; ++q) info[q] = 0;
     info[0] = (wave_ok ? 1 << LLMEM_KERNEL_WAVE : 0) | (batch_ok ? 1 << LLMEM_KERNEL_LANE_EVENTS : 0)
@@ -662,6 +670,7 @@ extern "C" int llmem_kernel_forms(const llmem_tables *tables, int32_t info[8])
     info[2] = args.p_slots;
     info[3] = args.s_slots;
     info[4] = args.n_slot_total;
+    if (prog_ok) { info[5] = stats[0] | (stats[1] << 16); info[6] = stats[2]; info[7] = stats[3]; }
     return LLMEM_OK;
 }
 
