@@ -12,6 +12,8 @@
  *   Sec. 5    m_peak^dp (ZeRO-3), m_peak^tp, m_back^tp
  *   Sec. 4.1  chunk size chosen to minimise waste (search over 2^k MiB, k = 2..10)
  *   Sec. 2.1 / Sec. 3.1  timeline traversal with live tensors, 512-byte blocks
+ *   Sec. 5    m_peak^{dp+tp}
+ *   Sec. 6    Algorithm 1 (largest batch size per method, scores, choice)
  *
  * The timeline is walked event by event, block by block; no closed form over the
  * L equal blocks is used here.
@@ -31,7 +33,10 @@ enum { ROLE_EMBED_TOK, ROLE_LM_HEAD, ROLE_OTHER };
 enum { SEG_A, SEG_F, SEG_H, SEG_B, SEG_Z, NSEG };
 enum { NDETAIL = 12 };
 enum { D_PEAK, D_PARAM, D_GRAD, D_OS, D_OUT, D_LM, D_BACK, D_K, D_LIVE, D_NPARAMS, D_TMAX, D_FLAGS };
-enum { ERR_ARCH = 1, ERR_METHOD = 2, ERR_D = 4, ERR_HEADS = 8, ERR_CHUNK = 16, CHUNK_INFEASIBLE = 32 };
+enum { ERR_ARCH = 1, ERR_METHOD = 2, ERR_D = 4, ERR_HEADS = 8, ERR_CHUNK = 16, CHUNK_INFEASIBLE = 32,
+       ERR_TP = 64, HYBRID_READINGS_DIFFER = 128, FALLBACK_READINGS_DIFFER = 256 };
+enum { NDECIDE = 12 };
+enum { C_METHOD, C_BS, C_BS_LIST, C_SCORE2 = C_BS_LIST + 4, C_PEAK = C_SCORE2 + 4, C_FLAGS };
 enum { CFG_LOGITS_FP32 = 1, CFG_TIED = 2, CFG_GRAD_ALIAS = 4 };
 enum { K_MIN = 2, K_MAX = 10, K_FIXED_MAX = 16 };
 
@@ -101,7 +106,7 @@ static int64_t compose(int method, int64_t d, int64_t m_base, int64_t m_p, int64
 
 static void estimate_one(const o_configs *c, int64_t i, const o_table *tables, int n_tables,
                          int64_t m_base, int64_t cu_p, int64_t align, int want_timeline,
-                         int64_t *out, int64_t *scratch, int *ovf)
+                         int64_t *out, int64_t *scratch, int *ovf, int64_t *m_p16_out)
 {
     for (int j = 0; j < NDETAIL; ++j) out[j] = 0;
     int err = 0;
@@ -187,6 +192,7 @@ static void estimate_one(const o_configs *c, int64_t i, const o_table *tables, i
                                    align, ovf) + grad_extra, ovf);
     }
     int flags = t_max > chunk_elems(k) ? CHUNK_INFEASIBLE : 0;
+    if (m_p16_out) *m_p16_out = m_p16;
 
     int64_t param_gpu, os_gpu;
     if (method == 0) { param_gpu = m_p; os_gpu = m_os; }
@@ -266,11 +272,146 @@ int llmem_oracle_estimate(const o_configs *cfg, int64_t n, const o_table *tables
         #pragma omp for schedule(dynamic, 256)
         for (int64_t i = 0; i < n; ++i) {
             int64_t row[NDETAIL];
-            estimate_one(cfg, i, tables, n_tables, m_base, cu_p, align, want_timeline, row, scratch, &ovf);
+            estimate_one(cfg, i, tables, n_tables, m_base, cu_p, align, want_timeline, row, scratch, &ovf, NULL);
             if (peaks) peaks[i] = row[D_PEAK];
             if (detail) for (int j = 0; j < NDETAIL; ++j) detail[i * NDETAIL + j] = row[j];
         }
         free(scratch);
+        any_ovf |= ovf;
+    }
+    return any_ovf;
+}
+
+/* ---- DP+TP and the method decision ------------------------------------------------- */
+
+/* One configuration given by value, so that method and batch size can be varied. */
+typedef struct {
+    uint8_t arch_id; uint32_t h; uint16_t L, n_heads, n_kv; uint32_t ffn, V, P; uint16_t bs, sl;
+    uint8_t method, d; int8_t chunk_k; uint8_t flags;
+} one_config;
+
+static one_config pick(const o_configs *c, int64_t i)
+{
+    one_config q = { c->arch_id[i], c->h[i], c->L[i], c->n_heads[i], c->n_kv[i], c->ffn[i], c->V[i],
+                     c->P[i], c->bs[i], c->sl[i], c->method[i], c->d[i], c->chunk_k[i], c->flags[i] };
+    return q;
+}
+
+static void estimate_value(const one_config *q, const o_table *tables, int n_tables, int64_t m_base,
+                           int64_t cu_p, int64_t align, int64_t *row, int *ovf, int64_t *m_p16)
+{
+    o_configs c = { &q->arch_id, &q->h, &q->L, &q->n_heads, &q->n_kv, &q->ffn, &q->V, &q->P, &q->bs,
+                    &q->sl, &q->method, &q->d, &q->chunk_k, &q->flags };
+    estimate_one(&c, 0, tables, n_tables, m_base, cu_p, align, 0, row, NULL, ovf, m_p16);
+}
+
+static int query_errors(const one_config *q, int tp_n, int n_tables)
+{
+    int err = 0;
+    if (q->arch_id >= n_tables) err |= ERR_ARCH;
+    if (q->d == 0) err |= ERR_D;
+    if (q->n_heads == 0) err |= ERR_HEADS;
+    if (!(q->chunk_k == -1 || (q->chunk_k >= 0 && q->chunk_k <= K_FIXED_MAX))) err |= ERR_CHUNK;
+    if (tp_n > 0 && q->d > 0 && q->d % tp_n != 0) err |= ERR_TP;
+    return err;
+}
+
+/* out[0..3] = m_peak^s, m_peak^dp, m_peak^tp, m_peak^{dp+tp}; out[4] = flags */
+static void method_peaks(const one_config *q0, int tp_n, const o_table *tables, int n_tables,
+                         int64_t m_base, int64_t cu_p, int64_t align, int64_t *out, int *ovf)
+{
+    int err = query_errors(q0, tp_n, n_tables);
+    if (err) { out[0] = out[1] = out[2] = out[3] = -1; out[4] = err; return; }
+    one_config q = *q0;
+    int64_t row[NDETAIL], m_p16 = 0, flags = 0;
+    for (int m = 0; m < 3; ++m) {
+        q.method = (uint8_t)m;
+        estimate_value(&q, tables, n_tables, m_base, cu_p, align, row, ovf, m == 1 ? &m_p16 : NULL);
+        out[m] = row[D_PEAK];
+        flags |= row[D_FLAGS];
+    }
+    if (tp_n > 0) {
+        /* Sec. 5: m_peak^dp - m_p16 * tp_n / gpu_n + m_back^tp of a group of tp_n GPUs */
+        int64_t gpu_n = q.d;
+        int64_t printed = up(cdiv(fit((i128)m_p16 * tp_n, ovf), gpu_n), align, ovf);
+        int64_t other = up(cdiv(fit((i128)m_p16 * (tp_n - 1), ovf), tp_n), align, ovf);
+        int64_t A = fit((i128)q.bs * q.sl * q.h, ovf);
+        int64_t m_back = fit((i128)cdiv(fit((i128)q.L * A * (tp_n - 1) * B16, ovf), (int64_t)tp_n * cu_p) * cu_p, ovf);
+        out[3] = fit((i128)out[1] - printed + m_back, ovf);
+        if (printed != other) flags |= HYBRID_READINGS_DIFFER;
+    } else {
+        out[3] = -1;
+    }
+    out[4] = flags;
+}
+
+/* peaks: n rows of 4 int64; flags: n int64.  Returns 0, 1 (overflow) or 2 (malformed table). */
+int llmem_oracle_methods(const o_configs *cfg, const uint8_t *tp_n, int64_t n, const o_table *tables,
+                         int n_tables, int64_t m_base, int64_t cu_p, int64_t align,
+                         int64_t *peaks, int64_t *flags, int threads)
+{
+    int any_ovf = 0;
+    #pragma omp parallel for schedule(dynamic, 256) num_threads(threads > 0 ? threads : 1) reduction(|:any_ovf)
+    for (int64_t i = 0; i < n; ++i) {
+        int ovf = 0;
+        int64_t out[5];
+        one_config q = pick(cfg, i);
+        method_peaks(&q, tp_n[i], tables, n_tables, m_base, cu_p, align, out, &ovf);
+        for (int j = 0; j < 4; ++j) peaks[i * 4 + j] = out[j];
+        flags[i] = out[4];
+        any_ovf |= ovf;
+    }
+    return any_ovf;
+}
+
+/* Algorithm 1 for n queries; rows: n rows of NDECIDE int64.  The batch size of a method is raised
+ * one by one from 1 until its estimate exceeds m_total or the query's bs (the cap) is passed. */
+int llmem_oracle_decide(const o_configs *cfg, const uint8_t *tp_n, int64_t n, const o_table *tables,
+                        int n_tables, int64_t m_base, int64_t cu_p, int64_t align, int64_t m_total,
+                        int64_t *rows, int threads)
+{
+    for (int a = 0; a < n_tables; ++a)
+        for (int j = 0; j < tables[a].n_params; ++j)
+            for (int q = 0; q < tables[a].params[j].ndims; ++q)
+                if (tables[a].params[j].dims[q] == DIM_BS) return 2;     /* parameter sizes must not depend on bs */
+    int any_ovf = 0;
+    #pragma omp parallel for schedule(dynamic, 16) num_threads(threads > 0 ? threads : 1) reduction(|:any_ovf)
+    for (int64_t i = 0; i < n; ++i) {
+        int ovf = 0;
+        int64_t *row = rows + i * NDECIDE;
+        for (int j = 0; j < NDECIDE; ++j) row[j] = 0;
+        one_config q = pick(cfg, i);
+        int tp = tp_n[i];
+        int err = query_errors(&q, tp, n_tables);
+        if (err) { row[C_METHOD] = -1; row[C_FLAGS] = err; continue; }
+        int64_t gpu_n = q.d, cap = q.bs, out[5];
+        q.bs = 1;
+        method_peaks(&q, tp, tables, n_tables, m_base, cu_p, align, out, &ovf);
+        int64_t flags = out[4];
+        int64_t bs_list[4] = {0, 0, 0, 0}, peak_at[4] = {0, 0, 0, 0};
+        for (int m = 0; m < (tp > 0 ? 4 : 3); ++m) {
+            int64_t bs = 1;
+            while (bs <= cap) {
+                q.bs = (uint16_t)bs;
+                method_peaks(&q, tp, tables, n_tables, m_base, cu_p, align, out, &ovf);
+                if (out[m] > m_total) break;
+                peak_at[m] = out[m];
+                ++bs;
+            }
+            bs_list[m] = bs - 1;
+        }
+        int64_t dp_n = tp > 0 ? gpu_n / tp : 0;
+        int64_t score2[4] = { 3 * bs_list[0] * gpu_n, 2 * bs_list[1] * gpu_n, 2 * bs_list[2], 2 * bs_list[3] * dp_n };
+        int idx = 0;
+        for (int m = 1; m < 4; ++m) if (score2[m] > score2[idx]) idx = m;
+        if (score2[2] != 0) {
+            row[C_METHOD] = idx; row[C_BS] = bs_list[idx]; row[C_PEAK] = peak_at[idx];
+        } else {
+            row[C_METHOD] = 4; row[C_BS] = 0; row[C_PEAK] = 0;
+            if (score2[0] | score2[1] | score2[3]) flags |= FALLBACK_READINGS_DIFFER;
+        }
+        for (int m = 0; m < 4; ++m) { row[C_BS_LIST + m] = bs_list[m]; row[C_SCORE2 + m] = score2[m]; }
+        row[C_FLAGS] = flags;
         any_ovf |= ovf;
     }
     return any_ovf;

@@ -16,12 +16,21 @@ What is computed, with the passage each function follows:
   Sec. 4.1   chunk size chosen to minimise waste                    -> `chunk_search`
   Sec. 2.1 / Sec. 3.1  traversal of the operator timeline with live tensors and
              512-byte blocks                                        -> `timeline_peak`, `event_list_peaks`
+  Sec. 5     m_peak^{dp+tp} (combination of DP and TP)              -> `hybrid_peak`, `method_peaks`
+  Sec. 6     Algorithm 1: largest batch size per method under the
+             GPU's capacity, scores, choice of the method           -> `decide_one`
 
 Readings adopted where the paper is silent (each is listed in the design notes):
 sizes named "param size" are element counts; ceil(x * a / b) is one exact rational
 ceiling; division by gpu_n is a ceiling, then rounded to the 512-byte block; the
 chunk size 2^k MiB is the byte size of one fp16 chunk; only the token embedding is
-embed_p; lm_head bytes are added unrounded and carry no optimizer state.
+embed_p; lm_head bytes are added unrounded and carry no optimizer state.  In the
+DP+TP equation the subtracted share of param fp16 is taken as printed
+(m_p16 * tp_n / gpu_n, the same ceiling-then-block division); a flag marks the
+configurations where the other natural reading, m_p16 * (tp_n - 1) / tp_n, differs.
+Algorithm 1: a method whose estimate exceeds the capacity already at bs = 1 gets
+batch size 0; the fallback test is the printed one (on the TP score alone), and a
+flag marks the queries where the prose's test (all scores zero) decides otherwise.
 
 Parity pins: tests/test_oracle_pins.py (closed forms, hand-worked example,
 special cases, invariants, brute-force allocator simulation).  The printed
@@ -42,7 +51,16 @@ NDETAIL = 12
 
 # flag bits of the detail column D_FLAGS
 ERR_ARCH, ERR_METHOD, ERR_D, ERR_HEADS, ERR_CHUNK, CHUNK_INFEASIBLE = 1, 2, 4, 8, 16, 32
-ERR_MASK = ERR_ARCH | ERR_METHOD | ERR_D | ERR_HEADS | ERR_CHUNK
+ERR_TP = 64                      # tp_n > 0 that does not divide gpu_n
+HYBRID_READINGS_DIFFER = 128     # the two readings of the DP+TP subtrahend differ
+FALLBACK_READINGS_DIFFER = 256   # Algorithm 1: listing and prose disagree on the fallback
+ERR_MASK = ERR_ARCH | ERR_METHOD | ERR_D | ERR_HEADS | ERR_CHUNK | ERR_TP
+
+# columns of a decision row (Algorithm 1)
+(C_METHOD, C_BS, C_BS_CDP, C_BS_ADP, C_BS_TP, C_BS_HYBRID, C_SCORE2_CDP, C_SCORE2_ADP, C_SCORE2_TP,
+ C_SCORE2_HYBRID, C_PEAK, C_FLAGS) = range(12)
+NDECIDE = 12
+METHOD_OFFLOAD = 4               # "4, 0": heterogeneous training with CPU memory
 
 # config flag bits
 CFG_LOGITS_FP32, CFG_TIED, CFG_GRAD_ALIAS = 1, 2, 4
@@ -313,6 +331,135 @@ def estimate(cfg: Dict[str, Sequence[int]], tables: Sequence, const, timeline: b
         c = {k: int(cfg[k][i]) for k in names}
         rows.append(estimate_one(c, tables, const, timeline))
     return rows
+
+
+# ---------------------------------------------------------------------------
+# DP+TP and the method decision
+# ---------------------------------------------------------------------------
+def hybrid_subtrahends(m_p16: int, tp_n: int, gpu_n: int, align: int) -> Tuple[int, int]:
+    """Sec. 5, equation for m_peak^{dp+tp}: the share of param fp16 that tensor
+    parallelism removes from a GPU.  Returns (as printed, other reading)."""
+    printed = up(cdiv(_fit(m_p16 * tp_n), gpu_n), align)
+    other = up(cdiv(_fit(m_p16 * (tp_n - 1)), tp_n), align)
+    return printed, other
+
+
+def hybrid_peak(c: Dict[str, int], tp_n: int, tables: Sequence, const) -> Tuple[int, int]:
+    """Sec. 5: m_peak^{dp+tp} = m_peak^dp - m_p16 * tp_n / gpu_n + m_back^tp, with
+    m_peak^dp the ZeRO-3 estimate over all gpu_n GPUs and the all-gather buffer
+    of a tensor-parallel group of tp_n GPUs.  `c` is a valid configuration with
+    d = gpu_n; tp_n divides gpu_n.  Returns (peak, flags)."""
+    gpu_n = c["d"]
+    assert tp_n >= 1 and gpu_n % tp_n == 0
+    dp = estimate_one(dict(c, method=1), tables, const, timeline=False)
+    table = tables[c["arch_id"]]
+    D = dim_vector(c)
+    embed_p, _lm_p, other_p, _t_max, _n, _e_n = param_census(table, D, bool(c["flags"] & CFG_TIED))
+    _m_p, m_p16, _m_p32 = param_memory(embed_p, other_p, chunk_elems(dp[D_K]), const.cu_p)
+    printed, other = hybrid_subtrahends(m_p16, tp_n, gpu_n, const.align)
+    m_back = tp_backward_memory(D, tp_n, const.cu_p)
+    flags = dp[D_FLAGS] | (HYBRID_READINGS_DIFFER if printed != other else 0)
+    return _fit(dp[D_PEAK] - printed + m_back), flags
+
+
+def _query_errors(c: Dict[str, int], tp_n: int, n_tables: int) -> int:
+    err = 0
+    if c["arch_id"] >= n_tables:
+        err |= ERR_ARCH
+    if c["d"] == 0:
+        err |= ERR_D
+    if c["n_heads"] == 0:
+        err |= ERR_HEADS
+    if not (c["chunk_k"] == -1 or 0 <= c["chunk_k"] <= K_FIXED_MAX):
+        err |= ERR_CHUNK
+    if tp_n > 0 and c["d"] > 0 and c["d"] % tp_n != 0:
+        err |= ERR_TP
+    return err
+
+
+def method_peaks(c: Dict[str, int], tp_n: int, tables: Sequence, const) -> List[int]:
+    """[m_peak^s, m_peak^dp, m_peak^tp, m_peak^{dp+tp}, flags] of one configuration
+    (its `method` field is not read; d is gpu_n).  tp_n = 0: no DP+TP set-up, that
+    entry is -1.  An invalid configuration gives -1 everywhere and its error bits."""
+    err = _query_errors(c, tp_n, len(tables))
+    if err:
+        return [-1, -1, -1, -1, err]
+    peaks, flags = [], 0
+    for method in (0, 1, 2):
+        row = estimate_one(dict(c, method=method), tables, const, timeline=False)
+        peaks.append(row[D_PEAK])
+        flags |= row[D_FLAGS]
+    if tp_n > 0:
+        peak, f = hybrid_peak(c, tp_n, tables, const)
+        peaks.append(peak)
+        flags |= f
+    else:
+        peaks.append(-1)
+    return peaks + [flags]
+
+
+def largest_batch(peak_of_bs, bs_cap: int, m_total: int) -> Tuple[int, int]:
+    """Algorithm 1, inner loop of one method: start at bs = 1 and add one until the
+    estimate exceeds m_total (or bs_cap is passed); the batch size before that is
+    the largest one that avoids running out of memory (0 if even bs = 1 does not
+    fit).  Returns (bs, estimate at that bs or 0)."""
+    bs, last_peak = 1, 0
+    while bs <= bs_cap:
+        m_peak = peak_of_bs(bs)
+        if m_peak > m_total:
+            break
+        last_peak = m_peak
+        bs += 1
+    return bs - 1, last_peak
+
+
+def scores_doubled(bs_list: Sequence[int], gpu_n: int, dp_n: int) -> List[int]:
+    """Algorithm 1: eval = [bs * gpu_n * 1.5, bs * gpu_n, bs, bs * dp_n] for CDP,
+    ADP, TP, DP+TP; returned times two so that every score is an integer."""
+    return [_fit(3 * bs_list[0] * gpu_n), _fit(2 * bs_list[1] * gpu_n), 2 * bs_list[2],
+            _fit(2 * bs_list[3] * dp_n)]
+
+
+def choose(score2: Sequence[int], bs_list: Sequence[int]) -> Tuple[int, int, bool]:
+    """Algorithm 1, last two steps: the first index of the highest score (ties go
+    to CDP, ADP, TP, DP+TP in that order) with its batch size, unless the TP score
+    is 0, which selects the CPU-memory alternative "4, 0".  The third value tells
+    whether the prose's test (all scores 0) would have decided differently."""
+    idx = 0
+    for i in range(1, len(score2)):
+        if score2[i] > score2[idx]:
+            idx = i
+    if score2[2] != 0:
+        return idx, bs_list[idx], False
+    return METHOD_OFFLOAD, 0, any(x != 0 for x in score2)
+
+
+def decide_one(q: Dict[str, int], tp_n: int, tables: Sequence, const, m_total: int) -> List[int]:
+    """Sec. 6, Algorithm 1, for one query: model shape, gpu_n (`d`), `sl`; `bs` is
+    the largest batch size considered, tp_n the tensor-parallel degree of the DP+TP
+    set-up (0: none, its batch size and score stay 0).  Returns a row of NDECIDE
+    columns."""
+    row = [0] * NDECIDE
+    err = _query_errors(q, tp_n, len(tables))
+    if err:
+        row[C_METHOD], row[C_FLAGS] = -1, err
+        return row
+    assert all("bs" not in p.dims for p in tables[q["arch_id"]].params), "parameter sizes must not depend on bs"
+    gpu_n, bs_cap = q["d"], q["bs"]
+    # which chunk is used and how the DP+TP term reads do not depend on bs
+    flags = method_peaks(dict(q, bs=1), tp_n, tables, const)[4]
+    bs_list, peak_at = [0, 0, 0, 0], [0, 0, 0, 0]
+    for i in range(4 if tp_n > 0 else 3):
+        bs_list[i], peak_at[i] = largest_batch(
+            lambda bs: method_peaks(dict(q, bs=bs), tp_n, tables, const)[i], bs_cap, m_total)
+    score2 = scores_doubled(bs_list, gpu_n, gpu_n // tp_n if tp_n > 0 else 0)
+    method, bs, differ = choose(score2, bs_list)
+    row[C_METHOD], row[C_BS] = method, bs
+    row[C_BS_CDP:C_BS_CDP + 4] = bs_list
+    row[C_SCORE2_CDP:C_SCORE2_CDP + 4] = score2
+    row[C_PEAK] = peak_at[method] if method < 4 else 0
+    row[C_FLAGS] = flags | (FALLBACK_READINGS_DIFFER if differ else 0)
+    return row
 
 
 # ---------------------------------------------------------------------------

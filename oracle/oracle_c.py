@@ -71,6 +71,14 @@ def _load():
         lib.llmem_oracle_event_lists.restype = ctypes.c_int
         lib.llmem_oracle_event_lists.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64,
                                                  ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.llmem_oracle_methods.restype = ctypes.c_int
+        lib.llmem_oracle_methods.argtypes = [
+            ctypes.POINTER(_Configs), ctypes.c_void_p, ctypes.c_int64, ctypes.POINTER(_Table), ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int]
+        lib.llmem_oracle_decide.restype = ctypes.c_int
+        lib.llmem_oracle_decide.argtypes = [
+            ctypes.POINTER(_Configs), ctypes.c_void_p, ctypes.c_int64, ctypes.POINTER(_Table), ctypes.c_int,
+            ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -118,6 +126,48 @@ def estimate(cfg: Dict[str, np.ndarray], tables: Sequence, const, timeline: bool
         raise ValueError("malformed table")
     del keep
     return peaks, detail
+
+
+def _raise(rc):
+    if rc == 1:
+        raise OverflowError("an intermediate value does not fit int64")
+    if rc:
+        raise ValueError("malformed table")
+
+
+def method_peaks(cfg: Dict[str, np.ndarray], tp_n: np.ndarray, tables: Sequence, const, threads: int = 1):
+    """Returns (peaks[n, 4], flags[n]): CDP, ZeRO-3, TP, DP+TP estimates of every configuration."""
+    lib = _load()
+    cols = {name: np.ascontiguousarray(cfg[name], dtype=dt) for name, dt in _CFG_FIELDS}
+    tp = np.ascontiguousarray(tp_n, dtype=np.uint8)
+    n = len(cols["h"])
+    c = _Configs(**{name: cols[name].ctypes.data for name, _ in _CFG_FIELDS})
+    arr, keep = _pack_tables(tables)
+    peaks = np.empty((n, 4), dtype=np.int64)
+    flags = np.empty(n, dtype=np.int64)
+    _raise(lib.llmem_oracle_methods(ctypes.byref(c), tp.ctypes.data, n, arr, len(tables), const.m_base,
+                                    const.cu_p, const.align, peaks.ctypes.data, flags.ctypes.data, threads))
+    del keep
+    return peaks, flags
+
+
+NDECIDE = 12
+
+
+def decide(cfg: Dict[str, np.ndarray], tp_n: np.ndarray, tables: Sequence, const, m_total: int,
+           threads: int = 1):
+    """Algorithm 1 for every query; returns rows[n, NDECIDE]."""
+    lib = _load()
+    cols = {name: np.ascontiguousarray(cfg[name], dtype=dt) for name, dt in _CFG_FIELDS}
+    tp = np.ascontiguousarray(tp_n, dtype=np.uint8)
+    n = len(cols["h"])
+    c = _Configs(**{name: cols[name].ctypes.data for name, _ in _CFG_FIELDS})
+    arr, keep = _pack_tables(tables)
+    rows = np.empty((n, NDECIDE), dtype=np.int64)
+    _raise(lib.llmem_oracle_decide(ctypes.byref(c), tp.ctypes.data, n, arr, len(tables), const.m_base,
+                                   const.cu_p, const.align, int(m_total), rows.ctypes.data, threads))
+    del keep
+    return rows
 
 
 def event_lists_peaks(events: np.ndarray, offsets: np.ndarray, threads: int = 1):

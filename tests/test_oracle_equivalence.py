@@ -1,7 +1,8 @@
 """Oracle B (C, int64 with overflow checks) restates oracle A (Python, unbounded
 integers): the two must agree on every detail column, on whole grid 1, on seeded
 samples of grids 2-4, on random tables with wild configurations and on explicit
-event lists.  Oracle A carries the pins; this extends them to B."""
+event lists, and on the DP+TP estimate and the method decision for seeded and
+random queries.  Oracle A carries the pins; this extends them to B."""
 import numpy as np
 import pytest
 
@@ -54,6 +55,50 @@ def test_event_lists():
     a1, r1 = A.event_lists_peaks(ev, off)
     a2, r2 = B.event_lists_peaks(ev, off)
     assert list(a2) == a1 and list(r2) == r1
+
+
+def _rows_a(cfg, tp, fn):
+    names = list(cfg.keys())
+    return np.asarray([fn({k: int(cfg[k][i]) for k in names}, int(tp[i])) for i in range(len(tp))], dtype=np.int64)
+
+
+def test_method_peaks_and_decision_on_query_grid():
+    tabs = [T.llama_table()]
+    cfg, tp = G.grid6(n=40, seed=0, first=777)
+    cfg["bs"] = (cfg["bs"] % 7).astype(np.uint16)                       # as configurations: small batch sizes
+    peaks, flags = B.method_peaks(cfg, tp, tabs, CONST, threads=2)
+    want = _rows_a(cfg, tp, lambda c, t: A.method_peaks(c, t, tabs, CONST))
+    assert (peaks == want[:, :4]).all() and (flags == want[:, 4]).all()
+    cfg["bs"][:] = 40                                                   # as queries: batch sizes up to 40
+    for m_total in (24 << 30, 80 << 30):
+        rows = B.decide(cfg, tp, tabs, CONST, m_total, threads=2)
+        want = _rows_a(cfg, tp, lambda c, t: A.decide_one(c, t, tabs, CONST, m_total))
+        assert (rows == want).all()
+        assert len(set(rows[:, A.C_METHOD])) >= 3
+
+
+def test_method_peaks_and_decision_random_tables_wild_queries():
+    rng = np.random.default_rng(11)
+    tabs = [T.random_table(rng, 9, 0, "r0"), T.gpt_table(), T.random_table(rng, 0, 0, "empty"),
+            T.random_table(rng, 40, 0, "r3")]
+    cfg, tp = G.random_queries(rng, 250, n_arch=len(tabs), wild=True, bs_cap=10)
+    for const in (T.Constants(m_base=1, cu_p=4096, align=512), T.Constants(m_base=0, cu_p=2 << 20, align=512)):
+        peaks, flags = B.method_peaks(cfg, tp, tabs, const)
+        want = _rows_a(cfg, tp, lambda c, t: A.method_peaks(c, t, tabs, const))
+        assert (peaks == want[:, :4]).all() and (flags == want[:, 4]).all()
+        valid = peaks[:, 0] >= 0
+        for m_total in (0, int(np.median(peaks[valid, 1])), int(np.median(peaks[valid, 0])), 1 << 62):
+            rows = B.decide(cfg, tp, tabs, const, m_total, threads=3)
+            want = _rows_a(cfg, tp, lambda c, t: A.decide_one(c, t, tabs, const, m_total))
+            assert (rows == want).all()
+    assert (flags & A.ERR_TP).any() and (peaks[:, 3] == -1).any()
+
+
+def test_decision_rejects_batch_dependent_parameters():
+    t = T.ArchTable("odd", (T.ParamEntry("w", 1, ("h", "bs"), "L", "OTHER", False),), ())
+    cfg, tp = G.random_queries(np.random.default_rng(0), 4)
+    with pytest.raises(ValueError):
+        B.decide(cfg, tp, [t], CONST, 1 << 40)
 
 
 def test_oracle_b_reports_overflow():

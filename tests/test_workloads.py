@@ -84,3 +84,19 @@ def test_event_lists_are_well_formed():
     assert mag.min() >= 32 and mag.max() < 2 ** 28 and (mag % 512 != 0).mean() > 0.9
     ev2, off2 = E.generate(10, seed=1, first=13)
     assert (ev2 == ev[off[10]:off[20]]).all()
+
+
+def test_query_grid():
+    cfg, tp = G.grid6(n=5000, seed=3, first=10)
+    d = cfg["d"].astype(int)
+    assert set(np.unique(d)) == {1, 2, 4, 8, 16}
+    assert (tp >= 1).all() and (d % tp == 0).all() and ((tp & (tp - 1)) == 0).all()
+    assert (cfg["bs"] == G.QUERY_BS_CAP).all() and (cfg["chunk_k"] == G.CHUNK_SEARCH).all()
+    # same model shapes as grid 4, slice-independent
+    g4 = G.grid4(n=5000, seed=3, first=10)
+    for k in ("h", "L", "n_heads", "n_kv", "ffn", "V", "sl", "flags"):
+        assert (cfg[k] == g4[k]).all()
+    part, tp_part = G.grid6(n=100, seed=3, first=110)
+    assert (part["d"] == cfg["d"][100:200]).all() and (tp_part == tp[100:200]).all()
+    # every admissible (gpu_n, tp_n) pair occurs
+    assert len({(int(a), int(b)) for a, b in zip(d, tp)}) == 15

@@ -1,6 +1,6 @@
 """Seeded configuration grids (structure-of-arrays, one numpy array per field).
 
-Five synthetic grids stand in for the paper's real models and dataset (Sec. 7.1
+Synthetic grids stand in for the paper's real models and dataset (Sec. 7.1
 fine-tunes OPT, BLOOM, CodeGen, GPT-Neo, LLaMA ... on alpaca at sl = 512); the
 estimator consumes only shapes, so each grid draws decoder shapes of those
 families.  Every random draw is   lo + mix64(seed, index, field) mod span   with
@@ -65,7 +65,7 @@ def _pack(cols: Dict[str, np.ndarray]) -> Dict[str, np.ndarray]:
 
 
 # hash field ids (fixed; part of the grid definitions)
-F_H, F_L, F_V, F_BS, F_SL, F_METHOD, F_D, F_K, F_NKV = range(9)
+F_H, F_L, F_V, F_BS, F_SL, F_METHOD, F_D, F_K, F_NKV, F_TP = range(10)
 
 
 def grid1() -> Dict[str, np.ndarray]:
@@ -123,6 +123,43 @@ def grid3(n: int = 1_000_000, seed: int = 0, first: int = 0):
 def grid4(n: int = 10_000_000, seed: int = 0, first: int = 0):
     """Grid 3's distribution, every configuration asking for the chunk-size search."""
     return _llama(n, seed, first, search=True)
+
+
+QUERY_BS_CAP = 4096      # largest batch size a query of grid 6 considers
+
+
+def grid6(n: int = 1_000_000, seed: int = 0, first: int = 0):
+    """Queries of the method decision (Sec. 6, Algorithm 1 inputs: model, gpu_n, sl):
+    grid 4's Llama-style shapes and sequence lengths, gpu_n in {1, 2, 4, 8, 16} in the
+    column `d`, the largest batch size considered in the column `bs`, chunk-size search.
+    Returns (configuration columns, tp_n): tp_n = 2^j, j uniform in [0, log2 gpu_n], is the
+    tensor-parallel degree of the DP+TP set-up."""
+    cols = _llama(n, seed, first, search=True)
+    i = np.arange(first, first + n, dtype=np.uint64)
+    log_g = (mix64(seed, i, F_D) % np.uint64(5)).astype(np.int64)
+    log_t = (mix64(seed, i, F_TP) % (log_g + 1).astype(np.uint64)).astype(np.int64)
+    cols["d"] = (1 << log_g).astype(np.uint8)
+    cols["bs"] = np.full(n, QUERY_BS_CAP, dtype=np.uint16)
+    cols["method"] = np.zeros(n, dtype=np.uint8)
+    return cols, np.ascontiguousarray((1 << log_t).astype(np.uint8))
+
+
+def random_queries(rng, n: int, n_arch: int = 1, wild: bool = False, bs_cap: int = 48):
+    """Unstructured queries for edge-case parity tests: `random_configs` with small
+    batch-size caps, plus a tp_n column (mostly a divisor of gpu_n, sometimes 0 = no
+    DP+TP set-up; `wild`: sometimes not a divisor)."""
+    cols = random_configs(rng, n, n_arch=n_arch, wild=wild)
+    cols["bs"] = rng.integers(0, bs_cap + 1, size=n).astype(np.uint16)
+    d = cols["d"].astype(np.int64)
+    tp = np.ones(n, dtype=np.int64)
+    for j in range(n):
+        g = int(d[j])
+        divs = [t for t in range(1, g + 1) if g % t == 0] or [1]
+        tp[j] = divs[int(rng.integers(0, len(divs)))]
+    tp = np.where(rng.random(n) < 0.1, 0, tp)
+    if wild:
+        tp = np.where(rng.random(n) < 0.1, rng.integers(0, 256, size=n), tp)
+    return cols, np.ascontiguousarray(tp.astype(np.uint8))
 
 
 GRIDS = {
