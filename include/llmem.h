@@ -6,7 +6,9 @@
  * conventional data parallelism) and Sec. 5 (ZeRO-3 "advanced DP", 1-D tensor
  * parallelism), the chunk-size choice of Sec. 4.1, and a traversal of the
  * operator timeline with live tensors and 512-byte allocator blocks (Sec. 2.1,
- * Sec. 3.1).  All arithmetic is exact int64 byte arithmetic.
+ * Sec. 3.1); further the estimate for combined DP+TP (Sec. 5) and the choice of
+ * the fine-tuning method with its largest batch size (Sec. 6, Algorithm 1).  All
+ * arithmetic is exact int64 byte arithmetic.
  *
  * Conventions
  *   DEV   pointer to device memory, owned by the caller; the library never
@@ -27,7 +29,7 @@
 extern "C" {
 #endif
 
-#define LLMEM_ABI_VERSION 1
+#define LLMEM_ABI_VERSION 2
 
 /* ---- error codes --------------------------------------------------------- */
 #define LLMEM_OK            0
@@ -67,6 +69,9 @@ typedef struct llmem_configs {
 #define LLMEM_METHOD_CDP   0   /* conventional data parallelism = single-GPU peak (Sec. 5) */
 #define LLMEM_METHOD_ZERO3 1   /* advanced data parallelism, ZeRO-3 (Sec. 5)              */
 #define LLMEM_METHOD_TP    2   /* 1-D tensor parallelism (Sec. 5)                         */
+/* results of llmem_decide only (llmem_estimate takes methods 0..2): */
+#define LLMEM_METHOD_HYBRID  3 /* DP+TP: tp_n GPUs per tensor-parallel group (Sec. 5)      */
+#define LLMEM_METHOD_OFFLOAD 4 /* "4, 0": no method fits, train with CPU memory (Sec. 6)   */
 
 #define LLMEM_CHUNK_SEARCH (-1) /* search k = 2..10: least padding waste among the chunk
                                    sizes that hold the largest tensor, ties to the smaller */
@@ -204,6 +209,12 @@ enum llmem_detail {
 #define LLMEM_F_ERR_CHUNK   16  /* chunk_k outside {-1} U [0, 16]                          */
 #define LLMEM_F_CHUNK_INFEASIBLE 32 /* the largest tensor exceeds the chunk used (a search
                                        without a feasible candidate falls back to k = 10) */
+/* llmem_estimate_methods / llmem_decide only: */
+#define LLMEM_F_ERR_TP      64  /* tp_n > 0 does not divide gpu_n                          */
+#define LLMEM_F_HYBRID_READINGS_DIFFER 128   /* m_p16 * tp_n / gpu_n (as printed, used) and
+                                       m_p16 * (tp_n - 1) / tp_n give different DP+TP estimates */
+#define LLMEM_F_FALLBACK_READINGS_DIFFER 256 /* the TP score is 0 (so the result is "4, 0" as
+                                       Algorithm 1 prints it) but another score is not    */
 
 /* ---- entry points ---------------------------------------------------------- */
 
@@ -222,6 +233,56 @@ int llmem_estimate(const llmem_configs *cfg, int64_t n, const llmem_tables *meth
  * NULL; out_peaks may be NULL when out_detail is given.                        */
 int llmem_estimate_ex(const llmem_configs *cfg, int64_t n, const llmem_tables *method_tables,
                       int64_t *out_peaks, int64_t *out_detail, void *hip_stream);
+
+/* m_peak of all four methods for n configurations: out_peaks[m * n + i] for m = 0..3 is
+ * m_peak^s, m_peak^dp, m_peak^tp (Sec. 4.2, Sec. 5) and m_peak^{dp+tp} = m_peak^dp -
+ * m_p16 * tp_n / gpu_n + m_back^tp (Sec. 5, "Combination of DP+TP"), where m_peak^dp is taken
+ * over all gpu_n = cfg.d GPUs, the division is the same ceiling-then-block rule as everywhere
+ * and m_back^tp is the buffer of a tensor-parallel group of tp_n GPUs.
+ *   cfg        as for llmem_estimate; the method column is not read
+ *   tp_n       DEV, n uint8: tensor-parallel degree of the DP+TP set-up; 0 = none (that
+ *              estimate is -1); NULL = none anywhere; otherwise it must divide gpu_n
+ *              (else LLMEM_F_ERR_TP: all four estimates -1)
+ *   out_peaks  DEV, 4 * n int64
+ *   out_flags  DEV, n int64 of LLMEM_F_* bits, or NULL
+ * The closed forms only: no timeline is walked.                                           */
+int llmem_estimate_methods(const llmem_configs *cfg, const uint8_t *tp_n, int64_t n,
+                           const llmem_tables *method_tables, int64_t *out_peaks, int64_t *out_flags,
+                           void *hip_stream);
+
+/* Decision columns: out_detail of llmem_decide is DEV, LLMEM_NDECIDE columns of n int64 each
+ * (column c of query i at out_detail[c * n + i]).  Scores are stored doubled so that CDP's
+ * factor 1.5 stays an integer.                                                            */
+enum llmem_decision {
+    LLMEM_C_METHOD = 0,     /* LLMEM_METHOD_* chosen (0..4); -1 for an invalid query        */
+    LLMEM_C_BS,             /* its batch size (0 with LLMEM_METHOD_OFFLOAD)                 */
+    LLMEM_C_BS_CDP, LLMEM_C_BS_ADP, LLMEM_C_BS_TP, LLMEM_C_BS_HYBRID,     /* bs_list       */
+    LLMEM_C_SCORE2_CDP, LLMEM_C_SCORE2_ADP, LLMEM_C_SCORE2_TP, LLMEM_C_SCORE2_HYBRID, /* 2 * eval */
+    LLMEM_C_PEAK,           /* the chosen method's estimate at the chosen batch size        */
+    LLMEM_C_FLAGS,          /* LLMEM_F_* bits                                               */
+    LLMEM_NDECIDE
+};
+
+/* Algorithm 1 (Sec. 6) for n queries (model, gpu_n, sl): for CDP, ADP (ZeRO-3), TP and DP+TP
+ * the largest batch size whose estimate does not exceed m_total; eval = bs * gpu_n * 1.5,
+ * bs * gpu_n, bs, bs * dp_n (dp_n = gpu_n / tp_n); the first highest score wins (ties in the
+ * order CDP, ADP, TP, DP+TP) unless the TP score is 0, which selects LLMEM_METHOD_OFFLOAD with
+ * batch size 0.  A method that does not fit even at bs = 1 has batch size and score 0.  The
+ * batch sizes are found by bisection, which equals the algorithm's one-by-one search because
+ * the estimates never decrease with bs.
+ *   queries    configurations whose bs column holds the largest batch size to consider and
+ *              whose method column is not read; d = gpu_n
+ *   tp_n       as for llmem_estimate_methods; 0 / NULL: DP+TP takes no part (score 0)
+ *   m_total    GPU memory capacity in bytes
+ *   out_method DEV, n int32 (LLMEM_C_METHOD), out_bs DEV, n int32 (LLMEM_C_BS); either may
+ *              be NULL when out_detail is given
+ *   out_detail DEV, LLMEM_NDECIDE * n int64, or NULL
+ * Invalid queries: method -1, all other columns 0 except the flags.  LLMEM_EINVAL_TABLE also
+ * when a parameter entry's size refers to LLMEM_DIM_BS.  Intermediate values at the largest
+ * batch size considered must fit int64.                                                   */
+int llmem_decide(const llmem_configs *queries, const uint8_t *tp_n, int64_t n,
+                 const llmem_tables *method_tables, int64_t m_total, int32_t *out_method,
+                 int32_t *out_bs, int64_t *out_detail, void *hip_stream);
 
 /* Peaks of explicit allocator timelines (Sec. 2.1 / Sec. 3.1: sequential
  * traversal with live tensors, sizes rounded to 512-byte blocks).
@@ -248,6 +309,13 @@ int llmem_timeline_peaks(const int64_t *events, const int64_t *offsets, int64_t 
  * first .. first+n-1 (grid 1: first + n <= 432, else LLMEM_EINVAL_ARG).       */
 int llmem_grid_generate(int grid_id, uint64_t seed, int64_t first, int64_t n,
                         const llmem_configs *cfg_out, void *hip_stream);
+
+/* Queries first .. first+n-1 of the decision grid: the model shapes and sequence lengths of
+ * grid 4, gpu_n in {1, 2, 4, 8, 16} in column d, tp_n = 2^j with j uniform in [0, log2 gpu_n]
+ * in tp_n_out (DEV, n uint8), LLMEM_QUERY_BS_CAP in column bs.                            */
+#define LLMEM_QUERY_BS_CAP 4096
+int llmem_queries_generate(uint64_t seed, int64_t first, int64_t n, const llmem_configs *cfg_out,
+                           uint8_t *tp_n_out, void *hip_stream);
 
 /* Event lists of configurations first .. first+n-1 of the explicit-timeline
  * grid.  Two steps, both asynchronous: llmem_events_count writes the n list

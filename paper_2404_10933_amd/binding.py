@@ -23,6 +23,11 @@ NDETAIL = 12
 DETAIL_COLUMNS = ("m_peak", "param_bytes_gpu", "grad_bytes_gpu", "os_bytes_gpu", "m_out", "m_lm",
                   "m_back", "k_chosen", "peak_live", "n_params", "t_max", "flags")
 
+NDECIDE = 12
+DECISION_COLUMNS = ("method", "bs", "bs_cdp", "bs_adp", "bs_tp", "bs_hybrid", "score2_cdp", "score2_adp",
+                    "score2_tp", "score2_hybrid", "m_peak", "flags")
+METHOD_CDP, METHOD_ZERO3, METHOD_TP, METHOD_HYBRID, METHOD_OFFLOAD = range(5)
+
 # column name -> (numpy dtype, torch dtype); order = struct llmem_configs
 CONFIG_COLUMNS = (
     ("arch_id", np.uint8, torch.uint8), ("h", np.uint32, torch.uint32), ("L", np.uint16, torch.uint16),
@@ -91,8 +96,12 @@ def load_library():
     lib.llmem_grid_generate.argtypes = [ci, u64, i64, i64, ctypes.POINTER(_Configs), vp]
     lib.llmem_events_count.argtypes = [u64, i64, i64, vp, vp]
     lib.llmem_events_generate.argtypes = [u64, i64, i64, vp, vp, vp]
+    lib.llmem_estimate_methods.argtypes = [ctypes.POINTER(_Configs), vp, i64, ctypes.POINTER(_Tables), vp, vp, vp]
+    lib.llmem_decide.argtypes = [ctypes.POINTER(_Configs), vp, i64, ctypes.POINTER(_Tables), i64, vp, vp, vp, vp]
+    lib.llmem_queries_generate.argtypes = [u64, i64, i64, ctypes.POINTER(_Configs), vp, vp]
     for f in (lib.llmem_estimate, lib.llmem_estimate_ex, lib.llmem_timeline_peaks, lib.llmem_grid_generate,
-              lib.llmem_events_count, lib.llmem_events_generate, lib.llmem_abi_version):
+              lib.llmem_events_count, lib.llmem_events_generate, lib.llmem_abi_version,
+              lib.llmem_estimate_methods, lib.llmem_decide, lib.llmem_queries_generate):
         f.restype = ci
     lib.llmem_config_bytes.argtypes = [i64]
     lib.llmem_config_bytes.restype = ctypes.c_size_t
@@ -227,6 +236,51 @@ def llmem_estimate_ex(cfg: DeviceConfigs, tables: Tables, out_peaks: Optional[to
         raise ValueError("out_detail: need contiguous int64 of NDETAIL * n values")
     _check(load_library().llmem_estimate_ex(ctypes.byref(cfg.struct), n, ctypes.byref(tables.struct),
                                             _ptr(out_peaks), _ptr(out_detail), _stream_handle(stream)))
+
+
+def _check_tp(tp_n: Optional[torch.Tensor], n: int):
+    if tp_n is not None and (tp_n.dtype != torch.uint8 or tp_n.numel() < n or not tp_n.is_contiguous()):
+        raise ValueError("tp_n: need contiguous uint8 of n values")
+
+
+def llmem_estimate_methods(cfg: DeviceConfigs, tp_n: Optional[torch.Tensor], tables: Tables,
+                           out_peaks: torch.Tensor, out_flags: Optional[torch.Tensor] = None, stream=None,
+                           n: Optional[int] = None) -> None:
+    """out_peaks: int64 tensor of shape (4, n); out_flags: int64 of n values or None."""
+    n = cfg.n if n is None else n
+    _check_tp(tp_n, n)
+    if out_peaks.dtype != torch.int64 or out_peaks.numel() < 4 * n or not out_peaks.is_contiguous():
+        raise ValueError("out_peaks: need contiguous int64 of 4 * n values")
+    if out_flags is not None and (out_flags.dtype != torch.int64 or out_flags.numel() < n):
+        raise ValueError("out_flags: need int64 of n values")
+    _check(load_library().llmem_estimate_methods(ctypes.byref(cfg.struct), _ptr(tp_n), n, ctypes.byref(tables.struct),
+                                                 _ptr(out_peaks), _ptr(out_flags), _stream_handle(stream)))
+
+
+def llmem_decide(queries: DeviceConfigs, tp_n: Optional[torch.Tensor], tables: Tables, m_total: int,
+                 out_method: Optional[torch.Tensor], out_bs: Optional[torch.Tensor],
+                 out_detail: Optional[torch.Tensor] = None, stream=None, n: Optional[int] = None) -> None:
+    """out_method, out_bs: int32 of n values; out_detail: int64 of shape (NDECIDE, n) or None."""
+    n = queries.n if n is None else n
+    _check_tp(tp_n, n)
+    for t in (out_method, out_bs):
+        if t is not None and (t.dtype != torch.int32 or t.numel() < n or not t.is_contiguous()):
+            raise ValueError("out_method / out_bs: need contiguous int32 of n values")
+    if out_detail is not None and (out_detail.dtype != torch.int64 or out_detail.numel() < NDECIDE * n
+                                   or not out_detail.is_contiguous()):
+        raise ValueError("out_detail: need contiguous int64 of NDECIDE * n values")
+    _check(load_library().llmem_decide(ctypes.byref(queries.struct), _ptr(tp_n), n, ctypes.byref(tables.struct),
+                                       int(m_total), _ptr(out_method), _ptr(out_bs), _ptr(out_detail),
+                                       _stream_handle(stream)))
+
+
+def llmem_queries_generate(seed: int, first: int, n: int, cfg_out: DeviceConfigs, tp_n_out: torch.Tensor,
+                           stream=None) -> None:
+    if cfg_out.n < n:
+        raise ValueError("cfg_out too small")
+    _check_tp(tp_n_out, n)
+    _check(load_library().llmem_queries_generate(seed, first, n, ctypes.byref(cfg_out.struct), _ptr(tp_n_out),
+                                                 _stream_handle(stream)))
 
 
 def llmem_timeline_peaks(events: torch.Tensor, offsets: torch.Tensor, out_allocated: torch.Tensor,

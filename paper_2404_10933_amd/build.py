@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libllmem.so")
-SOURCES = ("estimate.hip", "estimate_batch.hip", "timeline.hip", "generate.hip")
+SOURCES = ("estimate.hip", "estimate_batch.hip", "decide.hip", "timeline.hip", "generate.hip")
 HIPCC_FLAGS = ("--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops")
 

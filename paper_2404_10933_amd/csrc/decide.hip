@@ -1,0 +1,336 @@
+// Estimates of all four fine-tuning methods and the method decision, one lane
+// per query.
+//
+// A query is a model shape with gpu_n and sl.  What does not depend on the batch
+// size is computed once per query: the parameter census (embed_p, lm_p, other_p,
+// the largest tensor, m_os tensor by tensor), the chunk size, m_p / m_p16 / m_p32,
+// the sharded model states of ZeRO-3 and TP, the share of param fp16 that DP+TP
+// removes.  What grows with bs is a handful of products with per-query factors:
+//   m_out(bs) = up(bs * (e_n + L) * sl * h * 2),  logits up(bs * V * B * sl) and
+//   2 * up(bs * V * B * (sl - 1)),  m_back^tp(bs; t) = ceil(L * bs * sl * h * (t-1) * 2
+//   / (t * cu_p)) * cu_p.
+// llmem_estimate_methods evaluates the four estimates at the query's own bs.
+// llmem_decide finds, per method, the largest bs whose estimate does not exceed
+// m_total by building it bit by bit from the top (the estimates never decrease
+// with bs, so this is the batch size Algorithm 1 reaches by adding one at a time),
+// then scores and chooses.
+//
+// Closed forms: Sec. 4.2 and Sec. 5 of arXiv 2404.10933 (incl. the DP+TP equation);
+// chunk size: Sec. 4.1; decision: Sec. 6, Algorithm 1.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/llmem.h"
+#include "estimate_args.h"
+#include "wave.h"
+
+namespace llmem {
+
+void set_hip_error(hipError_t e);
+
+namespace {
+
+constexpr int DC_WAVES = 4;
+constexpr int DC_BLOCK = 64 * DC_WAVES;
+
+struct DecideArgs {
+    llmem_configs cfg;
+    const uint8_t *tp_n;             // may be null: no DP+TP set-up anywhere
+    long long n;
+    long long m_base, m_total;
+    int cu_shift, align_shift, n_arch;
+    int param_first[LLMEM_MAX_ARCH], n_param[LLMEM_MAX_ARCH];
+    const uint4 *params_dev;
+    long long *out_peaks, *out_flags;          // estimate_methods
+    int *out_method, *out_bs;                  // decide
+    long long *out_detail;
+};
+
+__device__ __forceinline__ u64 d_div(u64 x, u32 d, DivMagic m) { return d == 1 ? x : (__umul64hi(x, m.mul) >> m.shift); }
+__device__ __forceinline__ u64 d_cdiv(u64 x, u32 d, DivMagic m) { return d_div(x + (d - 1), d, m); }
+__device__ __forceinline__ u64 d_up(u64 x, int shift) { return ((x + ((1ull << shift) - 1)) >> shift) << shift; }
+__device__ __forceinline__ u32 d_uni(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
+
+// what a query needs to evaluate any method at any batch size
+struct QueryTerms {
+    u64 fixed[4];        // batch-independent part of m_peak^s, m_peak^dp, m_peak^tp, m_peak^{dp+tp}
+    u64 c_out;           // (e_n + L) * sl * h * B16
+    u64 c_logits, c_shifted;   // V * B * sl,  V * B * max(sl - 1, 0)
+    u64 c_back_tp, c_back_hy;  // L * sl * h * (t - 1) * B16 for t = gpu_n and t = tp_n
+    u32 gpu_n, tp_n;
+    DivMagic div_g, div_t;
+    int cu_shift;
+};
+
+__device__ __forceinline__ u64 pages_over(u64 bytes, u32 t, DivMagic m, int cu_shift)
+{
+    const u64 pages = (bytes + ((1ull << cu_shift) - 1)) >> cu_shift;
+    return d_cdiv(pages, t, m) << cu_shift;             // ceil(bytes / (t * cu_p)) * cu_p
+}
+
+// m_peak of method m (0..3) at batch size bs
+__device__ __forceinline__ i64 peak_at(const QueryTerms &q, int m, u32 bs)
+{
+    const u64 b = bs;
+    u64 x = q.fixed[m] + d_up(b * q.c_out, q.cu_shift) + d_up(b * q.c_logits, q.cu_shift)
+            + 2 * d_up(b * q.c_shifted, q.cu_shift);
+    if (m == LLMEM_METHOD_TP) x += pages_over(b * q.c_back_tp, q.gpu_n, q.div_g, q.cu_shift);
+    if (m == LLMEM_METHOD_HYBRID) x += pages_over(b * q.c_back_hy, q.tp_n, q.div_t, q.cu_shift);
+    return (i64)x;
+}
+
+template <bool DECIDE>
+__global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
+{
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const long long n = a.n;
+    const long long n_batch = (n + 63) >> 6;
+    const int cu_shift = a.cu_shift, align_shift = a.align_shift;
+
+    for (long long b = (long long)blockIdx.x * DC_WAVES + wave; b < n_batch; b += (long long)gridDim.x * DC_WAVES) {
+        const long long i = (b << 6) + lane;
+        const bool in_range = i < n;
+        u32 h = 1, ffn = 0, V = 0, P = 0, arch_id = 0, g = 1, cflags = 0, L = 0, n_heads = 1, n_kv = 0, bs = 0,
+            sl = 0, tp = 0;
+        int chunk_k = 0;
+        if (in_range) {
+            h = a.cfg.h[i]; ffn = a.cfg.ffn[i]; V = a.cfg.V[i]; P = a.cfg.P[i];
+            arch_id = a.cfg.arch_id[i]; g = a.cfg.d[i]; cflags = a.cfg.flags[i];
+            L = a.cfg.L[i]; n_heads = a.cfg.n_heads[i]; n_kv = a.cfg.n_kv[i];
+            chunk_k = a.cfg.chunk_k[i]; bs = a.cfg.bs[i]; sl = a.cfg.sl[i];
+            if (a.tp_n) tp = a.tp_n[i];
+        }
+        u32 err = 0;
+        if (arch_id >= (u32)a.n_arch) err |= LLMEM_F_ERR_ARCH;
+        if (g == 0) err |= LLMEM_F_ERR_D;
+        if (n_heads == 0) err |= LLMEM_F_ERR_HEADS;
+        if (!(chunk_k == -1 || (chunk_k >= 0 && chunk_k <= K_FIXED_MAX))) err |= LLMEM_F_ERR_CHUNK;
+        const DivMagic div_g = c_div.t[g & 255u], div_t = c_div.t[tp & 255u];
+        if (tp > 0 && g > 0 && g - (u32)d_div(g, tp, div_t) * tp != 0) err |= LLMEM_F_ERR_TP;
+        const bool valid = in_range && err == 0;
+
+        const u32 head_dim = h / (n_heads ? n_heads : 1u);
+        u32 D[16];
+        D[LLMEM_DIM_ONE] = 1; D[LLMEM_DIM_BS] = bs; D[LLMEM_DIM_SL] = sl; D[LLMEM_DIM_SL_M1] = sl ? sl - 1 : 0;
+        D[LLMEM_DIM_H] = h; D[LLMEM_DIM_FFN] = ffn; D[LLMEM_DIM_N_HEADS] = n_heads; D[LLMEM_DIM_N_KV] = n_kv;
+        D[LLMEM_DIM_HEAD_DIM] = head_dim; D[LLMEM_DIM_KV_DIM] = n_kv * head_dim; D[LLMEM_DIM_V] = V;
+        D[LLMEM_DIM_P] = P; D[LLMEM_DIM_L] = L;
+        const u32 Blog = (cflags & LLMEM_CFG_LOGITS_FP32) ? B32 : B16;
+        D[LLMEM_DIM_B_LOGITS] = Blog; D[LLMEM_DIM_D] = g; D[15] = 0;
+
+        // ---- parameter table (Notation table; Sec. 4.2, equation for m_os), architecture by architecture
+        u64 embed_p = 0, lm_p = 0, other_p = 0, t_max = 0, m_os = 0;
+        u32 e_n = 0;
+        unsigned long long todo = __builtin_amdgcn_ballot_w64(valid);
+        while (todo) {
+            const int first = __builtin_ctzll(todo);
+            const u32 ar = read_lane(arch_id, first);
+            const bool mine = valid && arch_id == ar;
+            todo &= ~__builtin_amdgcn_ballot_w64(mine);
+            if (!mine) continue;
+            const int n_param = (int)d_uni((u32)a.n_param[ar]), param_first = (int)d_uni((u32)a.param_first[ar]);
+            for (int j = 0; j < n_param; ++j) {
+                const uint4 pe = a.params_dev[param_first + j];               // wave-uniform
+                const u32 cls = pe.z & 255u, role = (pe.z >> 8) & 255u, per_layer = (pe.z >> 16) & 255u;
+                u64 t_p = (u64)pe.x * D[pe.y & 15u];
+                t_p *= D[(pe.y >> 8) & 15u];
+                t_p *= D[(pe.y >> 16) & 15u];
+                t_p *= D[(pe.y >> 24) & 15u];
+                const u64 copies = per_layer ? (u64)L : 1ull;
+                const u64 tot = t_p * copies;
+                if (role == LLMEM_ROLE_EMBED_TOK) embed_p += tot;
+                else if (role == LLMEM_ROLE_LM_HEAD) lm_p += tot;
+                else { other_p += tot; t_max = t_p > t_max ? t_p : t_max; }
+                if (cls <= LLMEM_CLS_LINEAR && role != LLMEM_ROLE_LM_HEAD)
+                    m_os += d_up(t_p * (u64)(B32 + B32), cu_shift) * copies;
+                if (cls == LLMEM_CLS_EMBEDDING && role != LLMEM_ROLE_LM_HEAD) ++e_n;
+            }
+        }
+
+        // ---- chunk size (Sec. 4.1): given, or the feasible candidate with the least padding waste
+        int k_used = chunk_k;
+        if (chunk_k == -1) {
+            u64 best_waste = ~0ull;
+            k_used = K_SEARCH_MAX;
+            for (int k = K_SEARCH_MIN; k <= K_SEARCH_MAX; ++k) {
+                const u64 cs_mask = (1ull << (k + 19)) - 1;
+                const u64 waste = ((other_p + cs_mask) & ~cs_mask) - other_p;
+                if (t_max <= cs_mask + 1 && waste < best_waste) { best_waste = waste; k_used = k; }
+            }
+        }
+        k_used = (k_used < 0 || k_used > K_FIXED_MAX) ? 0 : k_used;          // invalid lanes: any defined shift
+        const u64 cs_mask = (1ull << (k_used + 19)) - 1;
+        const u64 chunked = embed_p + ((other_p + cs_mask) & ~cs_mask);
+        const u64 m_p = d_up(chunked * (B16 + B32), cu_shift);
+        const u64 m_p16 = d_up(chunked * B16, cu_shift);
+        const u64 m_p32 = d_up(chunked * B32, cu_shift);
+        u32 flags = t_max > cs_mask + 1 ? LLMEM_F_CHUNK_INFEASIBLE : 0;
+
+        // ---- Sec. 4.1: gradients alias param fp16 unless switched off
+        u64 grad_cdp = 0, grad_sharded = 0;
+        if (!(cflags & LLMEM_CFG_GRAD_ALIAS)) {
+            grad_cdp = d_up((embed_p + other_p) * B16, cu_shift);
+            grad_sharded = d_up(d_cdiv(grad_cdp, g, div_g), align_shift);
+        }
+
+        // ---- batch-independent parts (Sec. 4.2, Sec. 5)
+        QueryTerms q;
+        const u64 head = lm_p * B16;
+        q.fixed[LLMEM_METHOD_CDP] = (u64)a.m_base + m_p + m_os + head + grad_cdp;
+        q.fixed[LLMEM_METHOD_ZERO3] = (u64)a.m_base + m_p16 + d_up(d_cdiv(m_p32 + m_os, g, div_g), align_shift) + head + grad_sharded;
+        q.fixed[LLMEM_METHOD_TP] = (u64)a.m_base + d_up(d_cdiv(m_p + m_os, g, div_g), align_shift) + head + grad_sharded;
+        // DP+TP: m_peak^dp minus the share of param fp16 that tensor parallelism removes
+        const u32 tp1 = tp ? tp : 1u;
+        const u64 removed = d_up(d_cdiv(m_p16 * tp1, g, div_g), align_shift);
+        const u64 removed_other = d_up(d_cdiv(m_p16 * (tp1 - 1), tp1, div_t), align_shift);
+        q.fixed[LLMEM_METHOD_HYBRID] = q.fixed[LLMEM_METHOD_ZERO3] - removed;
+        if (tp > 0 && removed != removed_other) flags |= LLMEM_F_HYBRID_READINGS_DIFFER;
+        const u64 slh = (u64)sl * h;
+        q.c_out = ((u64)e_n + L) * slh * B16;
+        q.c_logits = (u64)V * Blog * sl;
+        q.c_shifted = (u64)V * Blog * D[LLMEM_DIM_SL_M1];
+        q.c_back_tp = (u64)L * slh * (g - 1) * B16;
+        q.c_back_hy = (u64)L * slh * (tp1 - 1) * B16;
+        q.gpu_n = g; q.tp_n = tp1; q.div_g = div_g; q.div_t = div_t; q.cu_shift = cu_shift;
+
+        if (!DECIDE) {
+            if (in_range) {
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    i64 v = peak_at(q, m, bs);
+                    if (err || (m == LLMEM_METHOD_HYBRID && tp == 0)) v = -1;
+                    a.out_peaks[(long long)m * n + i] = v;
+                }
+                if (a.out_flags) a.out_flags[i] = err ? (i64)err : (i64)flags;
+            }
+            continue;
+        }
+
+        // ---- Algorithm 1: largest batch size per method, built from the highest bit down
+        const u32 cap = valid ? bs : 0u;
+        u32 widest = cap;                                                    // wave-wide OR of the caps
+        for (int s = 32; s >= 1; s >>= 1) widest |= (u32)__shfl_xor((int)widest, s, 64);
+        const int bits = 32 - __builtin_clz(d_uni(widest) | 1u);
+        u32 best[4] = {0, 0, 0, 0};
+        for (int bit = bits - 1; bit >= 0; --bit) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const u32 cand = best[m] | (1u << bit);
+                const bool fits = cand <= cap && peak_at(q, m, cand) <= a.m_total;
+                best[m] = fits ? cand : best[m];
+            }
+        }
+        if (tp == 0) best[LLMEM_METHOD_HYBRID] = 0;
+        // scores (doubled) and the choice
+        const u32 dp_n = tp ? (u32)d_div(g, tp, div_t) : 0u;
+        i64 score2[4];
+        score2[0] = 3ll * best[0] * g; score2[1] = 2ll * best[1] * g; score2[2] = 2ll * best[2];
+        score2[3] = 2ll * best[3] * dp_n;
+        int idx = 0;
+#pragma unroll
+        for (int m = 1; m < 4; ++m) idx = score2[m] > score2[idx] ? m : idx;
+        int method = idx;
+        u32 chosen_bs = idx == 0 ? best[0] : idx == 1 ? best[1] : idx == 2 ? best[2] : best[3];
+        i64 peak = peak_at(q, 0, chosen_bs);
+        if (idx == 1) peak = peak_at(q, 1, chosen_bs);
+        if (idx == 2) peak = peak_at(q, 2, chosen_bs);
+        if (idx == 3) peak = peak_at(q, 3, chosen_bs);
+        if (score2[2] == 0) {
+            method = LLMEM_METHOD_OFFLOAD; chosen_bs = 0; peak = 0;
+            if (score2[0] | score2[1] | score2[3]) flags |= LLMEM_F_FALLBACK_READINGS_DIFFER;
+        }
+        if (in_range) {
+            const bool bad = err != 0;
+            if (a.out_method) a.out_method[i] = bad ? -1 : method;
+            if (a.out_bs) a.out_bs[i] = bad ? 0 : (int)chosen_bs;
+            if (a.out_detail) {
+                long long *o = a.out_detail + i;
+                o[LLMEM_C_METHOD * n] = bad ? -1 : method;
+                o[LLMEM_C_BS * n] = bad ? 0 : (i64)chosen_bs;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    o[(LLMEM_C_BS_CDP + m) * n] = bad ? 0 : (i64)best[m];
+                    o[(LLMEM_C_SCORE2_CDP + m) * n] = bad ? 0 : score2[m];
+                }
+                o[LLMEM_C_PEAK * n] = bad ? 0 : peak;
+                o[LLMEM_C_FLAGS * n] = bad ? (i64)err : (i64)flags;
+            }
+        }
+    }
+}
+
+int launch(bool decide, const llmem_configs *cfg, const uint8_t *tp_n, int64_t n, const llmem_tables *tables,
+           DecideArgs &a, hipStream_t stream)
+{
+    if (!cfg || !tables) return LLMEM_EINVAL_NULL;
+    if (n < 0) return LLMEM_EINVAL_N;
+    EstimateArgs plan;
+    const int rc = check_tables(tables, &plan);
+    if (rc != LLMEM_OK) return rc;
+    if (decide) {
+        // a parameter size that depends on bs would make the estimates' fixed parts vary with bs
+        for (int ar = 0; ar < tables->n_arch; ++ar)
+            for (int j = 0; j < tables->arch[ar].n_param; ++j) {
+                const llmem_param_entry &p = tables->params_host[tables->arch[ar].param_first + j];
+                for (int q = 0; q < 4; ++q) if (p.dim[q] == LLMEM_DIM_BS) return LLMEM_EINVAL_TABLE;
+            }
+    }
+    if (n == 0) return LLMEM_OK;
+    if (!cfg->arch_id || !cfg->h || !cfg->L || !cfg->n_heads || !cfg->n_kv || !cfg->ffn || !cfg->V
+        || !cfg->P || !cfg->bs || !cfg->sl || !cfg->d || !cfg->chunk_k || !cfg->flags)
+        return LLMEM_EINVAL_NULL;
+    a.cfg = *cfg;
+    a.tp_n = tp_n;
+    a.n = n;
+    a.m_base = plan.m_base;
+    a.cu_shift = plan.cu_shift;
+    a.align_shift = plan.align_shift;
+    a.n_arch = plan.n_arch;
+    for (int ar = 0; ar < LLMEM_MAX_ARCH; ++ar) {
+        a.param_first[ar] = ar < plan.n_arch ? plan.arch[ar].param_first : 0;
+        a.n_param[ar] = ar < plan.n_arch ? plan.arch[ar].n_param : 0;
+    }
+    a.params_dev = reinterpret_cast<const uint4 *>(tables->params_dev);
+    const int64_t n_batch = (n + 63) / 64;
+    int64_t blocks = (n_batch + DC_WAVES - 1) / DC_WAVES;
+    const int64_t max_blocks = 256 * 8;                 // 256 CUs, up to 8 resident workgroups each
+    if (blocks > max_blocks) blocks = max_blocks;
+    if (decide)
+        hipLaunchKernelGGL(decide_kernel<true>, dim3((unsigned)blocks), dim3(DC_BLOCK), 0, stream, a);
+    else
+        hipLaunchKernelGGL(decide_kernel<false>, dim3((unsigned)blocks), dim3(DC_BLOCK), 0, stream, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_hip_error(e); return LLMEM_EHIP; }
+    return LLMEM_OK;
+}
+
+}  // namespace
+
+}  // namespace llmem
+
+extern "C" int llmem_estimate_methods(const llmem_configs *cfg, const uint8_t *tp_n, int64_t n,
+                                      const llmem_tables *method_tables, int64_t *out_peaks, int64_t *out_flags,
+                                      void *hip_stream)
+{
+    using namespace llmem;
+    if (!out_peaks) return LLMEM_EINVAL_NULL;
+    DecideArgs a = {};
+    a.out_peaks = reinterpret_cast<long long *>(out_peaks);
+    a.out_flags = reinterpret_cast<long long *>(out_flags);
+    return launch(false, cfg, tp_n, n, method_tables, a, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int llmem_decide(const llmem_configs *queries, const uint8_t *tp_n, int64_t n,
+                            const llmem_tables *method_tables, int64_t m_total, int32_t *out_method,
+                            int32_t *out_bs, int64_t *out_detail, void *hip_stream)
+{
+    using namespace llmem;
+    if (!out_detail && (!out_method || !out_bs)) return LLMEM_EINVAL_NULL;
+    DecideArgs a = {};
+    a.m_total = m_total;
+    a.out_method = out_method;
+    a.out_bs = out_bs;
+    a.out_detail = reinterpret_cast<long long *>(out_detail);
+    return launch(true, queries, tp_n, n, method_tables, a, reinterpret_cast<hipStream_t>(hip_stream));
+}

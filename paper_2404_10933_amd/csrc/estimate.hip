@@ -584,6 +584,13 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, 
     return LLMEM_OK;
 }
 
+int check_tables(const llmem_tables *tables, EstimateArgs *out)
+{
+    memset(out, 0, sizeof(*out));
+    bool wave_ok, batch_ok, prog_ok;
+    return plan_tables(tables, out, &wave_ok, &batch_ok, &prog_ok);
+}
+
 static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tables *tables,
                            int64_t *out_peaks, int64_t *out_detail, hipStream_t stream)
 {

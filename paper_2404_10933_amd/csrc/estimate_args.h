@@ -106,6 +106,9 @@ __host__ __device__ inline ClassKey make_class_key(uint32_t x, uint32_t y, uint3
     return k;
 }
 
+// Validates the host copy of the tables exactly as the estimator does and fills the constants
+// and per-architecture ranges of `out`; LLMEM_OK or LLMEM_EINVAL_*.
+int check_tables(const llmem_tables *tables, EstimateArgs *out);
 size_t batch_kernel_lds_bytes(const EstimateArgs &a);
 void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream);
 

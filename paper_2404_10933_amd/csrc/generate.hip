@@ -33,15 +33,17 @@ __host__ __device__ inline u64 mix64(u64 seed, u64 index, u64 field)
 }
 
 // hash field ids of the configuration grids
-enum { F_H, F_L, F_V, F_BS, F_SL, F_METHOD, F_D, F_K, F_NKV };
+enum { F_H, F_L, F_V, F_BS, F_SL, F_METHOD, F_D, F_K, F_NKV, F_TP };
 
 __device__ inline u64 uniform(u64 seed, u64 i, int field, u64 lo, u64 hi)
 {
     return lo + mix64(seed, i, (u64)field) % (hi - lo + 1);
 }
 
+// grid_id 6: the queries of the method decision (grid 4's shapes; gpu_n, the batch-size cap and
+// tp_n instead of d, bs and method); tp_out is only written for that grid
 __global__ __launch_bounds__(256) void grid_kernel(int grid_id, u64 seed, long long first, long long n,
-                                                   llmem_configs c)
+                                                   llmem_configs c, uint8_t *tp_out)
 {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= n) return;
@@ -88,8 +90,14 @@ __global__ __launch_bounds__(256) void grid_kernel(int grid_id, u64 seed, long l
         sl = sls[mix64(seed, i, F_SL) % 5];
         method = (unsigned)uniform(seed, i, F_METHOD, 0, 2);
         d = (unsigned)uniform(seed, i, F_D, 1, 16);
-        k = grid_id == 4 ? LLMEM_CHUNK_SEARCH : (int)uniform(seed, i, F_K, 4, 8);
+        k = grid_id >= 4 ? LLMEM_CHUNK_SEARCH : (int)uniform(seed, i, F_K, 4, 8);
         flags = LLMEM_CFG_LOGITS_FP32 | LLMEM_CFG_GRAD_ALIAS;
+        if (grid_id == 6) {
+            const unsigned log_g = (unsigned)(mix64(seed, i, F_D) % 5);
+            const unsigned log_t = (unsigned)(mix64(seed, i, F_TP) % (log_g + 1));
+            d = 1u << log_g; bs = LLMEM_QUERY_BS_CAP; method = 0;
+            tp_out[t] = (uint8_t)(1u << log_t);
+        }
     }
     c.arch_id[t] = (uint8_t)arch; c.h[t] = h; c.L[t] = (uint16_t)L; c.n_heads[t] = (uint16_t)n_heads;
     c.n_kv[t] = (uint16_t)n_kv; c.ffn[t] = ffn; c.V[t] = V; c.P[t] = P; c.bs[t] = (uint16_t)bs;
@@ -187,7 +195,22 @@ extern "C" int llmem_grid_generate(int grid_id, uint64_t seed, int64_t first, in
         || !c->sl || !c->method || !c->d || !c->chunk_k || !c->flags) return LLMEM_EINVAL_NULL;
     const unsigned blocks = (unsigned)((n + 255) / 256);
     hipLaunchKernelGGL(grid_kernel, dim3(blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream),
-                       grid_id, (u64)seed, (long long)first, (long long)n, *c);
+                       grid_id, (u64)seed, (long long)first, (long long)n, *c, (uint8_t *)nullptr);
+    return check_launch();
+}
+
+extern "C" int llmem_queries_generate(uint64_t seed, int64_t first, int64_t n, const llmem_configs *c,
+                                      uint8_t *tp_n_out, void *hip_stream)
+{
+    using namespace llmem;
+    if (!c) return LLMEM_EINVAL_NULL;
+    if (n < 0 || first < 0) return LLMEM_EINVAL_N;
+    if (n == 0) return LLMEM_OK;
+    if (!tp_n_out || !c->arch_id || !c->h || !c->L || !c->n_heads || !c->n_kv || !c->ffn || !c->V || !c->P
+        || !c->bs || !c->sl || !c->method || !c->d || !c->chunk_k || !c->flags) return LLMEM_EINVAL_NULL;
+    const unsigned blocks = (unsigned)((n + 255) / 256);
+    hipLaunchKernelGGL(grid_kernel, dim3(blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream),
+                       6, (u64)seed, (long long)first, (long long)n, *c, tp_n_out);
     return check_launch();
 }
 

@@ -37,3 +37,33 @@ def assert_same(name, got, want):
         bad = np.argwhere(got != want)
         i = tuple(bad[0])
         raise AssertionError(f"{name}: {len(bad)} mismatches, first at {i}: got {got[i]} want {want[i]}")
+
+
+def _tp_tensor(tp_np):
+    return None if tp_np is None else torch.from_numpy(np.ascontiguousarray(tp_np, dtype=np.uint8)).cuda()
+
+
+def hip_methods(cfg_np, tp_np, tables, const, flags=True, stream=None):
+    """Returns (peaks[n, 4], flags[n] or None): the four methods' estimates by the HIP kernel."""
+    dev = M.DeviceConfigs.from_numpy(cfg_np)
+    tab = M.Tables(tables, m_base=const.m_base, cu_p=const.cu_p, align=const.align)
+    n = dev.n
+    peaks = torch.full((4, max(n, 1)), -7, dtype=torch.int64, device="cuda")
+    fl = torch.full((max(n, 1),), -7, dtype=torch.int64, device="cuda") if flags else None
+    M.llmem_estimate_methods(dev, _tp_tensor(tp_np), tab, peaks, fl, stream=stream, n=n)
+    torch.cuda.synchronize()
+    return peaks.cpu().numpy()[:, :n].T.copy(), (fl.cpu().numpy()[:n] if flags else None)
+
+
+def hip_decide(cfg_np, tp_np, tables, const, m_total, detail=True, short=True, stream=None):
+    """Returns (method[n], bs[n], rows[n, 12] or None): Algorithm 1 by the HIP kernel."""
+    dev = M.DeviceConfigs.from_numpy(cfg_np)
+    tab = M.Tables(tables, m_base=const.m_base, cu_p=const.cu_p, align=const.align)
+    n = dev.n
+    method = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda") if short else None
+    bs = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda") if short else None
+    det = torch.full((M.NDECIDE, max(n, 1)), -7, dtype=torch.int64, device="cuda") if detail else None
+    M.llmem_decide(dev, _tp_tensor(tp_np), tab, m_total, method, bs, det, stream=stream, n=n)
+    torch.cuda.synchronize()
+    return (method.cpu().numpy()[:n] if short else None, bs.cpu().numpy()[:n] if short else None,
+            det.cpu().numpy()[:, :n].T.copy() if detail else None)

@@ -27,14 +27,15 @@ def test_exports_every_declared_symbol(lib):
     names = set(re.findall(r"\b(llmem_[a-z_]+)\s*\(", header))
     assert {"llmem_estimate", "llmem_estimate_ex", "llmem_timeline_peaks", "llmem_grid_generate",
             "llmem_events_count", "llmem_events_generate", "llmem_config_bytes", "llmem_events_bytes",
-            "llmem_strerror", "llmem_abi_version", "llmem_selftest_divide"} <= names
+            "llmem_strerror", "llmem_abi_version", "llmem_selftest_divide", "llmem_kernel_forms",
+            "llmem_estimate_methods", "llmem_decide", "llmem_queries_generate"} <= names
     for n in names:
         assert hasattr(lib, n), n
 
 
 def test_abi_and_sizes(lib):
     import paper_2404_10933_amd as M
-    assert M.llmem_abi_version() == 1
+    assert M.llmem_abi_version() == 2
     assert M.llmem_config_bytes(10) == 10 * 31 and M.llmem_config_bytes(-1) == 0
     assert M.llmem_events_bytes(2) == 2 * 6 * 3450 * 8
     assert "NULL" in M.llmem_strerror(-1) and "unknown" in M.llmem_strerror(-99)
@@ -120,6 +121,28 @@ def test_argument_validation_without_gpu(lib):
     assert lib.llmem_grid_generate(2, 0, 0, 4, ctypes.byref(cfg), None) == -1
     assert lib.llmem_events_count(0, 0, 4, None, None) == -1
     assert lib.llmem_events_generate(0, 0, 4, None, None, None) == -1
+
+    # estimates of all methods and the method decision: same table checks, own argument checks
+    em, dec = lib.llmem_estimate_methods, lib.llmem_decide
+    c, t_ok = ctypes.byref(cfg), ctypes.byref(ok)
+    assert em(c, None, 0, t_ok, out, None, None) == 0 and dec(c, None, 0, t_ok, 1 << 30, out, out, None, None) == 0
+    assert em(c, None, 0, t_ok, None, None, None) == -1                               # no output
+    assert dec(c, None, 0, t_ok, 1 << 30, out, None, None, None) == -1                # method without bs, no detail
+    assert dec(c, None, 0, t_ok, 1 << 30, None, None, out, None) == 0                 # detail alone is enough
+    assert em(c, None, -1, t_ok, out, None, None) == -2 and dec(c, None, -1, t_ok, 0, out, out, None, None) == -2
+    assert em(None, None, 0, t_ok, out, None, None) == -1 and dec(c, None, 0, None, 0, out, out, None, None) == -1
+    assert em(c, None, 3, t_ok, out, None, None) == -1 and dec(c, None, 3, t_ok, 0, out, out, None, None) == -1
+    t_bad = _host_tables(Bd, params, events, cu_p=3 << 20)
+    assert em(c, None, 0, ctypes.byref(t_bad), out, None, None) == -3
+    assert dec(c, None, 0, ctypes.byref(t_bad), 0, out, out, None, None) == -3
+    p_bs = params.copy()
+    p_bs["dim"][1, 2] = 1                                                              # LLMEM_DIM_BS in a parameter size
+    t_bs = _host_tables(Bd, p_bs, events)
+    assert em(c, None, 0, ctypes.byref(t_bs), out, None, None) == 0
+    assert dec(c, None, 0, ctypes.byref(t_bs), 0, out, out, None, None) == -3
+    qg = lib.llmem_queries_generate
+    assert qg(0, 0, 0, c, None, None) == 0 and qg(0, 0, -1, c, None, None) == -2 and qg(0, -1, 1, c, None, None) == -2
+    assert qg(0, 0, 4, c, None, None) == -1 and qg(0, 0, 4, None, out, None) == -1
 
 
 def test_table_packing_layout():
