@@ -25,6 +25,7 @@ PEAK_HBM_GBS = 8000.0
 # plain-copy reference; None while the kernel has changed since the counters were taken
 TRAFFIC_ESTIMATE = 1.3502e9     # 10^7 configurations, all detail columns
 TRAFFIC_TIMELINE = 8.0201e9     # 100 000 event lists, 1 000 110 810 events
+TRAFFIC_DECIDE = 5.4014e8       # 4 000 000 queries, all decision columns
 
 
 def algorithmic_lane_ops(forms, n_candidates):
@@ -46,6 +47,23 @@ def algorithmic_lane_ops(forms, n_candidates):
             + forms["peak_points"] * per_point + fixed + n_candidates * per_candidate + tail)
 
 
+def algorithmic_lane_ops_decide(n_param_entries, cap_bits):
+    """The method decision of one query in the same units: parameter census entry by entry, the
+    chunk-size candidates (waste and feasibility only), the batch-independent parts of the four
+    estimates, then per method one estimate of the batch-dependent terms per bit of the largest
+    batch size considered (bisection: the leanest known search, the estimates being monotone),
+    scores, choice and the chosen estimate."""
+    ADD, MUL32, MUL, UP, MAX, DIV = 1, 1, 3, 3, 3, 12
+    per_entry = MUL32 + MUL + (MUL32 + MUL + ADD) + (ADD + UP + MUL32 + MUL + ADD) + MAX
+    per_candidate = UP + ADD + MAX
+    fixed = 3 * (MUL + UP) + 2 * (DIV + UP) + 2 * (MUL + DIV + UP) + 12 * ADD + 5 * MUL
+    probe_plain = 3 * (MUL + UP) + 4 * ADD + MAX                 # m_out, logits, shifted logits; compare, keep
+    probe_gather = probe_plain + MUL + UP + DIV + ADD            # plus the all-gather buffer
+    tail = 4 * MUL32 + 3 * MAX + probe_gather + 4 * ADD
+    return (n_param_entries * per_entry + 9 * per_candidate + fixed
+            + cap_bits * (2 * probe_plain + 2 * probe_gather) + tail)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,6 +71,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--n", type=int, default=10_000_000, help="configurations per step (default: the 10^7 grid)")
     ap.add_argument("--lists", type=int, default=100_000, help="event lists of the explicit-timeline grid (0: skip)")
+    ap.add_argument("--queries", type=int, default=4_000_000, help="queries of the method-decision grid (0: skip)")
     ap.add_argument("--cpu-sample", type=int, default=600_000, help="configurations the CPU oracle is timed on (0: skip)")
     ap.add_argument("--kernel", choices=("auto", "wave", "lane"), default="auto",
                     help="estimator kernel: one wavefront or one lane per configuration (auto: the library chooses)")
@@ -174,6 +193,48 @@ def main():
         wa, wr = B.event_lists_peaks(ev_c, off_c)
         assert (oa[:64].cpu().numpy() == wa).all() and (orv[:64].cpu().numpy() == wr).all()
         del events
+
+    if args.queries > 0:
+        nq, m_total = args.queries, 80 << 30
+        del peaks, detail
+        qdev = M.DeviceConfigs.empty(nq)
+        tp = torch.empty(nq, dtype=torch.uint8, device="cuda")
+        M.llmem_queries_generate(0, 0, nq, qdev, tp)
+        qtab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align)
+        q_method = torch.empty(nq, dtype=torch.int32, device="cuda")
+        q_bs = torch.empty(nq, dtype=torch.int32, device="cuda")
+        q_det = torch.empty((M.NDECIDE, nq), dtype=torch.int64, device="cuda")
+        for _ in range(2):
+            M.llmem_decide(qdev, tp, qtab, m_total, q_method, q_bs, q_det)
+        torch.cuda.synchronize()
+        reps = 10
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            M.llmem_decide(qdev, tp, qtab, m_total, q_method, q_bs, q_det)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        q_ops = algorithmic_lane_ops_decide(len(table.params), G.QUERY_BS_CAP.bit_length())
+        q_achieved = q_ops * nq / (ms * 1e-3) / 1e12
+        ns = min(2000, nq)
+        qs, qs_tp = G.grid6(n=ns, seed=0)
+        t1 = time.perf_counter()
+        want = B.decide(qs, qs_tp, [table], const, m_total, threads=1)
+        dt = time.perf_counter() - t1
+        assert (q_det[:, :ns].cpu().numpy().T == want).all(), "decisions differ from the oracle"
+        result.setdefault("extra", {})["g6_method_decision"] = {
+            "workload": "g6: Algorithm 1 per query (Llama-style model, gpu_n, sl; batch sizes up to 4096; "
+                        "m_total 80 GiB), method + bs + all decision columns",
+            "n_queries": nq, "ms_per_launch": ms, "queries_per_s": nq / (ms * 1e-3),
+            "roofline": {"bound": "alu", "achieved": q_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
+                         "frac": q_achieved / PEAK_LANE_TOPS,
+                         "traffic": TRAFFIC_DECIDE if nq == 4_000_000 else None, "kernel": "decide_kernel<true>",
+                         "algorithmic_lane_ops_per_query": q_ops},
+            "cpu_oracle": {"value": ns / dt, "unit": "queries/s", "cores": 1,
+                           "sample": f"first {ns} queries, C oracle (one-by-one search), {dt:.1f} s"},
+            "verified_vs_oracle": ns}
 
     if args.cpu_sample > 0:
         ns = min(args.cpu_sample, n)
