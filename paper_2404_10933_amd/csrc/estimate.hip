@@ -404,6 +404,7 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
     if (nc > CLS_MAX || groups.size() > 255 || e_n > 255) return false;
     al->prog_first = (int)prog->size();
     prog->push_back((uint32_t)groups.size() | (e_n << 8) | ((uint32_t)nc << 16));
+    for (int q = 1; q < PROG_HEADER; ++q) prog->push_back(0u);     // segment boundaries, filled in below
     for (const Group &g : groups) {
         prog->push_back(g.coef);
         prog->push_back(descriptor_of(g.dims));
@@ -451,6 +452,7 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
                         | ((flags & LLMEM_EV_TIMES_L) ? DESC_TIMES_L : 0u) | (mask << DESC_MASK_SHIFT)
                         | ((uint32_t)neg_slot[c] << DESC_NEG_SLOT_SHIFT));
     }
+    for (int c = nc; c % PROG_CLASS_FETCH; ++c) { prog->push_back(0u); prog->push_back(0u); }   // empty classes
     for (int s = 0; s < LLMEM_NSEG; ++s) {
         al->prog_seg[s] = (int)prog->size();
         for (size_t j = 0; j < seg_sums[s].size(); ++j) {
@@ -471,8 +473,11 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
             // the flag sits in the first word of the sum's last group
             if (is_point) (*prog)[prog->size() - PROG_GROUP] |= PROG_END_POINT;
         }
+        // the kernel fetches PROG_FETCH words at a time: groups of padding terms fill the segment's tail
+        while ((prog->size() - (size_t)al->prog_seg[s]) % PROG_FETCH) prog->push_back(0u);
     }
     al->prog_seg[LLMEM_NSEG] = (int)prog->size();
+    for (int q = 0; q <= LLMEM_NSEG; ++q) (*prog)[al->prog_first + 1 + q] = (uint32_t)al->prog_seg[q];
     return prog->size() <= (size_t)PROG_WORDS;
 }
 

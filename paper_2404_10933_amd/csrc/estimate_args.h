@@ -25,18 +25,21 @@ constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
 // segment to the peak points no other point dominates (class-count vectors compared
 // component-wise) and passes the result in the kernel arguments.  Stream of 32-bit words per
 // architecture:
-//   header     n_groups | e_n << 8 | n_class << 16
+//   header     PROG_HEADER words: n_groups | e_n << 8 | n_class << 16; the first word of each
+//              segment's terms and the word after the last segment (absolute); padding
 //   per group  coefficient; descriptor; E_once | E_layer << 8 | LM_once << 16 | LM_layer << 24;
 //              OTHER_once | OTHER_layer << 8 | OS_once << 16 | OS_layer << 24
 //              (how many entries of the group count towards embed_p, lm_p, other_p, m_os, once or
 //              once per block)
-//   per class  coefficient * element bytes; descriptor
+//   per class  coefficient * element bytes; descriptor (padded with empty classes, 0 0, to a
+//              multiple of PROG_CLASS_FETCH)
 //   per segment A F H B Z its sums, each in groups of PROG_GROUP terms: the peak points, then
 //              the segment's net change.  A term is  slot * 512 | count << 16: the partial sum
 //              gains count * value[slot].  PROG_END_POINT in the first term of a group closes a
 //              peak point after that group (its sum competes for the segment's maximum and the
 //              partial sum restarts); the net change comes last and stays open.  Padding terms
-//              are 0 (slot 0 holds 0).  Slot c + 1 holds the value of class c; a class that some
+//              are 0 (slot 0 holds 0); whole groups of them pad a segment to PROG_FETCH words.
+//              Slot c + 1 holds the value of class c; a class that some
 //              sum counts negatively has a second slot holding minus its value.
 // Descriptor: number of dimensions (bits 0-2), their selectors (4 bits each from bit 4),
 // DESC_TP_GATHER, DESC_TIMES_L, method mask (3 bits from DESC_MASK_SHIFT), slot of the negated
@@ -45,9 +48,12 @@ constexpr unsigned DESC_TP_GATHER = 1u << 20, DESC_TIMES_L = 1u << 21;
 constexpr int DESC_MASK_SHIFT = 22, DESC_NEG_SLOT_SHIFT = 25;
 constexpr int PROG_SLOT_MAX = 100;
 constexpr int PROG_WORDS = 704;
+constexpr int PROG_HEADER = 8;
 constexpr int PROG_GROUP = 4;
+constexpr int PROG_CLASS_FETCH = 4;            // classes the list is padded to and read by
+constexpr int PROG_FETCH = 8;                  // words a segment's term list is padded to and read by
 constexpr unsigned PROG_OFFSET_MASK = 0xfe00, PROG_END_POINT = 0x1;
-constexpr size_t BATCH_LDS_LIMIT = 64 * 1024;  // dynamic LDS a launch may ask for
+constexpr size_t BATCH_LDS_LIMIT = 62 * 1024;  // dynamic LDS a launch may ask for (the kernel has 2 KB of its own)
 
 struct ArchLayout {
     int param_first, n_param;

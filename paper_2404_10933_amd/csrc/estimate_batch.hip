@@ -55,6 +55,11 @@ template <bool DETAIL>
 __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const EstimateArgs a)
 {
     extern __shared__ uint4 lds[];
+    // multipliers of the divisions by the partition degree: a lane looks its own d up, from LDS
+    // rather than from memory, so that no memory latency stands between a batch's inputs and its work
+    __shared__ u64 div_mul_of[256];
+    div_mul_of[threadIdx.x & 255u] = c_div.t[threadIdx.x & 255u].mul;
+    static_assert(BB_BLOCK == 256, "one thread per table entry");
     // LDS: class table | event codes | per-architecture counts | value slots of the waves
     // (the set-up's scratch shares the space of the value slots)
     uint4 *cls_tab = lds;                                                       // n_arch * CLS_MAX
@@ -116,6 +121,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
         }
     }
 
+    __syncthreads();
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const long long n = a.n;
@@ -128,19 +134,35 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                  + ((size_t)wave * (a.use_program ? a.p_slots : a.s_slots) * 64 + lane) * sizeof(i64);
     if (DETAIL) *reinterpret_cast<i64 *>(vals) = 0;
 
-    for (long long b = (long long)blockIdx.x * BB_WAVES + wave; b < n_batch;
-         b += (long long)gridDim.x * BB_WAVES) {
+    // the columns of one configuration as loaded; the next batch's are fetched while this one is worked on
+    struct Raw { u32 h, ffn, V, P, arch_id, method, d, cflags, L, n_heads, n_kv, bs, sl; int chunk_k; };
+    auto fetch = [&](long long batch) -> Raw {
+        Raw r = {1, 0, 0, 0, 0, 0, 1, 0, 0, 1, 0, 0, 0, 0};
+        const long long i = (batch << 6) + lane;
+        if (batch < n_batch && i < n) {
+            r.h = a.cfg.h[i]; r.ffn = a.cfg.ffn[i]; r.V = a.cfg.V[i]; r.P = a.cfg.P[i];
+            r.arch_id = a.cfg.arch_id[i]; r.method = a.cfg.method[i]; r.d = a.cfg.d[i]; r.cflags = a.cfg.flags[i];
+            r.L = a.cfg.L[i]; r.n_heads = a.cfg.n_heads[i]; r.n_kv = a.cfg.n_kv[i];
+            r.chunk_k = a.cfg.chunk_k[i]; r.bs = a.cfg.bs[i]; r.sl = a.cfg.sl[i];
+        }
+        return r;
+    };
+    const long long b_step = (long long)gridDim.x * BB_WAVES;
+    long long b = (long long)blockIdx.x * BB_WAVES + wave;
+    Raw ahead = fetch(b);
+    // the first batch's columns have arrived before the loop starts, so that inside the loop only
+    // the batch fetched one iteration earlier is ever waited for
+    asm volatile("" :: "v"(ahead.h), "v"(ahead.ffn), "v"(ahead.V), "v"(ahead.P), "v"(ahead.arch_id), "v"(ahead.method),
+                 "v"(ahead.d), "v"(ahead.cflags), "v"(ahead.L), "v"(ahead.n_heads), "v"(ahead.n_kv), "v"(ahead.bs),
+                 "v"(ahead.sl), "v"(ahead.chunk_k));
+    for (; b < n_batch; b += b_step) {
         const long long i = (b << 6) + lane;
         const bool in_range = i < n;
-        u32 h = 1, ffn = 0, V = 0, P = 0, arch_id = 0, method = 0, d = 1, cflags = 0, L = 0, n_heads = 1,
-            n_kv = 0, bs = 0, sl = 0;
-        int chunk_k = 0;
-        if (in_range) {
-            h = a.cfg.h[i]; ffn = a.cfg.ffn[i]; V = a.cfg.V[i]; P = a.cfg.P[i];
-            arch_id = a.cfg.arch_id[i]; method = a.cfg.method[i]; d = a.cfg.d[i]; cflags = a.cfg.flags[i];
-            L = a.cfg.L[i]; n_heads = a.cfg.n_heads[i]; n_kv = a.cfg.n_kv[i];
-            chunk_k = a.cfg.chunk_k[i]; bs = a.cfg.bs[i]; sl = a.cfg.sl[i];
-        }
+        const Raw now = ahead;
+        ahead = fetch(b + b_step);
+        const u32 h = now.h, ffn = now.ffn, V = now.V, P = now.P, arch_id = now.arch_id, method = now.method, d = now.d,
+                  cflags = now.cflags, L = now.L, n_heads = now.n_heads, n_kv = now.n_kv, bs = now.bs, sl = now.sl;
+        const int chunk_k = now.chunk_k;
         u32 err = 0;
         if (arch_id >= (u32)a.n_arch) err |= LLMEM_F_ERR_ARCH;
         if (method > 2) err |= LLMEM_F_ERR_METHOD;
@@ -158,9 +180,8 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
         D[LLMEM_DIM_P] = P; D[LLMEM_DIM_L] = L;
         const u32 Blog = (cflags & LLMEM_CFG_LOGITS_FP32) ? B32 : B16;
         D[LLMEM_DIM_B_LOGITS] = Blog; D[LLMEM_DIM_D] = d; D[15] = 0;
-        const DivMagic mg = c_div.t[d & 255u];
-        const u64 div_mul = mg.mul;
-        const u32 div_shift = mg.shift;
+        const u64 div_mul = div_mul_of[d & 255u];
+        const u32 div_shift = d > 1 ? 31u - (u32)__builtin_clz(d - 1) : 0u;        // ceil(log2 d) - 1
 
         i64 r_peak = err ? -1 : 0, r_param = 0, r_grad = 0, r_os = 0, r_out = 0, r_lm = 0, r_back = 0, r_k = 0,
             r_live = 0, r_np = 0, r_tmax = 0, r_flags = err;
@@ -173,7 +194,6 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
             todo &= ~__builtin_amdgcn_ballot_w64(mine);
             if (!mine) continue;
             const ArchLayout &al = a.arch[ar];
-            const int n_param = (int)uni((u32)al.n_param), param_first = (int)uni((u32)al.param_first);
 
             // size of a compiled expression for this lane's configuration (descriptor: see estimate_args.h)
             auto expression = [&](u32 coef, u32 desc) -> u64 {
@@ -189,11 +209,20 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
             u64 embed_p = 0, lm_p = 0, other_p = 0, t_max = 0, m_os = 0;
             u32 e_n = 0;
             int pc = 0;                                                    // read position in the compiled tables
+            u32 head = 0, seg_at[LLMEM_NSEG + 1] = {0, 0, 0, 0, 0, 0};     // header of the compiled tables
             if (a.use_program) {
                 // entries with the same size expression arrive as one group with the number of
                 // entries that count towards each sum, once and once per block
-                pc = (int)uni((u32)al.prog_first);
-                const u32 head = a.prog[pc++];
+                // start of the architecture's words: selected from reads at constant positions, so that
+                // every read of the compiled tables is a scalar load
+                pc = a.arch[0].prog_first;
+#pragma unroll
+                for (int q = 1; q < LLMEM_MAX_ARCH; ++q) pc = ar == (u32)q ? a.arch[q].prog_first : pc;
+                pc = (int)uni((u32)pc);
+                head = a.prog[pc];
+#pragma unroll
+                for (int q = 0; q <= LLMEM_NSEG; ++q) seg_at[q] = a.prog[pc + 1 + q];
+                pc += PROG_HEADER;
                 e_n = (head >> 8) & 255u;
                 const int n_groups = (int)(head & 255u);
                 for (int g = 0; g < n_groups; ++g, pc += 4) {
@@ -208,6 +237,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                     if (w3 >> 16) m_os += b_up(t_p * (u64)(B32 + B32), cu_shift) * (u64)(((w3 >> 16) & 255u) + (w3 >> 24) * L);
                 }
             } else {
+                const int n_param = (int)uni((u32)al.n_param), param_first = (int)uni((u32)al.param_first);
                 for (int j = 0; j < n_param; ++j) {
                     const uint4 pe = a.params_dev[param_first + j];           // wave-uniform
                     const u32 cls = pe.z & 255u, role = (pe.z >> 8) & 255u, per_layer = (pe.z >> 16) & 255u;
@@ -330,39 +360,63 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                 };
                 if (a.use_program) {
                     // ---- compiled timeline: classes and terms come from the kernel arguments ----
-                    const int nc = (int)((a.prog[(int)uni((u32)al.prog_first)] >> 16) & 255u);
-                    for (int c = 0; c < nc; ++c, pc += 2) {
-                        const u32 desc = a.prog[pc + 1];
-                        u64 x = expression(a.prog[pc], desc);
-                        if (desc & DESC_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
-                        u64 r = b_up(x, align_shift);
-                        if (desc & DESC_TIMES_L) r *= (u64)L;
-                        const u32 mask = (desc >> DESC_MASK_SHIFT) & 7u;
-                        if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
-                        *reinterpret_cast<u64 *>(vals + (c + 1) * 512) = r;
-                        const u32 neg = desc >> DESC_NEG_SLOT_SHIFT;
-                        if (neg) *reinterpret_cast<u64 *>(vals + neg * 512) = 0ull - r;
+                    const int nc = (int)((head >> 16) & 255u);
+                    // four classes per fetch (the host pads the list with empty classes)
+                    for (int c0 = 0; c0 < nc; c0 += PROG_CLASS_FETCH, pc += 2 * PROG_CLASS_FETCH) {
+                        u32 cw[2 * PROG_CLASS_FETCH];
+#pragma unroll
+                        for (int q = 0; q < 2 * PROG_CLASS_FETCH; ++q) cw[q] = a.prog[pc + q];
+#pragma unroll
+                        for (int u = 0; u < PROG_CLASS_FETCH; ++u) {
+                            const int c = c0 + u;
+                            const u32 desc = cw[2 * u + 1];
+                            u64 x = expression(cw[2 * u], desc);
+                            if (desc & DESC_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
+                            u64 r = b_up(x, align_shift);
+                            if (desc & DESC_TIMES_L) r *= (u64)L;
+                            const u32 mask = (desc >> DESC_MASK_SHIFT) & 7u;
+                            if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
+                            if (c < nc) *reinterpret_cast<u64 *>(vals + (c + 1) * 512) = r;
+                            const u32 neg = desc >> DESC_NEG_SLOT_SHIFT;
+                            if (neg) *reinterpret_cast<u64 *>(vals + neg * 512) = 0ull - r;
+                        }
                     }
                     for (int s = 0; s < LLMEM_NSEG; ++s) {
-                        // sums of count * value, four terms at a time, no branches: a flagged group
+                        // sums of count * value, two groups of four terms at a time, no branches: a flagged group
                         // ends a peak point; what is left open at the end is the net change
                         u64 acc = 0;
                         i64 top = LOWEST;
-                        const int w_begin = (int)uni((u32)al.prog_seg[s]), w_end = (int)uni((u32)al.prog_seg[s + 1]);
-                        for (int w = w_begin; w < w_end; w += PROG_GROUP) {
-                            const u32 t0 = a.prog[w], t1 = a.prog[w + 1], t2 = a.prog[w + 2], t3 = a.prog[w + 3];
-                            const u64 v0 = *reinterpret_cast<const u64 *>(vals + (t0 & PROG_OFFSET_MASK));
-                            const u64 v1 = *reinterpret_cast<const u64 *>(vals + (t1 & PROG_OFFSET_MASK));
-                            const u64 v2 = *reinterpret_cast<const u64 *>(vals + (t2 & PROG_OFFSET_MASK));
-                            const u64 v3 = *reinterpret_cast<const u64 *>(vals + (t3 & PROG_OFFSET_MASK));
+                        u32 w_from = seg_at[0], w_to = seg_at[1];
+#pragma unroll
+                        for (int q = 1; q < LLMEM_NSEG; ++q) { w_from = s == q ? seg_at[q] : w_from; w_to = s == q ? seg_at[q + 1] : w_to; }
+                        const int w_begin = (int)w_from, w_end = (int)w_to;
+                        for (int w = w_begin; w < w_end; w += PROG_FETCH) {
+                            const u32 t0 = a.prog[w], t1 = a.prog[w + 1], t2 = a.prog[w + 2], t3 = a.prog[w + 3],
+                                      t4 = a.prog[w + 4], t5 = a.prog[w + 5], t6 = a.prog[w + 6], t7 = a.prog[w + 7];
+#define LLMEM_SLOT(t) (*reinterpret_cast<const u64 *>(vals + ((t) & PROG_OFFSET_MASK)))
+                            const u64 v0 = LLMEM_SLOT(t0), v1 = LLMEM_SLOT(t1), v2 = LLMEM_SLOT(t2), v3 = LLMEM_SLOT(t3),
+                                      v4 = LLMEM_SLOT(t4), v5 = LLMEM_SLOT(t5), v6 = LLMEM_SLOT(t6), v7 = LLMEM_SLOT(t7);
+#undef LLMEM_SLOT
                             acc += v0 * (u64)(t0 >> 16);
                             acc += v1 * (u64)(t1 >> 16);
                             acc += v2 * (u64)(t2 >> 16);
                             acc += v3 * (u64)(t3 >> 16);
-                            const bool end = t0 & PROG_END_POINT;
-                            const bool up = end & ((i64)acc > top);
-                            top = up ? (i64)acc : top;
-                            acc = end ? 0ull : acc;
+                            {
+                                const bool end = t0 & PROG_END_POINT;
+                                const bool up = end & ((i64)acc > top);
+                                top = up ? (i64)acc : top;
+                                acc = end ? 0ull : acc;
+                            }
+                            acc += v4 * (u64)(t4 >> 16);
+                            acc += v5 * (u64)(t5 >> 16);
+                            acc += v6 * (u64)(t6 >> 16);
+                            acc += v7 * (u64)(t7 >> 16);
+                            {
+                                const bool end = t4 & PROG_END_POINT;
+                                const bool up = end & ((i64)acc > top);
+                                top = up ? (i64)acc : top;
+                                acc = end ? 0ull : acc;
+                            }
                         }
                         const i64 run = (i64)acc;
                         close_segment(s, run, top);
@@ -409,6 +463,11 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
             }
         }
 
+        // wait for the next batch's columns here, before this batch's stores are issued: memory
+        // operations complete in order, so waiting after the stores would wait for them as well
+        asm volatile("" :: "v"(ahead.h), "v"(ahead.ffn), "v"(ahead.V), "v"(ahead.P), "v"(ahead.arch_id), "v"(ahead.method),
+                     "v"(ahead.d), "v"(ahead.cflags), "v"(ahead.L), "v"(ahead.n_heads), "v"(ahead.n_kv), "v"(ahead.bs),
+                     "v"(ahead.sl), "v"(ahead.chunk_k));
         if (in_range) {
             if (a.out_peaks) a.out_peaks[i] = r_peak;
             if (DETAIL) {
