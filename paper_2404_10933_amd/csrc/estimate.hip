@@ -468,14 +468,14 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
                 ++stats[2];                                                         // (class, count) terms
             }
             stats[3] += is_point ? 1 : 0;                                           // peak points
-            if (prog->size() == group_first && is_point) prog->push_back(0u);      // a point with an empty sum
+            if (prog->size() == group_first) prog->push_back(0u);                   // an empty sum still has a group
             while ((prog->size() - group_first) % PROG_GROUP) prog->push_back(0u);
             // the flag sits in the first word of the sum's last group
-            if (is_point) (*prog)[prog->size() - PROG_GROUP] |= PROG_END_POINT;
+            (*prog)[prog->size() - PROG_GROUP] |= is_point ? PROG_END_POINT : PROG_END_SEGMENT;
         }
-        // the kernel fetches PROG_FETCH words at a time: groups of padding terms fill the segment's tail
-        while ((prog->size() - (size_t)al->prog_seg[s]) % PROG_FETCH) prog->push_back(0u);
     }
+    // the kernel fetches PROG_FETCH words at a time: groups of padding terms fill the tail
+    while ((prog->size() - (size_t)al->prog_seg[0]) % PROG_FETCH) prog->push_back(0u);
     al->prog_seg[LLMEM_NSEG] = (int)prog->size();
     for (int q = 0; q <= LLMEM_NSEG; ++q) (*prog)[al->prog_first + 1 + q] = (uint32_t)al->prog_seg[q];
     return prog->size() <= (size_t)PROG_WORDS;

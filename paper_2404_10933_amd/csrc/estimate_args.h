@@ -33,14 +33,15 @@ constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
 //              once per block)
 //   per class  coefficient * element bytes; descriptor (padded with empty classes, 0 0, to a
 //              multiple of PROG_CLASS_FETCH)
-//   per segment A F H B Z its sums, each in groups of PROG_GROUP terms: the peak points, then
-//              the segment's net change.  A term is  slot * 512 | count << 16: the partial sum
-//              gains count * value[slot].  PROG_END_POINT in the first term of a group closes a
-//              peak point after that group (its sum competes for the segment's maximum and the
-//              partial sum restarts); the net change comes last and stays open.  Padding terms
-//              are 0 (slot 0 holds 0); whole groups of them pad a segment to PROG_FETCH words.
-//              Slot c + 1 holds the value of class c; a class that some
-//              sum counts negatively has a second slot holding minus its value.
+//   the sums of the segments A F H B Z one after the other, each sum in groups of PROG_GROUP
+//              terms: a segment's peak points, then its net change.  A term is
+//              slot * 512 | count << 16: the partial sum gains count * value[slot].  A flag in
+//              the first term of a sum's last group closes it: PROG_END_POINT (the sum competes
+//              for the segment's maximum and the partial sum restarts) or PROG_END_SEGMENT (the
+//              sum is the segment's net change; the next segment starts).  Padding terms are 0
+//              (slot 0 holds 0); whole groups of them pad the list to PROG_FETCH words.
+//              Slot c + 1 holds the value of class c; a class that some sum counts negatively
+//              has a second slot holding minus its value.
 // Descriptor: number of dimensions (bits 0-2), their selectors (4 bits each from bit 4),
 // DESC_TP_GATHER, DESC_TIMES_L, method mask (3 bits from DESC_MASK_SHIFT), slot of the negated
 // value (from DESC_NEG_SLOT_SHIFT, 0 = none).
@@ -51,8 +52,8 @@ constexpr int PROG_WORDS = 704;
 constexpr int PROG_HEADER = 8;
 constexpr int PROG_GROUP = 4;
 constexpr int PROG_CLASS_FETCH = 4;            // classes the list is padded to and read by
-constexpr int PROG_FETCH = 8;                  // words a segment's term list is padded to and read by
-constexpr unsigned PROG_OFFSET_MASK = 0xfe00, PROG_END_POINT = 0x1;
+constexpr int PROG_FETCH = 16;                  // words a segment's term list is padded to and read by
+constexpr unsigned PROG_OFFSET_MASK = 0xfe00, PROG_END_POINT = 0x1, PROG_END_SEGMENT = 0x2;
 constexpr size_t BATCH_LDS_LIMIT = 62 * 1024;  // dynamic LDS a launch may ask for (the kernel has 2 KB of its own)
 
 struct ArchLayout {

@@ -381,45 +381,45 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                             if (neg) *reinterpret_cast<u64 *>(vals + neg * 512) = 0ull - r;
                         }
                     }
-                    for (int s = 0; s < LLMEM_NSEG; ++s) {
-                        // sums of count * value, two groups of four terms at a time, no branches: a flagged group
-                        // ends a peak point; what is left open at the end is the net change
+                    // sums of count * value, four groups of four terms per fetch, no branches but one: a
+                    // group flagged as a point's end lets its sum compete for the segment's maximum; the
+                    // group that ends a segment's net change closes the segment
+                    {
+                        int seg = 0;
                         u64 acc = 0;
                         i64 top = LOWEST;
-                        u32 w_from = seg_at[0], w_to = seg_at[1];
-#pragma unroll
-                        for (int q = 1; q < LLMEM_NSEG; ++q) { w_from = s == q ? seg_at[q] : w_from; w_to = s == q ? seg_at[q + 1] : w_to; }
-                        const int w_begin = (int)w_from, w_end = (int)w_to;
+                        const int w_begin = (int)seg_at[0], w_end = (int)seg_at[LLMEM_NSEG];
                         for (int w = w_begin; w < w_end; w += PROG_FETCH) {
-                            const u32 t0 = a.prog[w], t1 = a.prog[w + 1], t2 = a.prog[w + 2], t3 = a.prog[w + 3],
-                                      t4 = a.prog[w + 4], t5 = a.prog[w + 5], t6 = a.prog[w + 6], t7 = a.prog[w + 7];
-#define LLMEM_SLOT(t) (*reinterpret_cast<const u64 *>(vals + ((t) & PROG_OFFSET_MASK)))
-                            const u64 v0 = LLMEM_SLOT(t0), v1 = LLMEM_SLOT(t1), v2 = LLMEM_SLOT(t2), v3 = LLMEM_SLOT(t3),
-                                      v4 = LLMEM_SLOT(t4), v5 = LLMEM_SLOT(t5), v6 = LLMEM_SLOT(t6), v7 = LLMEM_SLOT(t7);
-#undef LLMEM_SLOT
-                            acc += v0 * (u64)(t0 >> 16);
-                            acc += v1 * (u64)(t1 >> 16);
-                            acc += v2 * (u64)(t2 >> 16);
-                            acc += v3 * (u64)(t3 >> 16);
-                            {
-                                const bool end = t0 & PROG_END_POINT;
+                            u32 t[PROG_FETCH];
+                            u64 v[PROG_FETCH];
+#pragma unroll
+                            for (int q = 0; q < PROG_FETCH; ++q) t[q] = a.prog[w + q];
+#pragma unroll
+                            for (int q = 0; q < PROG_FETCH; ++q) v[q] = *reinterpret_cast<const u64 *>(vals + (t[q] & PROG_OFFSET_MASK));
+#pragma unroll
+                            for (int g = 0; g < PROG_FETCH; g += PROG_GROUP) {
+                                const bool end = t[g] & PROG_END_POINT;
+                                // count * value: the low and the high halves of the values are summed apart
+                                // (each product is below 2^48) and joined once per group
+                                u64 part_lo = 0, part_hi = 0;
+#pragma unroll
+                                for (int q = g; q < g + PROG_GROUP; ++q) {
+                                    part_lo += (u64)(u32)v[q] * (t[q] >> 16);
+                                    part_hi += (u64)(u32)(v[q] >> 32) * (t[q] >> 16);
+                                }
+                                acc += part_lo + (part_hi << 32);
                                 const bool up = end & ((i64)acc > top);
                                 top = up ? (i64)acc : top;
                                 acc = end ? 0ull : acc;
-                            }
-                            acc += v4 * (u64)(t4 >> 16);
-                            acc += v5 * (u64)(t5 >> 16);
-                            acc += v6 * (u64)(t6 >> 16);
-                            acc += v7 * (u64)(t7 >> 16);
-                            {
-                                const bool end = t4 & PROG_END_POINT;
-                                const bool up = end & ((i64)acc > top);
-                                top = up ? (i64)acc : top;
-                                acc = end ? 0ull : acc;
+                                if (t[g] & PROG_END_SEGMENT) {                           // wave-uniform
+                                    asm volatile("" ::: "memory");
+                                    close_segment(seg, (i64)acc, top);
+                                    ++seg;
+                                    acc = 0;
+                                    top = LOWEST;
+                                }
                             }
                         }
-                        const i64 run = (i64)acc;
-                        close_segment(s, run, top);
                     }
                 } else {
                 // ---- size classes of the timeline: rounded bytes into the value slots ----
@@ -521,7 +521,9 @@ void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batc
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, BB_BLOCK, lds_bytes) != hipSuccess || per_cu < 1)
         per_cu = 1;
     long long blocks = (n_batch + BB_WAVES - 1) / BB_WAVES;
-    const long long resident = (long long)per_cu * cu_count;
+    // the compiled form has next to no set-up per workgroup: several times more workgroups than
+    // stay resident at once let the dispatcher even out the compute units (measured: 8 is enough)
+    const long long resident = (long long)per_cu * cu_count * (args.use_program ? 8 : 1);
     if (blocks > resident) blocks = resident;
     if (detail)
         hipLaunchKernelGGL(estimate_batch_kernel<true>, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
