@@ -464,7 +464,7 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
                 const int mag = v[c] < 0 ? -v[c] : v[c];
                 if (mag > 65535) return false;
                 const int slot = v[c] < 0 ? neg_slot[c] : c + 1;
-                prog->push_back(((uint32_t)slot << 9) | ((uint32_t)mag << 16));
+                prog->push_back((uint32_t)slot * SLOT_ROW | ((uint32_t)mag << 16));
                 ++stats[2];                                                         // (class, count) terms
             }
             stats[3] += is_point ? 1 : 0;                                           // peak points

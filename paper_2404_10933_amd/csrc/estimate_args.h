@@ -35,7 +35,7 @@ constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
 //              multiple of PROG_CLASS_FETCH)
 //   the sums of the segments A F H B Z one after the other, each sum in groups of PROG_GROUP
 //              terms: a segment's peak points, then its net change.  A term is
-//              slot * 512 | count << 16: the partial sum gains count * value[slot].  A flag in
+//              slot * SLOT_ROW | count << 16: the partial sum gains count * value[slot].  A flag in
 //              the first term of a sum's last group closes it: PROG_END_POINT (the sum competes
 //              for the segment's maximum and the partial sum restarts) or PROG_END_SEGMENT (the
 //              sum is the segment's net change; the next segment starts).  Padding terms are 0
@@ -53,7 +53,8 @@ constexpr int PROG_HEADER = 8;
 constexpr int PROG_GROUP = 4;
 constexpr int PROG_CLASS_FETCH = 4;            // classes the list is padded to and read by
 constexpr int PROG_FETCH = 16;                  // words a segment's term list is padded to and read by
-constexpr unsigned PROG_OFFSET_MASK = 0xfe00, PROG_END_POINT = 0x1, PROG_END_SEGMENT = 0x2;
+constexpr int SLOT_ROW = 256;                   // bytes of LDS per value slot and wavefront in the compiled form
+constexpr unsigned PROG_OFFSET_MASK = 0xff00, PROG_END_POINT = 0x1, PROG_END_SEGMENT = 0x2;
 constexpr size_t BATCH_LDS_LIMIT = 62 * 1024;  // dynamic LDS a launch may ask for (the kernel has 2 KB of its own)
 
 struct ArchLayout {
@@ -93,6 +94,8 @@ struct EstimateArgs {
     int use_program;                 // 1: the compiled timeline below is valid and used
     uint32_t prog[PROG_WORDS];
 };
+
+static_assert(sizeof(EstimateArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 // Events with equal keys have equal byte sizes for every configuration: same
 // coefficient, same multiset of dimensions, same element width, scaling flags

@@ -28,6 +28,7 @@
 // traversal per Sec. 2.1 / Sec. 3.1.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "../../include/llmem.h"
 #include "estimate_args.h"
@@ -51,7 +52,9 @@ __device__ __forceinline__ u32 uni(u32 v) { return (u32)__builtin_amdgcn_readfir
 
 }  // namespace
 
-template <bool DETAIL>
+// COMPILED: the tables come compiled in the kernel arguments (else the kernel reads the entries
+// from memory and walks every event)
+template <bool DETAIL, bool COMPILED>
 __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const EstimateArgs a)
 {
     extern __shared__ uint4 lds[];
@@ -65,13 +68,13 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
     uint4 *cls_tab = lds;                                                       // n_arch * CLS_MAX
     unsigned short *codes = reinterpret_cast<unsigned short *>(lds + a.n_arch * CLS_MAX);
     int *n_class = reinterpret_cast<int *>(codes + a.code_count);                // code_count is a multiple of 8
-    uint4 *dyn = a.use_program ? lds : reinterpret_cast<uint4 *>(n_class + LLMEM_MAX_ARCH);
+    uint4 *dyn = COMPILED ? lds : reinterpret_cast<uint4 *>(n_class + LLMEM_MAX_ARCH);
     uint4 *tmp_key = dyn;                                                        // max_events
     unsigned short *tmp_rep = reinterpret_cast<unsigned short *>(tmp_key + a.max_events);
     unsigned short *tmp_cid = tmp_rep + a.max_events;
 
     // ---- set-up: size classes, value slots and event codes of every architecture -----
-    if (DETAIL && !a.use_program) {
+    if (DETAIL && !COMPILED) {
         for (int t = threadIdx.x; t < a.code_count; t += BB_BLOCK) codes[t] = 0;  // padding: slot 0, no check
         for (int ar = 0; ar < a.n_arch; ++ar) {
             const ArchLayout &al = a.arch[ar];
@@ -128,11 +131,16 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
     const long long n_batch = (n + 63) >> 6;
     const int cu_shift = a.cu_shift, align_shift = a.align_shift;
     const u64 m_base = (u64)a.m_base;
-    // value slots of this wave: slot s of lane l at byte s * 512 + l * 8; an event code is the
-    // slot's byte offset with the check flag in bit 0
-    char *vals = reinterpret_cast<char *>(dyn)
-                 + ((size_t)wave * (a.use_program ? a.p_slots : a.s_slots) * 64 + lane) * sizeof(i64);
-    if (DETAIL) *reinterpret_cast<i64 *>(vals) = 0;
+    // value slots of this wave.  Events form: slot s of lane l at byte s * 512 + l * 8; an event
+    // code is the slot's byte offset with the check flag in bit 0.  Compiled form: a slot is a row
+    // of SLOT_ROW bytes holding either 64 values of 32 bits (sizes in allocator blocks, lane l at
+    // l * 4) or the 64-bit byte sizes of one half of the wave (lane l at (l % 32) * 8).
+    char *vals = reinterpret_cast<char *>(dyn) + (COMPILED ? (size_t)wave * a.p_slots * SLOT_ROW
+                                                           : ((size_t)wave * a.s_slots * 64 + lane) * sizeof(i64));
+    if (DETAIL) {
+        if (COMPILED) *reinterpret_cast<u32 *>(vals + lane * 4) = 0;
+        else *reinterpret_cast<i64 *>(vals) = 0;
+    }
 
     // the columns of one configuration as loaded; the next batch's are fetched while this one is worked on
     struct Raw { u32 h, ffn, V, P, arch_id, method, d, cflags, L, n_heads, n_kv, bs, sl; int chunk_k; };
@@ -210,7 +218,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
             u32 e_n = 0;
             int pc = 0;                                                    // read position in the compiled tables
             u32 head = 0, seg_at[LLMEM_NSEG + 1] = {0, 0, 0, 0, 0, 0};     // header of the compiled tables
-            if (a.use_program) {
+            if (COMPILED) {
                 // entries with the same size expression arrive as one group with the number of
                 // entries that count towards each sum, once and once per block
                 // start of the architecture's words: selected from reads at constant positions, so that
@@ -345,79 +353,126 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                 // after a segment: `at` is the live total at its start relative to the resident state,
                 // `run` its net change, `top` its highest prefix.  The L equal blocks shift the prefix
                 // linearly, so the maximum over the repetitions of F (or B) is at the first or last one.
-                auto close_segment = [&](int s, i64 run, i64 top) {
+                // `has_point`: the segment has a prefix that can be a peak (`top` is meaningful)
+                auto close_segment = [&](int s, i64 run, i64 top, bool has_point) {
                     const bool repeated = s == LLMEM_SEG_F || s == LLMEM_SEG_B;
                     if (repeated) {
                         const i64 shift = ((i64)L - 1) * run;
                         const i64 cand = at + top + (shift > 0 ? shift : 0);
-                        if (top != LOWEST && L != 0) best = cand > best ? cand : best;
+                        if (has_point && L != 0) best = cand > best ? cand : best;
                         at += (i64)L * run;
                     } else {
                         const i64 cand = at + top;
-                        if (top != LOWEST) best = cand > best ? cand : best;
+                        if (has_point) best = cand > best ? cand : best;
                         at += run;
                     }
                 };
-                if (a.use_program) {
+                if (COMPILED) {
                     // ---- compiled timeline: classes and terms come from the kernel arguments ----
                     const int nc = (int)((head >> 16) & 255u);
-                    // four classes per fetch (the host pads the list with empty classes)
-                    for (int c0 = 0; c0 < nc; c0 += PROG_CLASS_FETCH, pc += 2 * PROG_CLASS_FETCH) {
-                        u32 cw[2 * PROG_CLASS_FETCH];
+                    const int pc_classes = pc;
+                    // Classes: four per fetch (the host pads the list with empty classes).  NARROW: sizes
+                    // in allocator blocks as signed 32-bit values, all 64 lanes; else 64-bit byte sizes
+                    // of the lanes of one half of the wave.  Returns the OR of all sizes in blocks.
+                    auto store_classes = [&](auto narrow) -> u64 {
+                        constexpr bool NARROW = decltype(narrow)::value;
+                        char *row = vals + (NARROW ? lane * 4 : (lane & 31) * 8);
+                        u64 seen = 0;
+                        int at_word = pc_classes;
+                        for (int c0 = 0; c0 < nc; c0 += PROG_CLASS_FETCH, at_word += 2 * PROG_CLASS_FETCH) {
+                            u32 cw[2 * PROG_CLASS_FETCH];
 #pragma unroll
-                        for (int q = 0; q < 2 * PROG_CLASS_FETCH; ++q) cw[q] = a.prog[pc + q];
+                            for (int q = 0; q < 2 * PROG_CLASS_FETCH; ++q) cw[q] = a.prog[at_word + q];
 #pragma unroll
-                        for (int u = 0; u < PROG_CLASS_FETCH; ++u) {
-                            const int c = c0 + u;
-                            const u32 desc = cw[2 * u + 1];
-                            u64 x = expression(cw[2 * u], desc);
-                            if (desc & DESC_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
-                            u64 r = b_up(x, align_shift);
-                            if (desc & DESC_TIMES_L) r *= (u64)L;
-                            const u32 mask = (desc >> DESC_MASK_SHIFT) & 7u;
-                            if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
-                            if (c < nc) *reinterpret_cast<u64 *>(vals + (c + 1) * 512) = r;
-                            const u32 neg = desc >> DESC_NEG_SLOT_SHIFT;
-                            if (neg) *reinterpret_cast<u64 *>(vals + neg * 512) = 0ull - r;
+                            for (int u = 0; u < PROG_CLASS_FETCH; ++u) {
+                                const int c = c0 + u;
+                                const u32 desc = cw[2 * u + 1];
+                                u64 x = expression(cw[2 * u], desc);
+                                if (desc & DESC_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
+                                u64 r = (x + ((1ull << align_shift) - 1)) >> align_shift;         // blocks
+                                if (desc & DESC_TIMES_L) r *= (u64)L;
+                                const u32 mask = (desc >> DESC_MASK_SHIFT) & 7u;
+                                if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
+                                const u32 neg = desc >> DESC_NEG_SLOT_SHIFT;
+                                if (NARROW) {
+                                    seen |= r;
+                                    if (c < nc) *reinterpret_cast<u32 *>(row + (c + 1) * SLOT_ROW) = (u32)r;
+                                    if (neg) *reinterpret_cast<u32 *>(row + neg * SLOT_ROW) = 0u - (u32)r;
+                                } else {
+                                    const u64 bytes = r << align_shift;
+                                    if (c < nc) *reinterpret_cast<u64 *>(row + (c + 1) * SLOT_ROW) = bytes;
+                                    if (neg) *reinterpret_cast<u64 *>(row + neg * SLOT_ROW) = 0ull - bytes;
+                                }
+                            }
                         }
-                    }
-                    // sums of count * value, four groups of four terms per fetch, no branches but one: a
+                        return seen;
+                    };
+                    // Sums of count * value, four groups of four terms per fetch, no branches but one: a
                     // group flagged as a point's end lets its sum compete for the segment's maximum; the
-                    // group that ends a segment's net change closes the segment
-                    {
+                    // group that ends a segment's net change closes the segment.
+                    auto walk_terms = [&](auto narrow) {
+                        constexpr bool NARROW = decltype(narrow)::value;
+                        const char *row = vals + (NARROW ? lane * 4 : (lane & 31) * 8);
                         int seg = 0;
-                        u64 acc = 0;
-                        i64 top = LOWEST;
+                        bool has_point = false;                                           // wave-uniform
+                        i64 acc = 0, top = LOWEST;
                         const int w_begin = (int)seg_at[0], w_end = (int)seg_at[LLMEM_NSEG];
                         for (int w = w_begin; w < w_end; w += PROG_FETCH) {
                             u32 t[PROG_FETCH];
-                            u64 v[PROG_FETCH];
 #pragma unroll
                             for (int q = 0; q < PROG_FETCH; ++q) t[q] = a.prog[w + q];
+                            int v32[NARROW ? PROG_FETCH : 1];
+                            if (NARROW) {
 #pragma unroll
-                            for (int q = 0; q < PROG_FETCH; ++q) v[q] = *reinterpret_cast<const u64 *>(vals + (t[q] & PROG_OFFSET_MASK));
+                                for (int q = 0; q < PROG_FETCH; ++q)
+                                    v32[q] = *reinterpret_cast<const int *>(row + (t[q] & PROG_OFFSET_MASK));
+                            }
 #pragma unroll
                             for (int g = 0; g < PROG_FETCH; g += PROG_GROUP) {
                                 const bool end = t[g] & PROG_END_POINT;
-                                // count * value: the low and the high halves of the values are summed apart
-                                // (each product is below 2^48) and joined once per group
-                                u64 part_lo = 0, part_hi = 0;
+                                if (NARROW) {
+                                    // signed 32-bit blocks times a count below 2^16: one multiply-add each
 #pragma unroll
-                                for (int q = g; q < g + PROG_GROUP; ++q) {
-                                    part_lo += (u64)(u32)v[q] * (t[q] >> 16);
-                                    part_hi += (u64)(u32)(v[q] >> 32) * (t[q] >> 16);
+                                    for (int q = g; q < g + PROG_GROUP; ++q) acc += (i64)v32[q] * (i64)(int)(t[q] >> 16);
+                                } else {
+                                    // count * value: the low and the high halves of the values are summed
+                                    // apart (each product is below 2^48) and joined once per group
+                                    u64 part_lo = 0, part_hi = 0;
+#pragma unroll
+                                    for (int q = g; q < g + PROG_GROUP; ++q) {
+                                        const u64 v = *reinterpret_cast<const u64 *>(row + (t[q] & PROG_OFFSET_MASK));
+                                        part_lo += (u64)(u32)v * (t[q] >> 16);
+                                        part_hi += (u64)(u32)(v >> 32) * (t[q] >> 16);
+                                    }
+                                    acc = (i64)((u64)acc + part_lo + (part_hi << 32));
                                 }
-                                acc += part_lo + (part_hi << 32);
-                                const bool up = end & ((i64)acc > top);
-                                top = up ? (i64)acc : top;
-                                acc = end ? 0ull : acc;
+                                const bool up = end & (acc > top);
+                                top = up ? acc : top;
+                                acc = end ? 0 : acc;
+                                has_point |= end;
                                 if (t[g] & PROG_END_SEGMENT) {                           // wave-uniform
                                     asm volatile("" ::: "memory");
-                                    close_segment(seg, (i64)acc, top);
+                                    // the narrow sums are in blocks
+                                    const i64 run = NARROW ? (i64)((u64)acc << align_shift) : acc;
+                                    const i64 peak = NARROW ? (i64)((u64)top << align_shift) : top;
+                                    close_segment(seg, run, peak, has_point);
                                     ++seg;
                                     acc = 0;
                                     top = LOWEST;
+                                    has_point = false;
                                 }
+                            }
+                        }
+                    };
+                    const u64 seen = store_classes(std::true_type());
+                    // every size of every lane below 2^31 blocks: the 32-bit walk is exact
+                    if (__builtin_amdgcn_ballot_w64((seen >> 31) != 0) == 0) {
+                        walk_terms(std::true_type());
+                    } else {
+                        for (u32 half = 0; half < 2; ++half) {
+                            if ((u32)(lane >> 5) == half) {
+                                store_classes(std::false_type());
+                                walk_terms(std::false_type());
                             }
                         }
                     }
@@ -453,7 +508,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                         LLMEM_STEP(v4, c4) LLMEM_STEP(v5, c5) LLMEM_STEP(v6, c6) LLMEM_STEP(v7, c7)
 #undef LLMEM_STEP
                     }
-                    close_segment(s, run, top);
+                    close_segment(s, run, top, top != LOWEST);
                 }
                 }
                 const i64 prelude = (i64)(m_base + param_gpu + os_gpu + lm_p * B16 + grad_extra);
@@ -492,7 +547,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
 size_t batch_kernel_lds_bytes(const EstimateArgs &a)
 {
     if (a.use_program)                                                // compiled form: value slots only
-        return (sizeof(long long) * 64 * (size_t)a.p_slots * BATCH_WAVES + 15) & ~(size_t)15;
+        return ((size_t)SLOT_ROW * (size_t)a.p_slots * BATCH_WAVES + 15) & ~(size_t)15;
     const size_t values = sizeof(long long) * 64 * (size_t)a.s_slots * BATCH_WAVES;
     size_t fixed = sizeof(uint4) * (size_t)a.n_arch * CLS_MAX;        // class table
     fixed += sizeof(unsigned short) * (size_t)a.code_count;            // event codes
@@ -515,20 +570,20 @@ void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batc
         else
             cu_count = 256;
     }
+    typedef void (*Kernel)(const EstimateArgs);
+    const Kernel kernels[2][2] = {{estimate_batch_kernel<false, false>, estimate_batch_kernel<false, true>},
+                                  {estimate_batch_kernel<true, false>, estimate_batch_kernel<true, true>}};
+    const Kernel kernel = kernels[detail ? 1 : 0][args.use_program ? 1 : 0];
     int per_cu = 0;
-    const void *fn = detail ? reinterpret_cast<const void *>(&estimate_batch_kernel<true>)
-                            : reinterpret_cast<const void *>(&estimate_batch_kernel<false>);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, BB_BLOCK, lds_bytes) != hipSuccess || per_cu < 1)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), BB_BLOCK, lds_bytes)
+            != hipSuccess || per_cu < 1)
         per_cu = 1;
     long long blocks = (n_batch + BB_WAVES - 1) / BB_WAVES;
     // the compiled form has next to no set-up per workgroup: several times more workgroups than
     // stay resident at once let the dispatcher even out the compute units (measured: 8 is enough)
     const long long resident = (long long)per_cu * cu_count * (args.use_program ? 8 : 1);
     if (blocks > resident) blocks = resident;
-    if (detail)
-        hipLaunchKernelGGL(estimate_batch_kernel<true>, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
-    else
-        hipLaunchKernelGGL(estimate_batch_kernel<false>, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
 }
 
 }  // namespace llmem

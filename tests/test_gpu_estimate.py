@@ -114,6 +114,42 @@ def test_degenerate_and_flag_cases(U):
     _check(U, cfg, tabs)
 
 
+def test_sizes_on_both_sides_of_2_to_31_blocks(U):
+    """The compiled form walks 32-bit block counts while every size of a wavefront's 64
+    configurations is below 2^31 allocator blocks, and 64-bit bytes otherwise: wavefronts
+    entirely below, entirely above, and with single large configurations in either half."""
+    E = T.EventEntry
+    events = (E("a0", "A", +1, 3, ("V", "V"), 8), E("a1", "A", +1, 1, ("bs", "sl", "h"), 2),
+              E("f0", "F", +1, 1, ("V", "ffn"), 4), E("f1", "F", -1, 1, ("V", "ffn"), 4, times_L=False),
+              E("f2", "F", +1, 2, ("bs", "sl", "h"), 2), E("h0", "H", +1, 1, ("V", "V", "h"), 8, frozenset({0, 2})),
+              E("h1", "H", -1, 3, ("V", "V"), 8), E("b0", "B", +1, 5, ("V", "ffn"), 4, scale="tp_gather"),
+              E("b1", "B", -1, 2, ("bs", "sl", "h"), 2), E("z0", "Z", +1, 7, ("V", "V"), 1, times_L=True),
+              E("z1", "Z", -1, 1, ("V", "V", "h"), 8, frozenset({0, 2})))
+    table = T.ArchTable("wide", T.gpt_table().params, events)
+    rng = np.random.default_rng(4)
+    n = 64 * 8 + 9
+    cfg = G.random_configs(rng, n, n_arch=1)
+    cfg["V"][:] = rng.integers(1, 3000, size=n)             # 3 * V * V * 8 below 2^31 * 512
+    cfg["ffn"][:] = rng.integers(1, 20000, size=n)
+    big = np.zeros(n, dtype=bool)
+    big[64:128] = True                                       # a whole wavefront of large sizes
+    big[64 * 3 + 5] = True                                   # one configuration in the lower half
+    big[64 * 5 + 40] = True                                  # one in the upper half
+    big[64 * 6 + 31] = big[64 * 6 + 32] = True               # one in each half
+    big[n - 1] = True                                        # in the ragged tail
+    cfg["V"][big] = rng.integers(150_000, 200_000, size=int(big.sum()))
+    for const in (CONST, T.Constants(m_base=3, cu_p=4096, align=1), T.Constants(m_base=0, cu_p=1 << 30, align=1 << 20)):
+        _check(U, cfg, [table], const, expect=BOTH)
+    # sizes straddling the limit exactly: 2^31 blocks of 512 bytes = 2^40 bytes = coef * V * V * 8 with V = 2^18, coef = 2
+    edge = T.ArchTable("edge", T.gpt_table().params, (E("a", "A", +1, 2, ("V", "V"), 8), E("b", "A", -1, 2, ("V", "V"), 8),
+                                                     E("c", "F", +1, 1, ("V", "P"), 8)))
+    cfg = G.random_configs(rng, 64 * 3, n_arch=1)
+    cfg["V"][:] = 1 << 18
+    cfg["V"][::7] = (1 << 18) - 1
+    cfg["P"][:] = rng.integers(0, 3, size=64 * 3)
+    _check(U, cfg, [edge], CONST, expect=BOTH)
+
+
 def test_determinism_and_stream(U):
     cfg = G.grid3(n=20_000, seed=5)
     for kernel in BOTH:
