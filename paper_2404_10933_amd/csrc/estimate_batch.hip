@@ -414,7 +414,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                         constexpr bool NARROW = decltype(narrow)::value;
                         const char *row = vals + (NARROW ? lane * 4 : (lane & 31) * 8);
                         int seg = 0;
-                        bool has_point = false;                                           // wave-uniform
+                        u32 has_point = 0;                                                // wave-uniform, kept scalar
                         i64 acc = 0, top = LOWEST;
                         const int w_begin = (int)seg_at[0], w_end = (int)seg_at[LLMEM_NSEG];
                         for (int w = w_begin; w < w_end; w += PROG_FETCH) {
@@ -449,17 +449,17 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                                 const bool up = end & (acc > top);
                                 top = up ? acc : top;
                                 acc = end ? 0 : acc;
-                                has_point |= end;
+                                has_point |= t[g] & PROG_END_POINT;
                                 if (t[g] & PROG_END_SEGMENT) {                           // wave-uniform
                                     asm volatile("" ::: "memory");
                                     // the narrow sums are in blocks
                                     const i64 run = NARROW ? (i64)((u64)acc << align_shift) : acc;
                                     const i64 peak = NARROW ? (i64)((u64)top << align_shift) : top;
-                                    close_segment(seg, run, peak, has_point);
+                                    close_segment(seg, run, peak, has_point != 0);
                                     ++seg;
                                     acc = 0;
                                     top = LOWEST;
-                                    has_point = false;
+                                    has_point = 0;
                                 }
                             }
                         }
