@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--n", type=int, default=10_000_000, help="configurations per step (default: the 10^7 grid)")
     ap.add_argument("--lists", type=int, default=100_000, help="event lists of the explicit-timeline grid (0: skip)")
+    ap.add_argument("--full-traversal", type=int, default=10_000_000,
+                    help="configurations timed with the table without gradient checkpointing (0: skip)")
     ap.add_argument("--queries", type=int, default=4_000_000, help="queries of the method-decision grid (0: skip)")
     ap.add_argument("--cpu-sample", type=int, default=600_000, help="configurations the CPU oracle is timed on (0: skip)")
     ap.add_argument("--kernel", choices=("auto", "wave", "lane"), default="auto",
@@ -193,6 +195,42 @@ def main():
         wa, wr = B.event_lists_peaks(ev_c, off_c)
         assert (oa[:64].cpu().numpy() == wa).all() and (orv[:64].cpu().numpy() == wr).all()
         del events
+
+    if args.full_traversal > 0:
+        nf = min(args.full_traversal, n)
+        ftab = M.Tables([T.llama_table(checkpoint=False)], m_base=const.m_base + (64 << 20), cu_p=const.cu_p,
+                        align=const.align)
+        for _ in range(2):
+            M.llmem_estimate_ex(dev, ftab, peaks, detail, n=nf)
+        torch.cuda.synchronize()
+        reps = 10
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            M.llmem_estimate_ex(dev, ftab, peaks, detail, n=nf)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        fforms = M.llmem_kernel_forms(ftab)
+        f_ops = algorithmic_lane_ops(fforms, 9)
+        f_achieved = f_ops * nf / (ms * 1e-3) / 1e12
+        ns = min(4096, nf)
+        fconst = T.Constants(m_base=const.m_base + (64 << 20), cu_p=const.cu_p, align=const.align)
+        want_p, want_d = B.estimate(G.grid4(n=ns, seed=0), [T.llama_table(checkpoint=False)], fconst, threads=4)
+        assert (peaks[:ns].cpu().numpy() == want_p).all() and (detail.view(-1)[:M.NDETAIL * nf].view(M.NDETAIL, nf)[:, :ns]
+                                                                .cpu().numpy().T == want_d).all(), \
+            "full-traversal output differs from the oracle"
+        result.setdefault("extra", {})["g4_full_traversal"] = {
+            "workload": "g4 with the Llama table without gradient checkpointing (every saved forward output alive "
+                        "until its backward), 64 MiB allocator buffer added to m_base; all detail columns",
+            "n_configs": nf, "ms_per_launch": ms, "configs_per_s": nf / (ms * 1e-3),
+            "table_events": len(T.llama_table(checkpoint=False).events), "table_terms": fforms["terms"],
+            "table_peak_points": fforms["peak_points"],
+            "roofline": {"bound": "alu", "achieved": f_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
+                         "frac": f_achieved / PEAK_LANE_TOPS, "traffic": None, "kernel": kernel_name,
+                         "algorithmic_lane_ops_per_config": f_ops},
+            "verified_vs_oracle": ns}
 
     if args.queries > 0:
         nq, m_total = args.queries, 80 << 30

@@ -114,6 +114,19 @@ def test_degenerate_and_flag_cases(U):
     _check(U, cfg, tabs)
 
 
+@pytest.mark.parametrize("name,n,first", [("g2", 64 * 100 + 3, 0), ("g3", 64 * 120 + 37, 400_000), ("g4", 64 * 60 + 1, 5_000_000)])
+def test_full_traversal_tables(U, name, n, first):
+    """The tables without gradient checkpointing (every saved forward output stays alive until
+    its backward: much longer live ranges, Sec. 3.1), alone and mixed with the checkpointed
+    table of the same family inside every wavefront."""
+    spec = G.GRIDS[name]
+    make = T.FAMILIES[spec["family"]]
+    cfg = spec["make"](n=n, seed=0, first=first)
+    _check(U, cfg, [make(checkpoint=False)], expect=BOTH)
+    cfg["arch_id"] = (np.arange(n) % 2).astype(np.uint8)
+    _check(U, cfg, [make(checkpoint=False), make()], CONST)
+
+
 def test_sizes_on_both_sides_of_2_to_31_blocks(U):
     """The compiled form walks 32-bit block counts while every size of a wavefront's 64
     configurations is below 2^31 allocator blocks, and 64-bit bytes otherwise: wavefronts

@@ -409,6 +409,59 @@ def test_table_timeline_against_block_simulation():
         assert r[O.D_LIVE] == peak * 512, (trial, c)
 
 
+@pytest.mark.parametrize("family", ("gpt", "llama"))
+def test_family_timelines_with_and_without_checkpointing(family):
+    """The family tables themselves, checkpointed and as the full traversal that keeps
+    every saved forward output (Sec. 3.1): the block simulator walks the explicit event
+    sequence of one iteration on top of the resident state; from two blocks on the full
+    traversal never peaks below the checkpointed one, and its forward alone already holds L blocks'
+    worth of saved tensors."""
+    pyrng = random.Random(8)
+    make = T.FAMILIES[family]
+    for trial in range(6):
+        h = pyrng.choice((64, 128))
+        c = cfg(bs=pyrng.randint(1, 3), sl=pyrng.choice((1, 7, 33)), h=h, n_heads=h // 32, n_kv=pyrng.choice((1, 2)),
+                ffn=pyrng.choice((96, 172)), V=pyrng.choice((50, 301)), P=pyrng.choice((0, 40)), L=pyrng.randint(0, 3),
+                method=pyrng.randint(0, 2), d=pyrng.randint(1, 4), flags=pyrng.randint(0, 7))
+        D = O.dim_vector(c)
+        peaks = {}
+        for checkpoint in (True, False):
+            t = make(checkpoint=checkpoint)
+            const = T.Constants(m_base=pyrng.choice((0, 5 * 512)))
+            r = est(c, t, const, True)
+            _, lm_p, _, _, _, _ = O.param_census(t, D, False)
+            trainable_extra = r[O.D_PEAK] - (O.estimate_one(dict(c, flags=c["flags"] | G.FLAG_GRAD_ALIAS), [t], const, False)[O.D_PEAK])
+            resident = const.m_base + r[O.D_PARAM] + r[O.D_OS] + lm_p * 2 + trainable_extra
+            live_blocks, peak, after_forward = [], 0, None
+            for s in ["A"] + ["F"] * c["L"] + ["H"] + ["B"] * c["L"] + ["Z"]:
+                if s == "H" and after_forward is None:
+                    after_forward = sum(live_blocks)
+                for e in t.events:
+                    if e.seg != s or c["method"] not in e.methods:
+                        continue
+                    raw = e.coef * e.elem_bytes
+                    for dname in e.dims:
+                        raw *= D[dname]
+                    if e.scale == "tp_gather":
+                        q, rem = divmod(raw * (c["d"] - 1), c["d"])
+                        raw = q + (1 if rem else 0)
+                    for _ in range(c["L"] if e.times_L else 1):
+                        if e.sign > 0:
+                            live_blocks.append(_blocks(raw))
+                        else:
+                            live_blocks.remove(_blocks(raw))
+                    peak = max(peak, sum(live_blocks))
+            assert not live_blocks
+            assert r[O.D_LIVE] == resident + peak * 512, (trial, checkpoint, c)
+            peaks[checkpoint] = (r[O.D_LIVE] - resident, after_forward * 512)
+        if c["L"] >= 2:
+            assert peaks[False][0] >= peaks[True][0]
+            # saved tensors of every block are alive when the forward ends; a checkpointed block keeps one output
+            x_bytes = _blocks(c["bs"] * c["sl"] * c["h"] * 2) * 512
+            assert peaks[True][1] <= (c["L"] + 2) * x_bytes
+            assert peaks[False][1] >= 10 * c["L"] * x_bytes
+
+
 # ---------------------------------------------------------------------------
 # error reporting of a single configuration
 # ---------------------------------------------------------------------------

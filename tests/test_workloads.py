@@ -12,9 +12,9 @@ def test_default_tables_are_balanced():
     goes negative, for every method (sizes unrounded; pure bookkeeping check)."""
     D = dict(one=1, bs=3, sl=17, sl_m1=16, h=64, ffn=172, n_heads=4, n_kv=2, head_dim=16, kv_dim=32,
              V=1000, P=40, L=5, B_logits=4, d=3)
-    for fam, make in T.FAMILIES.items():
-        t = make()
-        assert 250 <= len(t.events) <= 400
+    for fam, make, checkpoint in [(f, m, c) for f, m in T.FAMILIES.items() for c in (True, False)]:
+        t = make(checkpoint=checkpoint)
+        assert (250 if checkpoint else 190) <= len(t.events) <= 400
         segs = [e.seg for e in t.events]
         assert segs == sorted(segs, key=T.SEGMENTS.index)
         for method in (0, 1, 2):
@@ -31,6 +31,20 @@ def test_default_tables_are_balanced():
                     live += e.sign * v * (D["L"] if e.times_L else 1)
                     assert live >= 0
             assert live == 0
+
+
+def test_uncheckpointed_tables_keep_what_autograd_saves():
+    """Without checkpointing the forward of a block frees nothing that autograd saved: its net
+    change is the block output plus the saved tensors, far above the checkpointed block's one
+    kept output; the parameter entries are the same."""
+    for fam, make in T.FAMILIES.items():
+        full, ckpt = make(checkpoint=False), make()
+        assert full.params == ckpt.params and full.name == ckpt.name + "_full"
+        net = lambda t: sum(e.sign for e in t.events if e.seg == "F")
+        assert net(ckpt) == 1 and net(full) >= 15
+        # no recomputation: the backward segment holds no forward operator
+        assert not any(e.name.startswith("re:") for e in full.events)
+        assert any(e.name.startswith("re:") for e in ckpt.events)
 
 
 def test_grid_shapes_and_ranges():

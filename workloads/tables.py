@@ -19,6 +19,12 @@ checkpointing, written as signed allocator events in five segments:
             then the block's kept output is freed
   Z  once   release of what A/H/B left alive, optimizer temporaries
 
+With `checkpoint=False` the builders give the iteration without gradient
+checkpointing, the full traversal of the computation graph that Sec. 3.1
+describes for DNNMem: F allocates every operator output of a block and keeps
+what autograd saves (and the block output) alive, B is the backward alone, and
+nothing is recomputed, so live ranges span the whole forward pass.
+
 The per-family operator lists are synthetic stand-ins of the shape a graph
 extraction of GPT-2 / OPT / LLaMA style blocks yields (about 60 operators per
 block counting forward and recompute); they are inputs, not part of the method.
@@ -125,12 +131,27 @@ def _backward_events(ops: Sequence[Op], seg: str, x_size, tp_size) -> List[Event
     then drop the previous gradient and the saved activation.  Last, the block's
     kept output (its checkpoint) is released.
     """
+    out: List[EventEntry] = _saving_forward_events(ops, seg, "re:")
+    return out + _gradient_events(ops, seg, x_size, tp_size, free_checkpoint=True)
+
+
+def _saving_forward_events(ops: Sequence[Op], seg: str, prefix: str) -> List[EventEntry]:
+    """Forward of one block with autograd recording: every output is allocated, a
+    tensor is freed after its last consumer unless autograd saved it."""
     out: List[EventEntry] = []
     for i, o in enumerate(ops):
-        out.append(_ev("re:" + o.name, seg, +1, o.size))
+        out.append(_ev(prefix + o.name, seg, +1, o.size))
         for p in ops[: i + 1]:
             if p.last == o.name and not p.saved:
-                out.append(_ev("free:re:" + p.name, seg, -1, p.size))
+                out.append(_ev("free:" + prefix + p.name, seg, -1, p.size))
+    return out
+
+
+def _gradient_events(ops: Sequence[Op], seg: str, x_size, tp_size, free_checkpoint: bool) -> List[EventEntry]:
+    """The operators of one block in reverse (see `_backward_events`); what the
+    forward with autograd left alive is released on the way; with
+    `free_checkpoint` the block's separately kept output goes last."""
+    out: List[EventEntry] = []
     alive = [p for p in ops if p.saved or p.last not in {q.name for q in ops}]
     alive_names = {p.name for p in alive}
     # the incoming gradient dY (size of the block output) was allocated before
@@ -148,7 +169,8 @@ def _backward_events(ops: Sequence[Op], seg: str, x_size, tp_size) -> List[Event
     assert prev[1] == x_size, "first operator of a block must have the block-input size"
     out.append(_ev("tp_allgather_buf", seg, +1, tp_size,
                    methods=frozenset((2,)), scale="tp_gather"))
-    out.append(_ev("free:kept_block_output", seg, -1, x_size))
+    if free_checkpoint:
+        out.append(_ev("free:kept_block_output", seg, -1, x_size))
     return out
 
 
@@ -313,7 +335,8 @@ def _tail_events(n_embed: int, opt_tmp) -> List[EventEntry]:
     return ev
 
 
-def _assemble(name: str, params: List[ParamEntry], n_embed: int, block: List[Op], norm: str) -> ArchTable:
+def _assemble(name: str, params: List[ParamEntry], n_embed: int, block: List[Op], norm: str,
+              checkpoint: bool = True) -> ArchTable:
     block = _fix_first(block)
     ev: List[EventEntry] = []
     for i in range(n_embed):
@@ -321,9 +344,14 @@ def _assemble(name: str, params: List[ParamEntry], n_embed: int, block: List[Op]
     if n_embed > 1:
         ev.append(_ev("embed_sum", "A", +1, _X()))
         ev.append(_ev("free:embed_sum", "A", -1, _X()))
-    ev += _forward_events(block, "F", block[-1].name)
-    ev += _head_events(norm)
-    ev += _backward_events(block, "B", _X(), _X())
+    if checkpoint:
+        ev += _forward_events(block, "F", block[-1].name)
+        ev += _head_events(norm)
+        ev += _backward_events(block, "B", _X(), _X())
+    else:
+        ev += _saving_forward_events(block, "F", "")
+        ev += _head_events(norm)
+        ev += _gradient_events(block, "B", _X(), _X(), free_checkpoint=False)
     ev += _tail_events(n_embed, (1, ("V", "h"), 4))
     return ArchTable(name, tuple(params), tuple(ev))
 
@@ -371,19 +399,19 @@ def _llama_params() -> List[ParamEntry]:
     ]
 
 
-def gpt_table() -> ArchTable:
+def gpt_table(checkpoint: bool = True) -> ArchTable:
     """GPT-2 style: learned positions, biases, LayerNorm, tanh-GELU MLP."""
-    return _assemble("gpt", _gpt_params(), 2, _gpt_block("gelu"), "layernorm")
+    return _assemble("gpt" if checkpoint else "gpt_full", _gpt_params(), 2, _gpt_block("gelu"), "layernorm", checkpoint)
 
 
-def opt_table() -> ArchTable:
+def opt_table(checkpoint: bool = True) -> ArchTable:
     """OPT style: as GPT but a ReLU MLP."""
-    return _assemble("opt", _gpt_params(), 2, _gpt_block("relu"), "layernorm")
+    return _assemble("opt" if checkpoint else "opt_full", _gpt_params(), 2, _gpt_block("relu"), "layernorm", checkpoint)
 
 
-def llama_table() -> ArchTable:
+def llama_table(checkpoint: bool = True) -> ArchTable:
     """LLaMA style: RMSNorm, rotary embedding, grouped-query attention, SwiGLU, no biases."""
-    return _assemble("llama", _llama_params(), 1, _llama_block(), "rmsnorm")
+    return _assemble("llama" if checkpoint else "llama_full", _llama_params(), 1, _llama_block(), "rmsnorm", checkpoint)
 
 
 def degenerate_table(base: ArchTable) -> ArchTable:
