@@ -6,7 +6,7 @@ all detail columns (component sizes, chosen chunk, timeline peak).  Inputs are
 generated on the device beforehand and stay resident in HBM.  The explicit
 event-list kernel is timed on its own 10^5-list grid and reported under "extra".
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line.
 """
 import argparse
 import json
@@ -34,7 +34,7 @@ def algorithmic_lane_ops(forms, n_candidates):
     timeline reduced to the peak points no other point dominates), priced in gfx950 vector
     instructions: add/sub 1, 32x32->64 multiply 1, multiply of a 64-bit value by a 32-bit one 3,
     round up to a power of two 3, compare-and-select (max) 3, ceil-divide by d 12.
-    `forms` = llmem_kernel_forms of the tables.  Derivation in the design doc, section 6."""
+    `forms` = llmem_kernel_forms of the tables."""
     ADD, MUL32, MUL, UP, MAX, DIV = 1, 1, 3, 3, 3, 12
     per_group = MUL32 + MUL + (MUL32 + MUL + ADD) + (ADD + UP + MUL32 + MUL + ADD) + MAX   # expression, role sum, m_os, t_max
     per_class = MUL32 + 2 * MUL + UP + ADD                                                 # expression, block round-up, store
@@ -81,7 +81,7 @@ def main():
                     help="only run a plain 1 GiB device copy ten times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; nothing is sharded and there are no collectives "
+        print("bench.py: the library runs on one GPU; nothing is sharded and there are no collectives "
               "(--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
 

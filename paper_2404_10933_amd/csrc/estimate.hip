@@ -349,17 +349,29 @@ static int log2_exact(int64_t v)
 }
 
 // Size expression as the compiled tables carry it: the selectors that are not LLMEM_DIM_ONE and
-// their number.  `sorted_dims` holds four selectors in ascending order, one per byte.
+// their number.  `sorted_dims` holds four selectors in ascending order, one per byte.  One batch
+// size and one sequence length together become the selector DIM_BS_SL of their product, which
+// the kernel keeps ready (both are below 2^16, so it fits 32 bits): one multiplication less.
 static uint32_t descriptor_of(uint32_t sorted_dims)
 {
-    uint32_t desc = 0, n = 0;
+    uint32_t sel[4], n = 0;
+    bool has_bs = false, has_sl = false;
     for (int q = 0; q < 4; ++q) {
-        const uint32_t sel = (sorted_dims >> (8 * q)) & 15u;
-        if (sel == LLMEM_DIM_ONE) continue;
-        desc |= sel << (4 + 4 * n);
-        ++n;
+        const uint32_t v = (sorted_dims >> (8 * q)) & 15u;
+        has_bs = has_bs || v == LLMEM_DIM_BS;
+        has_sl = has_sl || v == LLMEM_DIM_SL;
     }
-    return desc | n;
+    bool pair = has_bs && has_sl, bs_done = false, sl_done = false;
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t v = (sorted_dims >> (8 * q)) & 15u;
+        if (v == LLMEM_DIM_ONE) continue;
+        if (pair && v == LLMEM_DIM_BS && !bs_done) { bs_done = true; sel[n++] = DIM_BS_SL; continue; }
+        if (pair && v == LLMEM_DIM_SL && !sl_done) { sl_done = true; continue; }
+        sel[n++] = v;
+    }
+    uint32_t desc = n;
+    for (uint32_t q = 0; q < n; ++q) desc |= sel[q] << (4 + 4 * q);
+    return desc;
 }
 
 // Compiles the tables of one architecture for the lane-per-configuration kernel: parameter

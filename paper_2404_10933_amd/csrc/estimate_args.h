@@ -49,6 +49,8 @@ constexpr unsigned DESC_TP_GATHER = 1u << 20, DESC_TIMES_L = 1u << 21;
 constexpr int DESC_MASK_SHIFT = 22, DESC_NEG_SLOT_SHIFT = 25;
 constexpr int PROG_SLOT_MAX = 100;
 constexpr int PROG_WORDS = 704;
+constexpr int DIM_BS_SL = 15;                  // selector of bs * sl in the compiled descriptors (after the LLMEM_DIM_* ones)
+static_assert(LLMEM_NDIM == DIM_BS_SL, "the product's selector follows the public ones");
 constexpr int PROG_HEADER = 8;
 constexpr int PROG_GROUP = 4;
 constexpr int PROG_CLASS_FETCH = 4;            // classes the list is padded to and read by

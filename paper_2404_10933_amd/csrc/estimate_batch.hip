@@ -187,7 +187,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
         D[LLMEM_DIM_HEAD_DIM] = head_dim; D[LLMEM_DIM_KV_DIM] = n_kv * head_dim; D[LLMEM_DIM_V] = V;
         D[LLMEM_DIM_P] = P; D[LLMEM_DIM_L] = L;
         const u32 Blog = (cflags & LLMEM_CFG_LOGITS_FP32) ? B32 : B16;
-        D[LLMEM_DIM_B_LOGITS] = Blog; D[LLMEM_DIM_D] = d; D[15] = 0;
+        D[LLMEM_DIM_B_LOGITS] = Blog; D[LLMEM_DIM_D] = d; D[DIM_BS_SL] = bs * sl;        // both below 2^16
         const u64 div_mul = div_mul_of[d & 255u];
         const u32 div_shift = d > 1 ? 31u - (u32)__builtin_clz(d - 1) : 0u;        // ceil(log2 d) - 1
 
@@ -390,9 +390,16 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                                 u64 x = expression(cw[2 * u], desc);
                                 if (desc & DESC_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
                                 u64 r = (x + ((1ull << align_shift) - 1)) >> align_shift;         // blocks
-                                if (desc & DESC_TIMES_L) r *= (u64)L;
+                                // the rare descriptor flags are wave-uniform: real branches, no selects
+                                if (desc & DESC_TIMES_L) {
+                                    asm volatile("" ::: "memory");
+                                    r *= (u64)L;
+                                }
                                 const u32 mask = (desc >> DESC_MASK_SHIFT) & 7u;
-                                if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
+                                if (mask != 7u) {
+                                    asm volatile("" ::: "memory");
+                                    r = ((mask >> method) & 1u) ? r : 0ull;
+                                }
                                 const u32 neg = desc >> DESC_NEG_SLOT_SHIFT;
                                 if (NARROW) {
                                     seen |= r;
