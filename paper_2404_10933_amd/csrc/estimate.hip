@@ -16,6 +16,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "../../include/llmem.h"
@@ -414,6 +415,21 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
     }
     const int nc = (int)classes.size();
     if (nc > CLS_MAX || groups.size() > 255 || e_n > 255) return false;
+    // Classes with the same dimensions become neighbours, the smaller coefficient * element width
+    // first: where the next one's is 2^k times as large, its raw size is the previous one shifted.
+    {
+        std::vector<int> order(nc), place(nc);
+        for (int c = 0; c < nc; ++c) order[c] = c;
+        auto c64_of = [&](int c) { return (uint64_t)classes[c].coef * (classes[c].meta & 255u); };
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+            if (classes[a].dims != classes[b].dims) return classes[a].dims < classes[b].dims;
+            return c64_of(a) < c64_of(b);
+        });
+        std::vector<ClassKey> sorted(nc);
+        for (int q = 0; q < nc; ++q) { sorted[q] = classes[order[q]]; place[order[q]] = q; }
+        classes = sorted;
+        for (int j = 0; j < n_event; ++j) cls_of[j] = place[cls_of[j]];
+    }
     al->prog_first = (int)prog->size();
     prog->push_back((uint32_t)groups.size() | (e_n << 8) | ((uint32_t)nc << 16));
     for (int q = 1; q < PROG_HEADER; ++q) prog->push_back(0u);     // segment boundaries, filled in below
@@ -459,8 +475,14 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
         const uint64_t c64 = (uint64_t)k.coef * (k.meta & 255u);   // coefficient * element bytes
         if (c64 >> 32) return false;
         const uint32_t flags = (k.meta >> 8) & 255u, mask = (k.meta >> 16) & 7u;
-        prog->push_back((uint32_t)c64);
-        prog->push_back(descriptor_of(k.dims) | ((flags & LLMEM_EV_TP_GATHER) ? DESC_TP_GATHER : 0u)
+        uint32_t first_word = (uint32_t)c64, size_desc = descriptor_of(k.dims);
+        if (c > 0 && classes[c - 1].dims == k.dims) {
+            const uint64_t before = (uint64_t)classes[c - 1].coef * (classes[c - 1].meta & 255u);
+            for (uint32_t shift = 0; shift < 32 && before != 0; ++shift)
+                if (before << shift == c64) { first_word = shift; size_desc = DESC_FROM_PREVIOUS; break; }
+        }
+        prog->push_back(first_word);
+        prog->push_back(size_desc | ((flags & LLMEM_EV_TP_GATHER) ? DESC_TP_GATHER : 0u)
                         | ((flags & LLMEM_EV_TIMES_L) ? DESC_TIMES_L : 0u) | (mask << DESC_MASK_SHIFT)
                         | ((uint32_t)neg_slot[c] << DESC_NEG_SLOT_SHIFT));
     }

@@ -46,6 +46,8 @@ constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
 // DESC_TP_GATHER, DESC_TIMES_L, method mask (3 bits from DESC_MASK_SHIFT), slot of the negated
 // value (from DESC_NEG_SLOT_SHIFT, 0 = none).
 constexpr unsigned DESC_TP_GATHER = 1u << 20, DESC_TIMES_L = 1u << 21;
+constexpr unsigned DESC_FROM_PREVIOUS = 7;     // in place of the number of dimensions: the previous class's raw
+                                               // size shifted left by the first word
 constexpr int DESC_MASK_SHIFT = 22, DESC_NEG_SLOT_SHIFT = 25;
 constexpr int PROG_SLOT_MAX = 100;
 constexpr int PROG_WORDS = 704;

@@ -377,7 +377,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                     auto store_classes = [&](auto narrow) -> u64 {
                         constexpr bool NARROW = decltype(narrow)::value;
                         char *row = vals + (NARROW ? lane * 4 : (lane & 31) * 8);
-                        u64 seen = 0;
+                        u64 seen = 0, raw_before = 0;
                         int at_word = pc_classes;
                         for (int c0 = 0; c0 < nc; c0 += PROG_CLASS_FETCH, at_word += 2 * PROG_CLASS_FETCH) {
                             u32 cw[2 * PROG_CLASS_FETCH];
@@ -387,7 +387,14 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                             for (int u = 0; u < PROG_CLASS_FETCH; ++u) {
                                 const int c = c0 + u;
                                 const u32 desc = cw[2 * u + 1];
-                                u64 x = expression(cw[2 * u], desc);
+                                u64 x;
+                                if ((desc & 7u) == DESC_FROM_PREVIOUS) {
+                                    asm volatile("" ::: "memory");
+                                    x = raw_before << cw[2 * u];              // same dimensions, 2^k times the coefficient
+                                } else {
+                                    x = expression(cw[2 * u], desc);
+                                }
+                                raw_before = x;
                                 if (desc & DESC_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
                                 u64 r = (x + ((1ull << align_shift) - 1)) >> align_shift;         // blocks
                                 // the rare descriptor flags are wave-uniform: real branches, no selects
