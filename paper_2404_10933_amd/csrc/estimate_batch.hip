@@ -48,6 +48,15 @@ __device__ __forceinline__ u64 b_div(u64 x, u32 d, u64 mul, u32 shift)
 }
 __device__ __forceinline__ u64 b_cdiv(u64 x, u32 d, u64 mul, u32 shift) { return b_div(x + (d - 1), d, mul, shift); }
 __device__ __forceinline__ u64 b_up(u64 x, int shift) { return ((x + ((1ull << shift) - 1)) >> shift) << shift; }
+// x * m (mod 2^64) in three instructions: the 64-bit product of the low half, the low 32 bits of
+// the high half's product (kept as one v_mul_lo_u32, which issues at full rate on gfx950), one add
+__device__ __forceinline__ u64 mul_64x32(u64 x, u32 m)
+{
+    const u64 lo = (u64)(u32)x * (u64)m;
+    u32 hi_part;
+    asm("v_mul_lo_u32 %0, %1, %2" : "=v"(hi_part) : "v"((u32)(x >> 32)), "v"(m));
+    return ((u64)(hi_part + (u32)(lo >> 32)) << 32) | (u64)(u32)lo;
+}
 __device__ __forceinline__ u32 uni(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
 
 }  // namespace
@@ -208,9 +217,9 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                 const u32 nd = desc & 7u;
                 u64 x = coef;
                 if (nd > 0) x = (u64)coef * D[(desc >> 4) & 15u];
-                if (nd > 1) x *= D[(desc >> 8) & 15u];
-                if (nd > 2) x *= D[(desc >> 12) & 15u];
-                if (nd > 3) x *= D[(desc >> 16) & 15u];
+                if (nd > 1) x = mul_64x32(x, D[(desc >> 8) & 15u]);
+                if (nd > 2) x = mul_64x32(x, D[(desc >> 12) & 15u]);
+                if (nd > 3) x = mul_64x32(x, D[(desc >> 16) & 15u]);
                 return x;
             };
             // ---- parameter table (Notation table; Sec. 4.2, equation for m_os) ---------
@@ -395,12 +404,12 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                                     x = expression(cw[2 * u], desc);
                                 }
                                 raw_before = x;
-                                if (desc & DESC_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
+                                if (desc & DESC_TP_GATHER) x = b_cdiv(mul_64x32(x, d - 1), d, div_mul, div_shift);
                                 u64 r = (x + ((1ull << align_shift) - 1)) >> align_shift;         // blocks
                                 // the rare descriptor flags are wave-uniform: real branches, no selects
                                 if (desc & DESC_TIMES_L) {
                                     asm volatile("" ::: "memory");
-                                    r *= (u64)L;
+                                    r = mul_64x32(r, L);
                                 }
                                 const u32 mask = (desc >> DESC_MASK_SHIFT) & 7u;
                                 if (mask != 7u) {
