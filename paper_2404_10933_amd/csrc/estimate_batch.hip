@@ -64,7 +64,7 @@ __device__ __forceinline__ u32 uni(u32 v) { return (u32)__builtin_amdgcn_readfir
 // COMPILED: the tables come compiled in the kernel arguments (else the kernel reads the entries
 // from memory and walks every event)
 template <bool DETAIL, bool COMPILED>
-__global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const EstimateArgs a)
+__global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) void estimate_batch_kernel(const EstimateArgs a)
 {
     extern __shared__ uint4 lds[];
     // multipliers of the divisions by the partition degree: a lane looks its own d up, from LDS
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
         else *reinterpret_cast<i64 *>(vals) = 0;
     }
 
-    // the columns of one configuration as loaded; the next batch's are fetched while this one is worked on
+    // the columns of one configuration as loaded
     struct Raw { u32 h, ffn, V, P, arch_id, method, d, cflags, L, n_heads, n_kv, bs, sl; int chunk_k; };
     auto fetch = [&](long long batch) -> Raw {
         Raw r = {1, 0, 0, 0, 0, 0, 1, 0, 0, 1, 0, 0, 0, 0};
@@ -166,17 +166,10 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
     };
     const long long b_step = (long long)gridDim.x * BB_WAVES;
     long long b = (long long)blockIdx.x * BB_WAVES + wave;
-    Raw ahead = fetch(b);
-    // the first batch's columns have arrived before the loop starts, so that inside the loop only
-    // the batch fetched one iteration earlier is ever waited for
-    asm volatile("" :: "v"(ahead.h), "v"(ahead.ffn), "v"(ahead.V), "v"(ahead.P), "v"(ahead.arch_id), "v"(ahead.method),
-                 "v"(ahead.d), "v"(ahead.cflags), "v"(ahead.L), "v"(ahead.n_heads), "v"(ahead.n_kv), "v"(ahead.bs),
-                 "v"(ahead.sl), "v"(ahead.chunk_k));
     for (; b < n_batch; b += b_step) {
         const long long i = (b << 6) + lane;
         const bool in_range = i < n;
-        const Raw now = ahead;
-        ahead = fetch(b + b_step);
+        const Raw now = fetch(b);
         const u32 h = now.h, ffn = now.ffn, V = now.V, P = now.P, arch_id = now.arch_id, method = now.method, d = now.d,
                   cflags = now.cflags, L = now.L, n_heads = now.n_heads, n_kv = now.n_kv, bs = now.bs, sl = now.sl;
         const int chunk_k = now.chunk_k;
@@ -299,7 +292,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
             // that one.
             const bool search = chunk_k == -1;
             const bool any_search = __builtin_amdgcn_ballot_w64(search) != 0;
-            u64 m_peak = 0, mp = 0, mp16 = 0, mp32 = 0, best_waste = ~0ull;
+            u64 m_peak = 0, best_waste = ~0ull;
             int k_used = search ? K_SEARCH_MAX : chunk_k;
             bool found = !search;
             for (int j = 0; j <= K_SEARCH_MAX - K_SEARCH_MIN; ++j) {
@@ -326,7 +319,7 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
                 const bool take = search ? ((feasible && waste < best_waste) || (!found && j == K_SEARCH_MAX - K_SEARCH_MIN))
                                          : j == 0;
                 if (take) {
-                    m_peak = c_peak; mp = c_p; mp16 = c_p16; mp32 = c_p32; k_used = k;
+                    m_peak = c_peak; k_used = k;
                     if (feasible) { best_waste = waste; found = true; }
                 }
             }
@@ -334,6 +327,12 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
             r_peak = (i64)m_peak;
 
             if (DETAIL) {
+                // m_p, m_p16, m_p32 of the chunk size used (formed again here rather than carried
+                // through the candidates: fewer live registers)
+                const u64 used_mask = (1ull << (k_used + 19)) - 1;
+                const u64 used_chunked = embed_p + ((other_p + used_mask) & ~used_mask);
+                const u64 mp = b_up(used_chunked * (B16 + B32), cu_shift), mp16 = b_up(used_chunked * B16, cu_shift),
+                          mp32 = b_up(used_chunked * B32, cu_shift);
                 u64 param_gpu, os_gpu;
                 if (method == LLMEM_METHOD_CDP) {
                     param_gpu = mp; os_gpu = m_os;
@@ -541,11 +540,6 @@ __global__ __launch_bounds__(BB_BLOCK) void estimate_batch_kernel(const Estimate
             }
         }
 
-        // wait for the next batch's columns here, before this batch's stores are issued: memory
-        // operations complete in order, so waiting after the stores would wait for them as well
-        asm volatile("" :: "v"(ahead.h), "v"(ahead.ffn), "v"(ahead.V), "v"(ahead.P), "v"(ahead.arch_id), "v"(ahead.method),
-                     "v"(ahead.d), "v"(ahead.cflags), "v"(ahead.L), "v"(ahead.n_heads), "v"(ahead.n_kv), "v"(ahead.bs),
-                     "v"(ahead.sl), "v"(ahead.chunk_k));
         if (in_range) {
             if (a.out_peaks) a.out_peaks[i] = r_peak;
             if (DETAIL) {
