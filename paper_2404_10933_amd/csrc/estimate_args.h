@@ -56,7 +56,7 @@ static_assert(LLMEM_NDIM == DIM_BS_SL, "the product's selector follows the publi
 constexpr int PROG_HEADER = 8;
 constexpr int PROG_GROUP = 4;
 constexpr int PROG_CLASS_FETCH = 4;            // classes the list is padded to and read by
-constexpr int PROG_FETCH = 16;                  // words a segment's term list is padded to and read by
+constexpr int PROG_FETCH = 8;                   // words a segment's term list is padded to and read by
 constexpr int SLOT_ROW = 256;                   // bytes of LDS per value slot and wavefront in the compiled form
 constexpr unsigned PROG_OFFSET_MASK = 0xff00, PROG_END_POINT = 0x1, PROG_END_SEGMENT = 0x2;
 constexpr size_t BATCH_LDS_LIMIT = 62 * 1024;  // dynamic LDS a launch may ask for (the kernel has 2 KB of its own)

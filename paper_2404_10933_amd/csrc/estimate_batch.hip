@@ -429,7 +429,7 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                         }
                         return seen;
                     };
-                    // Sums of count * value, four groups of four terms per fetch, no branches but one: a
+                    // Sums of count * value, PROG_FETCH terms per fetch in groups of four, no branches but one: a
                     // group flagged as a point's end lets its sum compete for the segment's maximum; the
                     // group that ends a segment's net change closes the segment.
                     auto walk_terms = [&](auto narrow) {
