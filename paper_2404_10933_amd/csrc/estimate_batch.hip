@@ -295,6 +295,7 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
             u64 m_peak = 0, best_waste = ~0ull;
             int k_used = search ? K_SEARCH_MAX : chunk_k;
             bool found = !search;
+            const u64 rest = m_base + m_out + m_lm + grad_extra;               // the same for every candidate
             for (int j = 0; j <= K_SEARCH_MAX - K_SEARCH_MIN; ++j) {
                 if (j > 0 && !any_search) break;
                 const int k = search ? K_SEARCH_MIN + j : chunk_k;
@@ -302,16 +303,17 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                 const u64 cs_mask = (1ull << cs_shift) - 1;
                 const u64 other_chunked = (other_p + cs_mask) & ~cs_mask;     // ceil(other_p / cs) * cs
                 const u64 chunked = embed_p + other_chunked;
-                const u64 c_p = b_up(chunked * (B16 + B32), cu_shift);
-                const u64 c_p16 = b_up(chunked * B16, cu_shift);
-                const u64 c_p32 = b_up(chunked * B32, cu_shift);
-                const u64 to_shard = method == LLMEM_METHOD_ZERO3 ? c_p32 + m_os : c_p + m_os;
+                // ZeRO-3 shards m_p32 and keeps m_p16 whole; the other two methods use m_p = 6 bytes per element
+                const bool zero3 = method == LLMEM_METHOD_ZERO3;
+                const u64 wide_part = b_up((chunked << 2) + (zero3 ? 0ull : chunked << 1), cu_shift);   // m_p32 or m_p
+                const u64 c_p16 = b_up(chunked << 1, cu_shift);
+                const u64 to_shard = wide_part + m_os;
                 const u64 shard = b_up(b_cdiv(to_shard, d, div_mul, div_shift), align_shift);
                 u64 states;
-                if (method == LLMEM_METHOD_CDP) states = c_p + m_os;
-                else if (method == LLMEM_METHOD_ZERO3) states = c_p16 + shard;
+                if (method == LLMEM_METHOD_CDP) states = to_shard;
+                else if (zero3) states = c_p16 + shard;
                 else states = shard + m_back;
-                const u64 c_peak = m_base + states + m_out + m_lm + grad_extra;
+                const u64 c_peak = rest + states;
                 const u64 waste = other_chunked - other_p;
                 const bool feasible = t_max <= (1ull << cs_shift);
                 // search lanes: strictly smaller waste among feasible candidates; the last candidate
