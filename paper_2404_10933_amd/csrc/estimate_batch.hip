@@ -599,8 +599,8 @@ void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batc
         per_cu = 1;
     long long blocks = (n_batch + BB_WAVES - 1) / BB_WAVES;
     // the compiled form has next to no set-up per workgroup: several times more workgroups than
-    // stay resident at once let the dispatcher even out the compute units (measured: 8 is enough)
-    const long long resident = (long long)per_cu * cu_count * (args.use_program ? 8 : 1);
+    // stay resident at once let the dispatcher even out the compute units (measured: 16 is best)
+    const long long resident = (long long)per_cu * cu_count * (args.use_program ? 16 : 1);
     if (blocks > resident) blocks = resident;
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
 }
