@@ -23,7 +23,7 @@ PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12       # 256 CUs x one 64-lane vector in
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs under profiles/, scaled by the
 # plain-copy reference; None while the kernel has changed since the counters were taken
-TRAFFIC_ESTIMATE = 1.3519e9     # 10^7 configurations, all detail columns
+TRAFFIC_ESTIMATE = 1.3514e9     # 10^7 configurations, all detail columns
 TRAFFIC_TIMELINE = 8.0201e9     # 100 000 event lists, 1 000 110 810 events
 TRAFFIC_DECIDE = 5.4014e8       # 4 000 000 queries, all decision columns
 
