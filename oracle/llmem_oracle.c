@@ -14,6 +14,7 @@
  *   Sec. 2.1 / Sec. 3.1  timeline traversal with live tensors, 512-byte blocks
  *   Sec. 5    m_peak^{dp+tp}
  *   Sec. 6    Algorithm 1 (largest batch size per method, scores, choice)
+ *   Sec. 6    the statistics of a whole grid per (method, gpu_n): llmem_oracle_sweep
  *
  * The timeline is walked event by event, block by block; no closed form over the
  * L equal blocks is used here.
@@ -415,6 +416,51 @@ int llmem_oracle_decide(const o_configs *cfg, const uint8_t *tp_n, int64_t n, co
         any_ovf |= ovf;
     }
     return any_ovf;
+}
+
+/* ---- sweep: statistics of estimated configurations per (method, gpu_n) ---------------- */
+
+enum { SWEEP_D_MAX = 16, SWEEP_GROUPS = 48, NSWEEP = 8, SWEEP_INDEX_BITS = 40 };
+enum { S_COUNT, S_FIT, S_MAX_PEAK, S_MIN_PEAK, S_MAX_LIVE, S_BEST, S_K_SUM, S_MAX_NPARAMS_FIT };
+
+/* detail: the n rows that llmem_oracle_estimate wrote for cfg; configuration j has index
+ * first + j in its grid.  stats: NSWEEP columns of SWEEP_GROUPS values, column-major
+ * (stats[column * SWEEP_GROUPS + group]).  Returns 0, or 2 if an index does not fit 40 bits. */
+int llmem_oracle_sweep(const o_configs *cfg, int64_t n, int64_t first, const int64_t *detail,
+                       int64_t m_total, int64_t *stats)
+{
+    int64_t best_score[SWEEP_GROUPS], best_index[SWEEP_GROUPS];
+    if (first < 0 || first + n > ((int64_t)1 << SWEEP_INDEX_BITS)) return 2;
+    for (int q = 0; q < NSWEEP * SWEEP_GROUPS; ++q) stats[q] = 0;
+    for (int g = 0; g < SWEEP_GROUPS; ++g) {
+        stats[S_MIN_PEAK * SWEEP_GROUPS + g] = INT64_MAX;
+        best_score[g] = -1;
+        best_index[g] = 0;
+    }
+    for (int64_t j = 0; j < n; ++j) {
+        const int64_t *row = detail + j * NDETAIL;
+        const int method = cfg->method[j], d = cfg->d[j];
+        const int err_mask = ERR_ARCH | ERR_METHOD | ERR_D | ERR_HEADS | ERR_CHUNK | ERR_TP;
+        if (row[D_PEAK] < 0 || (row[D_FLAGS] & err_mask) || d > SWEEP_D_MAX) continue;
+        const int g = method * SWEEP_D_MAX + (d - 1);
+        int64_t *at = stats + g;
+        at[S_COUNT * SWEEP_GROUPS] += 1;
+        if (row[D_PEAK] > at[S_MAX_PEAK * SWEEP_GROUPS]) at[S_MAX_PEAK * SWEEP_GROUPS] = row[D_PEAK];
+        if (row[D_PEAK] < at[S_MIN_PEAK * SWEEP_GROUPS]) at[S_MIN_PEAK * SWEEP_GROUPS] = row[D_PEAK];
+        if (row[D_LIVE] > at[S_MAX_LIVE * SWEEP_GROUPS]) at[S_MAX_LIVE * SWEEP_GROUPS] = row[D_LIVE];
+        at[S_K_SUM * SWEEP_GROUPS] += row[D_K];
+        if (row[D_PEAK] > m_total) continue;
+        at[S_FIT * SWEEP_GROUPS] += 1;
+        if (row[D_NPARAMS] > at[S_MAX_NPARAMS_FIT * SWEEP_GROUPS]) at[S_MAX_NPARAMS_FIT * SWEEP_GROUPS] = row[D_NPARAMS];
+        const int64_t bs = cfg->bs[j];
+        const int64_t score2 = method == 0 ? 3 * bs * d : method == 1 ? 2 * bs * d : 2 * bs;
+        if (score2 > best_score[g]) { best_score[g] = score2; best_index[g] = first + j; }   /* j ascends: ties keep the lower index */
+    }
+    for (int g = 0; g < SWEEP_GROUPS; ++g)
+        if (best_score[g] >= 0)
+            stats[S_BEST * SWEEP_GROUPS + g] = (best_score[g] << SWEEP_INDEX_BITS)
+                                               | ((((int64_t)1 << SWEEP_INDEX_BITS) - 1) - best_index[g]);
+    return 0;
 }
 
 /* Explicit event lists: signed raw sizes, CSR offsets.  512-byte blocks; two

@@ -19,6 +19,9 @@ What is computed, with the passage each function follows:
   Sec. 5     m_peak^{dp+tp} (combination of DP and TP)              -> `hybrid_peak`, `method_peaks`
   Sec. 6     Algorithm 1: largest batch size per method under the
              GPU's capacity, scores, choice of the method           -> `decide_one`
+  Sec. 6     the same questions asked of a whole grid of configurations at
+             once (how many fit, the extremes, the best-scoring one that
+             fits, per method and gpu_n)                            -> `sweep`
 
 Readings adopted where the paper is silent (each is listed in the design notes):
 sizes named "param size" are element counts; ceil(x * a / b) is one exact rational
@@ -460,6 +463,88 @@ def decide_one(q: Dict[str, int], tp_n: int, tables: Sequence, const, m_total: i
     row[C_PEAK] = peak_at[method] if method < 4 else 0
     row[C_FLAGS] = flags | (FALLBACK_READINGS_DIFFER if differ else 0)
     return row
+
+
+# ---------------------------------------------------------------------------
+# sweep: statistics of a grid of configurations per (method, gpu_n)
+# ---------------------------------------------------------------------------
+SWEEP_D_MAX = 16
+SWEEP_GROUPS = 3 * SWEEP_D_MAX       # group = method * 16 + (gpu_n - 1)
+(S_COUNT, S_FIT, S_MAX_PEAK, S_MIN_PEAK, S_MAX_LIVE, S_BEST, S_K_SUM, S_MAX_NPARAMS_FIT) = range(8)
+NSWEEP = 8
+SWEEP_INDEX_BITS = 40                # indices below 2^40
+SWEEP_NONE = INT64_MAX               # S_MIN_PEAK of a group without configurations
+
+
+def config_score2(method: int, bs: int, gpu_n: int) -> int:
+    """Algorithm 1's score of one configuration, doubled: the batch processed per
+    step over all GPUs, times 1.5 for conventional DP; a TP group processes one
+    batch whatever its size."""
+    return [3 * bs * gpu_n, 2 * bs * gpu_n, 2 * bs][method]
+
+
+def pack_best(score2: int, index: int) -> int:
+    """One int64 that orders (higher score, then lower index) as plain numbers."""
+    assert 0 <= index < (1 << SWEEP_INDEX_BITS) and 0 <= score2 < (1 << 23)
+    return (score2 << SWEEP_INDEX_BITS) | ((1 << SWEEP_INDEX_BITS) - 1 - index)
+
+
+def unpack_best(best: int) -> Tuple[int, int]:
+    return best >> SWEEP_INDEX_BITS, (1 << SWEEP_INDEX_BITS) - 1 - (best & ((1 << SWEEP_INDEX_BITS) - 1))
+
+
+def sweep_rows(indices: Sequence[int], cfg: Dict[str, Sequence[int]], rows: Sequence[Sequence[int]],
+               m_total: int) -> List[List[int]]:
+    """Folds estimated configurations (`rows[j]` = detail row of configuration j,
+    whose index in the grid is `indices[j]`) into NSWEEP statistics per group:
+    how many there are, how many have m_peak <= m_total (Algorithm 1's test), the
+    largest and smallest m_peak, the largest peak of the timeline, the
+    best-scoring configuration that fits (ties: the lowest index; 0 if none), the
+    sum of the chunk exponents used, the largest parameter count that fits.  A
+    configuration with an input error, or with gpu_n above 16, counts nowhere.
+    Returns stats[column][group]."""
+    stats = [[0] * SWEEP_GROUPS for _ in range(NSWEEP)]
+    stats[S_MIN_PEAK] = [SWEEP_NONE] * SWEEP_GROUPS
+    best = [None] * SWEEP_GROUPS                 # (score2, index) of the best one that fits
+    for j, row in enumerate(rows):
+        method, d, bs = int(cfg["method"][j]), int(cfg["d"][j]), int(cfg["bs"][j])
+        if row[D_PEAK] < 0 or row[D_FLAGS] & ERR_MASK or d > SWEEP_D_MAX:
+            continue
+        g = method * SWEEP_D_MAX + (d - 1)
+        stats[S_COUNT][g] += 1
+        stats[S_MAX_PEAK][g] = max(stats[S_MAX_PEAK][g], row[D_PEAK])
+        stats[S_MIN_PEAK][g] = min(stats[S_MIN_PEAK][g], row[D_PEAK])
+        stats[S_MAX_LIVE][g] = max(stats[S_MAX_LIVE][g], row[D_LIVE])
+        stats[S_K_SUM][g] += row[D_K]
+        if row[D_PEAK] <= m_total:
+            stats[S_FIT][g] += 1
+            stats[S_MAX_NPARAMS_FIT][g] = max(stats[S_MAX_NPARAMS_FIT][g], row[D_NPARAMS])
+            score2, index = config_score2(method, bs, d), int(indices[j])
+            if best[g] is None or score2 > best[g][0] or (score2 == best[g][0] and index < best[g][1]):
+                best[g] = (score2, index)
+    for g in range(SWEEP_GROUPS):
+        if best[g] is not None:
+            stats[S_BEST][g] = pack_best(*best[g])
+    return stats
+
+
+def sweep(cfg: Dict[str, Sequence[int]], first: int, tables: Sequence, const, m_total: int) -> List[List[int]]:
+    """The statistics of `sweep_rows` for the configurations `cfg`, which are the
+    ones with indices first, first + 1, ... of their grid."""
+    rows = estimate(cfg, tables, const)
+    return sweep_rows(range(first, first + len(rows)), cfg, rows, m_total)
+
+
+def sweep_merge(a: Sequence[Sequence[int]], b: Sequence[Sequence[int]]) -> List[List[int]]:
+    """Statistics of the union of two disjoint sets of configurations."""
+    out = [list(col) for col in a]
+    for g in range(SWEEP_GROUPS):
+        for col in (S_COUNT, S_FIT, S_K_SUM):
+            out[col][g] = a[col][g] + b[col][g]
+        for col in (S_MAX_PEAK, S_MAX_LIVE, S_BEST, S_MAX_NPARAMS_FIT):
+            out[col][g] = max(a[col][g], b[col][g])
+        out[S_MIN_PEAK][g] = min(a[S_MIN_PEAK][g], b[S_MIN_PEAK][g])
+    return out
 
 
 # ---------------------------------------------------------------------------

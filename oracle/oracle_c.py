@@ -79,6 +79,9 @@ def _load():
         lib.llmem_oracle_decide.argtypes = [
             ctypes.POINTER(_Configs), ctypes.c_void_p, ctypes.c_int64, ctypes.POINTER(_Table), ctypes.c_int,
             ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int]
+        lib.llmem_oracle_sweep.restype = ctypes.c_int
+        lib.llmem_oracle_sweep.argtypes = [ctypes.POINTER(_Configs), ctypes.c_int64, ctypes.c_int64,
+                                           ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -168,6 +171,22 @@ def decide(cfg: Dict[str, np.ndarray], tp_n: np.ndarray, tables: Sequence, const
                                    const.cu_p, const.align, int(m_total), rows.ctypes.data, threads))
     del keep
     return rows
+
+
+NSWEEP, SWEEP_GROUPS = 8, 48
+
+
+def sweep(cfg: Dict[str, np.ndarray], first: int, tables: Sequence, const, m_total: int, threads: int = 1):
+    """Statistics per (method, gpu_n) of the configurations `cfg`, whose indices in their grid
+    start at `first`; returns stats[NSWEEP, SWEEP_GROUPS]."""
+    lib = _load()
+    _, detail = estimate(cfg, tables, const, threads=threads)
+    cols = {name: np.ascontiguousarray(cfg[name], dtype=dt) for name, dt in _CFG_FIELDS}
+    c = _Configs(**{name: cols[name].ctypes.data for name, _ in _CFG_FIELDS})
+    stats = np.empty((NSWEEP, SWEEP_GROUPS), dtype=np.int64)
+    _raise(lib.llmem_oracle_sweep(ctypes.byref(c), len(cols["h"]), int(first), detail.ctypes.data,
+                                  int(m_total), stats.ctypes.data))
+    return stats
 
 
 def event_lists_peaks(events: np.ndarray, offsets: np.ndarray, threads: int = 1):

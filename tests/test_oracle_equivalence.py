@@ -94,6 +94,26 @@ def test_method_peaks_and_decision_random_tables_wild_queries():
     assert (flags & A.ERR_TP).any() and (peaks[:, 3] == -1).any()
 
 
+def test_sweep_statistics():
+    """Oracle B's sweep against oracle A's, on grids and on unstructured configurations with
+    invalid ones among them, for capacities that let all, some and none fit."""
+    cases = [(G.grid1(), 0, [T.gpt_table()]), (G.grid4(n=150, seed=2, first=77), 77, [T.llama_table()])]
+    rng = np.random.default_rng(11)
+    wild = G.random_configs(rng, 200, n_arch=2, wild=True)
+    wild["d"] = np.minimum(wild["d"], 18).astype(wild["d"].dtype)
+    cases.append((wild, (1 << 40) - 200, [T.gpt_table(), T.llama_table()]))
+    for cfg, first, tabs in cases:
+        rows = A.estimate(cfg, tabs, CONST)
+        n = len(rows)
+        peaks = sorted(r[A.D_PEAK] for r in rows if r[A.D_PEAK] >= 0)
+        for m_total in (peaks[len(peaks) // 2], peaks[-1], peaks[0] - 1, peaks[0]):
+            a = A.sweep_rows(range(first, first + n), cfg, rows, m_total)
+            b = B.sweep(cfg, first, tabs, CONST, m_total, threads=2)
+            assert b.shape == (A.NSWEEP, A.SWEEP_GROUPS) and b.tolist() == a
+    with pytest.raises(ValueError):
+        B.sweep(G.grid1(), (1 << 40) - 431, [T.gpt_table()], CONST, 1 << 40)
+
+
 def test_decision_rejects_batch_dependent_parameters():
     t = T.ArchTable("odd", (T.ParamEntry("w", 1, ("h", "bs"), "L", "OTHER", False),), ())
     cfg, tp = G.random_queries(np.random.default_rng(0), 4)
