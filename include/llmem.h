@@ -29,7 +29,7 @@
 extern "C" {
 #endif
 
-#define LLMEM_ABI_VERSION 2
+#define LLMEM_ABI_VERSION 3
 
 /* ---- error codes --------------------------------------------------------- */
 #define LLMEM_OK            0
@@ -316,6 +316,38 @@ int llmem_grid_generate(int grid_id, uint64_t seed, int64_t first, int64_t n,
 #define LLMEM_QUERY_BS_CAP 4096
 int llmem_queries_generate(uint64_t seed, int64_t first, int64_t n, const llmem_configs *cfg_out,
                            uint8_t *tp_n_out, void *hip_stream);
+
+/* Sweep of a seeded grid without storing a configuration or an estimate: each
+ * configuration first .. first+n-1 of grid grid_id (1..4, as for llmem_grid_generate) is drawn in
+ * registers, estimated exactly as llmem_estimate_ex does (closed forms of Sec. 4.2 and Sec. 5,
+ * chunk search of Sec. 4.1, timeline of Sec. 2.1 / Sec. 3.1) and folded into statistics per
+ * group = method * 16 + (gpu_n - 1), the questions Algorithm 1 (Sec. 6) asks of one
+ * configuration asked of the whole grid.  stats is DEV, LLMEM_NSWEEP columns of
+ * LLMEM_SWEEP_GROUPS int64 (column c of group g at stats[c * LLMEM_SWEEP_GROUPS + g]).
+ * llmem_sweep ADDS to what stats holds (counts are added, extremes combined), so that the
+ * statistics of several index ranges, seeds or devices can share one array or be merged
+ * column by column afterwards; llmem_sweep_reset writes the empty statistics (0 everywhere,
+ * INT64_MAX in LLMEM_S_MIN_PEAK).  Both are asynchronous on hip_stream; neither allocates.
+ * Needs tables that admit a lane form (LLMEM_KERNEL_LANE_*), else LLMEM_EINVAL_TABLE;
+ * first + n <= 2^40, else LLMEM_EINVAL_ARG.                                               */
+#define LLMEM_SWEEP_GROUPS 48
+enum llmem_sweep_column {
+    LLMEM_S_COUNT = 0,          /* configurations of the group                                 */
+    LLMEM_S_FIT,                /* those with m_peak <= m_total                                */
+    LLMEM_S_MAX_PEAK,           /* largest m_peak                                              */
+    LLMEM_S_MIN_PEAK,           /* smallest m_peak (INT64_MAX: the group is empty)             */
+    LLMEM_S_MAX_LIVE,           /* largest timeline peak (LLMEM_D_PEAK_LIVE)                   */
+    LLMEM_S_BEST,               /* best-scoring configuration that fits: score2 << 40 |
+                                 * (2^40 - 1 - index); score2 is Algorithm 1's score doubled,
+                                 * 3 * bs * gpu_n (CDP), 2 * bs * gpu_n (ZeRO-3), 2 * bs (TP);
+                                 * equal scores: the lowest index; 0: nothing fits             */
+    LLMEM_S_K_SUM,              /* sum of the chunk exponents used (LLMEM_D_K)                 */
+    LLMEM_S_MAX_NPARAMS_FIT,    /* largest parameter count among those that fit                */
+    LLMEM_NSWEEP
+};
+int llmem_sweep_reset(int64_t *stats, void *hip_stream);
+int llmem_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, const llmem_tables *method_tables,
+                int64_t m_total, int64_t *stats, void *hip_stream);
 
 /* Event lists of configurations first .. first+n-1 of the explicit-timeline
  * grid.  Two steps, both asynchronous: llmem_events_count writes the n list

@@ -7,4 +7,5 @@ from .binding import (  # noqa: F401
     llmem_events_count, llmem_events_generate, llmem_config_bytes, llmem_events_bytes,
     llmem_strerror, llmem_abi_version, llmem_kernel_forms, NDETAIL, DETAIL_COLUMNS,
     llmem_estimate_methods, llmem_decide, llmem_queries_generate, NDECIDE, DECISION_COLUMNS,
+    llmem_sweep, llmem_sweep_reset, NSWEEP, SWEEP_GROUPS, SWEEP_COLUMNS,
 )

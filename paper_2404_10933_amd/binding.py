@@ -28,6 +28,9 @@ DECISION_COLUMNS = ("method", "bs", "bs_cdp", "bs_adp", "bs_tp", "bs_hybrid", "s
                     "score2_tp", "score2_hybrid", "m_peak", "flags")
 METHOD_CDP, METHOD_ZERO3, METHOD_TP, METHOD_HYBRID, METHOD_OFFLOAD = range(5)
 
+NSWEEP, SWEEP_GROUPS = 8, 48
+SWEEP_COLUMNS = ("count", "fit", "max_peak", "min_peak", "max_live", "best", "k_sum", "max_nparams_fit")
+
 # column name -> (numpy dtype, torch dtype); order = struct llmem_configs
 CONFIG_COLUMNS = (
     ("arch_id", np.uint8, torch.uint8), ("h", np.uint32, torch.uint32), ("L", np.uint16, torch.uint16),
@@ -99,9 +102,12 @@ def load_library():
     lib.llmem_estimate_methods.argtypes = [ctypes.POINTER(_Configs), vp, i64, ctypes.POINTER(_Tables), vp, vp, vp]
     lib.llmem_decide.argtypes = [ctypes.POINTER(_Configs), vp, i64, ctypes.POINTER(_Tables), i64, vp, vp, vp, vp]
     lib.llmem_queries_generate.argtypes = [u64, i64, i64, ctypes.POINTER(_Configs), vp, vp]
+    lib.llmem_sweep.argtypes = [ci, u64, i64, i64, ctypes.POINTER(_Tables), i64, vp, vp]
+    lib.llmem_sweep_reset.argtypes = [vp, vp]
     for f in (lib.llmem_estimate, lib.llmem_estimate_ex, lib.llmem_timeline_peaks, lib.llmem_grid_generate,
               lib.llmem_events_count, lib.llmem_events_generate, lib.llmem_abi_version,
-              lib.llmem_estimate_methods, lib.llmem_decide, lib.llmem_queries_generate):
+              lib.llmem_estimate_methods, lib.llmem_decide, lib.llmem_queries_generate, lib.llmem_sweep,
+              lib.llmem_sweep_reset):
         f.restype = ci
     lib.llmem_config_bytes.argtypes = [i64]
     lib.llmem_config_bytes.restype = ctypes.c_size_t
@@ -281,6 +287,24 @@ def llmem_queries_generate(seed: int, first: int, n: int, cfg_out: DeviceConfigs
     _check_tp(tp_n_out, n)
     _check(load_library().llmem_queries_generate(seed, first, n, ctypes.byref(cfg_out.struct), _ptr(tp_n_out),
                                                  _stream_handle(stream)))
+
+
+def _check_stats(stats: torch.Tensor) -> None:
+    if stats.dtype != torch.int64 or stats.numel() < NSWEEP * SWEEP_GROUPS or not stats.is_contiguous():
+        raise ValueError("stats: need contiguous int64 of NSWEEP * SWEEP_GROUPS values")
+
+
+def llmem_sweep_reset(stats: torch.Tensor, stream=None) -> None:
+    _check_stats(stats)
+    _check(load_library().llmem_sweep_reset(_ptr(stats), _stream_handle(stream)))
+
+
+def llmem_sweep(grid_id: int, seed: int, first: int, n: int, tables: Tables, m_total: int, stats: torch.Tensor,
+                stream=None) -> None:
+    """stats: int64 of shape (NSWEEP, SWEEP_GROUPS), added to (see llmem_sweep_reset)."""
+    _check_stats(stats)
+    _check(load_library().llmem_sweep(grid_id, seed, first, n, ctypes.byref(tables.struct), int(m_total),
+                                      _ptr(stats), _stream_handle(stream)))
 
 
 def llmem_timeline_peaks(events: torch.Tensor, offsets: torch.Tensor, out_allocated: torch.Tensor,

@@ -693,6 +693,54 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     return LLMEM_OK;
 }
 
+static int launch_status()
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        snprintf(g_hip_error, sizeof(g_hip_error), "HIP error: %s", hipGetErrorString(e));
+        return LLMEM_EHIP;
+    }
+    return LLMEM_OK;
+}
+
+static int launch_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, const llmem_tables *tables,
+                        int64_t m_total, int64_t *stats, hipStream_t stream)
+{
+    if (!tables || !stats) return LLMEM_EINVAL_NULL;
+    if (n < 0 || first < 0) return LLMEM_EINVAL_N;
+    if (grid_id < 1 || grid_id > 4) return LLMEM_EINVAL_ARG;
+    if (grid_id == 1 && first + n > 432) return LLMEM_EINVAL_ARG;
+    if (first > (1ll << SWEEP_INDEX_BITS) || n > (1ll << SWEEP_INDEX_BITS) - first) return LLMEM_EINVAL_ARG;
+    EstimateArgs args;
+    memset(&args, 0, sizeof(args));
+    bool wave_ok, batch_ok, prog_ok;
+    int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok);
+    if (rc != LLMEM_OK) return rc;
+    // the lane forms only; a hint that names one of them is honoured
+    const int hint = tables->kernel;
+    int choice;
+    switch (hint) {
+    case LLMEM_KERNEL_AUTO:
+    case LLMEM_KERNEL_LANE: choice = prog_ok ? LLMEM_KERNEL_LANE_COMPILED : batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1; break;
+    case LLMEM_KERNEL_LANE_EVENTS: choice = batch_ok ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_COMPILED: choice = prog_ok ? hint : -1; break;
+    default: choice = -1;
+    }
+    if (choice < 0) return LLMEM_EINVAL_TABLE;
+    if (n == 0) return LLMEM_OK;
+    args.use_program = choice == LLMEM_KERNEL_LANE_COMPILED ? 1 : 0;
+    args.n = n;
+    args.params_dev = reinterpret_cast<const uint4 *>(tables->params_dev);
+    args.events_dev = reinterpret_cast<const uint4 *>(tables->events_dev);
+    args.sweep_grid = grid_id;
+    args.sweep_seed = seed;
+    args.sweep_first = first;
+    args.m_total = m_total;
+    args.sweep_stats = reinterpret_cast<unsigned long long *>(stats);
+    launch_sweep_kernel(args, (n + 63) / 64, stream);
+    return launch_status();
+}
+
 const char *last_hip_error() { return g_hip_error; }
 
 }  // namespace llmem
@@ -727,6 +775,20 @@ extern "C" uint64_t llmem_selftest_divide(uint64_t x, uint32_t d)
     if (d == 1) return x;
     const unsigned __int128 prod = (unsigned __int128)x * table.t[d].mul;
     return (uint64_t)(prod >> 64) >> table.t[d].shift;
+}
+
+extern "C" int llmem_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, const llmem_tables *method_tables,
+                           int64_t m_total, int64_t *stats, void *hip_stream)
+{
+    return llmem::launch_sweep(grid_id, seed, first, n, method_tables, m_total, stats,
+                               reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int llmem_sweep_reset(int64_t *stats, void *hip_stream)
+{
+    if (!stats) return LLMEM_EINVAL_NULL;
+    llmem::launch_sweep_reset(reinterpret_cast<long long *>(stats), reinterpret_cast<hipStream_t>(hip_stream));
+    return llmem::launch_status();
 }
 
 extern "C" int llmem_estimate(const llmem_configs *cfg, int64_t n, const llmem_tables *method_tables,

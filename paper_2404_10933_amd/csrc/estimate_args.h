@@ -96,6 +96,13 @@ struct EstimateArgs {
     long long *out_peaks;
     long long *out_detail;
     int use_program;                 // 1: the compiled timeline below is valid and used
+    // sweep: configurations sweep_first .. sweep_first + n - 1 of grid sweep_grid are drawn in the
+    // kernel (cfg is not read) and folded into sweep_stats (nothing is stored per configuration)
+    int sweep_grid;
+    unsigned long long sweep_seed;
+    long long sweep_first;
+    long long m_total;
+    unsigned long long *sweep_stats;
     uint32_t prog[PROG_WORDS];
 };
 
@@ -125,5 +132,8 @@ __host__ __device__ inline ClassKey make_class_key(uint32_t x, uint32_t y, uint3
 int check_tables(const llmem_tables *tables, EstimateArgs *out);
 size_t batch_kernel_lds_bytes(const EstimateArgs &a);
 void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream);
+void launch_sweep_kernel(const EstimateArgs &args, long long n_batch, hipStream_t stream);
+void launch_sweep_reset(long long *stats, hipStream_t stream);
+constexpr int SWEEP_INDEX_BITS = 40;             // LLMEM_S_BEST: score2 << 40 | (2^40 - 1 - index)
 
 }  // namespace llmem

@@ -32,6 +32,7 @@
 
 #include "../../include/llmem.h"
 #include "estimate_args.h"
+#include "grid_draws.h"
 #include "wave.h"
 
 namespace llmem {
@@ -62,8 +63,10 @@ __device__ __forceinline__ u32 uni(u32 v) { return (u32)__builtin_amdgcn_readfir
 }  // namespace
 
 // COMPILED: the tables come compiled in the kernel arguments (else the kernel reads the entries
-// from memory and walks every event)
-template <bool DETAIL, bool COMPILED>
+// from memory and walks every event).  SWEEP: the configurations are drawn here instead of loaded,
+// and their results are folded into statistics per (method, d) instead of stored: LDS atomics per
+// configuration into the workgroup's copy, one global atomic per statistic when the workgroup ends.
+template <bool DETAIL, bool COMPILED, bool SWEEP>
 __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) void estimate_batch_kernel(const EstimateArgs a)
 {
     extern __shared__ uint4 lds[];
@@ -72,6 +75,12 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
     __shared__ u64 div_mul_of[256];
     div_mul_of[threadIdx.x & 255u] = c_div.t[threadIdx.x & 255u].mul;
     static_assert(BB_BLOCK == 256, "one thread per table entry");
+    constexpr int SWEEP_WORDS = LLMEM_NSWEEP * LLMEM_SWEEP_GROUPS;
+    __shared__ u64 sweep_acc[SWEEP ? SWEEP_WORDS : 1];
+    if (SWEEP) {
+        for (int t = threadIdx.x; t < SWEEP_WORDS; t += BB_BLOCK)
+            sweep_acc[t] = t / LLMEM_SWEEP_GROUPS == LLMEM_S_MIN_PEAK ? (u64)INT64_MAX : 0ull;
+    }
     // LDS: class table | event codes | per-architecture counts | value slots of the waves
     // (the set-up's scratch shares the space of the value slots)
     uint4 *cls_tab = lds;                                                       // n_arch * CLS_MAX
@@ -156,7 +165,14 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
     auto fetch = [&](long long batch) -> Raw {
         Raw r = {1, 0, 0, 0, 0, 0, 1, 0, 0, 1, 0, 0, 0, 0};
         const long long i = (batch << 6) + lane;
-        if (batch < n_batch && i < n) {
+        if (SWEEP) {
+            if (batch < n_batch && i < n) {
+                const DrawnConfig g = draw_config(a.sweep_grid, a.sweep_seed, (u64)(a.sweep_first + i));
+                r.h = g.h; r.ffn = g.ffn; r.V = g.V; r.P = g.P; r.arch_id = g.arch_id; r.method = g.method; r.d = g.d;
+                r.cflags = g.flags; r.L = g.L; r.n_heads = g.n_heads; r.n_kv = g.n_kv; r.chunk_k = g.chunk_k;
+                r.bs = g.bs; r.sl = g.sl;
+            }
+        } else if (batch < n_batch && i < n) {
             r.h = a.cfg.h[i]; r.ffn = a.cfg.ffn[i]; r.V = a.cfg.V[i]; r.P = a.cfg.P[i];
             r.arch_id = a.cfg.arch_id[i]; r.method = a.cfg.method[i]; r.d = a.cfg.d[i]; r.cflags = a.cfg.flags[i];
             r.L = a.cfg.L[i]; r.n_heads = a.cfg.n_heads[i]; r.n_kv = a.cfg.n_kv[i];
@@ -542,7 +558,33 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
             }
         }
 
-        if (in_range) {
+        if (SWEEP) {
+            // fold this configuration into its group's statistics (a group: method and d <= 16)
+            if (valid && d - 1u < 16u) {
+                u64 *at = sweep_acc + (method * 16u + (d - 1u));
+                auto add = [&](int col, u64 v) {
+                    __hip_atomic_fetch_add(at + col * LLMEM_SWEEP_GROUPS, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                };
+                auto raise = [&](int col, u64 v) {
+                    __hip_atomic_fetch_max(at + col * LLMEM_SWEEP_GROUPS, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                };
+                add(LLMEM_S_COUNT, 1);
+                add(LLMEM_S_K_SUM, (u64)r_k);
+                raise(LLMEM_S_MAX_PEAK, (u64)r_peak);
+                raise(LLMEM_S_MAX_LIVE, (u64)r_live);
+                __hip_atomic_fetch_min(at + LLMEM_S_MIN_PEAK * LLMEM_SWEEP_GROUPS, (u64)r_peak, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (r_peak <= a.m_total) {
+                    // Sec. 6, Algorithm 1: the batch per step over all GPUs, times 1.5 for conventional
+                    // DP, one batch for a TP group; doubled.  Higher score first, then the lower index.
+                    const u32 score2 = method == LLMEM_METHOD_CDP ? 3u * bs * d : method == LLMEM_METHOD_ZERO3 ? 2u * bs * d : 2u * bs;
+                    const u64 index_mask = (1ull << SWEEP_INDEX_BITS) - 1;
+                    add(LLMEM_S_FIT, 1);
+                    raise(LLMEM_S_MAX_NPARAMS_FIT, (u64)r_np);
+                    raise(LLMEM_S_BEST, ((u64)score2 << SWEEP_INDEX_BITS) | (index_mask - (u64)(a.sweep_first + i)));
+                }
+            }
+        } else if (in_range) {
             if (a.out_peaks) a.out_peaks[i] = r_peak;
             if (DETAIL) {
                 long long *o = a.out_detail + i;
@@ -561,6 +603,35 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
             }
         }
     }
+    if (SWEEP) {
+        // the workgroup's statistics join the caller's: sums add, extremes combine
+        __syncthreads();
+        for (int t = threadIdx.x; t < SWEEP_WORDS; t += BB_BLOCK) {
+            const int col = t / LLMEM_SWEEP_GROUPS;
+            const u64 v = sweep_acc[t];
+            u64 *to = a.sweep_stats + t;
+            if (col == LLMEM_S_MIN_PEAK) {
+                if (v != (u64)INT64_MAX) __hip_atomic_fetch_min(to, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else if (v != 0) {
+                if (col == LLMEM_S_COUNT || col == LLMEM_S_FIT || col == LLMEM_S_K_SUM)
+                    __hip_atomic_fetch_add(to, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                else
+                    __hip_atomic_fetch_max(to, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+// empty statistics: 0, and the largest value where a minimum is kept
+__global__ __launch_bounds__(256) void sweep_reset_kernel(long long *stats)
+{
+    for (int t = threadIdx.x; t < LLMEM_NSWEEP * LLMEM_SWEEP_GROUPS; t += 256)
+        stats[t] = t / LLMEM_SWEEP_GROUPS == LLMEM_S_MIN_PEAK ? INT64_MAX : 0;
+}
+
+void launch_sweep_reset(long long *stats, hipStream_t stream)
+{
+    hipLaunchKernelGGL(sweep_reset_kernel, dim3(1), dim3(256), 0, stream, stats);
 }
 
 size_t batch_kernel_lds_bytes(const EstimateArgs &a)
@@ -576,7 +647,7 @@ size_t batch_kernel_lds_bytes(const EstimateArgs &a)
     return ((fixed + (scratch > values ? scratch : values)) + 15) & ~(size_t)15;
 }
 
-void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream)
+static void launch_lane_kernel(const EstimateArgs &args, bool detail, bool sweep, long long n_batch, hipStream_t stream)
 {
     const size_t lds_bytes = batch_kernel_lds_bytes(args);
     // as many workgroups as stay resident at once; each strides over the batches
@@ -590,19 +661,31 @@ void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batc
             cu_count = 256;
     }
     typedef void (*Kernel)(const EstimateArgs);
-    const Kernel kernels[2][2] = {{estimate_batch_kernel<false, false>, estimate_batch_kernel<false, true>},
-                                  {estimate_batch_kernel<true, false>, estimate_batch_kernel<true, true>}};
-    const Kernel kernel = kernels[detail ? 1 : 0][args.use_program ? 1 : 0];
+    const Kernel kernels[3][2] = {{estimate_batch_kernel<false, false, false>, estimate_batch_kernel<false, true, false>},
+                                  {estimate_batch_kernel<true, false, false>, estimate_batch_kernel<true, true, false>},
+                                  {estimate_batch_kernel<true, false, true>, estimate_batch_kernel<true, true, true>}};
+    const Kernel kernel = kernels[sweep ? 2 : detail ? 1 : 0][args.use_program ? 1 : 0];
     int per_cu = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), BB_BLOCK, lds_bytes)
             != hipSuccess || per_cu < 1)
         per_cu = 1;
     long long blocks = (n_batch + BB_WAVES - 1) / BB_WAVES;
     // the compiled form has next to no set-up per workgroup: several times more workgroups than
-    // stay resident at once let the dispatcher even out the compute units (measured: 16 is best)
-    const long long resident = (long long)per_cu * cu_count * (args.use_program ? 16 : 1);
+    // stay resident at once let the dispatcher even out the compute units (measured: 16 is best);
+    // a sweep pays global atomics per workgroup and stays at the resident number
+    const long long resident = (long long)per_cu * cu_count * (args.use_program && !sweep ? 16 : 1);
     if (blocks > resident) blocks = resident;
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
+}
+
+void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream)
+{
+    launch_lane_kernel(args, detail, false, n_batch, stream);
+}
+
+void launch_sweep_kernel(const EstimateArgs &args, long long n_batch, hipStream_t stream)
+{
+    launch_lane_kernel(args, true, true, n_batch, stream);
 }
 
 }  // namespace llmem

@@ -1,16 +1,11 @@
-// Seeded synthetic inputs generated on the device, and the small host-only
-// entry points of the library.
-//
-// Every draw is  lo + mix64(seed, index, field) mod span  with splitmix64's
-// finaliser over  seed + 0x9E3779B97F4A7C15*(index+1) + 0xD1B54A32D192ED03*(field+1).
-// The grids draw decoder shapes of the model families the paper fine-tunes
-// (Sec. 7.1: OPT / GPT-style and LLaMA-style decoders); they stand in for its
-// real models, whose weights and dataset the estimator never reads.
+// Seeded synthetic inputs generated on the device (the draws themselves are in
+// grid_draws.h), and the small host-only entry points of the library.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
 
 #include "../../include/llmem.h"
+#include "grid_draws.h"
 
 namespace llmem {
 
@@ -23,86 +18,18 @@ void set_hip_error(hipError_t e)
 }
 const char *last_hip_error();   // the estimator keeps its own buffer
 
-__host__ __device__ inline u64 mix64(u64 seed, u64 index, u64 field)
-{
-    u64 x = seed + 0x9E3779B97F4A7C15ull * (index + 1) + 0xD1B54A32D192ED03ull * (field + 1);
-    x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
-    x ^= x >> 27; x *= 0x94D049BB133111EBull;
-    x ^= x >> 31;
-    return x;
-}
-
-// hash field ids of the configuration grids
-enum { F_H, F_L, F_V, F_BS, F_SL, F_METHOD, F_D, F_K, F_NKV, F_TP };
-
-__device__ inline u64 uniform(u64 seed, u64 i, int field, u64 lo, u64 hi)
-{
-    return lo + mix64(seed, i, (u64)field) % (hi - lo + 1);
-}
-
-// grid_id 6: the queries of the method decision (grid 4's shapes; gpu_n, the batch-size cap and
-// tp_n instead of d, bs and method); tp_out is only written for that grid
+// grid_id 6: the queries of the method decision; tp_out is only written for that grid
 __global__ __launch_bounds__(256) void grid_kernel(int grid_id, u64 seed, long long first, long long n,
                                                    llmem_configs c, uint8_t *tp_out)
 {
     const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= n) return;
-    const u64 i = (u64)(first + t);
-    unsigned arch = 0, h, L, n_heads, n_kv, ffn, V, P, bs, sl, method, d, flags;
-    int k;
-    if (grid_id == 1) {
-        // full Cartesian product, last factor fastest: bs x sl x method x d x chunk
-        u64 r = i;
-        const unsigned ik = r % 3; r /= 3;
-        const unsigned id = r % 4; r /= 4;
-        method = r % 3; r /= 3;
-        const unsigned isl = r % 3; r /= 3;
-        const unsigned ibs = r % 4;
-        h = 256; L = 4; n_heads = 4; n_kv = 4; ffn = 1024; V = 8192; P = 512;
-        bs = 1u << ibs; sl = 128u << isl; d = id + 1; k = 4 + (int)ik;
-        flags = LLMEM_CFG_GRAD_ALIAS;
-    } else if (grid_id == 2) {
-        const unsigned hs[5] = {768, 1024, 2048, 2560, 4096};
-        const unsigned vs[2] = {32000, 50272};
-        const unsigned sls[4] = {256, 512, 1024, 2048};
-        h = hs[mix64(seed, i, F_H) % 5];
-        L = (unsigned)uniform(seed, i, F_L, 12, 32);
-        n_heads = h / 64; n_kv = n_heads; ffn = 4 * h;
-        V = vs[mix64(seed, i, F_V) % 2]; P = 2048;
-        bs = (unsigned)uniform(seed, i, F_BS, 1, 32);
-        sl = sls[mix64(seed, i, F_SL) % 4];
-        method = (unsigned)uniform(seed, i, F_METHOD, 0, 2);
-        d = (unsigned)uniform(seed, i, F_D, 1, 16);
-        k = (int)uniform(seed, i, F_K, 4, 8);
-        flags = LLMEM_CFG_TIED_LM_HEAD | LLMEM_CFG_GRAD_ALIAS;
-    } else {
-        const unsigned hs[4] = {2048, 4096, 5120, 8192};
-        const unsigned kvs[3] = {1, 4, 8};
-        const unsigned vs[2] = {32000, 128256};
-        const unsigned sls[5] = {512, 1024, 2048, 4096, 8192};
-        h = hs[mix64(seed, i, F_H) % 4];
-        L = (unsigned)uniform(seed, i, F_L, 16, 80);
-        n_heads = h / 128;
-        n_kv = kvs[mix64(seed, i, F_NKV) % 3];
-        ffn = ((8 * h + 2) / 3 + 255) / 256 * 256;       // SwiGLU width: 8h/3 rounded up to 256
-        V = vs[mix64(seed, i, F_V) % 2]; P = 0;
-        bs = (unsigned)uniform(seed, i, F_BS, 1, 64);
-        sl = sls[mix64(seed, i, F_SL) % 5];
-        method = (unsigned)uniform(seed, i, F_METHOD, 0, 2);
-        d = (unsigned)uniform(seed, i, F_D, 1, 16);
-        k = grid_id >= 4 ? LLMEM_CHUNK_SEARCH : (int)uniform(seed, i, F_K, 4, 8);
-        flags = LLMEM_CFG_LOGITS_FP32 | LLMEM_CFG_GRAD_ALIAS;
-        if (grid_id == 6) {
-            const unsigned log_g = (unsigned)(mix64(seed, i, F_D) % 5);
-            const unsigned log_t = (unsigned)(mix64(seed, i, F_TP) % (log_g + 1));
-            d = 1u << log_g; bs = LLMEM_QUERY_BS_CAP; method = 0;
-            tp_out[t] = (uint8_t)(1u << log_t);
-        }
-    }
-    c.arch_id[t] = (uint8_t)arch; c.h[t] = h; c.L[t] = (uint16_t)L; c.n_heads[t] = (uint16_t)n_heads;
-    c.n_kv[t] = (uint16_t)n_kv; c.ffn[t] = ffn; c.V[t] = V; c.P[t] = P; c.bs[t] = (uint16_t)bs;
-    c.sl[t] = (uint16_t)sl; c.method[t] = (uint8_t)method; c.d[t] = (uint8_t)d; c.chunk_k[t] = (int8_t)k;
-    c.flags[t] = (uint8_t)flags;
+    const DrawnConfig g = draw_config(grid_id, seed, (u64)(first + t));
+    if (grid_id == 6) tp_out[t] = (uint8_t)g.tp_n;
+    c.arch_id[t] = (uint8_t)g.arch_id; c.h[t] = g.h; c.L[t] = (uint16_t)g.L; c.n_heads[t] = (uint16_t)g.n_heads;
+    c.n_kv[t] = (uint16_t)g.n_kv; c.ffn[t] = g.ffn; c.V[t] = g.V; c.P[t] = g.P; c.bs[t] = (uint16_t)g.bs;
+    c.sl[t] = (uint16_t)g.sl; c.method[t] = (uint8_t)g.method; c.d[t] = (uint8_t)g.d; c.chunk_k[t] = (int8_t)g.chunk_k;
+    c.flags[t] = (uint8_t)g.flags;
 }
 
 // ---- explicit event lists ---------------------------------------------------------

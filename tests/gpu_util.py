@@ -67,3 +67,16 @@ def hip_decide(cfg_np, tp_np, tables, const, m_total, detail=True, short=True, s
     torch.cuda.synchronize()
     return (method.cpu().numpy()[:n] if short else None, bs.cpu().numpy()[:n] if short else None,
             det.cpu().numpy()[:, :n].T.copy() if detail else None)
+
+
+def hip_sweep(grid_id, seed, first, n, tables, const, m_total, kernel=0, into=None, stream=None):
+    """Returns stats[NSWEEP, SWEEP_GROUPS] of a sweep by the HIP kernel; `into`: a device
+    array to go on accumulating into (else a freshly reset one)."""
+    tab = M.Tables(tables, m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=kernel)
+    stats = into
+    if stats is None:
+        stats = torch.full((M.NSWEEP, M.SWEEP_GROUPS), -7, dtype=torch.int64, device="cuda")
+        M.llmem_sweep_reset(stats, stream=stream)
+    M.llmem_sweep(grid_id, seed, first, n, tab, m_total, stats, stream=stream)
+    torch.cuda.synchronize()
+    return stats if into is not None else stats.cpu().numpy()

@@ -1,0 +1,146 @@
+"""Parity of the streaming sweep (configurations drawn, estimated and folded into
+statistics per (method, gpu_n) inside one kernel) with the CPU oracle: every
+statistic of every group, bit exact, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import llmem_oracle as A
+from oracle import oracle_c as B
+from workloads import grids as G
+from workloads import tables as T
+
+pytestmark = pytest.mark.gpu
+
+CONST = T.Constants(m_base=256 << 20)
+CONST0 = T.Constants(m_base=0)
+GIB = 1 << 30
+KERNEL_LANE_EVENTS = 3          # LLMEM_KERNEL_LANE_EVENTS
+GRIDS = {1: (G.grid1, "gpt"), 2: (G.grid2, "opt"), 3: (G.grid3, "llama"), 4: (G.grid4, "llama")}
+
+
+@pytest.fixture(scope="module")
+def U():
+    import gpu_util
+    return gpu_util
+
+
+def _grid(grid_id, n, seed, first):
+    if grid_id == 1:
+        return G.slice_configs(G.grid1(), np.arange(first, first + n))
+    return GRIDS[grid_id][0](n=n, seed=seed, first=first)
+
+
+def _check(U, grid_id, seed, first, n, m_total, const=CONST, tables=None, kernel=0, threads=8):
+    tables = tables or [T.FAMILIES[GRIDS[grid_id][1]]()]
+    want = B.sweep(_grid(grid_id, n, seed, first), first, tables, const, m_total, threads=threads)
+    got = U.hip_sweep(grid_id, seed, first, n, tables, const, m_total, kernel=kernel)
+    for c, name in enumerate(("count", "fit", "max_peak", "min_peak", "max_live", "best", "k_sum", "max_nparams_fit")):
+        U.assert_same(f"grid {grid_id} n {n} first {first} m_total {m_total}: {name}", got[c], want[c])
+    return want
+
+
+def test_worked_example_through_the_hip_path(U, golden):
+    """The hand-worked values of tests/golden directly, not via the oracle."""
+    g = golden("worked_sweep_gpt_tiny.txt")
+    s = U.hip_sweep(1, 0, 0, 432, [T.gpt_table()], CONST0, g["m_total"])
+    for method, d, name in ((0, 1, "cdp"), (0, 4, "cdp"), (1, 3, "adp3"), (2, 4, "tp4")):
+        q = method * 16 + d - 1
+        assert (s[A.S_COUNT][q], s[A.S_K_SUM][q], s[A.S_MAX_NPARAMS_FIT][q]) == (g["count"], g["k_sum"], g["n_params"])
+        assert (s[A.S_FIT][q], s[A.S_MAX_PEAK][q], s[A.S_MIN_PEAK][q]) == (
+            g[f"{name}_fit"], g[f"{name}_max_peak"], g[f"{name}_min_peak"])
+    for q, name in ((0, "cdp1"), (1, "cdp2"), (16 + 2, "adp3"), (32 + 3, "tp4")):
+        assert A.unpack_best(int(s[A.S_BEST][q])) == (g[f"{name}_best_score2"], g[f"{name}_best_index"])
+    s = U.hip_sweep(1, 0, 0, 432, [T.gpt_table()], CONST0, g["tight_m_total"])
+    q = 32 + 3
+    assert (s[A.S_FIT][q], s[A.S_BEST][q], s[A.S_MAX_NPARAMS_FIT][q], s[A.S_MIN_PEAK][q]) == (
+        0, 0, 0, g["tp4_min_peak"])
+
+
+def test_grid1_whole_and_in_parts(U):
+    for m_total in (190_840_832 + (256 << 20), 1 << 40, 0, -1):
+        _check(U, 1, 0, 0, 432, m_total)
+    _check(U, 1, 0, 0, 432, 190_840_832, const=CONST0)
+    _check(U, 1, 0, 400, 32, 300 << 20)
+    _check(U, 1, 0, 63, 130, 300 << 20)           # ragged at both ends of a wave's 64
+
+
+@pytest.mark.parametrize("grid_id,n", ((2, 20_000), (3, 30_000), (4, 30_000)))
+def test_random_grids(U, grid_id, n):
+    """Several workgroups' worth of batches and a ragged tail, capacities from 'nothing fits' to
+    'everything fits', a second seed, a range that does not start at 0."""
+    for seed, first, m_total in ((0, 0, 40 * GIB), (0, 0, 2 * GIB), (0, 0, 1 << 50), (7, 123_456_789, 80 * GIB)):
+        want = _check(U, grid_id, seed, first, n + 37, m_total)
+    assert want[A.S_COUNT].sum() == n + 37 and 0 < want[A.S_FIT].sum() < n + 37
+
+
+def test_events_form_of_the_kernel(U):
+    _check(U, 4, 0, 0, 5_000, 40 * GIB, kernel=KERNEL_LANE_EVENTS)
+    _check(U, 1, 0, 0, 432, 300 << 20, kernel=KERNEL_LANE_EVENTS)
+
+
+def test_full_traversal_tables_and_second_architecture_unused(U):
+    _check(U, 4, 3, 0, 8_000, 60 * GIB, tables=[T.llama_table(checkpoint=False), T.gpt_table()])
+
+
+def test_accumulates_over_ranges_and_streams(U):
+    """llmem_sweep adds to what the array holds: four consecutive ranges (one of them empty) on
+    a side stream give the statistics of the whole; index limits."""
+    import paper_2404_10933_amd as M
+    tables = [T.llama_table()]
+    n, m_total = 50_000, 40 * GIB
+    want = B.sweep(G.grid4(n=n, seed=5, first=1000), 1000, tables, CONST, m_total, threads=8)
+    stream = torch.cuda.Stream()
+    stats = torch.full((M.NSWEEP, M.SWEEP_GROUPS), -7, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        M.llmem_sweep_reset(stats, stream=stream)
+        for lo, hi in ((0, 1), (1, 20_001), (20_001, 20_001), (20_001, n)):
+            U.hip_sweep(4, 5, 1000 + lo, hi - lo, tables, CONST, m_total, into=stats, stream=stream)
+    torch.cuda.synchronize()
+    U.assert_same("accumulated", stats.cpu().numpy(), want)
+    # the last representable indices
+    first = (1 << 40) - 1000
+    _check(U, 4, 1, first, 1000, 40 * GIB)
+    tab = M.Tables(tables, m_base=CONST.m_base)
+    with pytest.raises(M.LlmemError):
+        M.llmem_sweep(4, 1, first, 1001, tab, m_total, stats)
+    with pytest.raises(M.LlmemError):
+        M.llmem_sweep(6, 1, 0, 10, tab, m_total, stats)
+
+
+def test_full_size_grid4_against_the_stored_path(U):
+    """10^7 configurations in the benchmark's launch configuration.  The oracle sweeps the first
+    and the last 150 000 of them exactly; for the whole range the counts must add up, and the
+    sweep must agree with the library's own estimates of the stored grid folded on the host
+    (a consistency check of the two HIP paths, not a parity claim), and the best entries of a few
+    groups are confirmed one by one by the oracle."""
+    import paper_2404_10933_amd as M
+    tables = [T.llama_table()]
+    n, m_total = 10_000_000, 64 * GIB
+    got = U.hip_sweep(4, 0, 0, n, tables, CONST, m_total)
+    assert got[A.S_COUNT].sum() == n
+    for lo in (0, n - 150_000):
+        _check(U, 4, 0, lo, 150_000, m_total)
+    dev = M.DeviceConfigs.empty(n)
+    M.llmem_grid_generate(4, 0, 0, n, dev)
+    tab = M.Tables(tables, m_base=CONST.m_base)
+    det = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
+    M.llmem_estimate_ex(dev, tab, None, det)
+    torch.cuda.synchronize()
+    group = dev.columns["method"].to(torch.int64) * 16 + dev.columns["d"].to(torch.int64) - 1
+    peak, live = det[A.D_PEAK], det[A.D_LIVE]
+    for q in range(48):
+        m = group == q
+        assert int(m.sum()) == got[A.S_COUNT][q]
+        assert int(peak[m].max()) == got[A.S_MAX_PEAK][q] and int(peak[m].min()) == got[A.S_MIN_PEAK][q]
+        assert int(live[m].max()) == got[A.S_MAX_LIVE][q]
+        assert int((peak[m] <= m_total).sum()) == got[A.S_FIT][q]
+        assert int(det[A.D_K][m].sum()) == got[A.S_K_SUM][q]
+    for q in (0, 5, 16 + 7, 32 + 15):
+        score2, index = A.unpack_best(int(got[A.S_BEST][q]))
+        cfg = G.grid4(n=1, seed=0, first=index)
+        row = A.estimate(cfg, tables, CONST)[0]
+        method, d, bs = int(cfg["method"][0]), int(cfg["d"][0]), int(cfg["bs"][0])
+        assert method * 16 + d - 1 == q and row[A.D_PEAK] <= m_total
+        assert A.config_score2(method, bs, d) == score2

@@ -28,14 +28,15 @@ def test_exports_every_declared_symbol(lib):
     assert {"llmem_estimate", "llmem_estimate_ex", "llmem_timeline_peaks", "llmem_grid_generate",
             "llmem_events_count", "llmem_events_generate", "llmem_config_bytes", "llmem_events_bytes",
             "llmem_strerror", "llmem_abi_version", "llmem_selftest_divide", "llmem_kernel_forms",
-            "llmem_estimate_methods", "llmem_decide", "llmem_queries_generate"} <= names
+            "llmem_estimate_methods", "llmem_decide", "llmem_queries_generate", "llmem_sweep",
+            "llmem_sweep_reset"} <= names
     for n in names:
         assert hasattr(lib, n), n
 
 
 def test_abi_and_sizes(lib):
     import paper_2404_10933_amd as M
-    assert M.llmem_abi_version() == 2
+    assert M.llmem_abi_version() == 3
     assert M.llmem_config_bytes(10) == 10 * 31 and M.llmem_config_bytes(-1) == 0
     assert M.llmem_events_bytes(2) == 2 * 6 * 3450 * 8
     assert "NULL" in M.llmem_strerror(-1) and "unknown" in M.llmem_strerror(-99)
@@ -143,6 +144,18 @@ def test_argument_validation_without_gpu(lib):
     qg = lib.llmem_queries_generate
     assert qg(0, 0, 0, c, None, None) == 0 and qg(0, 0, -1, c, None, None) == -2 and qg(0, -1, 1, c, None, None) == -2
     assert qg(0, 0, 4, c, None, None) == -1 and qg(0, 0, 4, None, out, None) == -1
+
+    # sweep: argument checks come before any launch
+    sw = lib.llmem_sweep
+    assert sw(4, 0, 0, 0, t_ok, 1 << 30, out, None) == 0                               # n == 0: no-op
+    assert sw(4, 0, 0, 8, None, 1 << 30, out, None) == -1 and sw(4, 0, 0, 8, t_ok, 1 << 30, None, None) == -1
+    assert sw(4, 0, 0, -1, t_ok, 0, out, None) == -2 and sw(4, 0, -1, 1, t_ok, 0, out, None) == -2
+    assert sw(0, 0, 0, 8, t_ok, 0, out, None) == -5 and sw(5, 0, 0, 8, t_ok, 0, out, None) == -5
+    assert sw(6, 0, 0, 8, t_ok, 0, out, None) == -5                                    # the query grid is not swept
+    assert sw(1, 0, 400, 33, t_ok, 0, out, None) == -5
+    assert sw(4, 0, (1 << 40) - 7, 8, t_ok, 0, out, None) == -5 and sw(4, 0, (1 << 40) - 8, 0, t_ok, 0, out, None) == 0
+    assert sw(4, 0, 0, 0, ctypes.byref(t_bad), 0, out, None) == -3
+    assert lib.llmem_sweep_reset(None, None) == -1
 
 
 def test_table_packing_layout():
