@@ -3,8 +3,10 @@
 A step is one pass of the whole hot path over the 10^7-configuration Llama-style
 grid with chunk-size search: one llmem_estimate_ex launch producing m_peak and
 all detail columns (component sizes, chosen chunk, timeline peak).  Inputs are
-generated on the device beforehand and stay resident in HBM.  The explicit
-event-list kernel is timed on its own 10^5-list grid and reported under "extra".
+generated on the device beforehand and stay resident in HBM.  Reported
+under "extra", each timed on its own: the explicit event-list kernel on the
+10^5-list grid, the same grid with the table without gradient checkpointing, the
+streaming sweep (draw, estimate, reduce in one kernel) and the method decision.
 
 Prints ONE JSON line.
 """
@@ -64,6 +66,19 @@ def algorithmic_lane_ops_decide(n_param_entries, cap_bits):
             + cap_bits * (2 * probe_plain + 2 * probe_gather) + tail)
 
 
+def algorithmic_lane_ops_sweep_extra():
+    """What the streaming sweep adds per configuration of grid 4, same units: eight counter-based
+    draws (splitmix64 finaliser: two 64 x 64-bit multiplies at 5, three xor-shifts at 2, one add;
+    then a remainder, 16 by a constant that is no power of two, else 1, and the offset), the SwiGLU
+    width, the value selections, the score and the eight statistics."""
+    ADD, MUL64, XORSHIFT, REM, DIV = 1, 5, 2, 16, 12
+    draw = ADD + 3 * XORSHIFT + 2 * MUL64
+    draws = 8 * draw + 4 * (REM + ADD) + 4 * (1 + ADD) + (MUL64 + 2 * ADD)
+    shape = (DIV + 3 * ADD) + 10                  # ffn = 8h/3 rounded up to 256; table look-ups as selects
+    fold = 3 + 2 + 8 + 4                          # score, packed best entry, eight statistics, group and test
+    return draws + shape + fold
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +88,8 @@ def main():
     ap.add_argument("--lists", type=int, default=100_000, help="event lists of the explicit-timeline grid (0: skip)")
     ap.add_argument("--full-traversal", type=int, default=10_000_000,
                     help="configurations timed with the table without gradient checkpointing (0: skip)")
+    ap.add_argument("--sweep", type=int, default=10_000_000,
+                    help="configurations of the streaming sweep (drawn, estimated and reduced in one kernel; 0: skip)")
     ap.add_argument("--queries", type=int, default=4_000_000, help="queries of the method-decision grid (0: skip)")
     ap.add_argument("--cpu-sample", type=int, default=600_000, help="configurations the CPU oracle is timed on (0: skip)")
     ap.add_argument("--kernel", choices=("auto", "wave", "lane"), default="auto",
@@ -131,7 +148,7 @@ def main():
     forms = M.llmem_kernel_forms(tab)
     ops = algorithmic_lane_ops(forms, 9)
     achieved = ops * n / (kernel_ms * 1e-3) / 1e12
-    kernel_name = "estimate_kernel<true>" if args.kernel == "wave" else "estimate_batch_kernel<true, true>"
+    kernel_name = "estimate_kernel<true>" if args.kernel == "wave" else "estimate_batch_kernel<true, true, false>"
     bytes_per_cfg = M.llmem_config_bytes(1) + 8 + 8 * M.NDETAIL
     result = {
         "metric": "configs estimated/sec (bit-exact vs oracle)",
@@ -230,6 +247,43 @@ def main():
             "roofline": {"bound": "alu", "achieved": f_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
                          "frac": f_achieved / PEAK_LANE_TOPS, "traffic": None, "kernel": kernel_name,
                          "algorithmic_lane_ops_per_config": f_ops},
+            "verified_vs_oracle": ns}
+
+    if args.sweep > 0:
+        nsw, m_total = args.sweep, 64 << 30
+        stats = torch.empty((M.NSWEEP, M.SWEEP_GROUPS), dtype=torch.int64, device="cuda")
+        for _ in range(2):
+            M.llmem_sweep_reset(stats)
+            M.llmem_sweep(4, 0, 0, nsw, tab, m_total, stats)
+        torch.cuda.synchronize()
+        reps = 10
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            M.llmem_sweep_reset(stats)
+            M.llmem_sweep(4, 0, 0, nsw, tab, m_total, stats)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        s_ops = ops + algorithmic_lane_ops_sweep_extra()
+        s_achieved = s_ops * nsw / (ms * 1e-3) / 1e12
+        ns = min(100_000, nsw)
+        head = torch.empty_like(stats)
+        M.llmem_sweep_reset(head)
+        M.llmem_sweep(4, 0, 0, ns, tab, m_total, head)
+        want = B.sweep(G.grid4(n=ns, seed=0), 0, [table], const, m_total, threads=4)
+        assert (head.cpu().numpy() == want).all(), "sweep statistics differ from the oracle"
+        assert int(stats[0].sum().item()) == nsw
+        result.setdefault("extra", {})["g4_streaming_sweep"] = {
+            "workload": "g4 drawn in registers, estimated (all of the hot path) and folded into 8 statistics per "
+                        "(method, gpu_n) against m_total 64 GiB; nothing per configuration touches HBM; reset + sweep",
+            "n_configs": nsw, "ms_per_launch": ms, "configs_per_s": nsw / (ms * 1e-3),
+            "configs_fitting": int(stats[1].sum().item()),
+            "roofline": {"bound": "alu", "achieved": s_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
+                         "frac": s_achieved / PEAK_LANE_TOPS, "traffic": None,
+                         "kernel": "estimate_batch_kernel<true, true, true>",
+                         "algorithmic_lane_ops_per_config": s_ops},
             "verified_vs_oracle": ns}
 
     if args.queries > 0:

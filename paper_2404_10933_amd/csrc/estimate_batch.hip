@@ -671,9 +671,9 @@ static void launch_lane_kernel(const EstimateArgs &args, bool detail, bool sweep
         per_cu = 1;
     long long blocks = (n_batch + BB_WAVES - 1) / BB_WAVES;
     // the compiled form has next to no set-up per workgroup: several times more workgroups than
-    // stay resident at once let the dispatcher even out the compute units (measured: 16 is best);
-    // a sweep pays global atomics per workgroup and stays at the resident number
-    const long long resident = (long long)per_cu * cu_count * (args.use_program && !sweep ? 16 : 1);
+    // stay resident at once let the dispatcher even out the compute units (measured: 16 is best,
+    // also for a sweep, whose workgroups each end with global atomics)
+    const long long resident = (long long)per_cu * cu_count * (args.use_program ? 16 : 1);
     if (blocks > resident) blocks = resident;
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
 }
