@@ -447,9 +447,10 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                         }
                         return seen;
                     };
-                    // Sums of count * value, PROG_FETCH terms per fetch in groups of four, no branches but one: a
-                    // group flagged as a point's end lets its sum compete for the segment's maximum; the
-                    // group that ends a segment's net change closes the segment.
+                    // Sums of count * value, PROG_FETCH terms per fetch in groups of four.  A group flagged as
+                    // a point's end lets its sum compete for the segment's maximum; the group that ends a
+                    // segment's net change closes the segment.  The flags are wave-uniform: groups inside a
+                    // sum cost their multiply-adds only.
                     auto walk_terms = [&](auto narrow) {
                         constexpr bool NARROW = decltype(narrow)::value;
                         const char *row = vals + (NARROW ? lane * 4 : (lane & 31) * 8);
@@ -469,11 +470,12 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                             }
 #pragma unroll
                             for (int g = 0; g < PROG_FETCH; g += PROG_GROUP) {
-                                const bool end = t[g] & PROG_END_POINT;
                                 if (NARROW) {
                                     // signed 32-bit blocks times a count below 2^16: one multiply-add each
+                                    i64 part = 0;
 #pragma unroll
-                                    for (int q = g; q < g + PROG_GROUP; ++q) acc += (i64)v32[q] * (i64)(int)(t[q] >> 16);
+                                    for (int q = g; q < g + PROG_GROUP; ++q) part += (i64)v32[q] * (i64)(int)(t[q] >> 16);
+                                    acc += part;
                                 } else {
                                     // count * value: the low and the high halves of the values are summed
                                     // apart (each product is below 2^48) and joined once per group
@@ -486,20 +488,23 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                                     }
                                     acc = (i64)((u64)acc + part_lo + (part_hi << 32));
                                 }
-                                const bool up = end & (acc > top);
-                                top = up ? acc : top;
-                                acc = end ? 0 : acc;
-                                has_point |= t[g] & PROG_END_POINT;
-                                if (t[g] & PROG_END_SEGMENT) {                           // wave-uniform
+                                // a sum ends with this group (wave-uniform): a point competes for the
+                                // segment's maximum, the net change closes the segment
+                                if (t[g] & (PROG_END_POINT | PROG_END_SEGMENT)) {
                                     asm volatile("" ::: "memory");
-                                    // the narrow sums are in blocks
-                                    const i64 run = NARROW ? (i64)((u64)acc << align_shift) : acc;
-                                    const i64 peak = NARROW ? (i64)((u64)top << align_shift) : top;
-                                    close_segment(seg, run, peak, has_point != 0);
-                                    ++seg;
+                                    if (t[g] & PROG_END_SEGMENT) {
+                                        // the narrow sums are in blocks
+                                        const i64 run = NARROW ? (i64)((u64)acc << align_shift) : acc;
+                                        const i64 peak = NARROW ? (i64)((u64)top << align_shift) : top;
+                                        close_segment(seg, run, peak, has_point != 0);
+                                        ++seg;
+                                        top = LOWEST;
+                                        has_point = 0;
+                                    } else {
+                                        top = acc > top ? acc : top;
+                                        has_point = 1;
+                                    }
                                     acc = 0;
-                                    top = LOWEST;
-                                    has_point = 0;
                                 }
                             }
                         }
