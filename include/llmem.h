@@ -22,8 +22,10 @@
 #ifndef LLMEM_H
 #define LLMEM_H
 
+#ifndef __HIPCC_RTC__            /* the run-time compiler brings the fixed-width types itself */
 #include <stddef.h>
 #include <stdint.h>
+#endif
 
 #ifdef __cplusplus
 extern "C" {
@@ -174,12 +176,21 @@ typedef struct llmem_tables {
  * the events of all architectures, dealt to lanes, to fit LLMEM_MAX_EVENT_SLOTS.
  * LLMEM_KERNEL_AUTO takes the first of compiled, events, wave that the tables allow;
  * LLMEM_KERNEL_LANE the first of compiled, events; a forced choice the tables do not
- * allow is LLMEM_EINVAL_TABLE.                                                  */
+ * allow is LLMEM_EINVAL_TABLE.
+ * LLMEM_KERNEL_LANE_SPECIALIZED is the compiled form taken one step further and is only
+ * used when asked for: the lane kernel's own source is compiled once more, at run time, with
+ * the compiled tables as constants, so that every table word becomes an immediate and every
+ * loop over table entries straight-line code.  The first call with a given set of tables (one
+ * architecture; the same condition as for the compiled form) takes a few seconds to build
+ * and load the kernel; the build is kept, per device, until the process ends.  Results are
+ * the same bit for bit.  A failure of the run-time compiler or loader is LLMEM_EHIP with its
+ * message in llmem_strerror.  llmem_estimate(_ex) and llmem_sweep honour it.            */
 #define LLMEM_KERNEL_AUTO 0
 #define LLMEM_KERNEL_WAVE 1
 #define LLMEM_KERNEL_LANE 2
 #define LLMEM_KERNEL_LANE_EVENTS 3
 #define LLMEM_KERNEL_LANE_COMPILED 4
+#define LLMEM_KERNEL_LANE_SPECIALIZED 5
 
 /* ---- outputs --------------------------------------------------------------- */
 /* Detail columns: out_detail is DEV, LLMEM_NDETAIL columns of n int64 each
@@ -364,7 +375,7 @@ size_t llmem_config_bytes(int64_t n);
 size_t llmem_events_bytes(int64_t n);
 
 /* Host-only: which kernel forms these tables allow and what they cost.  info[0] = bit mask
- * (bit k set: LLMEM_KERNEL_k is allowed, k = 1..4), info[1] = 32-bit words of the compiled
+ * (bit k set: LLMEM_KERNEL_k is allowed, k = 1..5), info[1] = 32-bit words of the compiled
  * tables (of LLMEM_PROGRAM_WORDS available), info[2] = value slots per wavefront in the
  * compiled form, info[3] = value slots per wavefront in the events form, info[4] = LDS slots
  * of the wavefront-per-configuration form; when the compiled form is allowed also info[5] =

@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libllmem.so")
 _lib = None
 
 MAX_ARCH = 8
-KERNEL_AUTO, KERNEL_WAVE, KERNEL_LANE = 0, 1, 2
+KERNEL_AUTO, KERNEL_WAVE, KERNEL_LANE, KERNEL_LANE_EVENTS, KERNEL_LANE_COMPILED, KERNEL_LANE_SPECIALIZED = range(6)
 NDETAIL = 12
 DETAIL_COLUMNS = ("m_peak", "param_bytes_gpu", "grad_bytes_gpu", "os_bytes_gpu", "m_out", "m_lm",
                   "m_back", "k_chosen", "peak_live", "n_params", "t_max", "flags")
@@ -343,7 +343,7 @@ def llmem_events_generate(seed: int, first: int, n: int, offsets: torch.Tensor, 
 def llmem_kernel_forms(tables: "Tables") -> Dict[str, int]:
     info = (ctypes.c_int32 * 8)()
     _check(load_library().llmem_kernel_forms(ctypes.byref(tables.struct), info))
-    return {"allowed": [k for k in range(1, 5) if info[0] >> k & 1], "program_words": info[1],
+    return {"allowed": [k for k in range(1, 6) if info[0] >> k & 1], "program_words": info[1],
             "compiled_slots": info[2], "event_slots": info[3], "wave_slots": info[4],
             "param_groups": info[5] & 0xffff, "size_classes": info[5] >> 16, "terms": info[6],
             "peak_points": info[7]}

@@ -651,11 +651,12 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     case LLMEM_KERNEL_WAVE: choice = wave_ok ? hint : -1; break;
     case LLMEM_KERNEL_LANE_EVENTS: choice = batch_ok ? hint : -1; break;
     case LLMEM_KERNEL_LANE_COMPILED: choice = prog_ok ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_SPECIALIZED: choice = (prog_ok && args.n_arch == 1) ? hint : -1; break;
     default: choice = -1;
     }
     if (choice < 0) return LLMEM_EINVAL_TABLE;
     const bool use_batch = choice != LLMEM_KERNEL_WAVE;
-    args.use_program = choice == LLMEM_KERNEL_LANE_COMPILED ? 1 : 0;
+    args.use_program = (choice == LLMEM_KERNEL_LANE_COMPILED || choice == LLMEM_KERNEL_LANE_SPECIALIZED) ? 1 : 0;
     if (n == 0) return LLMEM_OK;
     if (!cfg->arch_id || !cfg->h || !cfg->L || !cfg->n_heads || !cfg->n_kv || !cfg->ffn || !cfg->V
         || !cfg->P || !cfg->bs || !cfg->sl || !cfg->method || !cfg->d || !cfg->chunk_k || !cfg->flags)
@@ -668,6 +669,7 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     args.out_detail = reinterpret_cast<long long *>(out_detail);
 
     const int64_t n_batch = (n + 63) / 64;
+    if (choice == LLMEM_KERNEL_LANE_SPECIALIZED) return launch_specialized(args, out_detail ? 1 : 0, n_batch, stream);
     if (use_batch) {
         launch_batch_kernel(args, out_detail != nullptr, n_batch, stream);
         hipError_t e = hipGetLastError();
@@ -724,11 +726,12 @@ static int launch_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, co
     case LLMEM_KERNEL_LANE: choice = prog_ok ? LLMEM_KERNEL_LANE_COMPILED : batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1; break;
     case LLMEM_KERNEL_LANE_EVENTS: choice = batch_ok ? hint : -1; break;
     case LLMEM_KERNEL_LANE_COMPILED: choice = prog_ok ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_SPECIALIZED: choice = (prog_ok && args.n_arch == 1) ? hint : -1; break;
     default: choice = -1;
     }
     if (choice < 0) return LLMEM_EINVAL_TABLE;
     if (n == 0) return LLMEM_OK;
-    args.use_program = choice == LLMEM_KERNEL_LANE_COMPILED ? 1 : 0;
+    args.use_program = (choice == LLMEM_KERNEL_LANE_COMPILED || choice == LLMEM_KERNEL_LANE_SPECIALIZED) ? 1 : 0;
     args.n = n;
     args.params_dev = reinterpret_cast<const uint4 *>(tables->params_dev);
     args.events_dev = reinterpret_cast<const uint4 *>(tables->events_dev);
@@ -737,11 +740,13 @@ static int launch_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, co
     args.sweep_first = first;
     args.m_total = m_total;
     args.sweep_stats = reinterpret_cast<unsigned long long *>(stats);
+    if (choice == LLMEM_KERNEL_LANE_SPECIALIZED) return launch_specialized(args, 2, (n + 63) / 64, stream);
     launch_sweep_kernel(args, (n + 63) / 64, stream);
     return launch_status();
 }
 
 const char *last_hip_error() { return g_hip_error; }
+void set_error_text(const char *text) { snprintf(g_hip_error, sizeof(g_hip_error), "%s", text); }
 
 }  // namespace llmem
 
@@ -759,7 +764,8 @@ extern "C" int llmem_kernel_forms(const llmem_tables *tables, int32_t info[8])
     if (rc != LLMEM_OK) return rc;
     for (int q = 0; q < 8; ++q) info[q] = 0;
     info[0] = (wave_ok ? 1 << LLMEM_KERNEL_WAVE : 0) | (batch_ok ? 1 << LLMEM_KERNEL_LANE_EVENTS : 0)
-              | (prog_ok ? 1 << LLMEM_KERNEL_LANE_COMPILED : 0) | ((batch_ok || prog_ok) ? 1 << LLMEM_KERNEL_LANE : 0);
+              | (prog_ok ? 1 << LLMEM_KERNEL_LANE_COMPILED : 0) | ((batch_ok || prog_ok) ? 1 << LLMEM_KERNEL_LANE : 0)
+              | ((prog_ok && args.n_arch == 1) ? 1 << LLMEM_KERNEL_LANE_SPECIALIZED : 0);
     info[1] = words;
     info[2] = args.p_slots;
     info[3] = args.s_slots;

@@ -2,10 +2,16 @@
 // (one wavefront per configuration; one lane per configuration).
 #pragma once
 
+#ifndef __HIPCC_RTC__
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#endif
 
+#ifdef __HIPCC_RTC__
+#include "llmem.h"                 // the run-time compiler gets every file by its bare name
+#else
 #include "../../include/llmem.h"
+#endif
 
 namespace llmem {
 
@@ -129,11 +135,18 @@ __host__ __device__ inline ClassKey make_class_key(uint32_t x, uint32_t y, uint3
 
 // Validates the host copy of the tables exactly as the estimator does and fills the constants
 // and per-architecture ranges of `out`; LLMEM_OK or LLMEM_EINVAL_*.
+#ifndef __HIPCC_RTC__
 int check_tables(const llmem_tables *tables, EstimateArgs *out);
 size_t batch_kernel_lds_bytes(const EstimateArgs &a);
 void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream);
 void launch_sweep_kernel(const EstimateArgs &args, long long n_batch, hipStream_t stream);
 void launch_sweep_reset(long long *stats, hipStream_t stream);
+// Specialized form: the lane kernel compiled at run time with the compiled tables of `args` as
+// constants (one build per set of tables, flavour and device, kept until the process ends).
+// flavour: 0 m_peak only, 1 with the detail columns, 2 sweep.  LLMEM_OK, or LLMEM_EHIP with the
+// compiler's or the loader's message as the error text.
+int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch, hipStream_t stream);
+#endif
 constexpr int SWEEP_INDEX_BITS = 40;             // LLMEM_S_BEST: score2 << 40 | (2^40 - 1 - index)
 
 }  // namespace llmem

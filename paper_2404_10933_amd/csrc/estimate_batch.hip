@@ -26,18 +26,61 @@
 // Closed form: Sec. 4.2 (m_p, m_os, m_out, m_lm, m_peak^s) and Sec. 5 (m_peak^dp,
 // m_peak^tp, m_back^tp) of arXiv 2404.10933; chunk size per Sec. 4.1; timeline
 // traversal per Sec. 2.1 / Sec. 3.1.
+//
+// Specialized form (LLMEM_SPECIALIZED, see specialize.hip): this file is compiled again at run
+// time with the compiled tables of one set of architecture tables as constants
+// (specialized_prog.h).  The loops over parameter groups, classes and terms then have constant
+// bounds and are unrolled; every word, offset and count becomes an immediate and every flag test
+// disappears.  Only the path for sizes of 2^31 blocks and more keeps reading the words in loops.
+#ifndef __HIPCC_RTC__
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <type_traits>
+#else
+// the run-time compiler has no C library headers: the fixed-width types the headers below use
+typedef unsigned char uint8_t;
+typedef signed char int8_t;
+typedef unsigned short uint16_t;
+typedef unsigned int uint32_t;
+typedef int int32_t;
+typedef unsigned long long uint64_t;
+typedef long long int64_t;
+#define INT64_MAX 0x7fffffffffffffffll
+#endif
 
+#ifdef __HIPCC_RTC__
+#include "llmem.h"                 // the run-time compiler gets every file by its bare name
+#else
 #include "../../include/llmem.h"
+#endif
 #include "estimate_args.h"
 #include "grid_draws.h"
 #include "wave.h"
 
+#ifdef LLMEM_SPECIALIZED
+#include "specialized_prog.h"     // SPEC_PROG[] (constants), SPEC_PROG_MEM[] (the same words in memory), SPEC_WAVES
+#define LLMEM_PROG(i) SPEC_PROG[i]
+#define LLMEM_PROG_LOOP(i) SPEC_PROG_MEM[i]
+#define LLMEM_UNROLL_IF(flag) _Pragma("unroll")
+#define LLMEM_UNROLL_NARROW _Pragma("unroll NARROW ? 4096 : 1")
+// The value is the same afterwards, but the compiler cannot know: work that depends on it stays
+// behind this point instead of being hoisted to the start of the batch (registers).
+#define LLMEM_ANCHOR(x) asm volatile("" : "+v"(x))
+#define LLMEM_WAVES_PER_SIMD SPEC_WAVES
+#else
+#define LLMEM_PROG(i) a.prog[i]
+#define LLMEM_PROG_LOOP(i) a.prog[i]
+#define LLMEM_UNROLL_IF(flag)
+#define LLMEM_UNROLL_NARROW
+#define LLMEM_ANCHOR(x)
+#define LLMEM_WAVES_PER_SIMD 5
+#endif
+
 namespace llmem {
 
 namespace {
+
+struct Narrow { static constexpr bool value = true; };
+struct Wide { static constexpr bool value = false; };
 
 constexpr int BB_WAVES = BATCH_WAVES;
 constexpr int BB_BLOCK = 64 * BB_WAVES;
@@ -67,7 +110,7 @@ __device__ __forceinline__ u32 uni(u32 v) { return (u32)__builtin_amdgcn_readfir
 // and their results are folded into statistics per (method, d) instead of stored: LDS atomics per
 // configuration into the workgroup's copy, one global atomic per statistic when the workgroup ends.
 template <bool DETAIL, bool COMPILED, bool SWEEP>
-__global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) void estimate_batch_kernel(const EstimateArgs a)
+__device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 {
     extern __shared__ uint4 lds[];
     // multipliers of the divisions by the partition degree: a lane looks its own d up, from LDS
@@ -212,6 +255,11 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
         i64 r_peak = err ? -1 : 0, r_param = 0, r_grad = 0, r_os = 0, r_out = 0, r_lm = 0, r_back = 0, r_k = 0,
             r_live = 0, r_np = 0, r_tmax = 0, r_flags = err;
 
+#ifdef LLMEM_SPECIALIZED
+        // one architecture (a specialization is built for a single table): every valid lane at once
+        if (valid) {
+            const u32 ar = 0;
+#else
         unsigned long long todo = __builtin_amdgcn_ballot_w64(valid);
         while (todo) {
             const int first = __builtin_ctzll(todo);
@@ -219,6 +267,7 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
             const bool mine = valid && arch_id == ar;
             todo &= ~__builtin_amdgcn_ballot_w64(mine);
             if (!mine) continue;
+#endif
             const ArchLayout &al = a.arch[ar];
 
             // size of a compiled expression for this lane's configuration (descriptor: see estimate_args.h)
@@ -241,19 +290,24 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                 // entries that count towards each sum, once and once per block
                 // start of the architecture's words: selected from reads at constant positions, so that
                 // every read of the compiled tables is a scalar load
+#ifndef LLMEM_SPECIALIZED
                 pc = a.arch[0].prog_first;
 #pragma unroll
                 for (int q = 1; q < LLMEM_MAX_ARCH; ++q) pc = ar == (u32)q ? a.arch[q].prog_first : pc;
                 pc = (int)uni((u32)pc);
-                head = a.prog[pc];
+#endif
+                head = LLMEM_PROG(pc);
 #pragma unroll
-                for (int q = 0; q <= LLMEM_NSEG; ++q) seg_at[q] = a.prog[pc + 1 + q];
+                for (int q = 0; q <= LLMEM_NSEG; ++q) seg_at[q] = LLMEM_PROG(pc + 1 + q);
                 pc += PROG_HEADER;
                 e_n = (head >> 8) & 255u;
                 const int n_groups = (int)(head & 255u);
+                LLMEM_UNROLL_IF(true)
                 for (int g = 0; g < n_groups; ++g, pc += 4) {
-                    const u32 w2 = a.prog[pc + 2], w3 = a.prog[pc + 3];
-                    const u64 t_p = expression(a.prog[pc], a.prog[pc + 1]);
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) LLMEM_ANCHOR(D[q]);
+                    const u32 w2 = LLMEM_PROG(pc + 2), w3 = LLMEM_PROG(pc + 3);
+                    const u64 t_p = expression(LLMEM_PROG(pc), LLMEM_PROG(pc + 1));
                     if (w2 & 0xffffu) embed_p += t_p * (u64)((w2 & 255u) + ((w2 >> 8) & 255u) * L);
                     if (w2 >> 16) lm_p += t_p * (u64)(((w2 >> 16) & 255u) + (w2 >> 24) * L);
                     if (w3 & 0xffffu) {
@@ -312,6 +366,9 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
             int k_used = search ? K_SEARCH_MAX : chunk_k;
             bool found = !search;
             const u64 rest = m_base + m_out + m_lm + grad_extra;               // the same for every candidate
+#ifdef LLMEM_SPECIALIZED
+#pragma nounroll
+#endif
             for (int j = 0; j <= K_SEARCH_MAX - K_SEARCH_MIN; ++j) {
                 if (j > 0 && !any_search) break;
                 const int k = search ? K_SEARCH_MIN + j : chunk_k;
@@ -361,6 +418,29 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                     os_gpu = os_sh;
                 }
 
+#ifdef LLMEM_SPECIALIZED
+                // every column but the timeline peak is known: stored now, so that none of them
+                // occupies registers during the timeline
+                if (!SWEEP) {
+                    long long at_i = i;
+                    LLMEM_ANCHOR(at_i);
+                    if (a.out_peaks) a.out_peaks[at_i] = (i64)m_peak;
+                    long long *o = a.out_detail + at_i;
+                    o[(long long)LLMEM_D_PEAK * n] = (i64)m_peak;
+                    o[(long long)LLMEM_D_PARAM_GPU * n] = (i64)param_gpu;
+                    o[(long long)LLMEM_D_GRAD_GPU * n] = (i64)grad_logical;
+                    o[(long long)LLMEM_D_OS_GPU * n] = (i64)os_gpu;
+                    o[(long long)LLMEM_D_OUT * n] = (i64)m_out;
+                    o[(long long)LLMEM_D_LM * n] = (i64)m_lm;
+                    o[(long long)LLMEM_D_BACK * n] = (i64)m_back;
+                    o[(long long)LLMEM_D_K * n] = (i64)k_used;
+                    o[(long long)LLMEM_D_NPARAMS * n] = (i64)n_params;
+                    o[(long long)LLMEM_D_TMAX * n] = (i64)t_max;
+                    o[(long long)LLMEM_D_FLAGS * n] = (i64)flags;
+                }
+#endif
+                // what is resident before the iteration starts (one value instead of five during the timeline)
+                const i64 prelude = (i64)(m_base + param_gpu + os_gpu + lm_p * B16 + grad_extra);
                 i64 at = 0, best = 0;                                         // the empty prefix counts
                 // value of one size class for this lane's configuration: rounded bytes
                 auto class_value = [&](u32 coef, u32 dims, u32 meta) -> u64 {
@@ -405,10 +485,14 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                         char *row = vals + (NARROW ? lane * 4 : (lane & 31) * 8);
                         u64 seen = 0, raw_before = 0;
                         int at_word = pc_classes;
+                        LLMEM_UNROLL_NARROW
                         for (int c0 = 0; c0 < nc; c0 += PROG_CLASS_FETCH, at_word += 2 * PROG_CLASS_FETCH) {
+#pragma unroll
+                            for (int q = 0; q < 16; ++q) LLMEM_ANCHOR(D[q]);
                             u32 cw[2 * PROG_CLASS_FETCH];
 #pragma unroll
-                            for (int q = 0; q < 2 * PROG_CLASS_FETCH; ++q) cw[q] = a.prog[at_word + q];
+                            for (int q = 0; q < 2 * PROG_CLASS_FETCH; ++q)
+                                cw[q] = NARROW ? LLMEM_PROG(at_word + q) : LLMEM_PROG_LOOP(at_word + q);
 #pragma unroll
                             for (int u = 0; u < PROG_CLASS_FETCH; ++u) {
                                 const int c = c0 + u;
@@ -458,10 +542,11 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                         u32 has_point = 0;                                                // wave-uniform, kept scalar
                         i64 acc = 0, top = LOWEST;
                         const int w_begin = (int)seg_at[0], w_end = (int)seg_at[LLMEM_NSEG];
+                        LLMEM_UNROLL_NARROW
                         for (int w = w_begin; w < w_end; w += PROG_FETCH) {
                             u32 t[PROG_FETCH];
 #pragma unroll
-                            for (int q = 0; q < PROG_FETCH; ++q) t[q] = a.prog[w + q];
+                            for (int q = 0; q < PROG_FETCH; ++q) t[q] = NARROW ? LLMEM_PROG(w + q) : LLMEM_PROG_LOOP(w + q);
                             int v32[NARROW ? PROG_FETCH : 1];
                             if (NARROW) {
 #pragma unroll
@@ -509,15 +594,15 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                             }
                         }
                     };
-                    const u64 seen = store_classes(std::true_type());
+                    const u64 seen = store_classes(Narrow());
                     // every size of every lane below 2^31 blocks: the 32-bit walk is exact
                     if (__builtin_amdgcn_ballot_w64((seen >> 31) != 0) == 0) {
-                        walk_terms(std::true_type());
+                        walk_terms(Narrow());
                     } else {
                         for (u32 half = 0; half < 2; ++half) {
                             if ((u32)(lane >> 5) == half) {
-                                store_classes(std::false_type());
-                                walk_terms(std::false_type());
+                                store_classes(Wide());
+                                walk_terms(Wide());
                             }
                         }
                     }
@@ -556,7 +641,6 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                     close_segment(s, run, top, top != LOWEST);
                 }
                 }
-                const i64 prelude = (i64)(m_base + param_gpu + os_gpu + lm_p * B16 + grad_extra);
                 r_param = (i64)param_gpu; r_grad = (i64)grad_logical; r_os = (i64)os_gpu; r_out = (i64)m_out;
                 r_lm = (i64)m_lm; r_back = (i64)m_back; r_k = (i64)k_used; r_live = prelude + best;
                 r_np = (i64)n_params; r_tmax = (i64)t_max; r_flags = (i64)flags;
@@ -589,6 +673,19 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
                     raise(LLMEM_S_BEST, ((u64)score2 << SWEEP_INDEX_BITS) | (index_mask - (u64)(a.sweep_first + i)));
                 }
             }
+#ifdef LLMEM_SPECIALIZED
+        } else if (DETAIL && in_range) {
+            // valid configurations have stored the other columns already; invalid ones store them all
+            long long *o = a.out_detail + i;
+            if (valid) {
+                o[(long long)LLMEM_D_PEAK_LIVE * n] = r_live;
+            } else {
+                if (a.out_peaks) a.out_peaks[i] = -1;
+#pragma unroll
+                for (int c = 0; c < LLMEM_NDETAIL; ++c)
+                    o[(long long)c * n] = c == LLMEM_D_PEAK ? -1 : c == LLMEM_D_FLAGS ? (i64)err : 0;
+            }
+#endif
         } else if (in_range) {
             if (a.out_peaks) a.out_peaks[i] = r_peak;
             if (DETAIL) {
@@ -625,6 +722,32 @@ __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(5))) v
             }
         }
     }
+}
+
+#ifdef LLMEM_SPECIALIZED
+
+// the flavour of the specialized kernel this build is for (LLMEM_SPEC_FLAVOUR: 0 m_peak only, 1 with
+// the detail columns, 2 sweep)
+#if LLMEM_SPEC_FLAVOUR == 0
+extern "C" __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
+void llmem_specialized_peaks(const EstimateArgs a) { estimate_batch_body<false, true, false>(a); }
+#elif LLMEM_SPEC_FLAVOUR == 1
+extern "C" __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
+void llmem_specialized_detail(const EstimateArgs a) { estimate_batch_body<true, true, false>(a); }
+#else
+extern "C" __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
+void llmem_specialized_sweep(const EstimateArgs a) { estimate_batch_body<true, true, true>(a); }
+#endif
+
+}  // namespace llmem
+
+#else
+
+template <bool DETAIL, bool COMPILED, bool SWEEP>
+__global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
+void estimate_batch_kernel(const EstimateArgs a)
+{
+    estimate_batch_body<DETAIL, COMPILED, SWEEP>(a);
 }
 
 // empty statistics: 0, and the largest value where a minimum is kept
@@ -694,3 +817,5 @@ void launch_sweep_kernel(const EstimateArgs &args, long long n_batch, hipStream_
 }
 
 }  // namespace llmem
+
+#endif  // LLMEM_SPECIALIZED

@@ -9,10 +9,16 @@
 // real models, whose weights and dataset the estimator never reads.
 #pragma once
 
+#ifndef __HIPCC_RTC__
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#endif
 
+#ifdef __HIPCC_RTC__
+#include "llmem.h"                 // the run-time compiler gets every file by its bare name
+#else
 #include "../../include/llmem.h"
+#endif
 
 namespace llmem {
 

@@ -1,0 +1,160 @@
+// Specialized form of the lane kernel: estimate_batch.hip compiled at run time
+// (hiprtc) with the compiled tables of one set of architecture tables as
+// constants, loaded as a module and launched like the built-in kernels.
+//
+// One build per (device, table words, flavour), made on first use (a few seconds)
+// and kept until the process ends.  The sources come from embedded_sources.inc,
+// which the build step writes from the files next to this one, so that the
+// run-time build and the built-in kernels are the same code.
+#include <hip/hip_runtime.h>
+#include <hip/hiprtc.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/llmem.h"
+#include "estimate_args.h"
+#include "embedded_sources.inc"   // EMBEDDED_COUNT, EMBEDDED_NAMES[], EMBEDDED_TEXTS[]; entry 0 is estimate_batch.hip
+
+namespace llmem {
+
+void set_error_text(const char *text);          // estimate.hip: what llmem_strerror(LLMEM_EHIP) returns
+
+namespace {
+
+constexpr int SPECIALIZED_WAVES = 4;            // waves per SIMD the build aims at (128 registers)
+const char *const FLAVOUR_KERNEL[3] = {"llmem_specialized_peaks", "llmem_specialized_detail", "llmem_specialized_sweep"};
+
+struct Built {
+    hipModule_t module = nullptr;
+    hipFunction_t function = nullptr;
+    int per_cu = 1, cu_count = 256;
+};
+
+struct Key {
+    int device, flavour;
+    std::vector<uint32_t> words;
+    bool operator<(const Key &o) const
+    {
+        if (device != o.device) return device < o.device;
+        if (flavour != o.flavour) return flavour < o.flavour;
+        return words < o.words;
+    }
+};
+
+std::mutex g_lock;
+std::map<Key, Built> g_built;                   // never erased: modules stay loaded until the process ends
+
+int fail(const std::string &text)
+{
+    set_error_text(text.c_str());
+    return LLMEM_EHIP;
+}
+
+// the words of the compiled tables that the kernel reads: everything up to the end of the
+// architecture's terms
+size_t words_used(const EstimateArgs &args)
+{
+    const size_t n = (size_t)args.arch[0].prog_seg[LLMEM_NSEG];
+    return n < (size_t)PROG_WORDS ? n : (size_t)PROG_WORDS;
+}
+
+std::string constants_header(const std::vector<uint32_t> &words)
+{
+    std::string list;
+    char item[16];
+    for (size_t q = 0; q < words.size(); ++q) {
+        snprintf(item, sizeof(item), "0x%08xu,", words[q]);
+        list += item;
+        if (q % 8 == 7) list += "\n";
+    }
+    char head[256];
+    snprintf(head, sizeof(head), "#pragma once\nnamespace llmem {\nconstexpr int SPEC_WAVES = %d;\nconstexpr int SPEC_N = %zu;\n",
+             SPECIALIZED_WAVES, words.size());
+    return std::string(head) + "__device__ constexpr unsigned SPEC_PROG[SPEC_N] = {\n" + list + "};\n"
+           + "__constant__ unsigned SPEC_PROG_MEM[SPEC_N] = {\n" + list + "};\n}\n";
+}
+
+int build(const Key &key, Built *out)
+{
+    const std::string constants = constants_header(key.words);
+    std::vector<const char *> names, texts;
+    for (int q = 1; q < EMBEDDED_COUNT; ++q) { names.push_back(EMBEDDED_NAMES[q]); texts.push_back(EMBEDDED_TEXTS[q]); }
+    names.push_back("specialized_prog.h");
+    texts.push_back(constants.c_str());
+    hiprtcProgram program;
+    if (hiprtcCreateProgram(&program, EMBEDDED_TEXTS[0], EMBEDDED_NAMES[0], (int)names.size(), texts.data(), names.data())
+        != HIPRTC_SUCCESS)
+        return fail("run-time compiler: cannot create the program");
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, key.device) != hipSuccess) { hiprtcDestroyProgram(&program); return fail("no device properties"); }
+    const std::string arch = std::string("--offload-arch=") + prop.gcnArchName;
+    const std::string entry = std::string("-DLLMEM_SPEC_FLAVOUR=") + std::to_string(key.flavour);
+    const char *options[] = {arch.c_str(), "-O3", "-std=c++17", "-DLLMEM_SPECIALIZED", entry.c_str(),
+                             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    const hiprtcResult compiled = hiprtcCompileProgram(program, (int)(sizeof(options) / sizeof(options[0])), options);
+    if (compiled != HIPRTC_SUCCESS) {
+        size_t size = 0;
+        std::string log;
+        if (hiprtcGetProgramLogSize(program, &size) == HIPRTC_SUCCESS && size > 1) {
+            log.resize(size);
+            hiprtcGetProgramLog(program, &log[0]);
+        }
+        hiprtcDestroyProgram(&program);
+        return fail("run-time compiler: " + std::string(hiprtcGetErrorString(compiled)) + ": " + log.substr(0, 160));
+    }
+    size_t code_size = 0;
+    hiprtcGetCodeSize(program, &code_size);
+    std::vector<char> code(code_size);
+    hiprtcGetCode(program, code.data());
+    hiprtcDestroyProgram(&program);
+    hipError_t e = hipModuleLoadData(&out->module, code.data());
+    if (e != hipSuccess) return fail(std::string("loading the specialized kernel: ") + hipGetErrorString(e));
+    e = hipModuleGetFunction(&out->function, out->module, FLAVOUR_KERNEL[key.flavour]);
+    if (e != hipSuccess) return fail(std::string("specialized kernel not found in its module: ") + hipGetErrorString(e));
+    out->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    return LLMEM_OK;
+}
+
+}  // namespace
+
+int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch, hipStream_t stream)
+{
+    if (flavour < 0 || flavour > 2 || !args.use_program || args.n_arch != 1) return LLMEM_EINVAL_TABLE;
+    Key key;
+    if (hipGetDevice(&key.device) != hipSuccess) return fail("no current device");
+    key.flavour = flavour;
+    key.words.assign(args.prog, args.prog + words_used(args));
+    const size_t lds_bytes = batch_kernel_lds_bytes(args);
+    Built built;
+    {
+        std::lock_guard<std::mutex> hold(g_lock);
+        auto at = g_built.find(key);
+        if (at == g_built.end()) {
+            const int rc = build(key, &built);
+            if (rc != LLMEM_OK) return rc;
+            int per_cu = 0;
+            if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, built.function, 64 * BATCH_WAVES, lds_bytes)
+                    == hipSuccess && per_cu > 0)
+                built.per_cu = per_cu;
+            at = g_built.emplace(key, built).first;
+        }
+        built = at->second;
+    }
+    long long blocks = (n_batch + BATCH_WAVES - 1) / BATCH_WAVES;
+    const long long resident = (long long)built.per_cu * built.cu_count * 16;   // as for the built-in compiled form
+    if (blocks > resident) blocks = resident;
+    EstimateArgs copy = args;
+    void *params[] = {&copy};
+    const hipError_t e = hipModuleLaunchKernel(built.function, (unsigned)blocks, 1, 1, 64 * BATCH_WAVES, 1, 1,
+                                               (unsigned)lds_bytes, stream, params, nullptr);
+    if (e != hipSuccess) return fail(std::string("launching the specialized kernel: ") + hipGetErrorString(e));
+    return LLMEM_OK;
+}
+
+}  // namespace llmem

@@ -3,8 +3,10 @@
 // divisor through a multiply-high.
 #pragma once
 
+#ifndef __HIPCC_RTC__
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#endif
 
 namespace llmem {
 

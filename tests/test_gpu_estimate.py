@@ -20,19 +20,22 @@ def U():
     return gpu_util
 
 
-WAVE, LANE, LANE_EVENTS, LANE_COMPILED = 1, 2, 3, 4       # LLMEM_KERNEL_*
-BOTH = (WAVE, LANE_EVENTS, LANE_COMPILED)
+WAVE, LANE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED = 1, 2, 3, 4, 5       # LLMEM_KERNEL_*
+BOTH = (WAVE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED)
 
 
 def _check(U, cfg, tables, const=CONST, threads=8, expect=None):
     """Every kernel form the tables allow (one wavefront per configuration; one lane per
-    configuration walking all events; the same with the host-compiled tables), each forced,
-    plus the library's own choice, against the oracle.  `expect`: forms that must be allowed."""
+    configuration walking all events; the same with the host-compiled tables; the same built at
+    run time with those tables as constants), each forced, plus the library's own choice,
+    against the oracle.  `expect`: forms that must be allowed."""
     import paper_2404_10933_amd as M
     allowed = M.llmem_kernel_forms(M.Tables(tables, m_base=const.m_base, cu_p=const.cu_p, align=const.align,
                                             device=None))["allowed"]
     if expect is not None:
-        assert sorted(k for k in allowed if k != LANE) == sorted(expect), allowed
+        assert sorted(k for k in allowed if k not in (LANE, LANE_SPECIALIZED)) \
+            == sorted(k for k in expect if k != LANE_SPECIALIZED), allowed
+        assert (LANE_SPECIALIZED in allowed) == (LANE_COMPILED in allowed and len(tables) == 1)
     want_p, want_d = B.estimate(cfg, tables, const, threads=threads)
     for kernel in [0] + allowed:
         got_p, got_d = U.hip_estimate(cfg, tables, const, kernel=kernel)
@@ -40,7 +43,7 @@ def _check(U, cfg, tables, const=CONST, threads=8, expect=None):
         U.assert_same(f"peaks (kernel {kernel})", got_p, want_p)
         got_p2, _ = U.hip_estimate(cfg, tables, const, detail=False, kernel=kernel)
         U.assert_same(f"peaks, no detail (kernel {kernel})", got_p2, want_p)
-    for kernel in (WAVE, LANE, LANE_EVENTS, LANE_COMPILED):
+    for kernel in (WAVE, LANE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED):
         if kernel not in allowed:
             with pytest.raises(M.LlmemError) as e:
                 U.hip_estimate(cfg, tables, const, kernel=kernel)

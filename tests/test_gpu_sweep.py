@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 CONST = T.Constants(m_base=256 << 20)
 CONST0 = T.Constants(m_base=0)
 GIB = 1 << 30
-KERNEL_LANE_EVENTS = 3          # LLMEM_KERNEL_LANE_EVENTS
+KERNEL_LANE_EVENTS, KERNEL_LANE_SPECIALIZED = 3, 5          # LLMEM_KERNEL_*
 GRIDS = {1: (G.grid1, "gpt"), 2: (G.grid2, "opt"), 3: (G.grid3, "llama"), 4: (G.grid4, "llama")}
 
 
@@ -77,6 +77,22 @@ def test_random_grids(U, grid_id, n):
 def test_events_form_of_the_kernel(U):
     _check(U, 4, 0, 0, 5_000, 40 * GIB, kernel=KERNEL_LANE_EVENTS)
     _check(U, 1, 0, 0, 432, 300 << 20, kernel=KERNEL_LANE_EVENTS)
+
+
+@pytest.mark.parametrize("grid_id,n", ((1, 432), (2, 20_000), (4, 30_037)))
+def test_specialized_form_of_the_kernel(U, grid_id, n):
+    """The sweep built at run time with the tables as constants; a second table set in the same
+    process gets its own build."""
+    for seed, first, m_total in ((0, 0, 40 * GIB), (7, 123_456_789 if grid_id > 1 else 0, 2 * GIB)):
+        _check(U, grid_id, seed, first, n, m_total, kernel=KERNEL_LANE_SPECIALIZED)
+    if grid_id == 4:
+        _check(U, 4, 3, 0, 8_000, 60 * GIB, tables=[T.llama_table(checkpoint=False)], kernel=KERNEL_LANE_SPECIALIZED)
+        import paper_2404_10933_amd as M
+        two = M.Tables([T.llama_table(), T.gpt_table()], m_base=CONST.m_base, kernel=KERNEL_LANE_SPECIALIZED)
+        stats = torch.zeros((M.NSWEEP, M.SWEEP_GROUPS), dtype=torch.int64, device="cuda")
+        with pytest.raises(M.LlmemError) as e:                      # one architecture per specialization
+            M.llmem_sweep(4, 0, 0, 100, two, 40 * GIB, stats)
+        assert e.value.code == -3
 
 
 def test_full_traversal_tables_and_second_architecture_unused(U):
