@@ -25,7 +25,9 @@ PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12       # 256 CUs x one 64-lane vector in
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs under profiles/, scaled by the
 # plain-copy reference; None while the kernel has changed since the counters were taken
-TRAFFIC_ESTIMATE = 1.3514e9     # 10^7 configurations, all detail columns
+TRAFFIC_ESTIMATE = 1.3514e9     # 10^7 configurations, all detail columns, built-in compiled form
+TRAFFIC_SPECIALIZED = None      # the same workload, kernel built at run time
+TRAFFIC_SWEEP = None            # 10^7 configurations drawn and reduced in the kernel built at run time
 TRAFFIC_TIMELINE = 8.0201e9     # 100 000 event lists, 1 000 110 810 events
 TRAFFIC_DECIDE = 5.4014e8       # 4 000 000 queries, all decision columns
 
@@ -92,8 +94,10 @@ def main():
                     help="configurations of the streaming sweep (drawn, estimated and reduced in one kernel; 0: skip)")
     ap.add_argument("--queries", type=int, default=4_000_000, help="queries of the method-decision grid (0: skip)")
     ap.add_argument("--cpu-sample", type=int, default=600_000, help="configurations the CPU oracle is timed on (0: skip)")
-    ap.add_argument("--kernel", choices=("auto", "wave", "lane"), default="auto",
-                    help="estimator kernel: one wavefront or one lane per configuration (auto: the library chooses)")
+    ap.add_argument("--kernel", choices=("specialized", "auto", "wave", "lane"), default="specialized",
+                    help="estimator kernel: the lane kernel built at run time with the tables as constants (built "
+                         "during warm-up, build time reported), the library's own choice among the built-in forms, "
+                         "one wavefront or one lane per configuration")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy ten times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -123,11 +127,23 @@ def main():
     n = args.n
     dev = M.DeviceConfigs.empty(n)
     M.llmem_grid_generate(4, 0, 0, n, dev)
-    kernel = {"auto": 0, "wave": 1, "lane": 2}[args.kernel]
+    kernel = {"auto": 0, "wave": 1, "lane": 2, "specialized": 5}[args.kernel]
     tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=kernel)
     peaks = torch.empty(n, dtype=torch.int64, device="cuda")
     detail = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
     torch.cuda.synchronize()
+    build_s, kernel_note = None, args.kernel
+    if args.kernel == "specialized":
+        # the first call builds and loads the kernel for these tables; not part of the timed steps
+        t0 = time.perf_counter()
+        try:
+            M.llmem_estimate_ex(dev, tab, peaks, detail, n=64)
+            torch.cuda.synchronize()
+            build_s = time.perf_counter() - t0
+            kernel_note = f"specialized (built at run time before the warm-up: {build_s:.2f} s)"
+        except M.LlmemError as e:
+            kernel, kernel_note = 0, f"auto (the run-time build failed: {e})"
+            tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=0)
 
     for _ in range(args.warmup):
         M.llmem_estimate_ex(dev, tab, peaks, detail)
@@ -148,7 +164,7 @@ def main():
     forms = M.llmem_kernel_forms(tab)
     ops = algorithmic_lane_ops(forms, 9)
     achieved = ops * n / (kernel_ms * 1e-3) / 1e12
-    kernel_name = "estimate_kernel<true>" if args.kernel == "wave" else "estimate_batch_kernel<true, true, false>"
+    kernel_name = {1: "estimate_kernel<true>", 5: "llmem_specialized_detail"}.get(kernel, "estimate_batch_kernel<true, true, false>")
     bytes_per_cfg = M.llmem_config_bytes(1) + 8 + 8 * M.NDETAIL
     result = {
         "metric": "configs estimated/sec (bit-exact vs oracle)",
@@ -159,10 +175,10 @@ def main():
                                "m_peak + all detail columns incl. timeline peak",
                    "n_configs": n, "table_params": len(table.params), "table_events": len(table.events),
                    "table_size_classes": forms["size_classes"], "table_peak_points": forms["peak_points"],
-                   "table_terms": forms["terms"], "kernel": args.kernel, "seed": 0},
+                   "table_terms": forms["terms"], "kernel": kernel_note, "seed": 0},
         "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
                      "frac": achieved / PEAK_LANE_TOPS,
-                     "traffic": TRAFFIC_ESTIMATE if (n == 10_000_000 and args.kernel == "auto") else None,
+                     "traffic": ({0: TRAFFIC_ESTIMATE, 5: TRAFFIC_SPECIALIZED}.get(kernel) if n == 10_000_000 else None),
                      "kernel": kernel_name, "kernel_ms": kernel_ms,
                      "algorithmic_lane_ops_per_config": ops,
                      "hbm_gbs_algorithmic": bytes_per_cfg * n / (kernel_ms * 1e-3) / 1e9},
@@ -175,6 +191,31 @@ def main():
     assert (peaks[:len(idx)].cpu().numpy() == want_p).all() and \
         (detail[:, :len(idx)].cpu().numpy().T == want_d).all(), "bench output differs from the oracle"
     result["verified_vs_oracle"] = int(len(idx))
+
+    if kernel == 5:
+        itab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=0)
+        for _ in range(2):
+            M.llmem_estimate_ex(dev, itab, peaks, detail)
+        torch.cuda.synchronize()
+        reps = 10
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            M.llmem_estimate_ex(dev, itab, peaks, detail)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        i_achieved = ops * n / (ms * 1e-3) / 1e12
+        assert (peaks[:len(idx)].cpu().numpy() == want_p).all() and \
+            (detail[:, :len(idx)].cpu().numpy().T == want_d).all(), "built-in kernel's output differs from the oracle"
+        result.setdefault("extra", {})["g4_built_in_kernel"] = {
+            "workload": "the headline workload with the built-in compiled form (tables read from the kernel arguments)",
+            "n_configs": n, "ms_per_launch": ms, "configs_per_s": n / (ms * 1e-3),
+            "roofline": {"bound": "alu", "achieved": i_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
+                         "frac": i_achieved / PEAK_LANE_TOPS, "traffic": TRAFFIC_ESTIMATE if n == 10_000_000 else None,
+                         "kernel": "estimate_batch_kernel<true, true, false>", "algorithmic_lane_ops_per_config": ops},
+            "verified_vs_oracle": int(len(idx))}
 
     if args.lists > 0:
         nl = args.lists
@@ -201,12 +242,12 @@ def main():
         ms = e0.elapsed_time(e1) / reps
         nbytes = 8 * total + 8 * (nl + 1) + 16 * nl
         gbs = nbytes / (ms * 1e-3) / 1e9
-        result["extra"] = {"g5_event_lists": {
+        result.setdefault("extra", {})["g5_event_lists"] = {
             "workload": "g5: explicit allocator event lists (~10^4 events each)", "n_lists": nl,
             "n_events": total, "ms_per_launch": ms, "lists_per_s": nl / (ms * 1e-3),
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_TIMELINE if nl == 100_000 else None,
-                         "kernel": "timeline_kernel"}}}
+                         "kernel": "timeline_kernel"}}
         from workloads import events as E
         ev_c, off_c = E.generate(64, seed=0, first=0)
         wa, wr = B.event_lists_peaks(ev_c, off_c)
@@ -216,7 +257,7 @@ def main():
     if args.full_traversal > 0:
         nf = min(args.full_traversal, n)
         ftab = M.Tables([T.llama_table(checkpoint=False)], m_base=const.m_base + (64 << 20), cu_p=const.cu_p,
-                        align=const.align)
+                        align=const.align, kernel=kernel)
         for _ in range(2):
             M.llmem_estimate_ex(dev, ftab, peaks, detail, n=nf)
         torch.cuda.synchronize()
@@ -281,8 +322,9 @@ def main():
             "n_configs": nsw, "ms_per_launch": ms, "configs_per_s": nsw / (ms * 1e-3),
             "configs_fitting": int(stats[1].sum().item()),
             "roofline": {"bound": "alu", "achieved": s_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
-                         "frac": s_achieved / PEAK_LANE_TOPS, "traffic": None,
-                         "kernel": "estimate_batch_kernel<true, true, true>",
+                         "frac": s_achieved / PEAK_LANE_TOPS,
+                         "traffic": TRAFFIC_SWEEP if (kernel == 5 and nsw == 10_000_000) else None,
+                         "kernel": "llmem_specialized_sweep" if kernel == 5 else "estimate_batch_kernel<true, true, true>",
                          "algorithmic_lane_ops_per_config": s_ops},
             "verified_vs_oracle": ns}
 

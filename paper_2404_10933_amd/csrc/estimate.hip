@@ -441,8 +441,7 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
     }
     // ---- peak points and net change of every segment ----
     std::vector<std::vector<int>> seg_sums[LLMEM_NSEG];           // kept points, then the net change last
-    std::vector<int> neg_slot(nc, 0);                             // extra slot holding -value, if a count is negative
-    int n_slots = nc + 1;
+    const int n_slots = nc + 1;                                   // slot 0 holds 0, slot c + 1 minus the value of class c
     for (int s = 0; s < LLMEM_NSEG; ++s) {
         std::vector<std::vector<int>> points;
         std::vector<int> count(nc, 0);
@@ -462,8 +461,6 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
             if (!dominated) seg_sums[s].push_back(points[j]);
         }
         seg_sums[s].push_back(count);
-        for (const auto &v : seg_sums[s])
-            for (int c = 0; c < nc; ++c) if (v[c] < 0 && neg_slot[c] == 0) neg_slot[c] = n_slots++;
     }
     if (n_slots > PROG_SLOT_MAX) return false;
     stats[0] += (int)groups.size();
@@ -483,8 +480,7 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
         }
         prog->push_back(first_word);
         prog->push_back(size_desc | ((flags & LLMEM_EV_TP_GATHER) ? DESC_TP_GATHER : 0u)
-                        | ((flags & LLMEM_EV_TIMES_L) ? DESC_TIMES_L : 0u) | (mask << DESC_MASK_SHIFT)
-                        | ((uint32_t)neg_slot[c] << DESC_NEG_SLOT_SHIFT));
+                        | ((flags & LLMEM_EV_TIMES_L) ? DESC_TIMES_L : 0u) | (mask << DESC_MASK_SHIFT));
     }
     for (int c = nc; c % PROG_CLASS_FETCH; ++c) { prog->push_back(0u); prog->push_back(0u); }   // empty classes
     for (int s = 0; s < LLMEM_NSEG; ++s) {
@@ -495,10 +491,9 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
             const size_t group_first = prog->size();
             for (int c = 0; c < nc; ++c) {
                 if (v[c] == 0) continue;
-                const int mag = v[c] < 0 ? -v[c] : v[c];
-                if (mag > 65535) return false;
-                const int slot = v[c] < 0 ? neg_slot[c] : c + 1;
-                prog->push_back((uint32_t)slot * SLOT_ROW | ((uint32_t)mag << 16));
+                if (v[c] > 32767 || v[c] < -32767) return false;
+                // the slot holds minus the value: the factor is minus the count, as a signed 16-bit field
+                prog->push_back((uint32_t)(c + 1) * SLOT_ROW | ((uint32_t)(uint16_t)(int16_t)(-v[c]) << 16));
                 ++stats[2];                                                         // (class, count) terms
             }
             stats[3] += is_point ? 1 : 0;                                           // peak points

@@ -41,20 +41,20 @@ constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
 //              multiple of PROG_CLASS_FETCH)
 //   the sums of the segments A F H B Z one after the other, each sum in groups of PROG_GROUP
 //              terms: a segment's peak points, then its net change.  A term is
-//              slot * SLOT_ROW | count << 16: the partial sum gains count * value[slot].  A flag in
+//              slot * SLOT_ROW | factor << 16 with a signed 16-bit factor: the partial sum gains
+//              factor * slot value.  A flag in
 //              the first term of a sum's last group closes it: PROG_END_POINT (the sum competes
 //              for the segment's maximum and the partial sum restarts) or PROG_END_SEGMENT (the
 //              sum is the segment's net change; the next segment starts).  Padding terms are 0
 //              (slot 0 holds 0); whole groups of them pad the list to PROG_FETCH words.
-//              Slot c + 1 holds the value of class c; a class that some sum counts negatively
-//              has a second slot holding minus its value.
+//              Slot c + 1 holds MINUS the value of class c and the factor is minus the count, so
+//              that a value of exactly 2^31 allocator blocks still fits a signed 32-bit slot.
 // Descriptor: number of dimensions (bits 0-2), their selectors (4 bits each from bit 4),
-// DESC_TP_GATHER, DESC_TIMES_L, method mask (3 bits from DESC_MASK_SHIFT), slot of the negated
-// value (from DESC_NEG_SLOT_SHIFT, 0 = none).
+// DESC_TP_GATHER, DESC_TIMES_L, method mask (3 bits from DESC_MASK_SHIFT).
 constexpr unsigned DESC_TP_GATHER = 1u << 20, DESC_TIMES_L = 1u << 21;
 constexpr unsigned DESC_FROM_PREVIOUS = 7;     // in place of the number of dimensions: the previous class's raw
                                                // size shifted left by the first word
-constexpr int DESC_MASK_SHIFT = 22, DESC_NEG_SLOT_SHIFT = 25;
+constexpr int DESC_MASK_SHIFT = 22;
 constexpr int PROG_SLOT_MAX = 100;
 constexpr int PROG_WORDS = 704;
 constexpr int DIM_BS_SL = 15;                  // selector of bs * sl in the compiled descriptors (after the LLMEM_DIM_* ones)

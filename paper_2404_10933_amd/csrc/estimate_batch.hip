@@ -194,8 +194,8 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
     const u64 m_base = (u64)a.m_base;
     // value slots of this wave.  Events form: slot s of lane l at byte s * 512 + l * 8; an event
     // code is the slot's byte offset with the check flag in bit 0.  Compiled form: a slot is a row
-    // of SLOT_ROW bytes holding either 64 values of 32 bits (sizes in allocator blocks, lane l at
-    // l * 4) or the 64-bit byte sizes of one half of the wave (lane l at (l % 32) * 8).
+    // of SLOT_ROW bytes holding either 64 values of 32 bits (minus the sizes in allocator blocks, lane
+    // l at l * 4) or the 64-bit byte sizes of one half of the wave (lane l at (l % 32) * 8).
     char *vals = reinterpret_cast<char *>(dyn) + (COMPILED ? (size_t)wave * a.p_slots * SLOT_ROW
                                                            : ((size_t)wave * a.s_slots * 64 + lane) * sizeof(i64));
     if (DETAIL) {
@@ -478,8 +478,9 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                     const int nc = (int)((head >> 16) & 255u);
                     const int pc_classes = pc;
                     // Classes: four per fetch (the host pads the list with empty classes).  NARROW: sizes
-                    // in allocator blocks as signed 32-bit values, all 64 lanes; else 64-bit byte sizes
-                    // of the lanes of one half of the wave.  Returns the OR of all sizes in blocks.
+                    // in allocator blocks, negated, as signed 32-bit values, all 64 lanes; else 64-bit byte
+                    // sizes of the lanes of one half of the wave.  Returns a value that is below 2^32 if
+                    // every size is at most 2^31 blocks.
                     auto store_classes = [&](auto narrow) -> u64 {
                         constexpr bool NARROW = decltype(narrow)::value;
                         char *row = vals + (NARROW ? lane * 4 : (lane & 31) * 8);
@@ -517,15 +518,12 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                                     asm volatile("" ::: "memory");
                                     r = ((mask >> method) & 1u) ? r : 0ull;
                                 }
-                                const u32 neg = desc >> DESC_NEG_SLOT_SHIFT;
                                 if (NARROW) {
-                                    seen |= r;
-                                    if (c < nc) *reinterpret_cast<u32 *>(row + (c + 1) * SLOT_ROW) = (u32)r;
-                                    if (neg) *reinterpret_cast<u32 *>(row + neg * SLOT_ROW) = 0u - (u32)r;
+                                    // minus the size in blocks: sizes up to 2^31 blocks inclusive fit
+                                    seen |= r + 0x7fffffffull;
+                                    if (c < nc) *reinterpret_cast<u32 *>(row + (c + 1) * SLOT_ROW) = 0u - (u32)r;
                                 } else {
-                                    const u64 bytes = r << align_shift;
-                                    if (c < nc) *reinterpret_cast<u64 *>(row + (c + 1) * SLOT_ROW) = bytes;
-                                    if (neg) *reinterpret_cast<u64 *>(row + neg * SLOT_ROW) = 0ull - bytes;
+                                    if (c < nc) *reinterpret_cast<u64 *>(row + (c + 1) * SLOT_ROW) = r << align_shift;
                                 }
                             }
                         }
@@ -556,22 +554,23 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 #pragma unroll
                             for (int g = 0; g < PROG_FETCH; g += PROG_GROUP) {
                                 if (NARROW) {
-                                    // signed 32-bit blocks times a count below 2^16: one multiply-add each
+                                    // signed 32-bit blocks times a signed 16-bit factor: one multiply-add each
                                     i64 part = 0;
 #pragma unroll
-                                    for (int q = g; q < g + PROG_GROUP; ++q) part += (i64)v32[q] * (i64)(int)(t[q] >> 16);
+                                    for (int q = g; q < g + PROG_GROUP; ++q) part += (i64)v32[q] * (i64)((int)t[q] >> 16);
                                     acc += part;
                                 } else {
-                                    // count * value: the low and the high halves of the values are summed
-                                    // apart (each product is below 2^48) and joined once per group
-                                    u64 part_lo = 0, part_hi = 0;
+                                    // the rows hold the byte sizes themselves; the factor is minus the count.
+                                    // |count| * value from the low and the high half of the value (each
+                                    // product is below 2^48), added or subtracted by the factor's sign
 #pragma unroll
                                     for (int q = g; q < g + PROG_GROUP; ++q) {
                                         const u64 v = *reinterpret_cast<const u64 *>(row + (t[q] & PROG_OFFSET_MASK));
-                                        part_lo += (u64)(u32)v * (t[q] >> 16);
-                                        part_hi += (u64)(u32)(v >> 32) * (t[q] >> 16);
+                                        const int factor = (int)t[q] >> 16;
+                                        const u32 mag = (u32)(factor < 0 ? -factor : factor);
+                                        const u64 prod = (u64)(u32)v * mag + (((u64)(u32)(v >> 32) * mag) << 32);
+                                        acc = factor < 0 ? (i64)((u64)acc + prod) : (i64)((u64)acc - prod);
                                     }
-                                    acc = (i64)((u64)acc + part_lo + (part_hi << 32));
                                 }
                                 // a sum ends with this group (wave-uniform): a point competes for the
                                 // segment's maximum, the net change closes the segment
@@ -595,8 +594,8 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                         }
                     };
                     const u64 seen = store_classes(Narrow());
-                    // every size of every lane below 2^31 blocks: the 32-bit walk is exact
-                    if (__builtin_amdgcn_ballot_w64((seen >> 31) != 0) == 0) {
+                    // every size of every lane at most 2^31 blocks: the 32-bit walk is exact
+                    if (__builtin_amdgcn_ballot_w64((seen >> 32) != 0) == 0) {
                         walk_terms(Narrow());
                     } else {
                         for (u32 half = 0; half < 2; ++half) {

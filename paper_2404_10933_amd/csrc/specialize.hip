@@ -2,14 +2,19 @@
 // (hiprtc) with the compiled tables of one set of architecture tables as
 // constants, loaded as a module and launched like the built-in kernels.
 //
-// One build per (device, table words, flavour), made on first use (a few seconds)
-// and kept until the process ends.  The sources come from embedded_sources.inc,
+// One build per (device, table words, flavour), made on first use (a fraction of a
+// second to a few seconds) and kept until the process ends.  With the environment
+// variable LLMEM_KERNEL_CACHE naming a directory, built code objects are also kept
+// there and loaded from there by later processes (a file per build, verified
+// against the full key and the embedded sources before use).  The sources come from embedded_sources.inc,
 // which the build step writes from the files next to this one, so that the
 // run-time build and the built-in kernels are the same code.
 #include <hip/hip_runtime.h>
 #include <hip/hiprtc.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <stdlib.h>
+#include <unistd.h>
 #include <string.h>
 
 #include <map>
@@ -31,6 +36,9 @@ constexpr int SPECIALIZED_WAVES = 4;            // waves per SIMD the build aims
 const char *const FLAVOUR_KERNEL[3] = {"llmem_specialized_peaks", "llmem_specialized_detail", "llmem_specialized_sweep"};
 
 struct Built {
+    // the code object stays in memory as long as the module is loaded: tools that follow code
+    // objects (profilers) read it at its original address after the load call has returned
+    std::vector<char> *code = nullptr;
     hipModule_t module = nullptr;
     hipFunction_t function = nullptr;
     int per_cu = 1, cu_count = 256;
@@ -80,7 +88,81 @@ std::string constants_header(const std::vector<uint32_t> &words)
            + "__constant__ unsigned SPEC_PROG_MEM[SPEC_N] = {\n" + list + "};\n}\n";
 }
 
+// ---- code objects kept between processes (LLMEM_KERNEL_CACHE) ---------------------------------
+// File = the identity (architecture name, flavour, waves per SIMD, table words, every embedded
+// source) followed by the code object; a file whose identity differs in any byte is ignored.
+std::string identity(const Key &key, const char *arch_name)
+{
+    std::string id = std::string("llmem-specialized-1|") + arch_name + "|" + std::to_string(key.flavour) + "|"
+                     + std::to_string(SPECIALIZED_WAVES) + "|";
+    id.append(reinterpret_cast<const char *>(key.words.data()), key.words.size() * sizeof(uint32_t));
+    for (int q = 0; q < EMBEDDED_COUNT; ++q) { id += "|"; id += EMBEDDED_TEXTS[q]; }
+    return id;
+}
+
+std::string cache_path(const std::string &id)
+{
+    const char *dir = getenv("LLMEM_KERNEL_CACHE");
+    if (!dir || !dir[0]) return std::string();
+    unsigned long long h = 1469598103934665603ull;                       // FNV-1a: the file's name only
+    for (unsigned char c : id) { h ^= c; h *= 1099511628211ull; }
+    char name[64];
+    snprintf(name, sizeof(name), "/llmem-%016llx.co", h);
+    return std::string(dir) + name;
+}
+
+bool cache_read(const std::string &path, const std::string &id, std::vector<char> *code)
+{
+    FILE *f = fopen(path.c_str(), "rb");
+    if (!f) return false;
+    std::vector<char> all;
+    char chunk[65536];
+    size_t got;
+    while ((got = fread(chunk, 1, sizeof(chunk), f)) > 0) all.insert(all.end(), chunk, chunk + got);
+    fclose(f);
+    unsigned long long id_size = 0;
+    if (all.size() < sizeof(id_size)) return false;
+    memcpy(&id_size, all.data(), sizeof(id_size));
+    if (id_size != id.size() || all.size() <= sizeof(id_size) + id.size()) return false;
+    if (memcmp(all.data() + sizeof(id_size), id.data(), id.size()) != 0) return false;
+    code->assign(all.begin() + sizeof(id_size) + id.size(), all.end());
+    return true;
+}
+
+void cache_write(const std::string &path, const std::string &id, const std::vector<char> &code)
+{
+    const std::string tmp = path + ".tmp" + std::to_string((long long)getpid());
+    FILE *f = fopen(tmp.c_str(), "wb");
+    if (!f) return;                                                    // an unwritable cache is no error
+    const unsigned long long id_size = id.size();
+    const bool ok = fwrite(&id_size, sizeof(id_size), 1, f) == 1 && fwrite(id.data(), 1, id.size(), f) == id.size()
+                    && fwrite(code.data(), 1, code.size(), f) == code.size();
+    if (fclose(f) != 0 || !ok || rename(tmp.c_str(), path.c_str()) != 0) remove(tmp.c_str());
+}
+
+int compile(const Key &key, const char *arch_name, std::vector<char> *code);
+
 int build(const Key &key, Built *out)
+{
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, key.device) != hipSuccess) return fail("no device properties");
+    const std::string id = identity(key, prop.gcnArchName);
+    const std::string path = cache_path(id);
+    out->code = new std::vector<char>();
+    if (path.empty() || !cache_read(path, id, out->code)) {
+        const int rc = compile(key, prop.gcnArchName, out->code);
+        if (rc != LLMEM_OK) { delete out->code; out->code = nullptr; return rc; }
+        if (!path.empty()) cache_write(path, id, *out->code);
+    }
+    hipError_t e = hipModuleLoadData(&out->module, out->code->data());
+    if (e != hipSuccess) return fail(std::string("loading the specialized kernel: ") + hipGetErrorString(e));
+    e = hipModuleGetFunction(&out->function, out->module, FLAVOUR_KERNEL[key.flavour]);
+    if (e != hipSuccess) return fail(std::string("specialized kernel not found in its module: ") + hipGetErrorString(e));
+    out->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    return LLMEM_OK;
+}
+
+int compile(const Key &key, const char *arch_name, std::vector<char> *code)
 {
     const std::string constants = constants_header(key.words);
     std::vector<const char *> names, texts;
@@ -91,9 +173,7 @@ int build(const Key &key, Built *out)
     if (hiprtcCreateProgram(&program, EMBEDDED_TEXTS[0], EMBEDDED_NAMES[0], (int)names.size(), texts.data(), names.data())
         != HIPRTC_SUCCESS)
         return fail("run-time compiler: cannot create the program");
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, key.device) != hipSuccess) { hiprtcDestroyProgram(&program); return fail("no device properties"); }
-    const std::string arch = std::string("--offload-arch=") + prop.gcnArchName;
+    const std::string arch = std::string("--offload-arch=") + arch_name;
     const std::string entry = std::string("-DLLMEM_SPEC_FLAVOUR=") + std::to_string(key.flavour);
     const char *options[] = {arch.c_str(), "-O3", "-std=c++17", "-DLLMEM_SPECIALIZED", entry.c_str(),
                              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
@@ -110,14 +190,9 @@ int build(const Key &key, Built *out)
     }
     size_t code_size = 0;
     hiprtcGetCodeSize(program, &code_size);
-    std::vector<char> code(code_size);
-    hiprtcGetCode(program, code.data());
+    code->resize(code_size);
+    hiprtcGetCode(program, code->data());
     hiprtcDestroyProgram(&program);
-    hipError_t e = hipModuleLoadData(&out->module, code.data());
-    if (e != hipSuccess) return fail(std::string("loading the specialized kernel: ") + hipGetErrorString(e));
-    e = hipModuleGetFunction(&out->function, out->module, FLAVOUR_KERNEL[key.flavour]);
-    if (e != hipSuccess) return fail(std::string("specialized kernel not found in its module: ") + hipGetErrorString(e));
-    out->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     return LLMEM_OK;
 }
 

@@ -132,7 +132,7 @@ def test_full_traversal_tables(U, name, n, first):
 
 def test_sizes_on_both_sides_of_2_to_31_blocks(U):
     """The compiled form walks 32-bit block counts while every size of a wavefront's 64
-    configurations is below 2^31 allocator blocks, and 64-bit bytes otherwise: wavefronts
+    configurations is at most 2^31 allocator blocks, and 64-bit bytes otherwise: wavefronts
     entirely below, entirely above, and with single large configurations in either half."""
     E = T.EventEntry
     events = (E("a0", "A", +1, 3, ("V", "V"), 8), E("a1", "A", +1, 1, ("bs", "sl", "h"), 2),
@@ -160,8 +160,9 @@ def test_sizes_on_both_sides_of_2_to_31_blocks(U):
     edge = T.ArchTable("edge", T.gpt_table().params, (E("a", "A", +1, 2, ("V", "V"), 8), E("b", "A", -1, 2, ("V", "V"), 8),
                                                      E("c", "F", +1, 1, ("V", "P"), 8)))
     cfg = G.random_configs(rng, 64 * 3, n_arch=1)
-    cfg["V"][:] = 1 << 18
+    cfg["V"][:] = 1 << 18                                    # exactly 2^31 blocks: the last size the 32-bit walk takes
     cfg["V"][::7] = (1 << 18) - 1
+    cfg["V"][64 * 2 + 3::7] = (1 << 18) + 1                  # just above, in the last wavefront only
     cfg["P"][:] = rng.integers(0, 3, size=64 * 3)
     _check(U, cfg, [edge], CONST, expect=BOTH)
 
