@@ -25,9 +25,9 @@ PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12       # 256 CUs x one 64-lane vector in
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs under profiles/, scaled by the
 # plain-copy reference; None while the kernel has changed since the counters were taken
-TRAFFIC_ESTIMATE = 1.3514e9     # 10^7 configurations, all detail columns, built-in compiled form
-TRAFFIC_SPECIALIZED = None      # the same workload, kernel built at run time
-TRAFFIC_SWEEP = None            # 10^7 configurations drawn and reduced in the kernel built at run time
+TRAFFIC_ESTIMATE = 1.4743e9     # 10^7 configurations, all detail columns, built-in compiled form (incl. 12 B/lane of spill scratch)
+TRAFFIC_SPECIALIZED = 1.3503e9  # the same workload, kernel built at run time
+TRAFFIC_SWEEP = 5.0527e7        # 10^7 configurations drawn and reduced in the kernel built at run time
 TRAFFIC_TIMELINE = 8.0201e9     # 100 000 event lists, 1 000 110 810 events
 TRAFFIC_DECIDE = 5.4014e8       # 4 000 000 queries, all decision columns
 
@@ -70,10 +70,12 @@ def algorithmic_lane_ops_decide(n_param_entries, cap_bits):
 
 def algorithmic_lane_ops_sweep_extra():
     """What the streaming sweep adds per configuration of grid 4, same units: eight counter-based
-    draws (splitmix64 finaliser: two 64 x 64-bit multiplies at 5, three xor-shifts at 2, one add;
-    then a remainder, 16 by a constant that is no power of two, else 1, and the offset), the SwiGLU
-    width, the value selections, the score and the eight statistics."""
-    ADD, MUL64, XORSHIFT, REM, DIV = 1, 5, 2, 16, 12
+    draws (the part of the hash input that all fields share, once; per draw one add and the
+    splitmix64 finaliser: two 64 x 64-bit multiplies at 4 (two 32-bit products, one 32 x 32 -> 64
+    multiply-add, one add), three xor-shifts at 2; then a remainder, priced like a division, 12, by
+    a constant that is no power of two, else 1, and the offset), the SwiGLU width, the value
+    selections, the score and the eight statistics."""
+    ADD, MUL64, XORSHIFT, REM, DIV = 1, 4, 2, 12, 12
     draw = ADD + 3 * XORSHIFT + 2 * MUL64
     draws = 8 * draw + 4 * (REM + ADD) + 4 * (1 + ADD) + (MUL64 + 2 * ADD)
     shape = (DIV + 3 * ADD) + 10                  # ffn = 8h/3 rounded up to 256; table look-ups as selects
@@ -140,7 +142,8 @@ def main():
             M.llmem_estimate_ex(dev, tab, peaks, detail, n=64)
             torch.cuda.synchronize()
             build_s = time.perf_counter() - t0
-            kernel_note = f"specialized (built at run time before the warm-up: {build_s:.2f} s)"
+            kernel_note = (f"specialized (built at run time, or loaded from LLMEM_KERNEL_CACHE, before the warm-up: "
+                           f"{build_s:.2f} s)")
         except M.LlmemError as e:
             kernel, kernel_note = 0, f"auto (the run-time build failed: {e})"
             tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=0)

@@ -182,7 +182,9 @@ typedef struct llmem_tables {
  * the compiled tables as constants, so that every table word becomes an immediate and every
  * loop over table entries straight-line code.  The first call with a given set of tables (one
  * architecture; the same condition as for the compiled form) takes a few seconds to build
- * and load the kernel; the build is kept, per device, until the process ends.  Results are
+ * and load the kernel; the build is kept, per device, until the process ends, and also
+ * between processes when the environment variable LLMEM_KERNEL_CACHE names a writable
+ * directory (one file per build, used only if its recorded identity matches in full).  Results are
  * the same bit for bit.  A failure of the run-time compiler or loader is LLMEM_EHIP with its
  * message in llmem_strerror.  llmem_estimate(_ex) and llmem_sweep honour it.            */
 #define LLMEM_KERNEL_AUTO 0
