@@ -362,40 +362,104 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
             // that one.
             const bool search = chunk_k == -1;
             const bool any_search = __builtin_amdgcn_ballot_w64(search) != 0;
-            u64 m_peak = 0, best_waste = ~0ull;
+            const bool zero3 = method == LLMEM_METHOD_ZERO3;
+            u64 m_peak = 0;
             int k_used = search ? K_SEARCH_MAX : chunk_k;
             bool found = !search;
             const u64 rest = m_base + m_out + m_lm + grad_extra;               // the same for every candidate
+            // Page form of the candidates.  A chunk of 2^(k+19) elements is a whole number of pages
+            // (cu_p bytes) at 2, 4 and 6 bytes per element once k + 20 >= log2 cu_p; then the
+            // chunked part of m_p, m_p16, m_p32 needs no rounding, the embedding's part is rounded
+            // once, before the loop, and every size of a candidate is a count of pages or allocator
+            // blocks that fits 32 bits (checked through an upper bound in bytes): the division by d
+            // becomes a 32-bit one.  The same values as the byte form below, which waves with a
+            // lane outside these conditions take.  Only the specialized build has it: there the
+            // vector instructions are the bound, while the built-in forms would pay for the second
+            // loop with registers.
+#ifdef LLMEM_SPECIALIZED
+            const int k_low = search ? K_SEARCH_MIN : chunk_k, k_high = search ? K_SEARCH_MAX : chunk_k;
+            const u64 bytes_bound = 6 * (other_p + embed_p + (1ull << (k_high + 19))) + m_os + m_back + (4ull << cu_shift);
+            const bool pages_ok = cu_shift >= 1 && k_low + 20 >= cu_shift && ((other_p | embed_p) >> 50) == 0
+                                  && (bytes_bound >> (align_shift + 31)) == 0;
+            const bool page_form = __builtin_amdgcn_ballot_w64(!pages_ok) == 0;
+#else
+            const bool page_form = false;
+#endif
+            if (page_form) {
+#ifdef LLMEM_SPECIALIZED
+                const int half_shift = cu_shift - 1, page_shift = cu_shift - align_shift;
+                const u32 fw_half = zero3 ? 2u : 3u;                          // m_p32 or m_p: bytes per element / 2
+                const u64 half_round = (1ull << half_shift) - 1;
+                const u32 embed_wide_pages = (u32)((embed_p * fw_half + half_round) >> half_shift);
+                const u32 embed_p16_pages = (u32)((embed_p + half_round) >> half_shift);
+                const u32 os_pages = (u32)(m_os >> cu_shift);
+                const u32 back_blocks = (u32)(m_back >> align_shift);
+                const u32 need_shift = t_max > 1 ? 64u - (u32)__builtin_clzll(t_max - 1) : 0u;   // least s with t_max <= 2^s
+                u32 best_waste = ~0u;
 #ifdef LLMEM_SPECIALIZED
 #pragma nounroll
 #endif
-            for (int j = 0; j <= K_SEARCH_MAX - K_SEARCH_MIN; ++j) {
-                if (j > 0 && !any_search) break;
-                const int k = search ? K_SEARCH_MIN + j : chunk_k;
-                const int cs_shift = k + 19;                                  // 2^k MiB of fp16 values
-                const u64 cs_mask = (1ull << cs_shift) - 1;
-                const u64 other_chunked = (other_p + cs_mask) & ~cs_mask;     // ceil(other_p / cs) * cs
-                const u64 chunked = embed_p + other_chunked;
-                // ZeRO-3 shards m_p32 and keeps m_p16 whole; the other two methods use m_p = 6 bytes per element
-                const bool zero3 = method == LLMEM_METHOD_ZERO3;
-                const u64 wide_part = b_up((chunked << 2) + (zero3 ? 0ull : chunked << 1), cu_shift);   // m_p32 or m_p
-                const u64 c_p16 = b_up(chunked << 1, cu_shift);
-                const u64 to_shard = wide_part + m_os;
-                const u64 shard = b_up(b_cdiv(to_shard, d, div_mul, div_shift), align_shift);
-                u64 states;
-                if (method == LLMEM_METHOD_CDP) states = to_shard;
-                else if (zero3) states = c_p16 + shard;
-                else states = shard + m_back;
-                const u64 c_peak = rest + states;
-                const u64 waste = other_chunked - other_p;
-                const bool feasible = t_max <= (1ull << cs_shift);
-                // search lanes: strictly smaller waste among feasible candidates; the last candidate
-                // stands in when none is feasible.  Other lanes: iteration 0 is their estimate.
-                const bool take = search ? ((feasible && waste < best_waste) || (!found && j == K_SEARCH_MAX - K_SEARCH_MIN))
-                                         : j == 0;
-                if (take) {
-                    m_peak = c_peak; k_used = k;
-                    if (feasible) { best_waste = waste; found = true; }
+                for (int j = 0; j <= K_SEARCH_MAX - K_SEARCH_MIN; ++j) {
+                    if (j > 0 && !any_search) break;
+                    const int k = search ? K_SEARCH_MIN + j : chunk_k;
+                    const int cs_shift = k + 19;                              // 2^k MiB of fp16 values
+                    const u64 cs_mask = (1ull << cs_shift) - 1;
+                    const u64 other_chunked = (other_p + cs_mask) & ~cs_mask; // ceil(other_p / cs) * cs
+                    const u32 chunk_pages = (u32)(other_chunked >> half_shift);            // at 2 bytes per element
+                    const u32 to_shard_pages = chunk_pages * fw_half + embed_wide_pages + os_pages;
+                    const u32 to_shard_blocks = to_shard_pages << page_shift;
+                    // ceil(blocks / d): the multiply-high of the 64-bit constants with a 32-bit dividend
+                    const u32 dividend = to_shard_blocks + (d - 1);
+                    const u64 low = (u64)dividend * (u32)div_mul;
+                    const u64 high = (u64)dividend * (u32)(div_mul >> 32) + (low >> 32);
+                    const u32 shard_blocks = d == 1 ? to_shard_blocks : (u32)(high >> 32) >> div_shift;
+                    u32 state_blocks;
+                    if (method == LLMEM_METHOD_CDP) state_blocks = to_shard_blocks;
+                    else if (zero3) state_blocks = ((chunk_pages + embed_p16_pages) << page_shift) + shard_blocks;
+                    else state_blocks = shard_blocks + back_blocks;
+                    const u64 c_peak = rest + ((u64)state_blocks << align_shift);
+                    const u32 waste = (u32)other_chunked - (u32)other_p;      // below the chunk size: 32 bits hold it
+                    const bool feasible = need_shift <= (u32)cs_shift;
+                    const bool take = search ? ((feasible && waste < best_waste) || (!found && j == K_SEARCH_MAX - K_SEARCH_MIN))
+                                             : j == 0;
+                    if (take) {
+                        m_peak = c_peak; k_used = k;
+                        if (feasible) { best_waste = waste; found = true; }
+                    }
+                }
+#endif
+            } else {
+                u64 best_waste = ~0ull;
+#ifdef LLMEM_SPECIALIZED
+#pragma nounroll
+#endif
+                for (int j = 0; j <= K_SEARCH_MAX - K_SEARCH_MIN; ++j) {
+                    if (j > 0 && !any_search) break;
+                    const int k = search ? K_SEARCH_MIN + j : chunk_k;
+                    const int cs_shift = k + 19;                              // 2^k MiB of fp16 values
+                    const u64 cs_mask = (1ull << cs_shift) - 1;
+                    const u64 other_chunked = (other_p + cs_mask) & ~cs_mask; // ceil(other_p / cs) * cs
+                    const u64 chunked = embed_p + other_chunked;
+                    // ZeRO-3 shards m_p32 and keeps m_p16 whole; the other two methods use m_p = 6 bytes per element
+                    const u64 wide_part = b_up((chunked << 2) + (zero3 ? 0ull : chunked << 1), cu_shift);   // m_p32 or m_p
+                    const u64 c_p16 = b_up(chunked << 1, cu_shift);
+                    const u64 to_shard = wide_part + m_os;
+                    const u64 shard = b_up(b_cdiv(to_shard, d, div_mul, div_shift), align_shift);
+                    u64 states;
+                    if (method == LLMEM_METHOD_CDP) states = to_shard;
+                    else if (zero3) states = c_p16 + shard;
+                    else states = shard + m_back;
+                    const u64 c_peak = rest + states;
+                    const u64 waste = other_chunked - other_p;
+                    const bool feasible = t_max <= (1ull << cs_shift);
+                    // search lanes: strictly smaller waste among feasible candidates; the last candidate
+                    // stands in when none is feasible.  Other lanes: iteration 0 is their estimate.
+                    const bool take = search ? ((feasible && waste < best_waste) || (!found && j == K_SEARCH_MAX - K_SEARCH_MIN))
+                                             : j == 0;
+                    if (take) {
+                        m_peak = c_peak; k_used = k;
+                        if (feasible) { best_waste = waste; found = true; }
+                    }
                 }
             }
             const u32 flags = t_max > (1ull << (k_used + 19)) ? LLMEM_F_CHUNK_INFEASIBLE : 0;
