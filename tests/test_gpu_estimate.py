@@ -177,27 +177,85 @@ def test_determinism_and_stream(U):
         U.assert_same("detail twice", a[1], b[1])
 
 
-def test_full_size_grid4(U):
-    """10^7 configurations, in the launch configuration the benchmark times:
-    m_peak of every configuration against the oracle, and all detail columns
-    (including the timeline walk) on the first and last batches plus a seeded sample."""
+_FULL = {}
+
+
+def _full_size_reference():
+    """Oracle results for the 10^7 grid, computed once for both kernel forms."""
+    if not _FULL:
+        n = 10_000_000
+        cfg = G.grid4(n=n, seed=0)
+        tables = [T.llama_table()]
+        want_p, _ = B.estimate(cfg, tables, CONST, timeline=False, want_detail=False, threads=16)
+        rng = np.random.default_rng(0)
+        idx = np.unique(np.concatenate([np.arange(2048), np.arange(n - 2048, n), rng.integers(0, n, size=30_000)]))
+        _, want_d = B.estimate(G.slice_configs(cfg, idx), tables, CONST, threads=16)
+        _FULL.update(n=n, cfg=cfg, tables=tables, want_p=want_p, idx=idx, want_d=want_d)
+    return _FULL
+
+
+@pytest.mark.parametrize("kernel", (0, LANE_SPECIALIZED))
+def test_full_size_grid4(U, kernel):
+    """10^7 configurations, in the launch configurations the benchmark times (the kernel built at
+    run time with the tables as constants, and the library's own choice among the built-in forms):
+    m_peak of every configuration against the oracle, and all detail columns (including the
+    timeline walk) on the first and last batches plus a seeded sample."""
     import paper_2404_10933_amd as M
-    n = 10_000_000
-    cfg = G.grid4(n=n, seed=0)
-    tables = [T.llama_table()]
-    dev = M.DeviceConfigs.from_numpy(cfg)
-    tab = M.Tables(tables, m_base=CONST.m_base, cu_p=CONST.cu_p, align=CONST.align)
+    ref = _full_size_reference()
+    n, idx = ref["n"], ref["idx"]
+    dev = M.DeviceConfigs.from_numpy(ref["cfg"])
+    tab = M.Tables(ref["tables"], m_base=CONST.m_base, cu_p=CONST.cu_p, align=CONST.align, kernel=kernel)
     peaks = torch.empty(n, dtype=torch.int64, device="cuda")
     det = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
     M.llmem_estimate_ex(dev, tab, peaks, det)
     torch.cuda.synchronize()
     got_p = peaks.cpu().numpy()
-    want_p, _ = B.estimate(cfg, tables, CONST, timeline=False, want_detail=False, threads=16)
-    U.assert_same("m_peak, all 10^7", got_p, want_p)
-    rng = np.random.default_rng(0)
-    idx = np.unique(np.concatenate([np.arange(2048), np.arange(n - 2048, n), rng.integers(0, n, size=30_000)]))
-    sub = G.slice_configs(cfg, idx)
-    _, want_d = B.estimate(sub, tables, CONST, threads=16)
+    U.assert_same("m_peak, all 10^7", got_p, ref["want_p"])
     got_d = det[:, torch.from_numpy(idx).cuda()].cpu().numpy().T
-    U.assert_same("detail, sampled", got_d, want_d)
-    assert (got_p[idx] == want_d[:, 0]).all()
+    U.assert_same("detail, sampled", got_d, ref["want_d"])
+    assert (got_p[idx] == ref["want_d"][:, 0]).all()
+
+
+def test_built_kernels_are_kept_between_processes(U, tmp_path):
+    """LLMEM_KERNEL_CACHE: a build writes one file; a second process loads it instead of building
+    (the file is not rewritten) and computes the same; a file with a foreign identity is ignored."""
+    import os
+    import subprocess
+    import sys
+    import paper_2404_10933_amd as M
+    cache = tmp_path / "kernels"
+    cache.mkdir()
+    # a table no other test uses, so that this process has to build it
+    base = T.gpt_table()
+    table = T.ArchTable("cache", base.params, base.events[:-1] + (T.EventEntry("z9", "Z", +1, 77, ("h", "ffn"), 2),))
+    cfg = G.grid2(n=3000, seed=9)
+    want_p, want_d = B.estimate(cfg, [table], CONST, threads=8)
+    os.environ["LLMEM_KERNEL_CACHE"] = str(cache)
+    try:
+        got_p, got_d = U.hip_estimate(cfg, [table], CONST, kernel=LANE_SPECIALIZED)
+    finally:
+        del os.environ["LLMEM_KERNEL_CACHE"]
+    U.assert_same("detail", got_d, want_d)
+    files = sorted(cache.iterdir())
+    assert len(files) == 1 and files[0].suffix == ".co" and files[0].stat().st_size > 10_000
+    stamp = files[0].stat().st_mtime_ns
+    np.save(tmp_path / "want.npy", want_d)
+    child = (
+        "import sys, numpy as np\n"
+        f"sys.path[:0] = [{repr(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))}, {repr(os.path.dirname(os.path.abspath(__file__)))}]\n"
+        "import gpu_util as U\n"
+        "from workloads import grids as G, tables as T\n"
+        "base = T.gpt_table()\n"
+        "table = T.ArchTable('cache', base.params, base.events[:-1] + (T.EventEntry('z9', 'Z', +1, 77, ('h', 'ffn'), 2),))\n"
+        "p, d = U.hip_estimate(G.grid2(n=3000, seed=9), [table], T.Constants(m_base=256 << 20), kernel=5)\n"
+        f"assert (d == np.load({repr(str(tmp_path / 'want.npy'))})).all()\n"
+        "print('child ok')\n")
+    env = dict(os.environ, LLMEM_KERNEL_CACHE=str(cache))
+    out = subprocess.run([sys.executable, "-c", child], env=env, capture_output=True, text=True, timeout=170)
+    assert out.returncode == 0 and "child ok" in out.stdout, out.stderr[-2000:]
+    assert sorted(cache.iterdir()) == files and files[0].stat().st_mtime_ns == stamp     # loaded, not rebuilt
+    # a file under the expected name whose recorded identity is another one: rebuilt and replaced
+    files[0].write_bytes(b"\x05\x00\x00\x00\x00\x00\x00\x00wrong" + b"x" * 100)
+    out = subprocess.run([sys.executable, "-c", child], env=env, capture_output=True, text=True, timeout=170)
+    assert out.returncode == 0 and "child ok" in out.stdout, out.stderr[-2000:]
+    assert files[0].stat().st_size > 10_000

@@ -158,6 +158,20 @@ def test_argument_validation_without_gpu(lib):
     assert lib.llmem_sweep_reset(None, None) == -1
 
 
+def test_embedded_sources_cover_the_kernel_and_its_headers():
+    """The run-time build compiles the files that build.py embeds: every file the kernel source
+    or one of its headers includes by name must be among them (or be the constants header that
+    is written at run time)."""
+    from paper_2404_10933_amd import build
+    text = open(build.write_embedded_sources()).read()
+    embedded = [name for name, _ in build.EMBEDDED]
+    assert embedded[0] == "estimate_batch.hip" and text.count('R"LLMEM_SRC(') >= len(embedded)
+    for name, path in build.EMBEDDED:
+        assert f'"{name}"' in text
+        for inc in re.findall(r'#include "([^"]+)"', open(path).read()):
+            assert os.path.basename(inc) in embedded + ["specialized_prog.h"], (name, inc)
+
+
 def test_table_packing_layout():
     """The binding's 16-byte records match the C structs field by field."""
     Bd = _structs()
