@@ -543,12 +543,13 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                     const int pc_classes = pc;
                     // Classes: four per fetch (the host pads the list with empty classes).  NARROW: sizes
                     // in allocator blocks, negated, as signed 32-bit values, all 64 lanes; else 64-bit byte
-                    // sizes of the lanes of one half of the wave.  Returns a value that is below 2^32 if
-                    // every size is at most 2^31 blocks.
-                    auto store_classes = [&](auto narrow) -> u64 {
+                    // sizes of the lanes of one half of the wave.  Returns 0 if every size is at most
+                    // 2^31 blocks.
+                    auto store_classes = [&](auto narrow) -> u32 {
                         constexpr bool NARROW = decltype(narrow)::value;
                         char *row = vals + (NARROW ? lane * 4 : (lane & 31) * 8);
-                        u64 seen = 0, raw_before = 0;
+                        u64 raw_before = 0;
+                        u32 beyond = 0;                           // stays 0 while every size is at most 2^31 blocks
                         int at_word = pc_classes;
                         LLMEM_UNROLL_NARROW
                         for (int c0 = 0; c0 < nc; c0 += PROG_CLASS_FETCH, at_word += 2 * PROG_CLASS_FETCH) {
@@ -584,14 +585,14 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                                 }
                                 if (NARROW) {
                                     // minus the size in blocks: sizes up to 2^31 blocks inclusive fit
-                                    seen |= r + 0x7fffffffull;
+                                    beyond |= (u32)((r + 0x7fffffffull) >> 32);
                                     if (c < nc) *reinterpret_cast<u32 *>(row + (c + 1) * SLOT_ROW) = 0u - (u32)r;
                                 } else {
                                     if (c < nc) *reinterpret_cast<u64 *>(row + (c + 1) * SLOT_ROW) = r << align_shift;
                                 }
                             }
                         }
-                        return seen;
+                        return beyond;
                     };
                     // Sums of count * value, PROG_FETCH terms per fetch in groups of four.  A group flagged as
                     // a point's end lets its sum compete for the segment's maximum; the group that ends a
@@ -657,9 +658,9 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                             }
                         }
                     };
-                    const u64 seen = store_classes(Narrow());
+                    const u32 beyond = store_classes(Narrow());
                     // every size of every lane at most 2^31 blocks: the 32-bit walk is exact
-                    if (__builtin_amdgcn_ballot_w64((seen >> 32) != 0) == 0) {
+                    if (__builtin_amdgcn_ballot_w64(beyond != 0) == 0) {
                         walk_terms(Narrow());
                     } else {
                         for (u32 half = 0; half < 2; ++half) {
@@ -750,9 +751,13 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
             }
 #endif
         } else if (in_range) {
-            if (a.out_peaks) a.out_peaks[i] = r_peak;
+            // the index is formed again here (two instructions) rather than kept through the batch
+            int lane_again = lane;
+            asm volatile("" : "+v"(lane_again));
+            const long long at_i = (b << 6) + lane_again;
+            if (a.out_peaks) a.out_peaks[at_i] = r_peak;
             if (DETAIL) {
-                long long *o = a.out_detail + i;
+                long long *o = a.out_detail + at_i;
                 o[(long long)LLMEM_D_PEAK * n] = r_peak;
                 o[(long long)LLMEM_D_PARAM_GPU * n] = r_param;
                 o[(long long)LLMEM_D_GRAD_GPU * n] = r_grad;
@@ -789,7 +794,7 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 
 #ifdef LLMEM_SPECIALIZED
 
-// the flavour of the specialized kernel this build is for (LLMEM_SPEC_FLAVOUR: 0 m_peak only, 1 with
+// the flavour the run-time compile was asked for (LLMEM_SPEC_FLAVOUR: 0 m_peak only, 1 with
 // the detail columns, 2 sweep)
 #if LLMEM_SPEC_FLAVOUR == 0
 extern "C" __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
