@@ -180,8 +180,8 @@ typedef struct llmem_tables {
  * LLMEM_KERNEL_LANE_SPECIALIZED is the compiled form taken one step further and is only
  * used when asked for: the lane kernel's own source is compiled once more, at run time, with
  * the compiled tables as constants, so that every table word becomes an immediate and every
- * loop over table entries straight-line code.  The first call with a given set of tables (one
- * architecture; the same condition as for the compiled form) takes a few seconds to build
+ * loop over table entries straight-line code.  The first call with a given set of tables (the
+ * same condition as for the compiled form) takes a fraction of a second to a few seconds to build
  * and load the kernel; the build is kept, per device, until the process ends, and also
  * between processes when the environment variable LLMEM_KERNEL_CACHE names a writable
  * directory (one file per build, used only if its recorded identity matches in full).  Results are

@@ -646,7 +646,7 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     case LLMEM_KERNEL_WAVE: choice = wave_ok ? hint : -1; break;
     case LLMEM_KERNEL_LANE_EVENTS: choice = batch_ok ? hint : -1; break;
     case LLMEM_KERNEL_LANE_COMPILED: choice = prog_ok ? hint : -1; break;
-    case LLMEM_KERNEL_LANE_SPECIALIZED: choice = (prog_ok && args.n_arch == 1) ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_SPECIALIZED: choice = prog_ok ? hint : -1; break;
     default: choice = -1;
     }
     if (choice < 0) return LLMEM_EINVAL_TABLE;
@@ -721,7 +721,7 @@ static int launch_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, co
     case LLMEM_KERNEL_LANE: choice = prog_ok ? LLMEM_KERNEL_LANE_COMPILED : batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1; break;
     case LLMEM_KERNEL_LANE_EVENTS: choice = batch_ok ? hint : -1; break;
     case LLMEM_KERNEL_LANE_COMPILED: choice = prog_ok ? hint : -1; break;
-    case LLMEM_KERNEL_LANE_SPECIALIZED: choice = (prog_ok && args.n_arch == 1) ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_SPECIALIZED: choice = prog_ok ? hint : -1; break;
     default: choice = -1;
     }
     if (choice < 0) return LLMEM_EINVAL_TABLE;
@@ -760,7 +760,7 @@ extern "C" int llmem_kernel_forms(const llmem_tables *tables, int32_t info[8])
     for (int q = 0; q < 8; ++q) info[q] = 0;
     info[0] = (wave_ok ? 1 << LLMEM_KERNEL_WAVE : 0) | (batch_ok ? 1 << LLMEM_KERNEL_LANE_EVENTS : 0)
               | (prog_ok ? 1 << LLMEM_KERNEL_LANE_COMPILED : 0) | ((batch_ok || prog_ok) ? 1 << LLMEM_KERNEL_LANE : 0)
-              | ((prog_ok && args.n_arch == 1) ? 1 << LLMEM_KERNEL_LANE_SPECIALIZED : 0);
+              | (prog_ok ? 1 << LLMEM_KERNEL_LANE_SPECIALIZED : 0);
     info[1] = words;
     info[2] = args.p_slots;
     info[3] = args.s_slots;

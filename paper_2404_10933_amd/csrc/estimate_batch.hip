@@ -81,6 +81,10 @@ namespace {
 
 struct Narrow { static constexpr bool value = true; };
 struct Wide { static constexpr bool value = false; };
+// where an architecture's compiled tables start: read from the kernel arguments, or a constant
+struct WordsFromArguments { static constexpr bool from_arguments = true; static constexpr int first = 0; };
+template <int FIRST> struct WordsAt { static constexpr bool from_arguments = false; static constexpr int first = FIRST; };
+static_assert(LLMEM_MAX_ARCH == 8, "the architecture switch of the specialized build lists eight cases");
 
 constexpr int BB_WAVES = BATCH_WAVES;
 constexpr int BB_BLOCK = 64 * BB_WAVES;
@@ -255,19 +259,9 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
         i64 r_peak = err ? -1 : 0, r_param = 0, r_grad = 0, r_os = 0, r_out = 0, r_lm = 0, r_back = 0, r_k = 0,
             r_live = 0, r_np = 0, r_tmax = 0, r_flags = err;
 
-#ifdef LLMEM_SPECIALIZED
-        // one architecture (a specialization is built for a single table): every valid lane at once
-        if (valid) {
-            const u32 ar = 0;
-#else
-        unsigned long long todo = __builtin_amdgcn_ballot_w64(valid);
-        while (todo) {
-            const int first = __builtin_ctzll(todo);
-            const u32 ar = read_lane(arch_id, first);
-            const bool mine = valid && arch_id == ar;
-            todo &= ~__builtin_amdgcn_ballot_w64(mine);
-            if (!mine) continue;
-#endif
+        // The lanes of architecture `ar` (the active ones) estimate their configurations.
+        // `words`: where the architecture's compiled tables start, WordsFromArguments or WordsAt<N>.
+        auto for_architecture = [&](const u32 ar, auto words) {
             const ArchLayout &al = a.arch[ar];
 
             // size of a compiled expression for this lane's configuration (descriptor: see estimate_args.h)
@@ -290,12 +284,14 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                 // entries that count towards each sum, once and once per block
                 // start of the architecture's words: selected from reads at constant positions, so that
                 // every read of the compiled tables is a scalar load
-#ifndef LLMEM_SPECIALIZED
-                pc = a.arch[0].prog_first;
+                if constexpr (decltype(words)::from_arguments) {
+                    pc = a.arch[0].prog_first;
 #pragma unroll
-                for (int q = 1; q < LLMEM_MAX_ARCH; ++q) pc = ar == (u32)q ? a.arch[q].prog_first : pc;
-                pc = (int)uni((u32)pc);
-#endif
+                    for (int q = 1; q < LLMEM_MAX_ARCH; ++q) pc = ar == (u32)q ? a.arch[q].prog_first : pc;
+                    pc = (int)uni((u32)pc);
+                } else {
+                    pc = decltype(words)::first;
+                }
                 head = LLMEM_PROG(pc);
 #pragma unroll
                 for (int q = 0; q <= LLMEM_NSEG; ++q) seg_at[q] = LLMEM_PROG(pc + 1 + q);
@@ -708,6 +704,34 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                 r_param = (i64)param_gpu; r_grad = (i64)grad_logical; r_os = (i64)os_gpu; r_out = (i64)m_out;
                 r_lm = (i64)m_lm; r_back = (i64)m_back; r_k = (i64)k_used; r_live = prelude + best;
                 r_np = (i64)n_params; r_tmax = (i64)t_max; r_flags = (i64)flags;
+            }
+        };
+#ifdef LLMEM_SPECIALIZED
+        if (SPEC_ARCHS == 1) {
+            // one architecture: every valid lane at once, and no loop for the compiler to hoist out of
+            if (valid) for_architecture(0u, WordsAt<SPEC_FIRST[0]>());
+        } else
+#endif
+        {
+            // architecture by architecture: the lanes of the first remaining one together
+            unsigned long long todo = __builtin_amdgcn_ballot_w64(valid);
+            while (todo) {
+                const int first = __builtin_ctzll(todo);
+                const u32 ar = read_lane(arch_id, first);
+                const bool mine = valid && arch_id == ar;
+                todo &= ~__builtin_amdgcn_ballot_w64(mine);
+                if (mine) {
+#ifdef LLMEM_SPECIALIZED
+#define LLMEM_ARCH_CASE(q) case q: if (q < SPEC_ARCHS) for_architecture(ar, WordsAt<SPEC_FIRST[q < SPEC_ARCHS ? q : 0]>()); break;
+                    switch (ar) {
+                    LLMEM_ARCH_CASE(0) LLMEM_ARCH_CASE(1) LLMEM_ARCH_CASE(2) LLMEM_ARCH_CASE(3)
+                    LLMEM_ARCH_CASE(4) LLMEM_ARCH_CASE(5) LLMEM_ARCH_CASE(6) LLMEM_ARCH_CASE(7)
+                    }
+#undef LLMEM_ARCH_CASE
+#else
+                    for_architecture(ar, WordsFromArguments());
+#endif
+                }
             }
         }
 

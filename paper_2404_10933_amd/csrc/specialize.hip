@@ -32,7 +32,9 @@ void set_error_text(const char *text);          // estimate.hip: what llmem_stre
 
 namespace {
 
-constexpr int SPECIALIZED_WAVES = 4;            // waves per SIMD the build aims at (128 registers)
+// waves per SIMD the build aims at: four (128 registers, no spills) for one architecture; with
+// several, the code of each sits in a loop over the architectures and needs more registers
+inline int specialized_waves(size_t n_arch) { return n_arch == 1 ? 4 : 3; }
 const char *const FLAVOUR_KERNEL[3] = {"llmem_specialized_peaks", "llmem_specialized_detail", "llmem_specialized_sweep"};
 
 struct Built {
@@ -46,11 +48,13 @@ struct Built {
 
 struct Key {
     int device, flavour;
+    std::vector<int> first;                     // first word of every architecture
     std::vector<uint32_t> words;
     bool operator<(const Key &o) const
     {
         if (device != o.device) return device < o.device;
         if (flavour != o.flavour) return flavour < o.flavour;
+        if (first != o.first) return first < o.first;
         return words < o.words;
     }
 };
@@ -64,16 +68,19 @@ int fail(const std::string &text)
     return LLMEM_EHIP;
 }
 
-// the words of the compiled tables that the kernel reads: everything up to the end of the
+// the words of the compiled tables that the kernel reads: everything up to the end of the last
 // architecture's terms
 size_t words_used(const EstimateArgs &args)
 {
-    const size_t n = (size_t)args.arch[0].prog_seg[LLMEM_NSEG];
+    size_t n = 0;
+    for (int q = 0; q < args.n_arch; ++q)
+        if ((size_t)args.arch[q].prog_seg[LLMEM_NSEG] > n) n = (size_t)args.arch[q].prog_seg[LLMEM_NSEG];
     return n < (size_t)PROG_WORDS ? n : (size_t)PROG_WORDS;
 }
 
-std::string constants_header(const std::vector<uint32_t> &words)
+std::string constants_header(const Key &key)
 {
+    const std::vector<uint32_t> &words = key.words;
     std::string list;
     char item[16];
     for (size_t q = 0; q < words.size(); ++q) {
@@ -82,9 +89,11 @@ std::string constants_header(const std::vector<uint32_t> &words)
         if (q % 8 == 7) list += "\n";
     }
     char head[256];
-    snprintf(head, sizeof(head), "#pragma once\nnamespace llmem {\nconstexpr int SPEC_WAVES = %d;\nconstexpr int SPEC_N = %zu;\n",
-             SPECIALIZED_WAVES, words.size());
-    return std::string(head) + "__device__ constexpr unsigned SPEC_PROG[SPEC_N] = {\n" + list + "};\n"
+    snprintf(head, sizeof(head), "#pragma once\nnamespace llmem {\nconstexpr int SPEC_WAVES = %d;\nconstexpr int SPEC_N = %zu;\n"
+             "constexpr int SPEC_ARCHS = %zu;\n", specialized_waves(key.first.size()), words.size(), key.first.size());
+    std::string firsts = "constexpr int SPEC_FIRST[8] = {";
+    for (size_t q = 0; q < 8; ++q) firsts += std::to_string(q < key.first.size() ? key.first[q] : 0) + (q < 7 ? ", " : "};\n");
+    return std::string(head) + firsts + "__device__ constexpr unsigned SPEC_PROG[SPEC_N] = {\n" + list + "};\n"
            + "__constant__ unsigned SPEC_PROG_MEM[SPEC_N] = {\n" + list + "};\n}\n";
 }
 
@@ -94,7 +103,9 @@ std::string constants_header(const std::vector<uint32_t> &words)
 std::string identity(const Key &key, const char *arch_name)
 {
     std::string id = std::string("llmem-specialized-1|") + arch_name + "|" + std::to_string(key.flavour) + "|"
-                     + std::to_string(SPECIALIZED_WAVES) + "|";
+                     + std::to_string(specialized_waves(key.first.size())) + "|";
+    for (int f : key.first) id += std::to_string(f) + ",";
+    id += "|";
     id.append(reinterpret_cast<const char *>(key.words.data()), key.words.size() * sizeof(uint32_t));
     for (int q = 0; q < EMBEDDED_COUNT; ++q) { id += "|"; id += EMBEDDED_TEXTS[q]; }
     return id;
@@ -164,7 +175,7 @@ int build(const Key &key, Built *out)
 
 int compile(const Key &key, const char *arch_name, std::vector<char> *code)
 {
-    const std::string constants = constants_header(key.words);
+    const std::string constants = constants_header(key);
     std::vector<const char *> names, texts;
     for (int q = 1; q < EMBEDDED_COUNT; ++q) { names.push_back(EMBEDDED_NAMES[q]); texts.push_back(EMBEDDED_TEXTS[q]); }
     names.push_back("specialized_prog.h");
@@ -200,10 +211,12 @@ int compile(const Key &key, const char *arch_name, std::vector<char> *code)
 
 int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch, hipStream_t stream)
 {
-    if (flavour < 0 || flavour > 2 || !args.use_program || args.n_arch != 1) return LLMEM_EINVAL_TABLE;
+    if (flavour < 0 || flavour > 2 || !args.use_program || args.n_arch < 1 || args.n_arch > LLMEM_MAX_ARCH)
+        return LLMEM_EINVAL_TABLE;
     Key key;
     if (hipGetDevice(&key.device) != hipSuccess) return fail("no current device");
     key.flavour = flavour;
+    for (int q = 0; q < args.n_arch; ++q) key.first.push_back(args.arch[q].prog_first);
     key.words.assign(args.prog, args.prog + words_used(args));
     const size_t lds_bytes = batch_kernel_lds_bytes(args);
     Built built;

@@ -35,7 +35,7 @@ def _check(U, cfg, tables, const=CONST, threads=8, expect=None):
     if expect is not None:
         assert sorted(k for k in allowed if k not in (LANE, LANE_SPECIALIZED)) \
             == sorted(k for k in expect if k != LANE_SPECIALIZED), allowed
-        assert (LANE_SPECIALIZED in allowed) == (LANE_COMPILED in allowed and len(tables) == 1)
+        assert (LANE_SPECIALIZED in allowed) == (LANE_COMPILED in allowed)
     want_p, want_d = B.estimate(cfg, tables, const, threads=threads)
     for kernel in [0] + allowed:
         got_p, got_d = U.hip_estimate(cfg, tables, const, kernel=kernel)
