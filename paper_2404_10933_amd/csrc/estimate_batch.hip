@@ -334,9 +334,13 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
             const u64 n_params = embed_p + other_p + ((cflags & LLMEM_CFG_TIED_LM_HEAD) ? 0ull : lm_p);
 
             // ---- Sec. 4.2: m_out, m_lm; Sec. 5: m_back^tp -----------------------------------
-            const u64 A = (u64)bs * sl * h;
+            // (the batch size goes through an empty asm: what follows is then formed here, after the
+            // parameter table, instead of being hoisted in front of it and kept in registers across it)
+            u32 bs_here = bs;
+            asm volatile("" : "+v"(bs_here));
+            const u64 A = (u64)bs_here * sl * h;
             const u64 m_out = b_up(((u64)e_n + L) * A * B16, cu_shift);
-            const u64 row = (u64)bs * V * Blog;
+            const u64 row = (u64)bs_here * V * Blog;
             const u64 m_lm = b_up(row * sl, cu_shift) + 2 * b_up(row * D[LLMEM_DIM_SL_M1], cu_shift) + lm_p * B16;
             u64 m_back = 0;
             if (method == LLMEM_METHOD_TP) {
