@@ -121,6 +121,20 @@ def test_accumulates_over_ranges_and_streams(U):
         M.llmem_sweep(6, 1, 0, 10, tab, m_total, stats)
 
 
+def test_a_grid_that_would_not_fit_in_memory(U):
+    """2 * 10^9 configurations (62 GB of columns and 208 GB of detail output if they were stored):
+    every configuration is counted, the halves add up to the whole (counts add, extremes
+    combine), and the oracle confirms a slice in the middle exactly."""
+    tables = [T.llama_table()]
+    n, m_total = 2_000_000_000, 64 * GIB
+    whole = U.hip_sweep(4, 0, 0, n, tables, CONST, m_total, kernel=KERNEL_LANE_SPECIALIZED)
+    assert whole[A.S_COUNT].sum() == n and 0 < whole[A.S_FIT].sum() < n
+    low = U.hip_sweep(4, 0, 0, n // 2, tables, CONST, m_total, kernel=KERNEL_LANE_SPECIALIZED)
+    high = U.hip_sweep(4, 0, n // 2, n // 2, tables, CONST, m_total, kernel=KERNEL_LANE_SPECIALIZED)
+    U.assert_same("halves merged", np.array(A.sweep_merge(low.tolist(), high.tolist())), whole)
+    _check(U, 4, 0, 1_234_567_890, 50_000, m_total, kernel=KERNEL_LANE_SPECIALIZED)
+
+
 def test_full_size_grid4_against_the_stored_path(U):
     """10^7 configurations in the benchmark's launch configuration.  The oracle sweeps the first
     and the last 150 000 of them exactly; for the whole range the counts must add up, and the
