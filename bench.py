@@ -29,7 +29,7 @@ TRAFFIC_ESTIMATE = 1.4739e9     # 10^7 configurations, all detail columns, built
 TRAFFIC_SPECIALIZED = 1.3503e9  # the same workload, kernel built at run time
 TRAFFIC_SWEEP = 5.0536e7        # 10^7 configurations drawn and reduced in the kernel built at run time
 TRAFFIC_TIMELINE = 8.0201e9     # 100 000 event lists, 1 000 110 810 events
-TRAFFIC_DECIDE = 5.4014e8       # 4 000 000 queries, all decision columns
+TRAFFIC_DECIDE = 5.4014e8       # 4 000 000 queries, all decision columns (the search inside the kernel does not touch memory)
 
 
 def algorithmic_lane_ops(forms, n_candidates):
@@ -51,21 +51,23 @@ def algorithmic_lane_ops(forms, n_candidates):
             + forms["peak_points"] * per_point + fixed + n_candidates * per_candidate + tail)
 
 
-def algorithmic_lane_ops_decide(n_param_entries, cap_bits):
+def algorithmic_lane_ops_decide(n_param_entries, probes):
     """The method decision of one query in the same units: parameter census entry by entry, the
     chunk-size candidates (waste and feasibility only), the batch-independent parts of the four
-    estimates, then per method one estimate of the batch-dependent terms per bit of the largest
-    batch size considered (bisection: the leanest known search, the estimates being monotone),
-    scores, choice and the chosen estimate."""
+    estimates, then per method the bracket of the largest batch size (two quotients and their
+    conversions) and `probes` estimates of the batch-dependent terms (one to check the bracket's
+    lower end, the rest bisecting the bracket: the leanest known search, the estimates being
+    monotone and linear in bs up to page rounding), scores, choice and the chosen estimate."""
     ADD, MUL32, MUL, UP, MAX, DIV = 1, 1, 3, 3, 3, 12
     per_entry = MUL32 + MUL + (MUL32 + MUL + ADD) + (ADD + UP + MUL32 + MUL + ADD) + MAX
     per_candidate = UP + ADD + MAX
     fixed = 3 * (MUL + UP) + 2 * (DIV + UP) + 2 * (MUL + DIV + UP) + 12 * ADD + 5 * MUL
+    bracket = 2 * DIV + 6 * ADD + 2 * MAX                        # two quotients, conversions, clamps
     probe_plain = 3 * (MUL + UP) + 4 * ADD + MAX                 # m_out, logits, shifted logits; compare, keep
     probe_gather = probe_plain + MUL + UP + DIV + ADD            # plus the all-gather buffer
     tail = 4 * MUL32 + 3 * MAX + probe_gather + 4 * ADD
-    return (n_param_entries * per_entry + 9 * per_candidate + fixed
-            + cap_bits * (2 * probe_plain + 2 * probe_gather) + tail)
+    return (n_param_entries * per_entry + 9 * per_candidate + fixed + 4 * bracket
+            + probes * (2 * probe_plain + 2 * probe_gather) + tail)
 
 
 def algorithmic_lane_ops_sweep_extra():
@@ -353,7 +355,7 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / reps
-        q_ops = algorithmic_lane_ops_decide(len(table.params), G.QUERY_BS_CAP.bit_length())
+        q_ops = algorithmic_lane_ops_decide(len(table.params), 4)      # bracket check + 3 bisection steps (bracket of <= 7)
         q_achieved = q_ops * nq / (ms * 1e-3) / 1e12
         ns = min(2000, nq)
         qs, qs_tp = G.grid6(n=ns, seed=0)

@@ -281,8 +281,9 @@ enum llmem_decision {
  * bs * gpu_n, bs, bs * dp_n (dp_n = gpu_n / tp_n); the first highest score wins (ties in the
  * order CDP, ADP, TP, DP+TP) unless the TP score is 0, which selects LLMEM_METHOD_OFFLOAD with
  * batch size 0.  A method that does not fit even at bs = 1 has batch size and score 0.  The
- * batch sizes are found by bisection, which equals the algorithm's one-by-one search because
- * the estimates never decrease with bs.
+ * batch sizes are found by bisection inside a bracket derived from the estimates' linear growth
+ * with bs, which equals the algorithm's one-by-one search because the estimates never decrease
+ * with bs.
  *   queries    configurations whose bs column holds the largest batch size to consider and
  *              whose method column is not read; d = gpu_n
  *   tp_n       as for llmem_estimate_methods; 0 / NULL: DP+TP takes no part (score 0)

@@ -207,20 +207,51 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
             continue;
         }
 
-        // ---- Algorithm 1: largest batch size per method, built from the highest bit down
+        // ---- Algorithm 1: largest batch size per method ---------------------------------------
+        // The estimates never decrease with bs, so the largest batch size that fits is found by
+        // bisection; and they are a fixed part plus terms that grow linearly with bs up to page
+        // rounding, which brackets it first:
+        //   fixed + bs * growth  <=  m_peak(bs)  <=  fixed + bs * growth + 6 pages
+        // (growth: bytes per sample of m_out, the logits, the two shifted copies and 1/t of the TP
+        // buffer; four round-ups to a page plus two in the buffer).  The upper end is safe against
+        // the rounding of the single-precision quotient (two more than its integer part); the
+        // lower end is checked by an estimate of its own and dropped to 0 if it does not fit.
         const u32 cap = valid ? bs : 0u;
-        u32 widest = cap;                                                    // wave-wide OR of the caps
-        for (int s = 32; s >= 1; s >>= 1) widest |= (u32)__shfl_xor((int)widest, s, 64);
-        const int bits = 32 - __builtin_clz(d_uni(widest) | 1u);
-        u32 best[4] = {0, 0, 0, 0};
+        const float slope = (float)(q.c_out + q.c_logits + 2 * q.c_shifted);
+        const float six_pages = (float)(6ull << cu_shift);
+        u32 best[4], top[4], span = 0;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const i64 room = a.m_total - (i64)q.fixed[m];
+            const float back = m == LLMEM_METHOD_TP ? (float)q.c_back_tp / (float)(g ? g : 1u)
+                               : m == LLMEM_METHOD_HYBRID ? (float)q.c_back_hy / (float)(tp ? tp : 1u) : 0.0f;
+            u32 hi = cap, lo = 0;
+            if (room < 0) {
+                hi = 0;                                                   // not even the fixed part fits
+            } else if (slope + back > 0.0f) {
+                const float growth = slope + back;
+                const float upper = __fdividef((float)room, growth);
+                if (upper < (float)cap) hi = (u32)upper + 2u < cap ? (u32)upper + 2u : cap;
+                const float lower = __fdividef((float)room - six_pages, growth) - 1.0f;
+                if (lower > 0.0f) lo = lower < (float)hi ? (u32)lower : hi;
+            }
+            if (lo > 0 && peak_at(q, m, lo) > a.m_total) lo = 0;
+            best[m] = lo; top[m] = hi;
+            span |= hi - lo;
+        }
+        for (int s = 32; s >= 1; s >>= 1) span |= (u32)__shfl_xor((int)span, s, 64);
+        const int bits = 32 - __builtin_clz(d_uni(span) | 1u);
+        u32 offset[4] = {0, 0, 0, 0};                                       // best = lower end + offset
         for (int bit = bits - 1; bit >= 0; --bit) {
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                const u32 cand = best[m] | (1u << bit);
-                const bool fits = cand <= cap && peak_at(q, m, cand) <= a.m_total;
-                best[m] = fits ? cand : best[m];
+                const u32 cand = best[m] + (offset[m] | (1u << bit));
+                const bool fits = cand <= top[m] && peak_at(q, m, cand) <= a.m_total;
+                offset[m] = fits ? (offset[m] | (1u << bit)) : offset[m];
             }
         }
+#pragma unroll
+        for (int m = 0; m < 4; ++m) best[m] += offset[m];
         if (tp == 0) best[LLMEM_METHOD_HYBRID] = 0;
         // scores (doubled) and the choice
         const u32 dp_n = tp ? (u32)d_div(g, tp, div_t) : 0u;
