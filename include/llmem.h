@@ -7,8 +7,9 @@
  * parallelism), the chunk-size choice of Sec. 4.1, and a traversal of the
  * operator timeline with live tensors and 512-byte allocator blocks (Sec. 2.1,
  * Sec. 3.1); further the estimate for combined DP+TP (Sec. 5) and the choice of
- * the fine-tuning method with its largest batch size (Sec. 6, Algorithm 1).  All
- * arithmetic is exact int64 byte arithmetic.
+ * the fine-tuning method with its largest batch size (Sec. 6, Algorithm 1), and
+ * the same estimates for whole seeded grids that are drawn, estimated and reduced
+ * to statistics inside one kernel.  All arithmetic is exact int64 byte arithmetic.
  *
  * Conventions
  *   DEV   pointer to device memory, owned by the caller; the library never
