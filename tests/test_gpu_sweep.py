@@ -135,36 +135,19 @@ def test_a_grid_that_would_not_fit_in_memory(U):
     _check(U, 4, 0, 1_234_567_890, 50_000, m_total, kernel=KERNEL_LANE_SPECIALIZED)
 
 
-def test_full_size_grid4_against_the_stored_path(U):
-    """10^7 configurations in the benchmark's launch configuration.  The oracle sweeps the first
-    and the last 150 000 of them exactly; for the whole range the counts must add up, and the
-    sweep must agree with the library's own estimates of the stored grid folded on the host
-    (a consistency check of the two HIP paths, not a parity claim), and the best entries of a few
-    groups are confirmed one by one by the oracle."""
-    import paper_2404_10933_amd as M
+def test_full_size_grid4(U):
+    """10^7 configurations in the benchmark's launch configurations (the kernel built at run time
+    and the built-in one): every statistic of every group against the oracle's sweep of the whole
+    grid, and the best entries of a few groups confirmed one by one by oracle A."""
     tables = [T.llama_table()]
     n, m_total = 10_000_000, 64 * GIB
-    got = U.hip_sweep(4, 0, 0, n, tables, CONST, m_total)
-    assert got[A.S_COUNT].sum() == n
-    for lo in (0, n - 150_000):
-        _check(U, 4, 0, lo, 150_000, m_total)
-    dev = M.DeviceConfigs.empty(n)
-    M.llmem_grid_generate(4, 0, 0, n, dev)
-    tab = M.Tables(tables, m_base=CONST.m_base)
-    det = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
-    M.llmem_estimate_ex(dev, tab, None, det)
-    torch.cuda.synchronize()
-    group = dev.columns["method"].to(torch.int64) * 16 + dev.columns["d"].to(torch.int64) - 1
-    peak, live = det[A.D_PEAK], det[A.D_LIVE]
-    for q in range(48):
-        m = group == q
-        assert int(m.sum()) == got[A.S_COUNT][q]
-        assert int(peak[m].max()) == got[A.S_MAX_PEAK][q] and int(peak[m].min()) == got[A.S_MIN_PEAK][q]
-        assert int(live[m].max()) == got[A.S_MAX_LIVE][q]
-        assert int((peak[m] <= m_total).sum()) == got[A.S_FIT][q]
-        assert int(det[A.D_K][m].sum()) == got[A.S_K_SUM][q]
+    want = B.sweep(G.grid4(n=n, seed=0), 0, tables, CONST, m_total, threads=16)
+    assert want[A.S_COUNT].sum() == n
+    for kernel in (KERNEL_LANE_SPECIALIZED, 0):
+        got = U.hip_sweep(4, 0, 0, n, tables, CONST, m_total, kernel=kernel)
+        U.assert_same(f"all statistics, 10^7 (kernel {kernel})", got, want)
     for q in (0, 5, 16 + 7, 32 + 15):
-        score2, index = A.unpack_best(int(got[A.S_BEST][q]))
+        score2, index = A.unpack_best(int(want[A.S_BEST][q]))
         cfg = G.grid4(n=1, seed=0, first=index)
         row = A.estimate(cfg, tables, CONST)[0]
         method, d, bs = int(cfg["method"][0]), int(cfg["d"][0]), int(cfg["bs"][0])
