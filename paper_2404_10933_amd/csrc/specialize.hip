@@ -99,10 +99,19 @@ std::string constants_header(const Key &key)
 
 // ---- code objects kept between processes (LLMEM_KERNEL_CACHE) ---------------------------------
 // File = the identity (architecture name, flavour, waves per SIMD, table words, every embedded
-// source) followed by the code object; a file whose identity differs in any byte is ignored.
+// source), the code object's size and checksum, the code object.  A file whose identity differs
+// in any byte, or whose code object is not the one that was written (cut short, altered), is
+// ignored and replaced: the loader only ever sees what the compiler produced.
+unsigned long long checksum(const char *data, size_t size)
+{
+    unsigned long long h = 1469598103934665603ull;                       // FNV-1a
+    for (size_t q = 0; q < size; ++q) { h ^= (unsigned char)data[q]; h *= 1099511628211ull; }
+    return h;
+}
+
 std::string identity(const Key &key, const char *arch_name)
 {
-    std::string id = std::string("llmem-specialized-1|") + arch_name + "|" + std::to_string(key.flavour) + "|"
+    std::string id = std::string("llmem-specialized-2|") + arch_name + "|" + std::to_string(key.flavour) + "|"
                      + std::to_string(specialized_waves(key.first.size())) + "|";
     for (int f : key.first) id += std::to_string(f) + ",";
     id += "|";
@@ -131,12 +140,16 @@ bool cache_read(const std::string &path, const std::string &id, std::vector<char
     size_t got;
     while ((got = fread(chunk, 1, sizeof(chunk), f)) > 0) all.insert(all.end(), chunk, chunk + got);
     fclose(f);
-    unsigned long long id_size = 0;
+    unsigned long long id_size = 0, code_size = 0, code_sum = 0;
     if (all.size() < sizeof(id_size)) return false;
     memcpy(&id_size, all.data(), sizeof(id_size));
-    if (id_size != id.size() || all.size() <= sizeof(id_size) + id.size()) return false;
+    const size_t head = sizeof(id_size) + id.size() + sizeof(code_size) + sizeof(code_sum);
+    if (id_size != id.size() || all.size() <= head) return false;
     if (memcmp(all.data() + sizeof(id_size), id.data(), id.size()) != 0) return false;
-    code->assign(all.begin() + sizeof(id_size) + id.size(), all.end());
+    memcpy(&code_size, all.data() + sizeof(id_size) + id.size(), sizeof(code_size));
+    memcpy(&code_sum, all.data() + sizeof(id_size) + id.size() + sizeof(code_size), sizeof(code_sum));
+    if (code_size != all.size() - head || checksum(all.data() + head, all.size() - head) != code_sum) return false;
+    code->assign(all.begin() + head, all.end());
     return true;
 }
 
@@ -145,8 +158,9 @@ void cache_write(const std::string &path, const std::string &id, const std::vect
     const std::string tmp = path + ".tmp" + std::to_string((long long)getpid());
     FILE *f = fopen(tmp.c_str(), "wb");
     if (!f) return;                                                    // an unwritable cache is no error
-    const unsigned long long id_size = id.size();
+    const unsigned long long id_size = id.size(), code_size = code.size(), code_sum = checksum(code.data(), code.size());
     const bool ok = fwrite(&id_size, sizeof(id_size), 1, f) == 1 && fwrite(id.data(), 1, id.size(), f) == id.size()
+                    && fwrite(&code_size, sizeof(code_size), 1, f) == 1 && fwrite(&code_sum, sizeof(code_sum), 1, f) == 1
                     && fwrite(code.data(), 1, code.size(), f) == code.size();
     if (fclose(f) != 0 || !ok || rename(tmp.c_str(), path.c_str()) != 0) remove(tmp.c_str());
 }
@@ -160,17 +174,35 @@ int build(const Key &key, Built *out)
     const std::string id = identity(key, prop.gcnArchName);
     const std::string path = cache_path(id);
     out->code = new std::vector<char>();
-    if (path.empty() || !cache_read(path, id, out->code)) {
-        const int rc = compile(key, prop.gcnArchName, out->code);
-        if (rc != LLMEM_OK) { delete out->code; out->code = nullptr; return rc; }
-        if (!path.empty()) cache_write(path, id, *out->code);
-    }
-    hipError_t e = hipModuleLoadData(&out->module, out->code->data());
-    if (e != hipSuccess) return fail(std::string("loading the specialized kernel: ") + hipGetErrorString(e));
-    e = hipModuleGetFunction(&out->function, out->module, FLAVOUR_KERNEL[key.flavour]);
-    if (e != hipSuccess) return fail(std::string("specialized kernel not found in its module: ") + hipGetErrorString(e));
     out->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    return LLMEM_OK;
+    std::string problem;
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        // first a kept code object, if there is one; a kept one that does not load is built again
+        const bool kept = attempt == 0 && !path.empty() && cache_read(path, id, out->code);
+        if (!kept) {
+            const int rc = compile(key, prop.gcnArchName, out->code);
+            if (rc != LLMEM_OK) { delete out->code; out->code = nullptr; return rc; }
+            if (!path.empty()) cache_write(path, id, *out->code);
+        }
+        hipError_t e;
+        try {
+            e = hipModuleLoadData(&out->module, out->code->data());
+        } catch (...) {                          // the loader's own C++ errors must not cross the C boundary
+            e = hipErrorInvalidImage;
+        }
+        if (e == hipSuccess) {
+            e = hipModuleGetFunction(&out->function, out->module, FLAVOUR_KERNEL[key.flavour]);
+            if (e == hipSuccess) return LLMEM_OK;
+            (void)hipModuleUnload(out->module);
+            out->module = nullptr;
+        }
+        problem = std::string("loading the specialized kernel: ") + hipGetErrorString(e);
+        (void)hipGetLastError();
+        if (!kept) break;
+    }
+    delete out->code;
+    out->code = nullptr;
+    return fail(problem);
 }
 
 int compile(const Key &key, const char *arch_name, std::vector<char> *code)
