@@ -298,6 +298,8 @@ def main():
     if args.sweep > 0:
         nsw, m_total = args.sweep, 64 << 30
         stats = torch.empty((M.NSWEEP, M.SWEEP_GROUPS), dtype=torch.int64, device="cuda")
+        if kernel == 1:        # the sweep is a mode of the lane kernel: with --kernel wave the library chooses its form
+            tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=0)
         for _ in range(2):
             M.llmem_sweep_reset(stats)
             M.llmem_sweep(4, 0, 0, nsw, tab, m_total, stats)
