@@ -29,7 +29,7 @@ TRAFFIC_ESTIMATE = 1.4302e9     # 10^7 configurations, all detail columns, built
 TRAFFIC_SPECIALIZED = 1.3503e9  # the same workload, kernel built at run time
 TRAFFIC_SWEEP = 5.0558e7        # 10^7 configurations drawn and reduced in the kernel built at run time
 TRAFFIC_TIMELINE = 8.0201e9     # 100 000 event lists, 1 000 110 810 events
-TRAFFIC_DECIDE = 5.4019e8       # 4 000 000 queries, all decision columns (the search inside the kernel does not touch memory)
+TRAFFIC_DECIDE = 5.4029e8       # 4 000 000 queries, all decision columns (the search inside the kernel does not touch memory)
 
 
 def algorithmic_lane_ops(forms, n_candidates):
@@ -51,22 +51,23 @@ def algorithmic_lane_ops(forms, n_candidates):
             + forms["peak_points"] * per_point + fixed + n_candidates * per_candidate + tail)
 
 
-def algorithmic_lane_ops_decide(n_param_entries, probes):
-    """The method decision of one query in the same units: parameter census entry by entry, the
-    chunk-size candidates (waste and feasibility only), the batch-independent parts of the four
-    estimates, then per method the bracket of the largest batch size (two quotients and their
-    conversions) and `probes` estimates of the batch-dependent terms (one to check the bracket's
-    lower end, the rest bisecting the bracket: the leanest known search, the estimates being
-    monotone and linear in bs up to page rounding), scores, choice and the chosen estimate."""
-    ADD, MUL32, MUL, UP, MAX, DIV = 1, 1, 3, 3, 3, 12
-    per_entry = MUL32 + MUL + (MUL32 + MUL + ADD) + (ADD + UP + MUL32 + MUL + ADD) + MAX
-    per_candidate = UP + ADD + MAX
-    fixed = 3 * (MUL + UP) + 2 * (DIV + UP) + 2 * (MUL + DIV + UP) + 12 * ADD + 5 * MUL
-    bracket = 2 * DIV + 6 * ADD + 2 * MAX                        # two quotients, conversions, clamps
-    probe_plain = 3 * (MUL + UP) + 4 * ADD + MAX                 # m_out, logits, shifted logits; compare, keep
-    probe_gather = probe_plain + MUL + UP + DIV + ADD            # plus the all-gather buffer
-    tail = 4 * MUL32 + 3 * MAX + probe_gather + 4 * ADD
-    return (n_param_entries * per_entry + 9 * per_candidate + fixed + 4 * bracket
+def algorithmic_lane_ops_decide(n_param_groups, probes):
+    """The method decision of one query in the same units, leanest known form: parameter census
+    by groups of equal size expression, the chunk size in closed form (the smallest feasible
+    candidate is the one with the least waste), the batch-independent parts of the four estimates,
+    the per-page constants of the batch-dependent terms, then per method the bracket of the largest
+    batch size in single precision (one reciprocal, two products, conversions and clamps) and
+    `probes` estimates of the batch-dependent terms counted in 32-bit pages (one to check the
+    bracket's lower end, the rest bisecting the bracket), scores, choice and the chosen estimate."""
+    ADD, MUL32, MUL, UP, MAX, DIV, DIV32 = 1, 1, 3, 3, 3, 12, 5
+    per_group = MUL32 + MUL + (MUL32 + MUL + ADD) + (ADD + UP + MUL32 + MUL + ADD) + MAX
+    chunk = MAX + 3 * ADD                                        # bit length of t_max, clamp to 2..10
+    fixed = 3 * (MUL + UP) + 2 * (DIV + UP) + 2 * (MUL + DIV + UP) + 12 * ADD + 5 * MUL + 10 * ADD
+    bracket = 18                                                 # room in pages, growth, quotient, two clamped ends
+    probe_plain = MUL32 + 3 * (MUL32 + ADD) + 4 * ADD + MAX      # shared whole pages; three remainders; compare, keep
+    probe_gather = probe_plain + 2 * MUL32 + 2 * ADD + DIV32 + ADD   # plus the all-gather buffer, divided by t
+    tail = 4 * MUL32 + 3 * MAX + probe_gather + UP + 4 * ADD
+    return (n_param_groups * per_group + chunk + fixed + 4 * bracket
             + probes * (2 * probe_plain + 2 * probe_gather) + tail)
 
 
@@ -357,8 +358,11 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / reps
-        q_ops = algorithmic_lane_ops_decide(len(table.params), 4)      # bracket check + 3 bisection steps (bracket of <= 7)
+        # bracket check + one bisection step (brackets of <= 1 for this grid's models)
+        q_ops = algorithmic_lane_ops_decide(M.llmem_kernel_forms(qtab)["param_groups"], 2)
         q_achieved = q_ops * nq / (ms * 1e-3) / 1e12
+        q_bytes = 31 + 1 + 4 + 4 + 8 * M.NDECIDE                       # query columns, tp_n; method, bs, decision columns
+        q_gbs = q_bytes * nq / (ms * 1e-3) / 1e9
         ns = min(2000, nq)
         qs, qs_tp = G.grid6(n=ns, seed=0)
         t1 = time.perf_counter()
@@ -369,10 +373,13 @@ def main():
             "workload": "g6: Algorithm 1 per query (Llama-style model, gpu_n, sl; batch sizes up to 4096; "
                         "m_total 80 GiB), method + bs + all decision columns",
             "n_queries": nq, "ms_per_launch": ms, "queries_per_s": nq / (ms * 1e-3),
-            "roofline": {"bound": "alu", "achieved": q_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
-                         "frac": q_achieved / PEAK_LANE_TOPS,
+            # 136 B per query at 8 TB/s take longer than the census at the vector issue rate: HBM bounds it
+            "roofline": {"bound": "hbm", "achieved": q_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": q_gbs / PEAK_HBM_GBS,
                          "traffic": TRAFFIC_DECIDE if nq == 4_000_000 else None, "kernel": "decide_kernel<true>",
-                         "algorithmic_lane_ops_per_query": q_ops},
+                         "algorithmic_bytes_per_query": q_bytes,
+                         "alu": {"achieved": q_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
+                                 "frac": q_achieved / PEAK_LANE_TOPS, "algorithmic_lane_ops_per_query": q_ops}},
             "cpu_oracle": {"value": ns / dt, "unit": "queries/s", "cores": 1,
                            "sample": f"first {ns} queries, C oracle (one-by-one search), {dt:.1f} s"},
             "verified_vs_oracle": ns}

@@ -11,9 +11,14 @@
 //   / (t * cu_p)) * cu_p.
 // llmem_estimate_methods evaluates the four estimates at the query's own bs.
 // llmem_decide finds, per method, the largest bs whose estimate does not exceed
-// m_total by building it bit by bit from the top (the estimates never decrease
-// with bs, so this is the batch size Algorithm 1 reaches by adding one at a time),
-// then scores and chooses.
+// m_total (the estimates never decrease with bs, so this is the batch size
+// Algorithm 1 reaches by adding one at a time): a bracket from the linear growth
+// of the estimate, then bisection inside it; then it scores and chooses.
+// The parameter census reads the entries grouped by size expression (the groups
+// travel in the kernel arguments) and the probes of the search count pages in 32
+// bits where a query's sizes allow it; tables with too many groups and waves with
+// a query beyond that take the entry-by-entry and the 64-bit forms of the same
+// arithmetic.
 //
 // Closed forms: Sec. 4.2 and Sec. 5 of arXiv 2404.10933 (incl. the DP+TP equation);
 // chunk size: Sec. 4.1; decision: Sec. 6, Algorithm 1.
@@ -32,6 +37,7 @@ namespace {
 
 constexpr int DC_WAVES = 4;
 constexpr int DC_BLOCK = 64 * DC_WAVES;
+constexpr int DC_GROUPS_MAX = 160;             // parameter groups of all architectures that fit the kernel arguments
 
 struct DecideArgs {
     llmem_configs cfg;
@@ -44,12 +50,32 @@ struct DecideArgs {
     long long *out_peaks, *out_flags;          // estimate_methods
     int *out_method, *out_bs;                  // decide
     long long *out_detail;
+    // parameter entries grouped by size expression (four words per group, the compiled tables'
+    // format): architecture ar owns groups[group_first[ar] ..] (a word index), n_groups[ar] of them
+    int use_groups;
+    int group_first[LLMEM_MAX_ARCH], n_groups[LLMEM_MAX_ARCH], e_n[LLMEM_MAX_ARCH];
+    uint32_t groups[4 * DC_GROUPS_MAX];
 };
+static_assert(sizeof(DecideArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 __device__ __forceinline__ u64 d_div(u64 x, u32 d, DivMagic m) { return d == 1 ? x : (__umul64hi(x, m.mul) >> m.shift); }
 __device__ __forceinline__ u64 d_cdiv(u64 x, u32 d, DivMagic m) { return d_div(x + (d - 1), d, m); }
 __device__ __forceinline__ u64 d_up(u64 x, int shift) { return ((x + ((1ull << shift) - 1)) >> shift) << shift; }
 __device__ __forceinline__ u32 d_uni(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
+// x * m (mod 2^64): the 64-bit product of the low half plus the low 32 bits of the high half's
+__device__ __forceinline__ u64 d_mul(u64 x, u32 m)
+{
+    const u64 lo = (u64)(u32)x * (u64)m;
+    return ((u64)((u32)(x >> 32) * m + (u32)(lo >> 32)) << 32) | (u64)(u32)lo;
+}
+// ceil(x / d) for x + d - 1 < 2^32: the multiply-high of the 64-bit constant with a 32-bit dividend
+__device__ __forceinline__ u32 d_cdiv32(u32 x, u32 d, DivMagic m)
+{
+    const u32 dividend = x + (d - 1);
+    const u64 low = (u64)dividend * (u32)m.mul;
+    const u64 high = (u64)dividend * (u32)(m.mul >> 32) + (low >> 32);
+    return d == 1 ? x : (u32)(high >> 32) >> m.shift;
+}
 
 // what a query needs to evaluate any method at any batch size
 struct QueryTerms {
@@ -117,7 +143,7 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
         D[LLMEM_DIM_HEAD_DIM] = head_dim; D[LLMEM_DIM_KV_DIM] = n_kv * head_dim; D[LLMEM_DIM_V] = V;
         D[LLMEM_DIM_P] = P; D[LLMEM_DIM_L] = L;
         const u32 Blog = (cflags & LLMEM_CFG_LOGITS_FP32) ? B32 : B16;
-        D[LLMEM_DIM_B_LOGITS] = Blog; D[LLMEM_DIM_D] = g; D[15] = 0;
+        D[LLMEM_DIM_B_LOGITS] = Blog; D[LLMEM_DIM_D] = g; D[DIM_BS_SL] = bs * sl;      // both below 2^16
 
         // ---- parameter table (Notation table; Sec. 4.2, equation for m_os), architecture by architecture
         u64 embed_p = 0, lm_p = 0, other_p = 0, t_max = 0, m_os = 0;
@@ -129,6 +155,31 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
             const bool mine = valid && arch_id == ar;
             todo &= ~__builtin_amdgcn_ballot_w64(mine);
             if (!mine) continue;
+            if (a.use_groups) {
+                // entries with the same size expression arrive as one group with the number of
+                // entries that count towards each sum, once and once per block
+                const int n_groups = (int)d_uni((u32)a.n_groups[ar]);
+                int at = (int)d_uni((u32)a.group_first[ar]);
+                e_n = d_uni((u32)a.e_n[ar]);
+                for (int j = 0; j < n_groups; ++j, at += 4) {
+                    const u32 coef = a.groups[at], desc = a.groups[at + 1], w2 = a.groups[at + 2], w3 = a.groups[at + 3];
+                    const u32 nd = desc & 7u;
+                    u64 t_p = coef;
+                    if (nd > 0) t_p = (u64)coef * D[(desc >> 4) & 15u];
+                    if (nd > 1) t_p = d_mul(t_p, D[(desc >> 8) & 15u]);
+                    if (nd > 2) t_p = d_mul(t_p, D[(desc >> 12) & 15u]);
+                    if (nd > 3) t_p = d_mul(t_p, D[(desc >> 16) & 15u]);
+                    if (w2 & 0xffffu) embed_p += t_p * (u64)((w2 & 255u) + ((w2 >> 8) & 255u) * L);
+                    if (w2 >> 16) lm_p += t_p * (u64)(((w2 >> 16) & 255u) + (w2 >> 24) * L);
+                    if (w3 & 0xffffu) {
+                        other_p += t_p * (u64)((w3 & 255u) + ((w3 >> 8) & 255u) * L);
+                        t_max = t_p > t_max ? t_p : t_max;
+                    }
+                    if (w3 >> 16)
+                        m_os += d_up(t_p * (u64)(B32 + B32), cu_shift) * (u64)(((w3 >> 16) & 255u) + (w3 >> 24) * L);
+                }
+                continue;
+            }
             const int n_param = (int)d_uni((u32)a.n_param[ar]), param_first = (int)d_uni((u32)a.param_first[ar]);
             for (int j = 0; j < n_param; ++j) {
                 const uint4 pe = a.params_dev[param_first + j];               // wave-uniform
@@ -148,16 +199,15 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
             }
         }
 
-        // ---- chunk size (Sec. 4.1): given, or the feasible candidate with the least padding waste
+        // ---- chunk size (Sec. 4.1): given, or the feasible candidate with the least padding waste,
+        // ties to the smaller chunk.  The waste of candidate k, (-other_p) mod 2^(k+19), never
+        // decreases with k and the candidates from some k on are the feasible ones: the search
+        // ends at the smallest feasible candidate (the last one when none is feasible).
         int k_used = chunk_k;
         if (chunk_k == -1) {
-            u64 best_waste = ~0ull;
-            k_used = K_SEARCH_MAX;
-            for (int k = K_SEARCH_MIN; k <= K_SEARCH_MAX; ++k) {
-                const u64 cs_mask = (1ull << (k + 19)) - 1;
-                const u64 waste = ((other_p + cs_mask) & ~cs_mask) - other_p;
-                if (t_max <= cs_mask + 1 && waste < best_waste) { best_waste = waste; k_used = k; }
-            }
+            const int need = t_max > 1 ? 64 - __builtin_clzll(t_max - 1) : 0;       // least s with t_max <= 2^s
+            const int k = need - 19;
+            k_used = k < K_SEARCH_MIN ? K_SEARCH_MIN : k > K_SEARCH_MAX ? K_SEARCH_MAX : k;
         }
         k_used = (k_used < 0 || k_used > K_FIXED_MAX) ? 0 : k_used;          // invalid lanes: any defined shift
         const u64 cs_mask = (1ull << (k_used + 19)) - 1;
@@ -217,41 +267,113 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
         // the rounding of the single-precision quotient (two more than its integer part); the
         // lower end is checked by an estimate of its own and dropped to 0 if it does not fit.
         const u32 cap = valid ? bs : 0u;
-        const float slope = (float)(q.c_out + q.c_logits + 2 * q.c_shifted);
-        const float six_pages = (float)(6ull << cu_shift);
-        u32 best[4], top[4], span = 0;
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const i64 room = a.m_total - (i64)q.fixed[m];
-            const float back = m == LLMEM_METHOD_TP ? (float)q.c_back_tp / (float)(g ? g : 1u)
-                               : m == LLMEM_METHOD_HYBRID ? (float)q.c_back_hy / (float)(tp ? tp : 1u) : 0.0f;
-            u32 hi = cap, lo = 0;
-            if (room < 0) {
-                hi = 0;                                                   // not even the fixed part fits
-            } else if (slope + back > 0.0f) {
-                const float growth = slope + back;
-                const float upper = __fdividef((float)room, growth);
-                if (upper < (float)cap) hi = (u32)upper + 2u < cap ? (u32)upper + 2u : cap;
-                const float lower = __fdividef((float)room - six_pages, growth) - 1.0f;
-                if (lower > 0.0f) lo = lower < (float)hi ? (u32)lower : hi;
-            }
-            if (lo > 0 && peak_at(q, m, lo) > a.m_total) lo = 0;
-            best[m] = lo; top[m] = hi;
-            span |= hi - lo;
-        }
-        for (int s = 32; s >= 1; s >>= 1) span |= (u32)__shfl_xor((int)span, s, 64);
-        const int bits = 32 - __builtin_clz(d_uni(span) | 1u);
-        u32 offset[4] = {0, 0, 0, 0};                                       // best = lower end + offset
-        for (int bit = bits - 1; bit >= 0; --bit) {
+        u32 best[4], top[4];                                                // the bracket: lower and upper end
+
+        // Page form of the probes.  The batch-dependent part of an estimate is a whole number of
+        // pages: with c = w * cu_p + r per term, ceil(b * c / cu_p) = b * w + ceil(b * r / cu_p), so
+        // the whole parts of m_out, the logits and the two shifted copies share one product and
+        // everything after the b * r products is 32-bit; an estimate fits iff its pages do not
+        // exceed floor((m_total - fixed) / cu_p).  Used by waves whose queries all keep every
+        // count below 2^31 at their largest batch size; the others probe in bytes.
+        const u64 page_mask = (1ull << cu_shift) - 1;
+        const u64 whole_sum = (q.c_out >> cu_shift) + (q.c_logits >> cu_shift) + 2 * (q.c_shifted >> cu_shift)
+                              + (q.c_back_tp >> cu_shift) + (q.c_back_hy >> cu_shift);
+        const bool pages_ok = cu_shift <= 31 && ((q.c_out | q.c_logits | q.c_shifted | q.c_back_tp | q.c_back_hy) >> 58) == 0
+                              && (whole_sum >> 31) == 0 && (((whole_sum + 8) * cap) >> 31) == 0;
+        const bool page_form = __builtin_amdgcn_ballot_w64(valid && !pages_ok) == 0;
+        const u32 plain_whole = (u32)(q.c_out >> cu_shift) + (u32)(q.c_logits >> cu_shift) + 2u * (u32)(q.c_shifted >> cu_shift);
+        const u32 r_out = (u32)(q.c_out & page_mask), r_logits = (u32)(q.c_logits & page_mask),
+                  r_shifted = (u32)(q.c_shifted & page_mask);
+        const u32 back_whole_tp = (u32)(q.c_back_tp >> cu_shift), r_back_tp = (u32)(q.c_back_tp & page_mask);
+        const u32 back_whole_hy = (u32)(q.c_back_hy >> cu_shift), r_back_hy = (u32)(q.c_back_hy & page_mask);
+        auto ceil_pages = [&](u32 b, u32 r) -> u32 { return (u32)(((u64)b * r + page_mask) >> cu_shift); };
+        auto plain_pages = [&](u32 b) -> u32 {
+            return b * plain_whole + ceil_pages(b, r_out) + ceil_pages(b, r_logits) + 2u * ceil_pages(b, r_shifted);
+        };
+        auto back_pages = [&](u32 b, u32 whole, u32 r, u32 t, DivMagic div) -> u32 {
+            return d_cdiv32(b * whole + ceil_pages(b, r), t, div);
+        };
+
+        // lower end checked, then the bracket bisected
+        auto search = [&](auto fits) {
+            u32 span = 0;
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                const u32 cand = best[m] + (offset[m] | (1u << bit));
-                const bool fits = cand <= top[m] && peak_at(q, m, cand) <= a.m_total;
-                offset[m] = fits ? (offset[m] | (1u << bit)) : offset[m];
+                if (best[m] > 0 && !fits(m, best[m])) best[m] = 0;
+                span |= top[m] - best[m];
             }
-        }
+            for (int s = 32; s >= 1; s >>= 1) span |= (u32)__shfl_xor((int)span, s, 64);
+            const int bits = 32 - __builtin_clz(d_uni(span) | 1u);
+            for (int bit = bits - 1; bit >= 0; --bit) {                   // best + 2^bit, 2^bit above what is left of the span
 #pragma unroll
-        for (int m = 0; m < 4; ++m) best[m] += offset[m];
+                for (int m = 0; m < 4; ++m) {
+                    const u32 cand = best[m] + (1u << bit);
+                    const bool ok = cand <= top[m] && fits(m, cand);
+                    best[m] = ok ? cand : best[m];
+                }
+            }
+        };
+        if (page_form) {
+            // the bracket in pages: growth per sample G = (c_out + c_logits + 2 c_shifted + c_back / t) / cu_p,
+            // room R = floor((m_total - fixed) / cu_p); b * G <= pages(b) <= b * G + 6, so every b that
+            // fits is at most R / G and every b up to (R - 6) / G fits
+            const float per_page = __builtin_ldexpf(1.0f, -cu_shift);
+            const float slope = (float)plain_whole + ((float)r_out + (float)r_logits + 2.0f * (float)r_shifted) * per_page;
+            u32 room_pages[4];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const i64 room = a.m_total - (i64)q.fixed[m];
+                const u64 p = room < 0 ? 0ull : (u64)room >> cu_shift;
+                room_pages[m] = p > 0x7fffffffull ? 0x7fffffffu : (u32)p;     // no estimate here has more pages
+                float growth = slope;
+                if (m == LLMEM_METHOD_TP)
+                    growth += ((float)back_whole_tp + (float)r_back_tp * per_page) * __builtin_amdgcn_rcpf((float)(g ? g : 1u));
+                if (m == LLMEM_METHOD_HYBRID)
+                    growth += ((float)back_whole_hy + (float)r_back_hy * per_page) * __builtin_amdgcn_rcpf((float)tp1);
+                u32 hi = cap, lo = 0;
+                if (room < 0) {
+                    hi = 0;                                               // not even the fixed part fits
+                } else if (growth > 0.0f) {
+                    // single precision: G, 1 / G and the product are each within a few units of the
+                    // last place, the quotient within 10 * 2^-24 of R / G, which is below 0.04 for
+                    // quotients under the cap (at most 65535); the ends move out by 0.25
+                    const float inv = __builtin_amdgcn_rcpf(growth);
+                    const float upper = (float)room_pages[m] * inv;
+                    if (upper < (float)cap) { const u32 u = (u32)(upper + 0.25f); hi = u < cap ? u : cap; }
+                    const float lower = upper - 6.25f * inv - 0.25f;
+                    if (lower > 0.0f) lo = lower < (float)hi ? (u32)lower : hi;
+                }
+                best[m] = lo; top[m] = hi;
+            }
+            search([&](int m, u32 b) -> bool {
+                u32 p = plain_pages(b);
+                if (m == LLMEM_METHOD_TP) p += back_pages(b, back_whole_tp, r_back_tp, g, div_g);
+                if (m == LLMEM_METHOD_HYBRID) p += back_pages(b, back_whole_hy, r_back_hy, tp1, div_t);
+                return p <= room_pages[m];
+            });
+        } else {
+            // the same bracket in bytes
+            const float slope = (float)(q.c_out + q.c_logits + 2 * q.c_shifted);
+            const float six_pages = (float)(6ull << cu_shift);
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const i64 room = a.m_total - (i64)q.fixed[m];
+                const float back = m == LLMEM_METHOD_TP ? (float)q.c_back_tp / (float)(g ? g : 1u)
+                                   : m == LLMEM_METHOD_HYBRID ? (float)q.c_back_hy / (float)tp1 : 0.0f;
+                u32 hi = cap, lo = 0;
+                if (room < 0) {
+                    hi = 0;
+                } else if (slope + back > 0.0f) {
+                    const float growth = slope + back;
+                    const float upper = __fdividef((float)room, growth);
+                    if (upper < (float)cap) hi = (u32)upper + 2u < cap ? (u32)upper + 2u : cap;
+                    const float lower = __fdividef((float)room - six_pages, growth) - 1.0f;
+                    if (lower > 0.0f) lo = lower < (float)hi ? (u32)lower : hi;
+                }
+                best[m] = lo; top[m] = hi;
+            }
+            search([&](int m, u32 b) -> bool { return peak_at(q, m, b) <= a.m_total; });
+        }
         if (tp == 0) best[LLMEM_METHOD_HYBRID] = 0;
         // scores (doubled) and the choice
         const u32 dp_n = tp ? (u32)d_div(g, tp, div_t) : 0u;
@@ -263,20 +385,37 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
         for (int m = 1; m < 4; ++m) idx = score2[m] > score2[idx] ? m : idx;
         int method = idx;
         u32 chosen_bs = idx == 0 ? best[0] : idx == 1 ? best[1] : idx == 2 ? best[2] : best[3];
-        i64 peak = peak_at(q, 0, chosen_bs);
-        if (idx == 1) peak = peak_at(q, 1, chosen_bs);
-        if (idx == 2) peak = peak_at(q, 2, chosen_bs);
-        if (idx == 3) peak = peak_at(q, 3, chosen_bs);
+        // the chosen method's estimate at its batch size: one evaluation with that method's terms
+        const u64 fixed_chosen = idx == 0 ? q.fixed[0] : idx == 1 ? q.fixed[1] : idx == 2 ? q.fixed[2] : q.fixed[3];
+        const bool hybrid = idx == LLMEM_METHOD_HYBRID, gathers = idx >= LLMEM_METHOD_TP;
+        const u32 t_chosen = hybrid ? tp1 : g;
+        const DivMagic div_chosen = hybrid ? div_t : div_g;
+        i64 peak;
+        if (page_form) {
+            const u32 whole = !gathers ? 0u : hybrid ? back_whole_hy : back_whole_tp;
+            const u32 r = !gathers ? 0u : hybrid ? r_back_hy : r_back_tp;
+            const u32 pages = plain_pages(chosen_bs) + back_pages(chosen_bs, whole, r, t_chosen, div_chosen);
+            peak = (i64)(fixed_chosen + ((u64)pages << cu_shift));
+        } else {
+            const u64 b = chosen_bs;
+            const u64 c_back = !gathers ? 0ull : hybrid ? q.c_back_hy : q.c_back_tp;
+            peak = (i64)(fixed_chosen + d_up(b * q.c_out, cu_shift) + d_up(b * q.c_logits, cu_shift)
+                         + 2 * d_up(b * q.c_shifted, cu_shift) + pages_over(b * c_back, t_chosen, div_chosen, cu_shift));
+        }
         if (score2[2] == 0) {
             method = LLMEM_METHOD_OFFLOAD; chosen_bs = 0; peak = 0;
             if (score2[0] | score2[1] | score2[3]) flags |= LLMEM_F_FALLBACK_READINGS_DIFFER;
         }
         if (in_range) {
             const bool bad = err != 0;
-            if (a.out_method) a.out_method[i] = bad ? -1 : method;
-            if (a.out_bs) a.out_bs[i] = bad ? 0 : (int)chosen_bs;
+            // the index is formed again here (two instructions) rather than kept through the search
+            int lane_again = lane;
+            asm volatile("" : "+v"(lane_again));
+            const long long at = (b << 6) + lane_again;
+            if (a.out_method) a.out_method[at] = bad ? -1 : method;
+            if (a.out_bs) a.out_bs[at] = bad ? 0 : (int)chosen_bs;
             if (a.out_detail) {
-                long long *o = a.out_detail + i;
+                long long *o = a.out_detail + at;
                 o[LLMEM_C_METHOD * n] = bad ? -1 : method;
                 o[LLMEM_C_BS * n] = bad ? 0 : (i64)chosen_bs;
 #pragma unroll
@@ -323,6 +462,19 @@ int launch(bool decide, const llmem_configs *cfg, const uint8_t *tp_n, int64_t n
         a.n_param[ar] = ar < plan.n_arch ? plan.arch[ar].n_param : 0;
     }
     a.params_dev = reinterpret_cast<const uint4 *>(tables->params_dev);
+    // the entries grouped by size expression, if the groups of all architectures fit the arguments
+    a.use_groups = 1;
+    int n_group_total = 0;
+    for (int ar = 0; ar < plan.n_arch && a.use_groups; ++ar) {
+        uint32_t e_n = 0;
+        const int got = compile_param_groups(tables->params_host + plan.arch[ar].param_first, plan.arch[ar].n_param,
+                                             a.groups + 4 * n_group_total, DC_GROUPS_MAX - n_group_total, &e_n);
+        if (got < 0) { a.use_groups = 0; break; }
+        a.group_first[ar] = 4 * n_group_total;
+        a.n_groups[ar] = got;
+        a.e_n[ar] = (int)e_n;
+        n_group_total += got;
+    }
     const int64_t n_batch = (n + 63) / 64;
     int64_t blocks = (n_batch + DC_WAVES - 1) / DC_WAVES;
     const int64_t max_blocks = 256 * 8;                 // 256 CUs, up to 8 resident workgroups each

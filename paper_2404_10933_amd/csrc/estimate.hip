@@ -375,6 +375,37 @@ static uint32_t descriptor_of(uint32_t sorted_dims)
     return desc;
 }
 
+// Parameter entries of one architecture grouped by size expression, in the compiled tables'
+// format (estimate_args.h): four words per group into `words`, which holds up to `max_groups`
+// groups.  Returns the number of groups, or -1 if there are more; *e_n: the embedding tables
+// whose outputs are kept (Sec. 4.2, m_out).
+int compile_param_groups(const llmem_param_entry *pe, int n_param, uint32_t *words, int max_groups, uint32_t *e_n)
+{
+    struct Group { uint32_t coef, dims; uint32_t cnt[8]; };      // E, LM, OTHER, OS x once, per block
+    std::vector<Group> groups;
+    *e_n = 0;
+    for (int j = 0; j < n_param; ++j) {
+        const uint32_t *w = reinterpret_cast<const uint32_t *>(&pe[j]);
+        const ClassKey k = make_class_key(w[0], w[1], 0u);         // sorts the selectors
+        size_t g = 0;
+        for (; g < groups.size(); ++g) if (groups[g].coef == k.coef && groups[g].dims == k.dims) break;
+        if (g == groups.size()) groups.push_back(Group{k.coef, k.dims, {0, 0, 0, 0, 0, 0, 0, 0}});
+        const int layer = pe[j].per_layer ? 1 : 0;
+        const int role = pe[j].role == LLMEM_ROLE_EMBED_TOK ? 0 : pe[j].role == LLMEM_ROLE_LM_HEAD ? 1 : 2;
+        ++groups[g].cnt[2 * role + layer];
+        if (pe[j].cls <= LLMEM_CLS_LINEAR && pe[j].role != LLMEM_ROLE_LM_HEAD) ++groups[g].cnt[6 + layer];
+        if (pe[j].cls == LLMEM_CLS_EMBEDDING && pe[j].role != LLMEM_ROLE_LM_HEAD) ++*e_n;
+    }
+    if ((int)groups.size() > max_groups) return -1;
+    for (const Group &g : groups) {
+        *words++ = g.coef;
+        *words++ = descriptor_of(g.dims);
+        *words++ = g.cnt[0] | (g.cnt[1] << 8) | (g.cnt[2] << 16) | (g.cnt[3] << 24);
+        *words++ = g.cnt[4] | (g.cnt[5] << 8) | (g.cnt[6] << 16) | (g.cnt[7] << 24);
+    }
+    return (int)groups.size();
+}
+
 // Compiles the tables of one architecture for the lane-per-configuration kernel: parameter
 // entries grouped by size expression; size classes of the events; then per segment the
 // class-count vectors at the peak points (an allocation followed by a release or by the end of the
@@ -386,21 +417,8 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
                            int *stats)
 {
     // ---- parameter groups ----
-    struct Group { uint32_t coef, dims; uint32_t cnt[8]; };      // E, LM, OTHER, OS x once, per block
-    std::vector<Group> groups;
-    uint32_t e_n = 0;
-    for (int j = 0; j < n_param; ++j) {
-        const uint32_t *w = reinterpret_cast<const uint32_t *>(&pe[j]);
-        const ClassKey k = make_class_key(w[0], w[1], 0u);         // sorts the selectors
-        size_t g = 0;
-        for (; g < groups.size(); ++g) if (groups[g].coef == k.coef && groups[g].dims == k.dims) break;
-        if (g == groups.size()) groups.push_back(Group{k.coef, k.dims, {0, 0, 0, 0, 0, 0, 0, 0}});
-        const int layer = pe[j].per_layer ? 1 : 0;
-        const int role = pe[j].role == LLMEM_ROLE_EMBED_TOK ? 0 : pe[j].role == LLMEM_ROLE_LM_HEAD ? 1 : 2;
-        ++groups[g].cnt[2 * role + layer];
-        if (pe[j].cls <= LLMEM_CLS_LINEAR && pe[j].role != LLMEM_ROLE_LM_HEAD) ++groups[g].cnt[6 + layer];
-        if (pe[j].cls == LLMEM_CLS_EMBEDDING && pe[j].role != LLMEM_ROLE_LM_HEAD) ++e_n;
-    }
+    uint32_t group_words[4 * 255], e_n = 0;
+    const int n_groups = compile_param_groups(pe, n_param, group_words, 255, &e_n);
     // ---- size classes ----
     std::vector<ClassKey> classes;
     std::vector<int> cls_of(n_event);
@@ -414,7 +432,7 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
         cls_of[j] = c;
     }
     const int nc = (int)classes.size();
-    if (nc > CLS_MAX || groups.size() > 255 || e_n > 255) return false;
+    if (nc > CLS_MAX || n_groups < 0 || e_n > 255) return false;
     // Classes with the same dimensions become neighbours, the smaller coefficient * element width
     // first: where the next one's is 2^k times as large, its raw size is the previous one shifted.
     {
@@ -431,14 +449,9 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
         for (int j = 0; j < n_event; ++j) cls_of[j] = place[cls_of[j]];
     }
     al->prog_first = (int)prog->size();
-    prog->push_back((uint32_t)groups.size() | (e_n << 8) | ((uint32_t)nc << 16));
+    prog->push_back((uint32_t)n_groups | (e_n << 8) | ((uint32_t)nc << 16));
     for (int q = 1; q < PROG_HEADER; ++q) prog->push_back(0u);     // segment boundaries, filled in below
-    for (const Group &g : groups) {
-        prog->push_back(g.coef);
-        prog->push_back(descriptor_of(g.dims));
-        prog->push_back(g.cnt[0] | (g.cnt[1] << 8) | (g.cnt[2] << 16) | (g.cnt[3] << 24));
-        prog->push_back(g.cnt[4] | (g.cnt[5] << 8) | (g.cnt[6] << 16) | (g.cnt[7] << 24));
-    }
+    for (int q = 0; q < 4 * n_groups; ++q) prog->push_back(group_words[q]);
     // ---- peak points and net change of every segment ----
     std::vector<std::vector<int>> seg_sums[LLMEM_NSEG];           // kept points, then the net change last
     const int n_slots = nc + 1;                                   // slot 0 holds 0, slot c + 1 minus the value of class c
@@ -463,7 +476,7 @@ static bool compile_tables(const llmem_param_entry *pe, int n_param, const llmem
         seg_sums[s].push_back(count);
     }
     if (n_slots > PROG_SLOT_MAX) return false;
-    stats[0] += (int)groups.size();
+    stats[0] += n_groups;
     stats[1] += nc;
     if (n_slots > *p_slots) *p_slots = n_slots;
     // ---- emit: classes, then the terms of every segment ----

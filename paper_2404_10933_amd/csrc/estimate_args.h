@@ -137,6 +137,10 @@ __host__ __device__ inline ClassKey make_class_key(uint32_t x, uint32_t y, uint3
 // and per-architecture ranges of `out`; LLMEM_OK or LLMEM_EINVAL_*.
 #ifndef __HIPCC_RTC__
 int check_tables(const llmem_tables *tables, EstimateArgs *out);
+// Parameter entries of one architecture grouped by size expression: four words per group as in
+// the compiled tables above, into `words` (room for max_groups groups).  Returns the number of
+// groups, -1 if there are more than max_groups; *e_n = embedding tables whose outputs are kept.
+int compile_param_groups(const llmem_param_entry *pe, int n_param, uint32_t *words, int max_groups, uint32_t *e_n);
 size_t batch_kernel_lds_bytes(const EstimateArgs &a);
 void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream);
 void launch_sweep_kernel(const EstimateArgs &args, long long n_batch, hipStream_t stream);

@@ -160,6 +160,43 @@ def test_large_batch_size_caps(U):
     assert ((rows[:, A.C_BS_CDP] > 4097) & (rows[:, A.C_BS_CDP] < 32767)).any()
 
 
+def _size_expressions(table):
+    return {(p.coef, tuple(sorted(d for d in p.dims if d != "one"))) for p in table.params}
+
+
+def test_entry_form_census_and_byte_form_probes(U):
+    """The forms the kernel falls back to: tables with more distinct parameter sizes than travel
+    in the kernel arguments (census entry by entry), and queries whose page counts pass 2^31 at
+    their cap or whose page is above 2^31 bytes (probes in bytes)."""
+    rng = np.random.default_rng(33)
+    tabs = [T.random_table(rng, 64, 0, f"r{j}") for j in range(8)]
+    assert sum(len(_size_expressions(t)) for t in tabs) > 200
+    cfg, tp = G.random_queries(rng, 64 * 12 + 5, n_arch=len(tabs), wild=True, bs_cap=300)
+    const = T.Constants(m_base=77, cu_p=1 << 14, align=64)
+    _check_methods(U, cfg, tp, tabs, const)
+    peaks, _ = B.method_peaks(cfg, tp, tabs, const, threads=8)
+    ok = peaks[:, 0] >= 0
+    for m_total in (int(np.percentile(peaks[ok, 2], 40)), int(np.median(peaks[ok, 1])), 1 << 55):
+        _check_decide(U, cfg, tp, tabs, m_total, const)
+
+    tables = [T.llama_table()]
+    n = 64 * 9 + 3
+    cfg, tp = G.grid6(n=n, seed=12, first=500)
+    cfg["bs"] = rng.choice([65535, 40000, 4096, 300, 7, 1, 0], size=n).astype(np.uint16)
+    small_page = T.Constants(m_base=3, cu_p=512, align=512)
+    beyond = (((cfg["L"].astype(np.int64) + 1) * cfg["sl"] * cfg["h"] * 2) >> 9) * cfg["bs"] >= 1 << 31
+    assert beyond.any() and not beyond.all()
+    for m_total in (80 * GIB, 1 << 41, 1 << 45):
+        rows = _check_decide(U, cfg, tp, tables, m_total, small_page, threads=16)
+    assert rows[:, A.C_BS].max() == 65535
+    huge_page = T.Constants(m_base=0, cu_p=1 << 33, align=512)
+    for m_total in (400 * GIB, 1 << 41, 1 << 44):
+        _check_decide(U, cfg, tp, tables, m_total, huge_page, threads=16)
+    cfg["bs"] = np.minimum(cfg["bs"], 900).astype(np.uint16)               # the page form again, small pages
+    for m_total in (80 * GIB, 1 << 40):
+        _check_decide(U, cfg, tp, tables, m_total, T.Constants(m_base=3, cu_p=4096, align=512), threads=16)
+
+
 def test_determinism_and_stream(U):
     tables = [T.llama_table()]
     cfg, tp = G.grid6(n=5000, seed=9, first=0)
