@@ -172,6 +172,59 @@ def test_embedded_sources_cover_the_kernel_and_its_headers():
             assert os.path.basename(inc) in embedded + ["specialized_prog.h"], (name, inc)
 
 
+def _compiled_counts(table):
+    """What the host compiler of the tables should arrive at, counted here from the table's own
+    definition: parameter groups (equal size expressions), size classes of the events, and per
+    segment the peak points (an allocation followed by a release or the segment's end) that no
+    other point of the segment dominates, plus the terms of the kept points and net changes."""
+    from workloads import tables as T
+
+    def product(dims):
+        return tuple(sorted(d for d in dims if d != "one"))
+
+    groups = {(p.coef, product(p.dims)) for p in table.params}
+    key = lambda e: (e.coef, product(e.dims), e.elem_bytes, e.times_L, e.scale == "tp_gather", frozenset(e.methods))
+    classes = sorted({key(e) for e in table.events}, key=repr)
+    terms = points = 0
+    for seg in T.SEGMENTS:
+        evs = [e for e in table.events if e.seg == seg]
+        count, seen = {c: 0 for c in classes}, []
+        for j, e in enumerate(evs):
+            count[key(e)] += e.sign
+            if e.sign > 0 and (j + 1 == len(evs) or evs[j + 1].sign < 0):
+                seen.append(tuple(count[c] for c in classes))
+        kept = []
+        for j, v in enumerate(seen):
+            dominated = any(k != j and all(a <= b for a, b in zip(v, w)) and (v != w or k < j) for k, w in enumerate(seen))
+            if not dominated:
+                kept.append(v)
+        points += len(kept)
+        terms += sum(1 for v in kept + [tuple(count[c] for c in classes)] for x in v if x != 0)
+    return dict(param_groups=len(groups), size_classes=len(classes), terms=terms, peak_points=points)
+
+
+def test_table_compiler_statistics(lib):
+    """llmem_kernel_forms reports what the host made of the tables (no device involved)."""
+    import paper_2404_10933_amd as M
+    from workloads import tables as T
+    rng = np.random.default_rng(8)
+    cases = [T.gpt_table(), T.opt_table(), T.llama_table(), T.llama_table(checkpoint=False),
+             T.random_table(rng, 20, 60, "r", n_sizes=7), T.random_table(rng, 40, 90, "s", n_sizes=12)]
+    for t in cases:
+        forms = M.llmem_kernel_forms(M.Tables([t], device=None))
+        want = _compiled_counts(t)
+        assert {k: forms[k] for k in want} == want, t.name
+        assert 4 in forms["allowed"] and 5 in forms["allowed"]
+    llama = M.llmem_kernel_forms(M.Tables([T.llama_table()], device=None))
+    assert (llama["param_groups"], llama["size_classes"], llama["peak_points"], llama["terms"]) == (5, 20, 33, 125)
+    both = M.llmem_kernel_forms(M.Tables([T.gpt_table(), T.llama_table()], device=None))
+    assert both["param_groups"] == _compiled_counts(T.gpt_table())["param_groups"] + 5
+    # more size classes than the lane kernels take: only the wavefront-per-configuration kernel is left
+    many = T.random_table(rng, 5, 400, "many")
+    assert _compiled_counts(many)["size_classes"] > 48
+    assert M.llmem_kernel_forms(M.Tables([many], device=None))["allowed"] == [1]
+
+
 def test_table_packing_layout():
     """The binding's 16-byte records match the C structs field by field."""
     Bd = _structs()
