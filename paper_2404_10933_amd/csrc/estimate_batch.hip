@@ -106,6 +106,9 @@ __device__ __forceinline__ u64 mul_64x32(u64 x, u32 m)
     return ((u64)(hi_part + (u32)(lo >> 32)) << 32) | (u64)(u32)lo;
 }
 __device__ __forceinline__ u32 uni(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
+// Results are written once and not read again: streaming stores, which do not keep the lines in
+// the L2 at the expense of what the kernel still reads.
+__device__ __forceinline__ void put(long long *p, i64 v) { __builtin_nontemporal_store((long long)v, p); }
 
 }  // namespace
 
@@ -488,19 +491,19 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                 if (!SWEEP) {
                     long long at_i = i;
                     LLMEM_ANCHOR(at_i);
-                    if (a.out_peaks) a.out_peaks[at_i] = (i64)m_peak;
+                    if (a.out_peaks) put(&a.out_peaks[at_i], (i64)m_peak);
                     long long *o = a.out_detail + at_i;
-                    o[(long long)LLMEM_D_PEAK * n] = (i64)m_peak;
-                    o[(long long)LLMEM_D_PARAM_GPU * n] = (i64)param_gpu;
-                    o[(long long)LLMEM_D_GRAD_GPU * n] = (i64)grad_logical;
-                    o[(long long)LLMEM_D_OS_GPU * n] = (i64)os_gpu;
-                    o[(long long)LLMEM_D_OUT * n] = (i64)m_out;
-                    o[(long long)LLMEM_D_LM * n] = (i64)m_lm;
-                    o[(long long)LLMEM_D_BACK * n] = (i64)m_back;
-                    o[(long long)LLMEM_D_K * n] = (i64)k_used;
-                    o[(long long)LLMEM_D_NPARAMS * n] = (i64)n_params;
-                    o[(long long)LLMEM_D_TMAX * n] = (i64)t_max;
-                    o[(long long)LLMEM_D_FLAGS * n] = (i64)flags;
+                    put(&o[(long long)LLMEM_D_PEAK * n], (i64)m_peak);
+                    put(&o[(long long)LLMEM_D_PARAM_GPU * n], (i64)param_gpu);
+                    put(&o[(long long)LLMEM_D_GRAD_GPU * n], (i64)grad_logical);
+                    put(&o[(long long)LLMEM_D_OS_GPU * n], (i64)os_gpu);
+                    put(&o[(long long)LLMEM_D_OUT * n], (i64)m_out);
+                    put(&o[(long long)LLMEM_D_LM * n], (i64)m_lm);
+                    put(&o[(long long)LLMEM_D_BACK * n], (i64)m_back);
+                    put(&o[(long long)LLMEM_D_K * n], (i64)k_used);
+                    put(&o[(long long)LLMEM_D_NPARAMS * n], (i64)n_params);
+                    put(&o[(long long)LLMEM_D_TMAX * n], (i64)t_max);
+                    put(&o[(long long)LLMEM_D_FLAGS * n], (i64)flags);
                 }
 #endif
                 // what is resident before the iteration starts (one value instead of five during the timeline)
@@ -770,12 +773,12 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
             // valid configurations have stored the other columns already; invalid ones store them all
             long long *o = a.out_detail + i;
             if (valid) {
-                o[(long long)LLMEM_D_PEAK_LIVE * n] = r_live;
+                put(&o[(long long)LLMEM_D_PEAK_LIVE * n], r_live);
             } else {
-                if (a.out_peaks) a.out_peaks[i] = -1;
+                if (a.out_peaks) put(&a.out_peaks[i], -1);
 #pragma unroll
                 for (int c = 0; c < LLMEM_NDETAIL; ++c)
-                    o[(long long)c * n] = c == LLMEM_D_PEAK ? -1 : c == LLMEM_D_FLAGS ? (i64)err : 0;
+                    put(&o[(long long)c * n], c == LLMEM_D_PEAK ? -1 : c == LLMEM_D_FLAGS ? (i64)err : 0);
             }
 #endif
         } else if (in_range) {
@@ -783,21 +786,21 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
             int lane_again = lane;
             asm volatile("" : "+v"(lane_again));
             const long long at_i = (b << 6) + lane_again;
-            if (a.out_peaks) a.out_peaks[at_i] = r_peak;
+            if (a.out_peaks) put(&a.out_peaks[at_i], r_peak);
             if (DETAIL) {
                 long long *o = a.out_detail + at_i;
-                o[(long long)LLMEM_D_PEAK * n] = r_peak;
-                o[(long long)LLMEM_D_PARAM_GPU * n] = r_param;
-                o[(long long)LLMEM_D_GRAD_GPU * n] = r_grad;
-                o[(long long)LLMEM_D_OS_GPU * n] = r_os;
-                o[(long long)LLMEM_D_OUT * n] = r_out;
-                o[(long long)LLMEM_D_LM * n] = r_lm;
-                o[(long long)LLMEM_D_BACK * n] = r_back;
-                o[(long long)LLMEM_D_K * n] = r_k;
-                o[(long long)LLMEM_D_PEAK_LIVE * n] = r_live;
-                o[(long long)LLMEM_D_NPARAMS * n] = r_np;
-                o[(long long)LLMEM_D_TMAX * n] = r_tmax;
-                o[(long long)LLMEM_D_FLAGS * n] = r_flags;
+                put(&o[(long long)LLMEM_D_PEAK * n], r_peak);
+                put(&o[(long long)LLMEM_D_PARAM_GPU * n], r_param);
+                put(&o[(long long)LLMEM_D_GRAD_GPU * n], r_grad);
+                put(&o[(long long)LLMEM_D_OS_GPU * n], r_os);
+                put(&o[(long long)LLMEM_D_OUT * n], r_out);
+                put(&o[(long long)LLMEM_D_LM * n], r_lm);
+                put(&o[(long long)LLMEM_D_BACK * n], r_back);
+                put(&o[(long long)LLMEM_D_K * n], r_k);
+                put(&o[(long long)LLMEM_D_PEAK_LIVE * n], r_live);
+                put(&o[(long long)LLMEM_D_NPARAMS * n], r_np);
+                put(&o[(long long)LLMEM_D_TMAX * n], r_tmax);
+                put(&o[(long long)LLMEM_D_FLAGS * n], r_flags);
             }
         }
     }
