@@ -30,6 +30,8 @@ constexpr int BLOCK_SHIFT = 9;                   // log2(LLMEM_BLOCK)
 constexpr int SPLIT_BLOCKS = LLMEM_POOL_SPLIT / LLMEM_BLOCK;
 static_assert((1 << BLOCK_SHIFT) == LLMEM_BLOCK, "block size");
 
+typedef long long pair64 __attribute__((ext_vector_type(2)));
+
 void set_hip_error(hipError_t e);
 
 __global__ __launch_bounds__(TL_BLOCK) void timeline_kernel(const long long *__restrict__ events,
@@ -62,7 +64,8 @@ __global__ __launch_bounds__(TL_BLOCK) void timeline_kernel(const long long *__r
                 const long long e = base + j * 128 + 2 * lane;
                 i64 a0 = 0, a1 = 0;
                 if (e >= first && e + 1 < last) {
-                    const longlong2 p = *reinterpret_cast<const longlong2 *>(events + e);
+                    // every event is read once: a streaming load, which does not keep the line in the L2
+                    const pair64 p = __builtin_nontemporal_load(reinterpret_cast<const pair64 *>(events + e));
                     a0 = p.x; a1 = p.y;
                 } else {
                     if (e >= first && e < last) a0 = events[e];
