@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC_ESTIMATE = 1.3694e9     # 10^7 configurations, all detail columns, built-in compiled form (incl. 8 B/lane of spill scratch)
 TRAFFIC_SPECIALIZED = 1.3503e9  # the same workload, kernel built at run time
 TRAFFIC_SWEEP = 5.0558e7        # 10^7 configurations drawn and reduced in the kernel built at run time
-TRAFFIC_TIMELINE = 8.0201e9     # 100 000 event lists, 1 000 110 810 events
-TRAFFIC_DECIDE = 5.4026e8       # 4 000 000 queries, all decision columns (the search inside the kernel does not touch memory)
+TRAFFIC_TIMELINE = 8.0182e9     # 100 000 event lists, 1 000 110 810 events
+TRAFFIC_DECIDE = 5.4028e8       # 4 000 000 queries, all decision columns (the search inside the kernel does not touch memory)
 
 
 def algorithmic_lane_ops(forms, n_candidates):

@@ -53,9 +53,10 @@ __global__ __launch_bounds__(TL_BLOCK) void timeline_kernel(const long long *__r
         const long long first = offsets[li], last = offsets[li + 1];
         i64 carry_s = 0, carry_l = 0;                 // live bytes of the pools before the tile
         i64 best_s = 0, best_l = 0, best_t = 0;       // per-lane maxima; the empty prefix counts
-        // tiles start at a 16-byte boundary of the event array; what lies before `first` or at
-        // and after `last` is read as 0 (an event of 0 bytes changes nothing)
-        const long long lead = (long long)((reinterpret_cast<uintptr_t>(events + first) >> 3) & 1);
+        // tiles start at a 128-byte boundary of the event array, so that no cache line is shared by
+        // two load instructions (a streaming load does not find it in the L2 the second time); what
+        // lies before `first` or at and after `last` is read as 0 (an event of 0 bytes changes nothing)
+        const long long lead = (long long)((reinterpret_cast<uintptr_t>(events + first) >> 3) & 15);
         for (long long base = first - lead; base < last; base += TL_TILE) {
             // ---- coalesced loads: load j covers events base + j*128 .. +127, two per lane ----
             u32 high_bits = 0;

@@ -44,6 +44,20 @@ def test_random_ragged_lists(U):
         lists.append(list(np.where(rng.random(n) < 0.5, mag, -mag)))   # arbitrary signs: prefixes go negative
     ev, off = E.from_lists(lists)
     _check(U, ev, off)
+    # the event array at every 8-byte position within a 128-byte line (the kernel reads whole lines)
+    import paper_2404_10933_amd as M
+    want_a, want_r = B.event_lists_peaks(ev, off, threads=8)
+    n = len(off) - 1
+    off_dev = torch.from_numpy(off).cuda()
+    for shift in (1, 2, 7, 15):
+        padded = torch.full((len(ev) + 32,), 1 << 40, dtype=torch.int64, device="cuda")    # what surrounds the lists must not count
+        padded[shift:shift + len(ev)] = torch.from_numpy(ev).cuda()
+        a = torch.full((n,), -7, dtype=torch.int64, device="cuda")
+        r = torch.full((n,), -7, dtype=torch.int64, device="cuda")
+        M.llmem_timeline_peaks(padded[shift:shift + len(ev)], off_dev, a, r)
+        torch.cuda.synchronize()
+        U.assert_same(f"allocated, array shifted by {shift}", a.cpu().numpy(), want_a)
+        U.assert_same(f"reserved, array shifted by {shift}", r.cpu().numpy(), want_r)
 
 
 def test_wide_events_take_the_64_bit_path(U):
