@@ -197,6 +197,46 @@ def test_entry_form_census_and_byte_form_probes(U):
         _check_decide(U, cfg, tp, tables, m_total, T.Constants(m_base=3, cu_p=4096, align=512), threads=16)
 
 
+def test_capacities_at_the_edge_of_a_batch_size(U):
+    """m_total equal to an estimate at some batch size, and one byte either side of it, for batch
+    sizes up to the 16-bit cap: where a bracket that is off by one would show.  The oracle's
+    estimates at the answers decide: the answer fits, the next batch size does not."""
+    tables = [T.gpt_table()]
+    rng = np.random.default_rng(44)
+    n = 128
+    cfg = {k: np.repeat(v, n) for k, v in _one(h=64, L=2, n_heads=1, n_kv=1, ffn=256, V=1000, P=16, sl=16).items()}
+    cfg["h"] = (64 * rng.integers(1, 5, size=n)).astype(np.uint32)
+    cfg["L"] = rng.integers(1, 6, size=n).astype(np.uint16)
+    cfg["sl"] = rng.choice([1, 2, 16, 100, 128], size=n).astype(np.uint16)
+    cfg["V"] = rng.choice([1000, 1024, 32768], size=n).astype(np.uint32)
+    cfg["d"] = rng.choice([1, 2, 3, 4, 8, 16], size=n).astype(np.uint8)
+    cfg["bs"] = np.full(n, 65535, np.uint16)
+    tp = np.where(rng.random(n) < 0.5, 1, cfg["d"]).astype(np.uint8)
+    const = T.Constants(m_base=12345)
+
+    def peaks_at(bs):
+        at = dict(cfg)
+        at["bs"] = bs.astype(np.uint16)
+        return B.method_peaks(at, tp, tables, const, threads=8)[0]
+
+    capacities = set()
+    for b in (1, 2, 999, 4097, 30000, 65534, 65535):
+        p = peaks_at(np.full(n, b))
+        for j, m in zip(rng.integers(0, n, size=3), rng.integers(0, 4, size=3)):
+            capacities |= {int(p[j, m]) - 1, int(p[j, m]), int(p[j, m]) + 1}
+    assert len(capacities) > 50
+    for m_total in sorted(capacities):
+        _, _, rows = U.hip_decide(cfg, tp, tables, const, m_total)
+        for m in range(4):
+            best = rows[:, A.C_BS_CDP + m]
+            assert ((best >= 0) & (best <= 65535)).all()
+            here, above = peaks_at(best)[:, m], peaks_at(np.minimum(best + 1, 65535))[:, m]
+            assert ((here <= m_total) | (best == 0)).all(), (m_total, m)
+            assert ((above > m_total) | (best == 65535)).all(), (m_total, m)
+            first = peaks_at(np.ones(n))[:, m]
+            assert ((best > 0) | (first > m_total)).all(), (m_total, m)
+
+
 def test_determinism_and_stream(U):
     tables = [T.llama_table()]
     cfg, tp = G.grid6(n=5000, seed=9, first=0)
