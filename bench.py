@@ -25,11 +25,11 @@ PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12       # 256 CUs x one 64-lane vector in
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs under profiles/, scaled by the
 # plain-copy reference; None while the kernel has changed since the counters were taken
-TRAFFIC_ESTIMATE = 1.3694e9     # 10^7 configurations, all detail columns, built-in compiled form (incl. 8 B/lane of spill scratch)
+TRAFFIC_ESTIMATE = 1.3691e9     # 10^7 configurations, all detail columns, built-in compiled form (incl. 8 B/lane of spill scratch)
 TRAFFIC_SPECIALIZED = 1.3503e9  # the same workload, kernel built at run time
 TRAFFIC_SWEEP = 5.0558e7        # 10^7 configurations drawn and reduced in the kernel built at run time
 TRAFFIC_TIMELINE = 8.0182e9     # 100 000 event lists, 1 000 110 810 events
-TRAFFIC_DECIDE = 5.4028e8       # 4 000 000 queries, all decision columns (the search inside the kernel does not touch memory)
+TRAFFIC_DECIDE = 5.4027e8       # 4 000 000 queries, all decision columns (the search inside the kernel does not touch memory)
 
 
 def algorithmic_lane_ops(forms, n_candidates):

@@ -57,9 +57,16 @@ __global__ __launch_bounds__(TL_BLOCK) void timeline_kernel(const long long *__r
         // two load instructions (a streaming load does not find it in the L2 the second time); what
         // lies before `first` or at and after `last` is read as 0 (an event of 0 bytes changes nothing)
         const long long lead = (long long)((reinterpret_cast<uintptr_t>(events + first) >> 3) & 15);
-        for (long long base = first - lead; base < last; base += TL_TILE) {
-            // ---- coalesced loads: load j covers events base + j*128 .. +127, two per lane ----
-            u32 high_bits = 0;
+        // coalesced loads of one tile into registers: load j covers events base + j*128 .. +127, two per lane
+        auto request = [&](long long base, i64 (&v)[2 * (TL_TILE / 128)]) {
+            if (base >= first && base + TL_TILE <= last) {                // a tile inside the list: nothing to mask
+#pragma unroll
+                for (int j = 0; j < TL_TILE / 128; ++j) {
+                    const pair64 p = __builtin_nontemporal_load(reinterpret_cast<const pair64 *>(events + base + j * 128 + 2 * lane));
+                    v[2 * j] = p.x; v[2 * j + 1] = p.y;
+                }
+                return;
+            }
 #pragma unroll
             for (int j = 0; j < TL_TILE / 128; ++j) {
                 const long long e = base + j * 128 + 2 * lane;
@@ -72,10 +79,23 @@ __global__ __launch_bounds__(TL_BLOCK) void timeline_kernel(const long long *__r
                     if (e >= first && e < last) a0 = events[e];
                     if (e + 1 >= first && e + 1 < last) a1 = events[e + 1];
                 }
+                v[2 * j] = a0; v[2 * j + 1] = a1;
+            }
+        };
+        // the next tile is requested before the current one is walked, so that its loads are in
+        // flight meanwhile (past `last` nothing is loaded)
+        i64 tile[2 * (TL_TILE / 128)];
+        request(first - lead, tile);
+        for (long long base = first - lead; base < last; base += TL_TILE) {
+            u32 high_bits = 0;
+#pragma unroll
+            for (int j = 0; j < TL_TILE / 128; ++j) {
+                const i64 a0 = tile[2 * j], a1 = tile[2 * j + 1];
                 const u32 h0 = (u32)((u64)a0 >> 32), h1 = (u32)((u64)a1 >> 32);
                 high_bits |= (h0 ^ (u32)((int)h0 >> 31)) | (h1 ^ (u32)((int)h1 >> 31));
                 *reinterpret_cast<longlong2 *>(mine + put0 + j * (128 / TL_RUN) * TL_ROW) = make_longlong2(a0, a1);
             }
+            request(base + TL_TILE, tile);
             const bool narrow = __builtin_amdgcn_ballot_w64(high_bits >= 8u) == 0;   // all |raw| < 2^35
 
             i64 run_s, run_l, top_s, top_l, top_t;    // relative to the run's start; tops >= 0 (the start itself)
