@@ -2,7 +2,8 @@
 //
 // Sequential traversal with live tensors and 512-byte blocks (Sec. 2.1 / Sec. 3.1
 // of arXiv 2404.10933) as a scan.  A wave streams its list in tiles of 1024
-// events: coalesced 16-byte loads, a transpose through wave-private LDS so that
+// events: coalesced 16-byte streaming loads into registers (the next tile is
+// requested before the current one is walked), a transpose through wave-private LDS so that
 // every lane owns 16 consecutive events, a sequential walk of those 16 keeping
 // running sums and running maxima of the two pools relative to the run's start,
 // then a wave prefix sum over the runs' totals that places each run on the list's
