@@ -225,6 +225,50 @@ def test_table_compiler_statistics(lib):
     assert M.llmem_kernel_forms(M.Tables([many], device=None))["allowed"] == [1]
 
 
+def test_every_entry_point_raises_without_the_library():
+    """No fallback of any kind: with the shared library absent every binding call raises, and the
+    package does not import the oracle."""
+    import subprocess
+    import sys
+    code = """
+import sys
+sys.path.insert(0, %r)
+import torch
+import paper_2404_10933_amd as M
+from paper_2404_10933_amd import binding
+from workloads import tables as T
+binding._LIB_PATH = "/nonexistent/libllmem.so"
+binding._lib = None
+assert not any(name == "oracle" or name.startswith("oracle.") for name in sys.modules)
+n = 8
+cfg = M.DeviceConfigs.empty(n, device="cpu")              # host tensors: nothing here reaches a kernel
+tab = M.Tables([T.gpt_table()], device=None)
+i64 = lambda *shape: torch.zeros(shape, dtype=torch.int64)
+i32 = lambda *shape: torch.zeros(shape, dtype=torch.int32)
+tp = torch.ones(n, dtype=torch.uint8)
+calls = [lambda: M.llmem_abi_version(), lambda: M.llmem_config_bytes(3), lambda: M.llmem_events_bytes(3),
+         lambda: M.llmem_strerror(0), lambda: M.llmem_kernel_forms(tab),
+         lambda: M.llmem_estimate(cfg, tab, i64(n)), lambda: M.llmem_estimate_ex(cfg, tab, i64(n), i64(M.NDETAIL, n)),
+         lambda: M.llmem_estimate_methods(cfg, tp, tab, i64(4, n)),
+         lambda: M.llmem_decide(cfg, tp, tab, 1 << 30, i32(n), i32(n), i64(M.NDECIDE, n)),
+         lambda: M.llmem_sweep(4, 0, 0, n, tab, 1 << 30, i64(M.NSWEEP, M.SWEEP_GROUPS)),
+         lambda: M.llmem_sweep_reset(i64(M.NSWEEP, M.SWEEP_GROUPS)),
+         lambda: M.llmem_timeline_peaks(i64(4), i64(2), i64(1), i64(1)),
+         lambda: M.llmem_grid_generate(4, 0, 0, n, cfg), lambda: M.llmem_queries_generate(0, 0, n, cfg, tp),
+         lambda: M.llmem_events_count(0, 0, 1, i64(1)), lambda: M.llmem_events_generate(0, 0, 1, i64(2), i64(4))]
+for j, call in enumerate(calls):
+    try:
+        call()
+    except FileNotFoundError as e:
+        assert "no CPU fallback" in str(e), j
+    else:
+        raise SystemExit("call %%d returned without the library" %% j)
+print("ok")
+""" % ROOT
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0 and out.stdout.strip() == "ok", out.stdout + out.stderr
+
+
 def test_table_packing_layout():
     """The binding's 16-byte records match the C structs field by field."""
     Bd = _structs()
