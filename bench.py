@@ -30,6 +30,20 @@ TRAFFIC_SPECIALIZED = 1.3503e9  # the same workload, kernel built at run time
 TRAFFIC_SWEEP = 5.0558e7        # 10^7 configurations drawn and reduced in the kernel built at run time
 TRAFFIC_TIMELINE = 8.0182e9     # 100 000 event lists, 1 000 110 810 events
 TRAFFIC_DECIDE = 5.4027e8       # 4 000 000 queries, all decision columns (the search inside the kernel does not touch memory)
+# Vector instructions issued per wave of 64 units (SQ_INSTS_VALU of the same runs), i.e. per unit and lane;
+# with them `issued` = the share of the nominal vector issue slots the kernel fills, whatever the census says
+VALU_ESTIMATE = 1815            # built-in compiled form, per configuration
+VALU_SPECIALIZED = 1332         # kernel built at run time
+VALU_SWEEP = 1483
+VALU_DECIDE = 938.6             # per query
+
+
+def issued(valu_per_unit, units_per_s):
+    """Vector lane-instructions issued per second against the nominal issue rate (None: no counter for this kernel)."""
+    if valu_per_unit is None:
+        return None
+    rate = valu_per_unit * units_per_s / 1e12
+    return {"valu_per_unit": valu_per_unit, "achieved": rate, "frac": rate / PEAK_LANE_TOPS}
 
 
 def algorithmic_lane_ops(forms, n_candidates):
@@ -86,6 +100,21 @@ def algorithmic_lane_ops_sweep_extra():
     return draws + shape + fold
 
 
+def timed_ms(fn, reps=3):
+    """Mean duration of fn() in ms by HIP events on the current stream, after one untimed call."""
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -131,7 +160,7 @@ def main():
     table = T.llama_table()
     n = args.n
     dev = M.DeviceConfigs.empty(n)
-    M.llmem_grid_generate(4, 0, 0, n, dev)
+    generators = {"grid4_ms": timed_ms(lambda: M.llmem_grid_generate(4, 0, 0, n, dev)), "grid4_configs": n}
     kernel = {"auto": 0, "wave": 1, "lane": 2, "specialized": 5}[args.kernel]
     tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=kernel)
     peaks = torch.empty(n, dtype=torch.int64, device="cuda")
@@ -187,6 +216,8 @@ def main():
                      "traffic": ({0: TRAFFIC_ESTIMATE, 5: TRAFFIC_SPECIALIZED}.get(kernel) if n == 10_000_000 else None),
                      "kernel": kernel_name, "kernel_ms": kernel_ms,
                      "algorithmic_lane_ops_per_config": ops,
+                     "issued": issued({0: VALU_ESTIMATE, 5: VALU_SPECIALIZED}.get(kernel) if n == 10_000_000 else None,
+                                      n / (kernel_ms * 1e-3)),
                      "hbm_gbs_algorithmic": bytes_per_cfg * n / (kernel_ms * 1e-3) / 1e9},
     }
 
@@ -220,7 +251,8 @@ def main():
             "n_configs": n, "ms_per_launch": ms, "configs_per_s": n / (ms * 1e-3),
             "roofline": {"bound": "alu", "achieved": i_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
                          "frac": i_achieved / PEAK_LANE_TOPS, "traffic": TRAFFIC_ESTIMATE if n == 10_000_000 else None,
-                         "kernel": "estimate_batch_kernel<true, true, false>", "algorithmic_lane_ops_per_config": ops},
+                         "kernel": "estimate_batch_kernel<true, true, false>", "algorithmic_lane_ops_per_config": ops,
+                         "issued": issued(VALU_ESTIMATE if n == 10_000_000 else None, n / (ms * 1e-3))},
             "verified_vs_oracle": int(len(idx))}
 
     if args.lists > 0:
@@ -231,7 +263,8 @@ def main():
         offsets[1:] = torch.cumsum(counts, 0)
         total = int(offsets[-1].item())
         events = torch.empty(total, dtype=torch.int64, device="cuda")
-        M.llmem_events_generate(0, 0, nl, offsets, events)
+        generators["event_lists_ms"] = timed_ms(lambda: M.llmem_events_generate(0, 0, nl, offsets, events))
+        generators["event_lists"] = nl
         oa = torch.empty(nl, dtype=torch.int64, device="cuda")
         orv = torch.empty(nl, dtype=torch.int64, device="cuda")
         for _ in range(2):
@@ -333,7 +366,8 @@ def main():
                          "frac": s_achieved / PEAK_LANE_TOPS,
                          "traffic": TRAFFIC_SWEEP if (kernel == 5 and nsw == 10_000_000) else None,
                          "kernel": "llmem_specialized_sweep" if kernel == 5 else "estimate_batch_kernel<true, true, true>",
-                         "algorithmic_lane_ops_per_config": s_ops},
+                         "algorithmic_lane_ops_per_config": s_ops,
+                         "issued": issued(VALU_SWEEP if (kernel == 5 and nsw == 10_000_000) else None, nsw / (ms * 1e-3))},
             "verified_vs_oracle": ns}
 
     if args.queries > 0:
@@ -341,7 +375,8 @@ def main():
         del peaks, detail
         qdev = M.DeviceConfigs.empty(nq)
         tp = torch.empty(nq, dtype=torch.uint8, device="cuda")
-        M.llmem_queries_generate(0, 0, nq, qdev, tp)
+        generators["queries_ms"] = timed_ms(lambda: M.llmem_queries_generate(0, 0, nq, qdev, tp))
+        generators["queries"] = nq
         qtab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align)
         q_method = torch.empty(nq, dtype=torch.int32, device="cuda")
         q_bs = torch.empty(nq, dtype=torch.int32, device="cuda")
@@ -379,7 +414,8 @@ def main():
                          "traffic": TRAFFIC_DECIDE if nq == 4_000_000 else None, "kernel": "decide_kernel<true>",
                          "algorithmic_bytes_per_query": q_bytes,
                          "alu": {"achieved": q_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
-                                 "frac": q_achieved / PEAK_LANE_TOPS, "algorithmic_lane_ops_per_query": q_ops}},
+                                 "frac": q_achieved / PEAK_LANE_TOPS, "algorithmic_lane_ops_per_query": q_ops,
+                                 "issued": issued(VALU_DECIDE if nq == 4_000_000 else None, nq / (ms * 1e-3))}},
             "cpu_oracle": {"value": ns / dt, "unit": "queries/s", "cores": 1,
                            "sample": f"first {ns} queries, C oracle (one-by-one search), {dt:.1f} s"},
             "verified_vs_oracle": ns}
@@ -394,6 +430,8 @@ def main():
                                   "sample": f"first {ns} configurations of the same grid, all detail columns, "
                                             f"C oracle single-threaded, {dt:.1f} s",
                                   "host_cores_visible": os.cpu_count()}
+    # the seeded inputs are generated on the device before anything is timed; what generating them takes
+    result["generators"] = generators
     print(json.dumps(result))
 
 
