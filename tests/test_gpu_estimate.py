@@ -194,6 +194,44 @@ def _full_size_reference():
     return _FULL
 
 
+def test_host_threads_with_their_own_tables_and_streams(U):
+    """Four host threads, each with its own tables (so each makes the library build its own
+    specialized kernel), stream and outputs, calling at the same time: the builds are serialized
+    inside the library, the launches are not, every result equals the oracle's."""
+    import threading
+    rng = np.random.default_rng(61)
+    jobs = []
+    for j, tables in enumerate(([T.gpt_table()], [T.opt_table()], [T.llama_table()],
+                                [T.random_table(rng, 12, 40, "t", n_sizes=6), T.gpt_table()])):
+        cfg = G.random_configs(np.random.default_rng(70 + j), 64 * 20 + 9, n_arch=len(tables))
+        const = T.Constants(m_base=1000 + j)
+        jobs.append((cfg, tables, const, B.estimate(cfg, tables, const, threads=8)))
+    results, errors = [None] * len(jobs), []
+
+    def work(j):
+        try:
+            cfg, tables, const, _ = jobs[j]
+            stream = torch.cuda.Stream()
+            out = []
+            for _ in range(3):
+                with torch.cuda.stream(stream):
+                    out.append(U.hip_estimate(cfg, tables, const, stream=stream, kernel=LANE_SPECIALIZED))
+            results[j] = out
+        except Exception as e:                                  # reported by the main thread
+            errors.append((j, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(j,)) for j in range(len(jobs))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=200)
+    assert not errors, errors
+    for j, (_, _, _, (want_p, want_d)) in enumerate(jobs):
+        for got_p, got_d in results[j]:
+            U.assert_same(f"peaks, thread {j}", got_p, want_p)
+            U.assert_same(f"detail, thread {j}", got_d, want_d)
+
+
 @pytest.mark.parametrize("kernel", (0, LANE_SPECIALIZED))
 def test_full_size_grid4(U, kernel):
     """10^7 configurations, in the launch configurations the benchmark times (the kernel built at
