@@ -17,6 +17,9 @@
  *   HOST  pointer to host memory, read during the call only.
  *   Every call enqueues its kernels on `hip_stream` (a hipStream_t passed as
  *   void*; NULL = the default stream) and returns without synchronising.
+ *   A call only validates on the host and launches kernels, so it may be recorded
+ *   while its stream is capturing into a HIP graph; with LLMEM_KERNEL_LANE_SPECIALIZED
+ *   a call outside the capture must have built the kernel for those tables first.
  *   Return value: LLMEM_OK or a negative error code; on an error nothing has been
  *   enqueued and no output is written.
  */

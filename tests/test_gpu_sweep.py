@@ -153,3 +153,60 @@ def test_full_size_grid4(U):
         method, d, bs = int(cfg["method"][0]), int(cfg["d"][0]), int(cfg["bs"][0])
         assert method * 16 + d - 1 == q and row[A.D_PEAK] <= m_total
         assert A.config_score2(method, bs, d) == score2
+
+
+@pytest.mark.parametrize("kernel", (0, 5))
+def test_calls_recorded_in_a_graph_and_replayed(U, kernel):
+    """The entry points allocate nothing and do not synchronize (the run-time build aside, done by
+    a call before the capture): estimate, decision, sweep reset and sweep recorded into one HIP
+    graph, replayed with new inputs in the same buffers and eager work in between; every replay
+    equals the oracle."""
+    import paper_2404_10933_amd as M
+    n, m_total = 64 * 25 + 7, 70 << 30
+    tables = [T.llama_table()]
+    tab = M.Tables(tables, m_base=CONST.m_base, cu_p=CONST.cu_p, align=CONST.align, kernel=kernel)
+    qtab = M.Tables(tables, m_base=CONST.m_base, cu_p=CONST.cu_p, align=CONST.align)
+    dev, qdev = M.DeviceConfigs.empty(n), M.DeviceConfigs.empty(n)
+    tp = torch.empty(n, dtype=torch.uint8, device="cuda")
+    peaks = torch.empty(n, dtype=torch.int64, device="cuda")
+    det = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
+    rows = torch.empty((M.NDECIDE, n), dtype=torch.int64, device="cuda")
+    stats = torch.empty((M.NSWEEP, M.SWEEP_GROUPS), dtype=torch.int64, device="cuda")
+
+    def calls():
+        M.llmem_estimate_ex(dev, tab, peaks, det)
+        M.llmem_decide(qdev, tp, qtab, m_total, None, None, rows)
+        M.llmem_sweep_reset(stats)
+        M.llmem_sweep(4, 11, 1000, n, tab, m_total, stats)
+
+    def load(first):
+        cfg = G.grid4(n=n, seed=3, first=first)
+        q, q_tp = G.grid6(n=n, seed=3, first=first)
+        for k, v in cfg.items():
+            dev.columns[k].copy_(torch.from_numpy(v).cuda())
+        for k, v in q.items():
+            qdev.columns[k].copy_(torch.from_numpy(v).cuda())
+        tp.copy_(torch.from_numpy(q_tp).cuda())
+        return cfg, q, q_tp
+
+    load(0)
+    calls()                                               # builds the specialized kernels where asked for
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        calls()
+    want_stats = B.sweep(G.grid4(n=n, seed=11, first=1000), 1000, tables, CONST, m_total, threads=8)
+    for rep, first in enumerate((0, 12345, 999_000)):
+        cfg, q, q_tp = load(first)
+        for t in (peaks, det, rows, stats):
+            t.fill_(-3)                                   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want_p, want_d = B.estimate(cfg, tables, CONST, threads=8)
+        U.assert_same(f"peaks, replay {rep}", peaks.cpu().numpy(), want_p)
+        U.assert_same(f"detail, replay {rep}", det.cpu().numpy().T, want_d)
+        U.assert_same(f"decision, replay {rep}", rows.cpu().numpy().T, B.decide(q, q_tp, tables, CONST, m_total, threads=8))
+        U.assert_same(f"sweep, replay {rep}", stats.cpu().numpy(), want_stats)
