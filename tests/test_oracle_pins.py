@@ -55,6 +55,30 @@ def test_worked_example(golden):
     embed_p, lm_p, other_p, t_max, n_params, e_n = O.param_census(gpt, D, False)
     assert (other_p, e_n) == (g["other_p"], 2)
     assert O.param_memory(embed_p, other_p, O.chunk_elems(4), CU_P) == (g["m_p"], g["m_p16"], g["m_p32"])
+    # gradients with a space of their own, and the per-GPU shares of the model states (d = 7: no
+    # page count of the example is a multiple of 7, so every ceiling and block round-up shows)
+    no_alias = G.FLAG_GRAD_ALIAS ^ cfg()["flags"]
+    assert no_alias & G.FLAG_GRAD_ALIAS == 0
+    c0 = est(cfg(flags=no_alias), gpt)
+    assert (c0[O.D_PEAK], c0[O.D_GRAD]) == (g["peak_cdp_noalias"], g["grad_logical_cdp"])
+    assert c0[O.D_PEAK] - r[O.D_PEAK] == g["grad_pages_bytes"]
+    assert r[O.D_GRAD] == g["grad_logical_cdp"]                       # reported also when it shares param fp16's space
+    for method, name in ((1, "zero3"), (2, "tp")):
+        shared = est(cfg(method=method, d=7), gpt)
+        own = est(cfg(method=method, d=7, flags=no_alias), gpt)
+        assert shared[O.D_PEAK] == g[f"peak_{name}_d7"]
+        assert own[O.D_PEAK] == g[f"peak_{name}_d7_noalias"]
+        assert own[O.D_PEAK] - shared[O.D_PEAK] == g["grad_extra_d7"]
+        assert own[O.D_GRAD] == shared[O.D_GRAD] == g["grad_logical_d7"]
+        assert own[O.D_PARAM] == shared[O.D_PARAM] == g[f"param_gpu_{name}_d7"]
+        assert own[O.D_OS] == shared[O.D_OS] == g["os_gpu_d7"]
+        assert est(cfg(method=method, d=3, flags=no_alias), gpt)[O.D_PEAK] == g[f"peak_{name}_d3_noalias"]
+        assert est(cfg(method=method, d=3, flags=no_alias), gpt)[O.D_GRAD] == g["grad_logical_d3"]
+        assert est(cfg(method=method, d=5), gpt)[O.D_OS] == g["os_gpu_d5"]
+        five = est(cfg(method=method, d=5, flags=no_alias), gpt)
+        assert five[O.D_PEAK] - est(cfg(method=method, d=5), gpt)[O.D_PEAK] == g["grad_extra_d5"]
+    assert est(cfg(method=1, d=5, flags=no_alias), gpt)[O.D_PEAK] == g["peak_zero3_d5_noalias"]
+    assert est(cfg(method=1, d=7), gpt)[O.D_PEAK] - g["m_p16"] - g["m_out"] - g["m_lm"] == g["zero3_share_d7"]
 
 
 def _tiny_timeline_table():
@@ -519,6 +543,40 @@ MUTANTS = {
                                                    O.up(O.cdiv(m_p + m_os, d), align))),
     "gradient always separate": ("gradient_terms", lambda method, d, trainable, grad_alias, cu_p, align:
                                  (trainable * 2, O.up(trainable * 2, cu_p))),
+    "gradient shard not block-rounded": ("gradient_terms", lambda method, d, trainable, grad_alias, cu_p, align: (
+        trainable * 2 if method == 0 else O.cdiv(trainable * 2, d),
+        0 if grad_alias else O.up(trainable * 2, cu_p) if method == 0 else O.cdiv(O.up(trainable * 2, cu_p), d))),
+    "gradient divided before page rounding": ("gradient_terms", lambda method, d, trainable, grad_alias, cu_p, align: (
+        trainable * 2 if method == 0 else O.cdiv(trainable * 2, d),
+        0 if grad_alias else O.up(trainable * 2, cu_p) if method == 0 else O.up(O.cdiv(trainable * 2, d), align))),
+    "gradient shard page-rounded": ("gradient_terms", lambda method, d, trainable, grad_alias, cu_p, align: (
+        trainable * 2 if method == 0 else O.cdiv(trainable * 2, d),
+        0 if grad_alias else O.up(trainable * 2, cu_p) if method == 0 else O.up(O.cdiv(O.up(trainable * 2, cu_p), d), cu_p))),
+    "gradient not shared out": ("gradient_terms", lambda method, d, trainable, grad_alias, cu_p, align: (
+        trainable * 2 if method == 0 else O.cdiv(trainable * 2, d), 0 if grad_alias else O.up(trainable * 2, cu_p))),
+    "logical gradient not shared out": ("gradient_terms", lambda method, d, trainable, grad_alias, cu_p, align: (
+        trainable * 2, 0 if grad_alias else O.up(trainable * 2, cu_p) if method == 0
+        else O.up(O.cdiv(O.up(trainable * 2, cu_p), d), align))),
+    "logical gradient page-rounded": ("gradient_terms", lambda method, d, trainable, grad_alias, cu_p, align: (
+        O.up(trainable * 2, cu_p) if method == 0 else O.cdiv(O.up(trainable * 2, cu_p), d),
+        0 if grad_alias else O.up(trainable * 2, cu_p) if method == 0 else O.up(O.cdiv(O.up(trainable * 2, cu_p), d), align))),
+    "os shard not rounded": ("resident_bytes", lambda method, d, m_p, m_p16, m_p32, m_os, align: (
+        (m_p, m_os) if method == 0 else (m_p16 + O.up(O.cdiv(m_p32, d), align), O.cdiv(m_os, d)) if method == 1
+        else (O.up(O.cdiv(m_p, d), align), O.cdiv(m_os, d)))),
+    "os not shared out": ("resident_bytes", lambda method, d, m_p, m_p16, m_p32, m_os, align: (
+        (m_p, m_os) if method == 0 else (m_p16 + O.up(O.cdiv(m_p32, d), align), m_os) if method == 1
+        else (O.up(O.cdiv(m_p, d), align), m_os))),
+    "TP param shard uses m_p16": ("resident_bytes", lambda method, d, m_p, m_p16, m_p32, m_os, align: (
+        (m_p, m_os) if method == 0 else (m_p16 + O.up(O.cdiv(m_p32, d), align), O.up(O.cdiv(m_os, d), align)) if method == 1
+        else (O.up(O.cdiv(m_p16, d), align), O.up(O.cdiv(m_os, d), align)))),
+    "TP param shard not rounded": ("resident_bytes", lambda method, d, m_p, m_p16, m_p32, m_os, align: (
+        (m_p, m_os) if method == 0 else (m_p16 + O.up(O.cdiv(m_p32, d), align), O.up(O.cdiv(m_os, d), align)) if method == 1
+        else (O.cdiv(m_p, d), O.up(O.cdiv(m_os, d), align)))),
+    "ZeRO-3 param shard includes fp16": ("resident_bytes", lambda method, d, m_p, m_p16, m_p32, m_os, align: (
+        (m_p, m_os) if method == 0 else (O.up(O.cdiv(m_p, d), align), O.up(O.cdiv(m_os, d), align)))),
+    "ZeRO-3 param shard not rounded": ("resident_bytes", lambda method, d, m_p, m_p16, m_p32, m_os, align: (
+        (m_p, m_os) if method == 0 else (m_p16 + O.cdiv(m_p32, d), O.up(O.cdiv(m_os, d), align)) if method == 1
+        else (O.up(O.cdiv(m_p, d), align), O.up(O.cdiv(m_os, d), align)))),
     "search prefers large chunks": ("chunk_search", lambda embed_p, other_p, t_max, cu_p: (10, True)),
     "events not rounded": ("event_value", lambda e, D, method, align: 0 if method not in e.methods else
                            e.sign * O.monomial(e.coef, e.dims, D) * e.elem_bytes * (D["L"] if e.times_L else 1)),
