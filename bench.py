@@ -2,17 +2,31 @@
 
 A step is one pass of the whole hot path over the 10^7-configuration Llama-style
 grid with chunk-size search: one llmem_estimate_ex launch producing m_peak and
-all detail columns (component sizes, chosen chunk, timeline peak).  Inputs are
-generated on the device beforehand and stay resident in HBM.  Reported
-under "extra", each timed on its own: the explicit event-list kernel on the
-10^5-list grid, the same grid with the table without gradient checkpointing, the
-streaming sweep (draw, estimate, reduce in one kernel) and the method decision.
+all detail columns (component sizes, chosen chunk, timeline peak), with the
+kernel the library chooses by itself (the specialized kernel built into it for
+the Llama-style table).  Inputs are generated on the device beforehand and stay
+resident in HBM.  Reported under "extra", each timed on its own: the literal
+llmem_estimate call (m_peak only), grids 1 to 3, the same workload through the
+other kernel forms, the explicit event-list kernel on the 10^5-list grid, the
+table without gradient checkpointing, the streaming sweep and the method decision.
 
-Prints ONE JSON line.
+Roofline fractions of the integer-bound kernels are the share of the vector issue
+slots the kernel fills: vector instructions per configuration as the hardware
+counters gave them (profiles/counters.json, valid only while the kernel sources
+are the ones that were profiled) times the measured rate, over the nominal issue
+rate.  Next to it, "census": the operations of the method itself in its leanest
+form, counted on the oracle's side from the tables alone, over the same time.
+
+Prints ONE JSON line.  `--import-counters DIR` (no GPU needed) instead turns the
+rocprofv3 counter files under DIR into profiles/counters.json.
 """
 import argparse
+import collections
+import csv
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -23,87 +37,116 @@ if ROOT not in sys.path:
 # MI355X nominal peaks used for the roofline fractions
 PEAK_LANE_TOPS = 256 * 64 * 2.4e9 / 1e12       # 256 CUs x one 64-lane vector instruction per clock x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs under profiles/, scaled by the
-# plain-copy reference; None while the kernel has changed since the counters were taken
-TRAFFIC_ESTIMATE = 1.3691e9     # 10^7 configurations, all detail columns, built-in compiled form (incl. 8 B/lane of spill scratch)
-TRAFFIC_SPECIALIZED = 1.3503e9  # the same workload, kernel built at run time
-TRAFFIC_SWEEP = 5.0558e7        # 10^7 configurations drawn and reduced in the kernel built at run time
-TRAFFIC_TIMELINE = 8.0182e9     # 100 000 event lists, 1 000 110 810 events
-TRAFFIC_DECIDE = 5.4027e8       # 4 000 000 queries, all decision columns (the search inside the kernel does not touch memory)
-# Vector instructions issued per wave of 64 units (SQ_INSTS_VALU of the same runs), i.e. per unit and lane;
-# with them `issued` = the share of the nominal vector issue slots the kernel fills, whatever the census says
-VALU_ESTIMATE = 1815            # built-in compiled form, per configuration
-VALU_SPECIALIZED = 1332         # kernel built at run time
-VALU_SWEEP = 1483
-VALU_DECIDE = 938.6             # per query
+
+COUNTERS_FILE = os.path.join(ROOT, "profiles", "counters.json")
+CSRC = os.path.join("paper_2404_10933_amd", "csrc")
+LANE_SOURCES = [os.path.join(CSRC, f) for f in ("estimate_batch.hip", "estimate_args.h", "wave.h", "grid_draws.h")] \
+    + [os.path.join("include", "llmem.h"), os.path.join("workloads", "tables.py")]
+# key -> (substring of the kernel's name, work-items of a launch over the whole workload: at least, below,
+#         units per launch, sources the kernel is compiled from)
+PROFILED = {
+    "g4_detail": ("llmem_aot_llama_detail", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
+    "g4_peaks": ("llmem_aot_llama_peaks", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
+    "g4_sweep": ("llmem_aot_llama_sweep", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
+    "g4_full_traversal": ("llmem_aot_llama_full_detail", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
+    "g4_compiled": ("estimate_batch_kernel<true, true, false>", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
+    "g3_detail": ("llmem_aot_llama_detail", 500_000, 2_000_000, 1_000_000, LANE_SOURCES),
+    "g2_detail": ("llmem_aot_opt_detail", 50_000, 500_000, 100_000, LANE_SOURCES),
+    "g5_lists": ("timeline_kernel", 0, 1 << 62, 100_000, [os.path.join(CSRC, "timeline.hip"), os.path.join(CSRC, "wave.h")]),
+    "g6_decide": ("decide_kernel<true>", 0, 1 << 62, 4_000_000,
+                  [os.path.join(CSRC, "decide.hip"), os.path.join(CSRC, "estimate_args.h"), os.path.join(CSRC, "wave.h")]),
+}
 
 
-def issued(valu_per_unit, units_per_s):
-    """Vector lane-instructions issued per second against the nominal issue rate (None: no counter for this kernel)."""
-    if valu_per_unit is None:
+def source_checksum(paths):
+    """Checksum of the kernel sources as the compiler sees them: comments and white space do not count."""
+    h = hashlib.sha256()
+    for p in paths:
+        text = open(os.path.join(ROOT, p)).read()
+        if p.endswith(".py"):
+            text = re.sub(r"#[^\n]*", "", text)
+        else:
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            text = re.sub(r"//[^\n]*", "", text)
+        h.update(re.sub(r"\s+", " ", text).encode())
+    return h.hexdigest()[:16]
+
+
+def counters_for(key, units):
+    """The profiled counters of a kernel, or None when the sources have changed since or the workload differs."""
+    try:
+        entry = json.load(open(COUNTERS_FILE))["kernels"][key]
+    except (OSError, KeyError, ValueError):
         return None
-    rate = valu_per_unit * units_per_s / 1e12
-    return {"valu_per_unit": valu_per_unit, "achieved": rate, "frac": rate / PEAK_LANE_TOPS}
+    if entry["units"] != units or entry["checksum"] != source_checksum(PROFILED[key][4]):
+        return None
+    return entry
 
 
-def algorithmic_lane_ops(forms, n_candidates):
-    """Integer work of one configuration in 64-bit lane operations of the method itself, in its
-    leanest known form (equal size expressions evaluated once, the L equal blocks collapsed, the
-    timeline reduced to the peak points no other point dominates), priced in gfx950 vector
-    instructions: add/sub 1, 32x32->64 multiply 1, multiply of a 64-bit value by a 32-bit one 3,
-    round up to a power of two 3, compare-and-select (max) 3, ceil-divide by d 12.
-    `forms` = llmem_kernel_forms of the tables."""
-    ADD, MUL32, MUL, UP, MAX, DIV = 1, 1, 3, 3, 3, 12
-    per_group = MUL32 + MUL + (MUL32 + MUL + ADD) + (ADD + UP + MUL32 + MUL + ADD) + MAX   # expression, role sum, m_os, t_max
-    per_class = MUL32 + 2 * MUL + UP + ADD                                                 # expression, block round-up, store
-    per_term = MUL + ADD
-    per_point = MAX
-    fixed = (2 * MUL + MUL + UP) + (2 * MUL + 2 * (MUL + UP) + 3 * ADD) + (3 * MUL + UP + DIV) + 2 * MUL + DIV
-    per_candidate = 2 * ADD + 3 * (MUL + UP) + DIV + UP + 5 * ADD + 2 * MAX
-    tail = 2 * (DIV + UP) + 5 * (MUL + MAX + 2 * ADD) + 4 * ADD
-    return (forms["param_groups"] * per_group + forms["size_classes"] * per_class + forms["terms"] * per_term
-            + forms["peak_points"] * per_point + fixed + n_candidates * per_candidate + tail)
+def import_counters(folder):
+    """profiles/counters.json from rocprofv3 --pmc runs of this file under `folder`: sub-folders
+    pmc_sq, pmc_fetch, pmc_write (this benchmark) and copy_fetch, copy_write (--calibrate-copy),
+    each holding *_counter_collection.csv."""
+    def read(sub, want, lo=0, hi=1 << 62):
+        agg = collections.defaultdict(list)
+        names = [f for f in os.listdir(os.path.join(folder, sub)) if f.endswith("counter_collection.csv")]
+        for r in csv.DictReader(open(os.path.join(folder, sub, names[0]))):
+            if want in r["Kernel_Name"] and lo <= int(r["Grid_Size"]) < hi:
+                agg[r["Counter_Name"]].append(float(r["Counter_Value"]))
+        return {k: sum(v) / len(v) for k, v in agg.items()}
+
+    copy_fetch = read("copy_fetch", "copyBuffer")["FETCH_SIZE"]
+    copy_write = read("copy_write", "copyBuffer")["WRITE_SIZE"]
+    scale_f, scale_w = (1 << 20) / copy_fetch, (1 << 20) / copy_write        # a 1 GiB copy reads and writes 2^20 KiB
+    out = {"note": "written by `python bench.py --import-counters DIR` from rocprofv3 --pmc runs of bench.py; "
+                   "per launch over the whole workload; a kernel's entry is used only while `checksum` equals "
+                   "the checksum of its sources (comments and white space aside)",
+           "copy_reference": {"fetch_kib_per_gib_copied": copy_fetch, "write_kib_per_gib_copied": copy_write,
+                              "fetch_scale": scale_f, "write_scale": scale_w},
+           "kernels": {}}
+    for key, (want, lo, hi, units, sources) in PROFILED.items():
+        sq = read("pmc_sq", want, lo, hi)
+        f = read("pmc_fetch", want, lo, hi).get("FETCH_SIZE")
+        w = read("pmc_write", want, lo, hi).get("WRITE_SIZE")
+        if not sq or f is None or w is None:
+            print(f"{key}: not in the counter files, left out", file=sys.stderr)
+            continue
+        out["kernels"][key] = {
+            "kernel": want, "units": units, "checksum": source_checksum(sources),
+            "valu_per_unit": sq["SQ_INSTS_VALU"] * 64 / units, "salu_per_64_units": sq.get("SQ_INSTS_SALU", 0) * 64 / units,
+            "lds_per_64_units": sq.get("SQ_INSTS_LDS", 0) * 64 / units,
+            "valu_per_cu_clock": sq["SQ_INSTS_VALU"] / sq["SQ_BUSY_CU_CYCLES"] if sq.get("SQ_BUSY_CU_CYCLES") else None,
+            "fetch_kib": f, "write_kib": w, "traffic_bytes": (f * scale_f + w * scale_w) * 1024}
+    with open(COUNTERS_FILE, "w") as fh:
+        json.dump(out, fh, indent=1, sort_keys=True)
+        fh.write("\n")
+    print(f"{COUNTERS_FILE}: {sorted(out['kernels'])}")
 
 
-def algorithmic_lane_ops_decide(n_param_groups, probes):
-    """The method decision of one query in the same units, leanest known form: parameter census
-    by groups of equal size expression, the chunk size in closed form (the smallest feasible
-    candidate is the one with the least waste), the batch-independent parts of the four estimates,
-    the per-page constants of the batch-dependent terms, then per method the bracket of the largest
-    batch size in single precision (one reciprocal, two products, conversions and clamps) and
-    `probes` estimates of the batch-dependent terms counted in 32-bit pages (one to check the
-    bracket's lower end, the rest bisecting the bracket), scores, choice and the chosen estimate."""
-    ADD, MUL32, MUL, UP, MAX, DIV, DIV32 = 1, 1, 3, 3, 3, 12, 5
-    per_group = MUL32 + MUL + (MUL32 + MUL + ADD) + (ADD + UP + MUL32 + MUL + ADD) + MAX
-    chunk = MAX + 3 * ADD                                        # bit length of t_max, clamp to 2..10
-    fixed = 3 * (MUL + UP) + 2 * (DIV + UP) + 2 * (MUL + DIV + UP) + 12 * ADD + 5 * MUL + 10 * ADD
-    bracket = 18                                                 # room in pages, growth, quotient, two clamped ends
-    probe_plain = MUL32 + 3 * (MUL32 + ADD) + 4 * ADD + MAX      # shared whole pages; three remainders; compare, keep
-    probe_gather = probe_plain + 2 * MUL32 + 2 * ADD + DIV32 + ADD   # plus the all-gather buffer, divided by t
-    tail = 4 * MUL32 + 3 * MAX + probe_gather + UP + 4 * ADD
-    return (n_param_groups * per_group + chunk + fixed + 4 * bracket
-            + probes * (2 * probe_plain + 2 * probe_gather) + tail)
+def alu_roofline(key, units, ms, kernel_name, census_ops=None):
+    """Roofline object of an integer-bound kernel: issue-slot share from the counters, census beside it."""
+    c = counters_for(key, units) if key in PROFILED else None
+    rate = units / (ms * 1e-3)
+    out = {"bound": "alu", "achieved": None, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s", "frac": None,
+           "basis": "vector instructions issued per unit (hardware counter) x units per second; null: no counters "
+                    "for this kernel and workload, or its sources have changed since those in profiles/counters.json "
+                    "were taken",
+           "traffic": None, "kernel": kernel_name, "kernel_ms": ms}
+    if c is not None:
+        out.update(achieved=c["valu_per_unit"] * rate / 1e12, frac=c["valu_per_unit"] * rate / 1e12 / PEAK_LANE_TOPS,
+                   traffic=c["traffic_bytes"], valu_per_unit=c["valu_per_unit"])
+    if census_ops is not None:
+        out["census"] = {"lane_ops_per_unit": census_ops, "achieved": census_ops * rate / 1e12,
+                         "frac": census_ops * rate / 1e12 / PEAK_LANE_TOPS,
+                         "basis": "operations of the method in its leanest form, counted from the tables by oracle/census.py"}
+    return out
 
 
-def algorithmic_lane_ops_sweep_extra():
-    """What the streaming sweep adds per configuration of grid 4, same units: eight counter-based
-    draws (the part of the hash input that all fields share, once; per draw one add and the
-    splitmix64 finaliser: two 64 x 64-bit multiplies at 4 (two 32-bit products, one 32 x 32 -> 64
-    multiply-add, one add), three xor-shifts at 2; then a remainder, priced like a division, 12, by
-    a constant that is no power of two, else 1, and the offset), the SwiGLU width, the value
-    selections, the score and the eight statistics."""
-    ADD, MUL64, XORSHIFT, REM, DIV = 1, 4, 2, 12, 12
-    draw = ADD + 3 * XORSHIFT + 2 * MUL64
-    draws = 8 * draw + 4 * (REM + ADD) + 4 * (1 + ADD) + (MUL64 + 2 * ADD)
-    shape = (DIV + 3 * ADD) + 10                  # ffn = 8h/3 rounded up to 256; table look-ups as selects
-    fold = 3 + 2 + 8 + 4                          # score, packed best entry, eight statistics, group and test
-    return draws + shape + fold
-
-
-def timed_ms(fn, reps=3):
-    """Mean duration of fn() in ms by HIP events on the current stream, after one untimed call."""
+def timed_ms(fn, reps=10, warm=2):
+    """Mean duration of fn() in ms by HIP events on the current stream, after untimed calls."""
     import torch
-    fn()
+    for _ in range(warm):
+        fn()
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
@@ -127,14 +170,21 @@ def main():
     ap.add_argument("--sweep", type=int, default=10_000_000,
                     help="configurations of the streaming sweep (drawn, estimated and reduced in one kernel; 0: skip)")
     ap.add_argument("--queries", type=int, default=4_000_000, help="queries of the method-decision grid (0: skip)")
+    ap.add_argument("--grids", type=int, default=1, help="also time grids 1 to 3 and the m_peak-only call (0: skip)")
+    ap.add_argument("--forms", type=int, default=1, help="also time the other kernel forms on the headline workload (0: skip)")
     ap.add_argument("--cpu-sample", type=int, default=600_000, help="configurations the CPU oracle is timed on (0: skip)")
-    ap.add_argument("--kernel", choices=("specialized", "auto", "wave", "lane"), default="specialized",
-                    help="estimator kernel: the lane kernel built at run time with the tables as constants (built "
-                         "during warm-up, build time reported), the library's own choice among the built-in forms, "
-                         "one wavefront or one lane per configuration")
+    ap.add_argument("--kernel", choices=("auto", "compiled", "runtime", "wave", "events"), default="auto",
+                    help="estimator kernel of the headline: the library's own choice (the specialized kernel built into "
+                         "it for the shipped tables), the lane kernel that reads the compiled tables from its arguments, "
+                         "the specialized kernel built at run time (before the warm-up, build time reported), one "
+                         "wavefront per configuration, one lane per configuration walking every event")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy ten times (reference for the HBM byte counters)")
+    ap.add_argument("--import-counters", metavar="DIR", help="write profiles/counters.json from rocprofv3 output (no GPU)")
     args = ap.parse_args()
+    if args.import_counters:
+        import_counters(args.import_counters)
+        return
     if args.gpus != 1:
         print("bench.py: the library runs on one GPU; nothing is sharded and there are no collectives "
               "(--gpus must be 1)", file=sys.stderr)
@@ -156,29 +206,36 @@ def main():
         print(json.dumps({"calibrate_copy": {"bytes_read": src.numel() * 8, "bytes_written": src.numel() * 8,
                                              "launches": 10}}))
         return
+    # the oracle: checks of what is timed, the operation census, and the CPU baseline at the end
+    from oracle import census as C
+    from oracle import oracle_c as B
+
     const = T.Constants(m_base=256 << 20)
     table = T.llama_table()
     n = args.n
     dev = M.DeviceConfigs.empty(n)
-    generators = {"grid4_ms": timed_ms(lambda: M.llmem_grid_generate(4, 0, 0, n, dev)), "grid4_configs": n}
-    kernel = {"auto": 0, "wave": 1, "lane": 2, "specialized": 5}[args.kernel]
-    tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=kernel)
+    generators = {"grid4_ms": timed_ms(lambda: M.llmem_grid_generate(4, 0, 0, n, dev), 3, 1), "grid4_configs": n}
+    kernel = {"auto": 0, "wave": 1, "events": 3, "compiled": 4, "runtime": 6}[args.kernel]
+
+    def tables_of(tabs, k=0, m_base=const.m_base):
+        return M.Tables(tabs, m_base=m_base, cu_p=const.cu_p, align=const.align, kernel=k)
+
+    tab = tables_of([table], kernel)
+    forms = M.llmem_kernel_forms(tab)
     peaks = torch.empty(n, dtype=torch.int64, device="cuda")
     detail = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
     torch.cuda.synchronize()
-    build_s, kernel_note = None, args.kernel
-    if args.kernel == "specialized":
+    kernel_note = {"auto": "auto: the specialized kernel built into the library for this table"
+                           if forms["prebuilt"][1] else "auto: no built-in specialization matches, compiled form",
+                   "compiled": "compiled tables read from the kernel arguments", "wave": "one wavefront per configuration",
+                   "events": "one lane per configuration, every event walked"}.get(args.kernel)
+    if args.kernel == "runtime":
         # the first call builds and loads the kernel for these tables; not part of the timed steps
         t0 = time.perf_counter()
-        try:
-            M.llmem_estimate_ex(dev, tab, peaks, detail, n=64)
-            torch.cuda.synchronize()
-            build_s = time.perf_counter() - t0
-            kernel_note = (f"specialized (built at run time, or loaded from LLMEM_KERNEL_CACHE, before the warm-up: "
-                           f"{build_s:.2f} s)")
-        except M.LlmemError as e:
-            kernel, kernel_note = 0, f"auto (the run-time build failed: {e})"
-            tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=0)
+        M.llmem_estimate_ex(dev, tab, peaks, detail, n=64)
+        torch.cuda.synchronize()
+        kernel_note = (f"specialized kernel built at run time, or loaded from LLMEM_KERNEL_CACHE, before the warm-up: "
+                       f"{time.perf_counter() - t0:.2f} s")
 
     for _ in range(args.warmup):
         M.llmem_estimate_ex(dev, tab, peaks, detail)
@@ -196,11 +253,17 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     value = n / (ms_per_step * 1e-3)
 
-    forms = M.llmem_kernel_forms(tab)
-    ops = algorithmic_lane_ops(forms, 9)
-    achieved = ops * n / (kernel_ms * 1e-3) / 1e12
-    kernel_name = {1: "estimate_kernel<true>", 5: "llmem_specialized_detail"}.get(kernel, "estimate_batch_kernel<true, true, false>")
+    census = C.estimate_census(table, 9)
+    assert {k: census[k] for k in ("param_groups", "size_classes", "terms", "peak_points")} \
+        == {k: forms[k] for k in ("param_groups", "size_classes", "terms", "peak_points")}
+    headline_key = {"auto": "g4_detail", "compiled": "g4_compiled"}.get(args.kernel, "none")
+    kernel_name = {"auto": "llmem_aot_llama_detail" if forms["prebuilt"][1] else "estimate_batch_kernel<true, true, false>",
+                   "compiled": "estimate_batch_kernel<true, true, false>", "runtime": "llmem_specialized_detail",
+                   "wave": "estimate_kernel<true>", "events": "estimate_batch_kernel<true, false, false>"}[args.kernel]
     bytes_per_cfg = M.llmem_config_bytes(1) + 8 + 8 * M.NDETAIL
+    roofline = alu_roofline(headline_key, n, kernel_ms, kernel_name, census["lane_ops"])
+    roofline["census"]["ops_by_kind"] = census["ops"]
+    roofline["hbm_gbs_algorithmic"] = bytes_per_cfg * n / (kernel_ms * 1e-3) / 1e9
     result = {
         "metric": "configs estimated/sec (bit-exact vs oracle)",
         "value": value, "unit": "configs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -211,49 +274,83 @@ def main():
                    "n_configs": n, "table_params": len(table.params), "table_events": len(table.events),
                    "table_size_classes": forms["size_classes"], "table_peak_points": forms["peak_points"],
                    "table_terms": forms["terms"], "kernel": kernel_note, "seed": 0},
-        "roofline": {"bound": "alu", "achieved": achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
-                     "frac": achieved / PEAK_LANE_TOPS,
-                     "traffic": ({0: TRAFFIC_ESTIMATE, 5: TRAFFIC_SPECIALIZED}.get(kernel) if n == 10_000_000 else None),
-                     "kernel": kernel_name, "kernel_ms": kernel_ms,
-                     "algorithmic_lane_ops_per_config": ops,
-                     "issued": issued({0: VALU_ESTIMATE, 5: VALU_SPECIALIZED}.get(kernel) if n == 10_000_000 else None,
-                                      n / (kernel_ms * 1e-3)),
-                     "hbm_gbs_algorithmic": bytes_per_cfg * n / (kernel_ms * 1e-3) / 1e9},
+        "roofline": roofline,
     }
+    extra = result.setdefault("extra", {})
 
     # sanity: the benchmark's own output on a slice equals the oracle (not timed)
-    from oracle import oracle_c as B
     idx = np.arange(0, min(n, 4096))
     want_p, want_d = B.estimate(G.grid4(n=len(idx), seed=0), [table], const, threads=4)
-    assert (peaks[:len(idx)].cpu().numpy() == want_p).all() and \
-        (detail[:, :len(idx)].cpu().numpy().T == want_d).all(), "bench output differs from the oracle"
+
+    def same_as_oracle():
+        return bool((peaks[:len(idx)].cpu().numpy() == want_p).all()
+                    and (detail.view(-1)[:M.NDETAIL * n].view(M.NDETAIL, n)[:, :len(idx)].cpu().numpy().T == want_d).all())
+
+    assert same_as_oracle(), "bench output differs from the oracle"
     result["verified_vs_oracle"] = int(len(idx))
 
-    if kernel == 5:
-        itab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=0)
-        for _ in range(2):
-            M.llmem_estimate_ex(dev, itab, peaks, detail)
-        torch.cuda.synchronize()
-        reps = 10
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            M.llmem_estimate_ex(dev, itab, peaks, detail)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        i_achieved = ops * n / (ms * 1e-3) / 1e12
-        assert (peaks[:len(idx)].cpu().numpy() == want_p).all() and \
-            (detail[:, :len(idx)].cpu().numpy().T == want_d).all(), "built-in kernel's output differs from the oracle"
-        result.setdefault("extra", {})["g4_built_in_kernel"] = {
-            "workload": "the headline workload with the built-in compiled form (tables read from the kernel arguments)",
+    if args.grids:
+        # the plain entry point: m_peak only, on the default stream (which is torch's current one here)
+        assert torch.cuda.current_stream().cuda_stream == 0
+        peaks.fill_(-7)
+        ptab = tables_of([table])
+        ms = timed_ms(lambda: M.llmem_estimate(dev, ptab, peaks))
+        assert (peaks[:len(idx)].cpu().numpy() == want_p).all(), "llmem_estimate differs from the oracle"
+        extra["g4_peaks_only"] = {
+            "workload": "llmem_estimate(configs, n, method_tables, out_peaks): g4, m_peak only (39 B per configuration; "
+                        "no timeline walk: peak_live is a detail column)",
             "n_configs": n, "ms_per_launch": ms, "configs_per_s": n / (ms * 1e-3),
-            "roofline": {"bound": "alu", "achieved": i_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
-                         "frac": i_achieved / PEAK_LANE_TOPS, "traffic": TRAFFIC_ESTIMATE if n == 10_000_000 else None,
-                         "kernel": "estimate_batch_kernel<true, true, false>", "algorithmic_lane_ops_per_config": ops,
-                         "issued": issued(VALU_ESTIMATE if n == 10_000_000 else None, n / (ms * 1e-3))},
-            "verified_vs_oracle": int(len(idx))}
+            "hbm_gbs_algorithmic": (M.llmem_config_bytes(1) + 8) * n / (ms * 1e-3) / 1e9,
+            "roofline": alu_roofline("g4_peaks", n, ms, "llmem_aot_llama_peaks"), "verified_vs_oracle": int(len(idx))}
+        for name, make, family, n_grid in (("g1", G.grid1, "gpt", 432), ("g2", G.grid2, "opt", 100_000),
+                                           ("g3", G.grid3, "llama", 1_000_000)):
+            gtab_py = T.FAMILIES[family]()
+            gtab = tables_of([gtab_py])
+            gdev = M.DeviceConfigs.empty(n_grid)
+            M.llmem_grid_generate(int(name[1]), 0, 0, n_grid, gdev)
+            gp = torch.empty(n_grid, dtype=torch.int64, device="cuda")
+            gd = torch.empty((M.NDETAIL, n_grid), dtype=torch.int64, device="cuda")
+            ms = timed_ms(lambda: M.llmem_estimate_ex(gdev, gtab, gp, gd), 20, 3)
+            ns = min(n_grid, 4096)
+            gcfg = make() if name == "g1" else make(n=ns, seed=0)
+            wp, wd = B.estimate(gcfg, [gtab_py], const, threads=4)
+            assert (gp[:ns].cpu().numpy() == wp).all() and (gd[:, :ns].cpu().numpy().T == wd).all(), name
+            gcensus = C.estimate_census(gtab_py, 1)              # the chunk size is given in grids 1 to 3
+            t1 = time.perf_counter()
+            B.estimate(gcfg, [gtab_py], const, timeline=True, threads=1)
+            dt = time.perf_counter() - t1
+            extra[name] = {
+                "workload": {"g1": "g1: tiny Cartesian grid, GPT-style table, all detail columns (a latency: two workgroups)",
+                             "g2": "g2: 10^5 OPT-style configurations, all detail columns",
+                             "g3": "g3: 10^6 Llama-style configurations, all detail columns"}[name],
+                "n_configs": n_grid, "ms_per_launch": ms, "configs_per_s": n_grid / (ms * 1e-3),
+                "roofline": alu_roofline(name + "_detail", n_grid, ms, f"llmem_aot_{family}_detail", gcensus["lane_ops"]),
+                "cpu_oracle": {"value": ns / dt, "unit": "configs/s", "cores": 1, "sample": f"first {ns} configurations, {dt:.2f} s"},
+                "verified_vs_oracle": ns}
+            del gdev, gp, gd
+
+    if args.forms and args.kernel == "auto":
+        for name, k, key, kname in (("g4_compiled_form", 4, "g4_compiled", "estimate_batch_kernel<true, true, false>"),
+                                    ("g4_built_at_run_time", 6, "none", "llmem_specialized_detail")):
+            ftab = tables_of([table], k)
+            t1 = time.perf_counter()
+            try:
+                M.llmem_estimate_ex(dev, ftab, peaks, detail, n=64)
+                torch.cuda.synchronize()
+            except M.LlmemError as e:                          # e.g. the run-time compiler inside a profiled process
+                extra[name] = {"skipped": str(e)}
+                continue
+            first_call_s = time.perf_counter() - t1
+            peaks.fill_(-7)
+            ms = timed_ms(lambda: M.llmem_estimate_ex(dev, ftab, peaks, detail))
+            assert same_as_oracle(), name
+            extra[name] = {
+                "workload": {4: "the headline workload with the lane kernel that reads the compiled tables from its arguments "
+                                "(what tables without a built-in specialization get from LLMEM_KERNEL_AUTO)",
+                             6: "the headline workload with the specialized kernel built at run time (hiprtc; "
+                                "LLMEM_KERNEL_LANE_RUNTIME), first call incl. the build reported"}[k],
+                "n_configs": n, "ms_per_launch": ms, "configs_per_s": n / (ms * 1e-3), "first_call_s": first_call_s,
+                "roofline": alu_roofline(key, n, ms, kname, census["lane_ops"]), "verified_vs_oracle": int(len(idx))}
 
     if args.lists > 0:
         nl = args.lists
@@ -263,30 +360,20 @@ def main():
         offsets[1:] = torch.cumsum(counts, 0)
         total = int(offsets[-1].item())
         events = torch.empty(total, dtype=torch.int64, device="cuda")
-        generators["event_lists_ms"] = timed_ms(lambda: M.llmem_events_generate(0, 0, nl, offsets, events))
+        generators["event_lists_ms"] = timed_ms(lambda: M.llmem_events_generate(0, 0, nl, offsets, events), 3, 1)
         generators["event_lists"] = nl
         oa = torch.empty(nl, dtype=torch.int64, device="cuda")
         orv = torch.empty(nl, dtype=torch.int64, device="cuda")
-        for _ in range(2):
-            M.llmem_timeline_peaks(events, offsets, oa, orv)
-        torch.cuda.synchronize()
-        reps = 10
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            M.llmem_timeline_peaks(events, offsets, oa, orv)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
+        ms = timed_ms(lambda: M.llmem_timeline_peaks(events, offsets, oa, orv))
         nbytes = 8 * total + 8 * (nl + 1) + 16 * nl
         gbs = nbytes / (ms * 1e-3) / 1e9
-        result.setdefault("extra", {})["g5_event_lists"] = {
+        c = counters_for("g5_lists", nl)
+        extra["g5_event_lists"] = {
             "workload": "g5: explicit allocator event lists (~10^4 events each)", "n_lists": nl,
             "n_events": total, "ms_per_launch": ms, "lists_per_s": nl / (ms * 1e-3),
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_TIMELINE if nl == 100_000 else None,
-                         "kernel": "timeline_kernel"}}
+                         "frac": gbs / PEAK_HBM_GBS, "traffic": c["traffic_bytes"] if c else None,
+                         "algorithmic_bytes": nbytes, "kernel": "timeline_kernel"}}
         from workloads import events as E
         ev_c, off_c = E.generate(64, seed=0, first=0)
         wa, wr = B.event_lists_peaks(ev_c, off_c)
@@ -295,79 +382,51 @@ def main():
 
     if args.full_traversal > 0:
         nf = min(args.full_traversal, n)
-        ftab = M.Tables([T.llama_table(checkpoint=False)], m_base=const.m_base + (64 << 20), cu_p=const.cu_p,
-                        align=const.align, kernel=kernel)
-        for _ in range(2):
-            M.llmem_estimate_ex(dev, ftab, peaks, detail, n=nf)
-        torch.cuda.synchronize()
-        reps = 10
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            M.llmem_estimate_ex(dev, ftab, peaks, detail, n=nf)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
+        full = T.llama_table(checkpoint=False)
+        ftab = tables_of([full], kernel, const.m_base + (64 << 20))
+        ms = timed_ms(lambda: M.llmem_estimate_ex(dev, ftab, peaks, detail, n=nf))
         fforms = M.llmem_kernel_forms(ftab)
-        f_ops = algorithmic_lane_ops(fforms, 9)
-        f_achieved = f_ops * nf / (ms * 1e-3) / 1e12
         ns = min(4096, nf)
         fconst = T.Constants(m_base=const.m_base + (64 << 20), cu_p=const.cu_p, align=const.align)
-        want_p, want_d = B.estimate(G.grid4(n=ns, seed=0), [T.llama_table(checkpoint=False)], fconst, threads=4)
-        assert (peaks[:ns].cpu().numpy() == want_p).all() and (detail.view(-1)[:M.NDETAIL * nf].view(M.NDETAIL, nf)[:, :ns]
-                                                                .cpu().numpy().T == want_d).all(), \
+        wp, wd = B.estimate(G.grid4(n=ns, seed=0), [full], fconst, threads=4)
+        assert (peaks[:ns].cpu().numpy() == wp).all() and (detail.view(-1)[:M.NDETAIL * nf].view(M.NDETAIL, nf)[:, :ns]
+                                                            .cpu().numpy().T == wd).all(), \
             "full-traversal output differs from the oracle"
-        result.setdefault("extra", {})["g4_full_traversal"] = {
+        extra["g4_full_traversal"] = {
             "workload": "g4 with the Llama table without gradient checkpointing (every saved forward output alive "
                         "until its backward), 64 MiB allocator buffer added to m_base; all detail columns",
             "n_configs": nf, "ms_per_launch": ms, "configs_per_s": nf / (ms * 1e-3),
-            "table_events": len(T.llama_table(checkpoint=False).events), "table_terms": fforms["terms"],
-            "table_peak_points": fforms["peak_points"],
-            "roofline": {"bound": "alu", "achieved": f_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
-                         "frac": f_achieved / PEAK_LANE_TOPS, "traffic": None, "kernel": kernel_name,
-                         "algorithmic_lane_ops_per_config": f_ops},
+            "table_events": len(full.events), "table_terms": fforms["terms"], "table_peak_points": fforms["peak_points"],
+            "roofline": alu_roofline("g4_full_traversal" if kernel == 0 else "none", nf, ms,
+                                     "llmem_aot_llama_full_detail" if kernel == 0 else kernel_name,
+                                     C.estimate_census(full, 9)["lane_ops"]),
             "verified_vs_oracle": ns}
 
     if args.sweep > 0:
         nsw, m_total = args.sweep, 64 << 30
         stats = torch.empty((M.NSWEEP, M.SWEEP_GROUPS), dtype=torch.int64, device="cuda")
-        if kernel == 1:        # the sweep is a mode of the lane kernel: with --kernel wave the library chooses its form
-            tab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align, kernel=0)
-        for _ in range(2):
+        stab = tables_of([table], 0 if kernel in (1, 3) else kernel)        # the sweep is a mode of the lane kernel
+
+        def reset_and_sweep():
             M.llmem_sweep_reset(stats)
-            M.llmem_sweep(4, 0, 0, nsw, tab, m_total, stats)
-        torch.cuda.synchronize()
-        reps = 10
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            M.llmem_sweep_reset(stats)
-            M.llmem_sweep(4, 0, 0, nsw, tab, m_total, stats)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        s_ops = ops + algorithmic_lane_ops_sweep_extra()
-        s_achieved = s_ops * nsw / (ms * 1e-3) / 1e12
+            M.llmem_sweep(4, 0, 0, nsw, stab, m_total, stats)
+
+        ms = timed_ms(reset_and_sweep)
         ns = min(100_000, nsw)
         head = torch.empty_like(stats)
         M.llmem_sweep_reset(head)
-        M.llmem_sweep(4, 0, 0, ns, tab, m_total, head)
+        M.llmem_sweep(4, 0, 0, ns, stab, m_total, head)
         want = B.sweep(G.grid4(n=ns, seed=0), 0, [table], const, m_total, threads=4)
         assert (head.cpu().numpy() == want).all(), "sweep statistics differ from the oracle"
         assert int(stats[0].sum().item()) == nsw
-        result.setdefault("extra", {})["g4_streaming_sweep"] = {
+        extra["g4_streaming_sweep"] = {
             "workload": "g4 drawn in registers, estimated (all of the hot path) and folded into 8 statistics per "
                         "(method, gpu_n) against m_total 64 GiB; nothing per configuration touches HBM; reset + sweep",
             "n_configs": nsw, "ms_per_launch": ms, "configs_per_s": nsw / (ms * 1e-3),
             "configs_fitting": int(stats[1].sum().item()),
-            "roofline": {"bound": "alu", "achieved": s_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
-                         "frac": s_achieved / PEAK_LANE_TOPS,
-                         "traffic": TRAFFIC_SWEEP if (kernel == 5 and nsw == 10_000_000) else None,
-                         "kernel": "llmem_specialized_sweep" if kernel == 5 else "estimate_batch_kernel<true, true, true>",
-                         "algorithmic_lane_ops_per_config": s_ops,
-                         "issued": issued(VALU_SWEEP if (kernel == 5 and nsw == 10_000_000) else None, nsw / (ms * 1e-3))},
+            "roofline": alu_roofline("g4_sweep" if kernel == 0 else "none", nsw, ms,
+                                     "llmem_aot_llama_sweep" if kernel == 0 else "lane kernel, sweep mode",
+                                     census["lane_ops"] + C.sweep_extra_census()["lane_ops"]),
             "verified_vs_oracle": ns}
 
     if args.queries > 0:
@@ -375,27 +434,16 @@ def main():
         del peaks, detail
         qdev = M.DeviceConfigs.empty(nq)
         tp = torch.empty(nq, dtype=torch.uint8, device="cuda")
-        generators["queries_ms"] = timed_ms(lambda: M.llmem_queries_generate(0, 0, nq, qdev, tp))
+        generators["queries_ms"] = timed_ms(lambda: M.llmem_queries_generate(0, 0, nq, qdev, tp), 3, 1)
         generators["queries"] = nq
-        qtab = M.Tables([table], m_base=const.m_base, cu_p=const.cu_p, align=const.align)
+        qtab = tables_of([table])
         q_method = torch.empty(nq, dtype=torch.int32, device="cuda")
         q_bs = torch.empty(nq, dtype=torch.int32, device="cuda")
         q_det = torch.empty((M.NDECIDE, nq), dtype=torch.int64, device="cuda")
-        for _ in range(2):
-            M.llmem_decide(qdev, tp, qtab, m_total, q_method, q_bs, q_det)
-        torch.cuda.synchronize()
-        reps = 10
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            M.llmem_decide(qdev, tp, qtab, m_total, q_method, q_bs, q_det)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
+        ms = timed_ms(lambda: M.llmem_decide(qdev, tp, qtab, m_total, q_method, q_bs, q_det))
+        ms_short = timed_ms(lambda: M.llmem_decide(qdev, tp, qtab, m_total, q_method, q_bs, None))
         # bracket check + one bisection step (brackets of <= 1 for this grid's models)
-        q_ops = algorithmic_lane_ops_decide(M.llmem_kernel_forms(qtab)["param_groups"], 2)
-        q_achieved = q_ops * nq / (ms * 1e-3) / 1e12
+        q_census = C.decide_census(table, 2)
         q_bytes = 31 + 1 + 4 + 4 + 8 * M.NDECIDE                       # query columns, tp_n; method, bs, decision columns
         q_gbs = q_bytes * nq / (ms * 1e-3) / 1e9
         ns = min(2000, nq)
@@ -404,18 +452,20 @@ def main():
         want = B.decide(qs, qs_tp, [table], const, m_total, threads=1)
         dt = time.perf_counter() - t1
         assert (q_det[:, :ns].cpu().numpy().T == want).all(), "decisions differ from the oracle"
-        result.setdefault("extra", {})["g6_method_decision"] = {
+        assert (q_method[:ns].cpu().numpy() == want[:, 0]).all() and (q_bs[:ns].cpu().numpy() == want[:, 1]).all()
+        c = counters_for("g6_decide", nq)
+        alu = alu_roofline("g6_decide", nq, ms, "decide_kernel<true>", q_census["lane_ops"])
+        extra["g6_method_decision"] = {
             "workload": "g6: Algorithm 1 per query (Llama-style model, gpu_n, sl; batch sizes up to 4096; "
                         "m_total 80 GiB), method + bs + all decision columns",
             "n_queries": nq, "ms_per_launch": ms, "queries_per_s": nq / (ms * 1e-3),
             # 136 B per query at 8 TB/s take longer than the census at the vector issue rate: HBM bounds it
             "roofline": {"bound": "hbm", "achieved": q_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                         "frac": q_gbs / PEAK_HBM_GBS,
-                         "traffic": TRAFFIC_DECIDE if nq == 4_000_000 else None, "kernel": "decide_kernel<true>",
-                         "algorithmic_bytes_per_query": q_bytes,
-                         "alu": {"achieved": q_achieved, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s",
-                                 "frac": q_achieved / PEAK_LANE_TOPS, "algorithmic_lane_ops_per_query": q_ops,
-                                 "issued": issued(VALU_DECIDE if nq == 4_000_000 else None, nq / (ms * 1e-3))}},
+                         "frac": q_gbs / PEAK_HBM_GBS, "traffic": c["traffic_bytes"] if c else None,
+                         "kernel": "decide_kernel<true>", "algorithmic_bytes_per_query": q_bytes, "alu": alu},
+            "method_and_bs_only": {"workload": "the same queries, out_detail = NULL (40 B per query)", "ms_per_launch": ms_short,
+                                   "queries_per_s": nq / (ms_short * 1e-3),
+                                   "hbm_gbs_algorithmic": 40 * nq / (ms_short * 1e-3) / 1e9},
             "cpu_oracle": {"value": ns / dt, "unit": "queries/s", "cores": 1,
                            "sample": f"first {ns} queries, C oracle (one-by-one search), {dt:.1f} s"},
             "verified_vs_oracle": ns}

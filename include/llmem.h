@@ -13,13 +13,16 @@
  *
  * Conventions
  *   DEV   pointer to device memory, owned by the caller; the library never
- *         allocates, frees or retains it.
+ *         allocates, frees or retains it.  (The one exception to "never allocates" is the
+ *         kernel built at run time, see LLMEM_KERNEL_LANE_SPECIALIZED: its first call with a
+ *         set of tables allocates host memory for the build and device memory for the code.)
  *   HOST  pointer to host memory, read during the call only.
  *   Every call enqueues its kernels on `hip_stream` (a hipStream_t passed as
  *   void*; NULL = the default stream) and returns without synchronising.
  *   A call only validates on the host and launches kernels, so it may be recorded
- *   while its stream is capturing into a HIP graph; with LLMEM_KERNEL_LANE_SPECIALIZED
- *   a call outside the capture must have built the kernel for those tables first.
+ *   while its stream is capturing into a HIP graph; a kernel built at run time
+ *   (LLMEM_KERNEL_LANE_SPECIALIZED with tables the library has no built-in specialization for,
+ *   LLMEM_KERNEL_LANE_RUNTIME) must have been built by a call outside the capture first.
  *   Return value: LLMEM_OK or a negative error code; on an error nothing has been
  *   enqueued and no output is written.
  */
@@ -35,7 +38,7 @@
 extern "C" {
 #endif
 
-#define LLMEM_ABI_VERSION 3
+#define LLMEM_ABI_VERSION 4
 
 /* ---- error codes --------------------------------------------------------- */
 #define LLMEM_OK            0
@@ -178,25 +181,38 @@ typedef struct llmem_tables {
  * walks every event (LLMEM_KERNEL_LANE_EVENTS).  LLMEM_KERNEL_WAVE gives a whole
  * wavefront to each configuration with the lanes spread over table entries; it needs
  * the events of all architectures, dealt to lanes, to fit LLMEM_MAX_EVENT_SLOTS.
- * LLMEM_KERNEL_AUTO takes the first of compiled, events, wave that the tables allow;
- * LLMEM_KERNEL_LANE the first of compiled, events; a forced choice the tables do not
- * allow is LLMEM_EINVAL_TABLE.
- * LLMEM_KERNEL_LANE_SPECIALIZED is the compiled form taken one step further and is only
- * used when asked for: the lane kernel's own source is compiled once more, at run time, with
- * the compiled tables as constants, so that every table word becomes an immediate and every
- * loop over table entries straight-line code.  The first call with a given set of tables (the
- * same condition as for the compiled form) takes a fraction of a second to a few seconds to build
- * and load the kernel; the build is kept, per device, until the process ends, and also
- * between processes when the environment variable LLMEM_KERNEL_CACHE names a writable
- * directory (one file per build, used only if its recorded identity matches in full).  Results are
- * the same bit for bit.  A failure of the run-time compiler or loader is LLMEM_EHIP with its
- * message in llmem_strerror.  llmem_estimate(_ex) and llmem_sweep honour it.            */
+ * LLMEM_KERNEL_LANE_SPECIALIZED is the compiled form taken one step further: the lane kernel's
+ * own source compiled once more with the compiled tables as constants, so that every table word
+ * becomes an immediate and every loop over table entries straight-line code.  Results are the
+ * same bit for bit.  Such kernels exist in two ways.
+ *   Built into the library, for the table sets it ships with (the GPT-, OPT- and Llama-style
+ *   tables of its workloads module, with and without gradient checkpointing, each alone, and the
+ *   three checkpointed ones together): a call whose tables compile to exactly the same words
+ *   launches the built-in kernel; nothing is compiled, loaded or allocated.
+ *   Built at run time (hiprtc) for any other tables the compiled form admits: the first call with
+ *   a given set of tables takes a fraction of a second to a few seconds to build and load the
+ *   kernel and allocates host memory for the build and device memory for the loaded code object;
+ *   the build is kept, per device, until the process ends, and also between processes when the
+ *   environment variable LLMEM_KERNEL_CACHE names a writable directory (one file per build, used
+ *   only if its recorded identity matches in full).  A failure of the run-time compiler or loader
+ *   is LLMEM_EHIP with its message in llmem_strerror.  The run-time compiler is not started in a
+ *   process that a profiler has been loaded into (ROCP_TOOL_LIBRARIES set, or LD_PRELOAD /
+ *   HSA_TOOLS_LIB naming a rocprofiler library): without a kept code object such a call is
+ *   LLMEM_EHIP; fill LLMEM_KERNEL_CACHE in an unprofiled run first.  A call recorded into a HIP
+ *   graph must not be the one that builds.
+ * LLMEM_KERNEL_AUTO takes a built-in specialization when one matches, else the first of
+ * compiled, events, wave that the tables allow; LLMEM_KERNEL_LANE the same without wave; it
+ * never builds at run time.  LLMEM_KERNEL_LANE_SPECIALIZED takes a built-in specialization when
+ * one matches and builds at run time otherwise; LLMEM_KERNEL_LANE_RUNTIME always builds at run
+ * time.  A forced choice the tables do not allow is LLMEM_EINVAL_TABLE.  llmem_estimate(_ex) and
+ * llmem_sweep honour all of these.                                                          */
 #define LLMEM_KERNEL_AUTO 0
 #define LLMEM_KERNEL_WAVE 1
 #define LLMEM_KERNEL_LANE 2
 #define LLMEM_KERNEL_LANE_EVENTS 3
 #define LLMEM_KERNEL_LANE_COMPILED 4
 #define LLMEM_KERNEL_LANE_SPECIALIZED 5
+#define LLMEM_KERNEL_LANE_RUNTIME 6
 
 /* ---- outputs --------------------------------------------------------------- */
 /* Detail columns: out_detail is DEV, LLMEM_NDETAIL columns of n int64 each
@@ -382,7 +398,9 @@ size_t llmem_config_bytes(int64_t n);
 size_t llmem_events_bytes(int64_t n);
 
 /* Host-only: which kernel forms these tables allow and what they cost.  info[0] = bit mask
- * (bit k set: LLMEM_KERNEL_k is allowed, k = 1..5), info[1] = 32-bit words of the compiled
+ * (bit k set: LLMEM_KERNEL_k is allowed, k = 1..6; LLMEM_FORMS_PREBUILT_*: the library holds a
+ * built-in specialization for these tables, for m_peak only / with the detail columns / for
+ * llmem_sweep), info[1] = 32-bit words of the compiled
  * tables (of LLMEM_PROGRAM_WORDS available), info[2] = value slots per wavefront in the
  * compiled form, info[3] = value slots per wavefront in the events form, info[4] = LDS slots
  * of the wavefront-per-configuration form; when the compiled form is allowed also info[5] =
@@ -390,11 +408,27 @@ size_t llmem_events_bytes(int64_t n);
  * kept, summed over the architectures (else 0).  Returns LLMEM_OK or the error the estimator
  * would return for these tables.                                                          */
 #define LLMEM_PROGRAM_WORDS 704
+#define LLMEM_FORMS_PREBUILT_PEAKS  (1 << 8)
+#define LLMEM_FORMS_PREBUILT_DETAIL (1 << 9)
+#define LLMEM_FORMS_PREBUILT_SWEEP  (1 << 10)
 int llmem_kernel_forms(const llmem_tables *method_tables, int32_t info[8]);
 
-/* Host-only self-test hook: floor(x / d) computed by the multiply-high constants
- * the kernels use for their divisions by the partition degree (0 <= x < 2^63,
- * 1 <= d <= 255; returns 0 for d outside that range).                          */
+/* Host-only: the compiled form of these tables, the 32-bit words a specialized kernel holds as
+ * constants (parameter groups, size classes, peak points and net changes of the timeline
+ * segments of every architecture; the library's build step makes its built-in specializations
+ * from them, and a built-in one is used when a call's tables compile to the same words).
+ *   words      HOST, room for max_words values
+ *   first      HOST, LLMEM_MAX_ARCH values: the first word of each architecture (0 beyond n_arch)
+ * Returns the number of words (>= 0), LLMEM_EINVAL_ARG if max_words is too small,
+ * LLMEM_EINVAL_TABLE if the tables do not admit the compiled form, or the estimator's error
+ * for these tables.  The device pointers of method_tables are not dereferenced.            */
+int llmem_compiled_tables(const llmem_tables *method_tables, uint32_t *words, int32_t max_words,
+                          int32_t first[LLMEM_MAX_ARCH]);
+
+/* Host-only diagnostic, not part of the estimator: floor(x / d) computed by the
+ * multiply-high constants the kernels use for their divisions by the partition degree
+ * (0 <= x < 2^63, 1 <= d <= 255; returns 0 for d outside that range).  Lets a host test
+ * compare the constants with integer division without a GPU.                              */
 uint64_t llmem_selftest_divide(uint64_t x, uint32_t d);
 
 const char *llmem_strerror(int code);

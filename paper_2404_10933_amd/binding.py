@@ -18,7 +18,9 @@ _LIB_PATH = os.path.join(_HERE, "libllmem.so")
 _lib = None
 
 MAX_ARCH = 8
-KERNEL_AUTO, KERNEL_WAVE, KERNEL_LANE, KERNEL_LANE_EVENTS, KERNEL_LANE_COMPILED, KERNEL_LANE_SPECIALIZED = range(6)
+(KERNEL_AUTO, KERNEL_WAVE, KERNEL_LANE, KERNEL_LANE_EVENTS, KERNEL_LANE_COMPILED, KERNEL_LANE_SPECIALIZED,
+ KERNEL_LANE_RUNTIME) = range(7)
+PROGRAM_WORDS = 704
 NDETAIL = 12
 DETAIL_COLUMNS = ("m_peak", "param_bytes_gpu", "grad_bytes_gpu", "os_bytes_gpu", "m_out", "m_lm",
                   "m_back", "k_chosen", "peak_live", "n_params", "t_max", "flags")
@@ -117,6 +119,9 @@ def load_library():
     lib.llmem_strerror.restype = ctypes.c_char_p
     lib.llmem_kernel_forms.argtypes = [ctypes.POINTER(_Tables), ctypes.POINTER(ctypes.c_int32)]
     lib.llmem_kernel_forms.restype = ci
+    lib.llmem_compiled_tables.argtypes = [ctypes.POINTER(_Tables), ctypes.POINTER(ctypes.c_uint32), ctypes.c_int32,
+                                          ctypes.POINTER(ctypes.c_int32)]
+    lib.llmem_compiled_tables.restype = ci
     lib.llmem_selftest_divide.argtypes = [u64, ctypes.c_uint32]
     lib.llmem_selftest_divide.restype = u64
     _lib = lib
@@ -343,10 +348,22 @@ def llmem_events_generate(seed: int, first: int, n: int, offsets: torch.Tensor, 
 def llmem_kernel_forms(tables: "Tables") -> Dict[str, int]:
     info = (ctypes.c_int32 * 8)()
     _check(load_library().llmem_kernel_forms(ctypes.byref(tables.struct), info))
-    return {"allowed": [k for k in range(1, 6) if info[0] >> k & 1], "program_words": info[1],
+    return {"allowed": [k for k in range(1, 7) if info[0] >> k & 1],
+            "prebuilt": [bool(info[0] >> (8 + flavour) & 1) for flavour in range(3)],
+            "program_words": info[1],
             "compiled_slots": info[2], "event_slots": info[3], "wave_slots": info[4],
             "param_groups": info[5] & 0xffff, "size_classes": info[5] >> 16, "terms": info[6],
             "peak_points": info[7]}
+
+
+def llmem_compiled_tables(tables: "Tables"):
+    """(words, first): the compiled form of the tables and the first word of each architecture."""
+    words = (ctypes.c_uint32 * PROGRAM_WORDS)()
+    first = (ctypes.c_int32 * MAX_ARCH)()
+    n = load_library().llmem_compiled_tables(ctypes.byref(tables.struct), words, PROGRAM_WORDS, first)
+    if n < 0:
+        _check(n)
+    return list(words[:n]), list(first)
 
 
 def llmem_config_bytes(n: int) -> int:

@@ -651,20 +651,24 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     if (rc != LLMEM_OK) return rc;
     // which kernel (see LLMEM_KERNEL_* in the header)
     const int hint = tables->kernel;
+    const int flavour = out_detail ? 1 : 0;
+    args.use_program = prog_ok ? 1 : 0;
+    const int lane_form = !prog_ok ? (batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1)
+                          : has_prebuilt(args, flavour) ? LLMEM_KERNEL_LANE_SPECIALIZED : LLMEM_KERNEL_LANE_COMPILED;
     int choice;
     switch (hint) {
-    case LLMEM_KERNEL_AUTO: choice = prog_ok ? LLMEM_KERNEL_LANE_COMPILED : batch_ok ? LLMEM_KERNEL_LANE_EVENTS
-                                     : wave_ok ? LLMEM_KERNEL_WAVE : -1; break;
-    case LLMEM_KERNEL_LANE: choice = prog_ok ? LLMEM_KERNEL_LANE_COMPILED : batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1; break;
+    case LLMEM_KERNEL_AUTO: choice = lane_form >= 0 ? lane_form : wave_ok ? LLMEM_KERNEL_WAVE : -1; break;
+    case LLMEM_KERNEL_LANE: choice = lane_form; break;
     case LLMEM_KERNEL_WAVE: choice = wave_ok ? hint : -1; break;
     case LLMEM_KERNEL_LANE_EVENTS: choice = batch_ok ? hint : -1; break;
-    case LLMEM_KERNEL_LANE_COMPILED: choice = prog_ok ? hint : -1; break;
-    case LLMEM_KERNEL_LANE_SPECIALIZED: choice = prog_ok ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_COMPILED:
+    case LLMEM_KERNEL_LANE_SPECIALIZED:
+    case LLMEM_KERNEL_LANE_RUNTIME: choice = prog_ok ? hint : -1; break;
     default: choice = -1;
     }
     if (choice < 0) return LLMEM_EINVAL_TABLE;
     const bool use_batch = choice != LLMEM_KERNEL_WAVE;
-    args.use_program = (choice == LLMEM_KERNEL_LANE_COMPILED || choice == LLMEM_KERNEL_LANE_SPECIALIZED) ? 1 : 0;
+    args.use_program = (choice >= LLMEM_KERNEL_LANE_COMPILED) ? 1 : 0;
     if (n == 0) return LLMEM_OK;
     if (!cfg->arch_id || !cfg->h || !cfg->L || !cfg->n_heads || !cfg->n_kv || !cfg->ffn || !cfg->V
         || !cfg->P || !cfg->bs || !cfg->sl || !cfg->method || !cfg->d || !cfg->chunk_k || !cfg->flags)
@@ -677,7 +681,8 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     args.out_detail = reinterpret_cast<long long *>(out_detail);
 
     const int64_t n_batch = (n + 63) / 64;
-    if (choice == LLMEM_KERNEL_LANE_SPECIALIZED) return launch_specialized(args, out_detail ? 1 : 0, n_batch, stream);
+    if (choice == LLMEM_KERNEL_LANE_SPECIALIZED || choice == LLMEM_KERNEL_LANE_RUNTIME)
+        return launch_specialized(args, flavour, n_batch, stream, choice == LLMEM_KERNEL_LANE_RUNTIME);
     if (use_batch) {
         launch_batch_kernel(args, out_detail != nullptr, n_batch, stream);
         hipError_t e = hipGetLastError();
@@ -728,18 +733,22 @@ static int launch_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, co
     if (rc != LLMEM_OK) return rc;
     // the lane forms only; a hint that names one of them is honoured
     const int hint = tables->kernel;
+    args.use_program = prog_ok ? 1 : 0;
+    const int lane_form = !prog_ok ? (batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1)
+                          : has_prebuilt(args, 2) ? LLMEM_KERNEL_LANE_SPECIALIZED : LLMEM_KERNEL_LANE_COMPILED;
     int choice;
     switch (hint) {
     case LLMEM_KERNEL_AUTO:
-    case LLMEM_KERNEL_LANE: choice = prog_ok ? LLMEM_KERNEL_LANE_COMPILED : batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1; break;
+    case LLMEM_KERNEL_LANE: choice = lane_form; break;
     case LLMEM_KERNEL_LANE_EVENTS: choice = batch_ok ? hint : -1; break;
-    case LLMEM_KERNEL_LANE_COMPILED: choice = prog_ok ? hint : -1; break;
-    case LLMEM_KERNEL_LANE_SPECIALIZED: choice = prog_ok ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_COMPILED:
+    case LLMEM_KERNEL_LANE_SPECIALIZED:
+    case LLMEM_KERNEL_LANE_RUNTIME: choice = prog_ok ? hint : -1; break;
     default: choice = -1;
     }
     if (choice < 0) return LLMEM_EINVAL_TABLE;
     if (n == 0) return LLMEM_OK;
-    args.use_program = (choice == LLMEM_KERNEL_LANE_COMPILED || choice == LLMEM_KERNEL_LANE_SPECIALIZED) ? 1 : 0;
+    args.use_program = (choice >= LLMEM_KERNEL_LANE_COMPILED) ? 1 : 0;
     args.n = n;
     args.params_dev = reinterpret_cast<const uint4 *>(tables->params_dev);
     args.events_dev = reinterpret_cast<const uint4 *>(tables->events_dev);
@@ -748,7 +757,8 @@ static int launch_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, co
     args.sweep_first = first;
     args.m_total = m_total;
     args.sweep_stats = reinterpret_cast<unsigned long long *>(stats);
-    if (choice == LLMEM_KERNEL_LANE_SPECIALIZED) return launch_specialized(args, 2, (n + 63) / 64, stream);
+    if (choice == LLMEM_KERNEL_LANE_SPECIALIZED || choice == LLMEM_KERNEL_LANE_RUNTIME)
+        return launch_specialized(args, 2, (n + 63) / 64, stream, choice == LLMEM_KERNEL_LANE_RUNTIME);
     launch_sweep_kernel(args, (n + 63) / 64, stream);
     return launch_status();
 }
@@ -773,13 +783,36 @@ extern "C" int llmem_kernel_forms(const llmem_tables *tables, int32_t info[8])
     for (int q = 0; q < 8; ++q) info[q] = 0;
     info[0] = (wave_ok ? 1 << LLMEM_KERNEL_WAVE : 0) | (batch_ok ? 1 << LLMEM_KERNEL_LANE_EVENTS : 0)
               | (prog_ok ? 1 << LLMEM_KERNEL_LANE_COMPILED : 0) | ((batch_ok || prog_ok) ? 1 << LLMEM_KERNEL_LANE : 0)
-              | (prog_ok ? 1 << LLMEM_KERNEL_LANE_SPECIALIZED : 0);
+              | (prog_ok ? (1 << LLMEM_KERNEL_LANE_SPECIALIZED) | (1 << LLMEM_KERNEL_LANE_RUNTIME) : 0);
+    if (prog_ok) {
+        args.use_program = 1;
+        for (int flavour = 0; flavour < 3; ++flavour)
+            if (has_prebuilt(args, flavour)) info[0] |= LLMEM_FORMS_PREBUILT_PEAKS << flavour;
+    }
     info[1] = words;
     info[2] = args.p_slots;
     info[3] = args.s_slots;
     info[4] = args.n_slot_total;
     if (prog_ok) { info[5] = stats[0] | (stats[1] << 16); info[6] = stats[2]; info[7] = stats[3]; }
     return LLMEM_OK;
+}
+
+extern "C" int llmem_compiled_tables(const llmem_tables *tables, uint32_t *words, int32_t max_words,
+                                     int32_t first[LLMEM_MAX_ARCH])
+{
+    using namespace llmem;
+    if (!tables || !words || !first) return LLMEM_EINVAL_NULL;
+    EstimateArgs args;
+    memset(&args, 0, sizeof(args));
+    bool wave_ok, batch_ok, prog_ok;
+    int n_words = 0;
+    const int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok, &n_words);
+    if (rc != LLMEM_OK) return rc;
+    if (!prog_ok) return LLMEM_EINVAL_TABLE;
+    if (n_words > max_words) return LLMEM_EINVAL_ARG;
+    for (int q = 0; q < n_words; ++q) words[q] = args.prog[q];
+    for (int q = 0; q < LLMEM_MAX_ARCH; ++q) first[q] = q < args.n_arch ? args.arch[q].prog_first : 0;
+    return n_words;
 }
 
 extern "C" uint64_t llmem_selftest_divide(uint64_t x, uint32_t d)

@@ -145,11 +145,14 @@ size_t batch_kernel_lds_bytes(const EstimateArgs &a);
 void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream);
 void launch_sweep_kernel(const EstimateArgs &args, long long n_batch, hipStream_t stream);
 void launch_sweep_reset(long long *stats, hipStream_t stream);
-// Specialized form: the lane kernel compiled at run time with the compiled tables of `args` as
-// constants (one build per set of tables, flavour and device, kept until the process ends).
-// flavour: 0 m_peak only, 1 with the detail columns, 2 sweep.  LLMEM_OK, or LLMEM_EHIP with the
-// compiler's or the loader's message as the error text.
-int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch, hipStream_t stream);
+// Specialized form: the lane kernel compiled with the compiled tables of `args` as constants:
+// a kernel built into the library when the tables are those of a set it ships with
+// (has_prebuilt), else, or when at_run_time is set, one built at run time (one build per set of
+// tables, flavour and device, kept until the process ends).  flavour: 0 m_peak only, 1 with the
+// detail columns, 2 sweep.  LLMEM_OK, or LLMEM_EHIP with the compiler's or the loader's message
+// as the error text.
+bool has_prebuilt(const EstimateArgs &args, int flavour);
+int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch, hipStream_t stream, bool at_run_time);
 #endif
 constexpr int SWEEP_INDEX_BITS = 40;             // LLMEM_S_BEST: score2 << 40 | (2^40 - 1 - index)
 

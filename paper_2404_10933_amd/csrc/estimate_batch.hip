@@ -27,11 +27,12 @@
 // m_peak^tp, m_back^tp) of arXiv 2404.10933; chunk size per Sec. 4.1; timeline
 // traversal per Sec. 2.1 / Sec. 3.1.
 //
-// Specialized form (LLMEM_SPECIALIZED, see specialize.hip): this file is compiled again at run
-// time with the compiled tables of one set of architecture tables as constants
-// (specialized_prog.h).  The loops over parameter groups, classes and terms then have constant
-// bounds and are unrolled; every word, offset and count becomes an immediate and every flag test
-// disappears.  Only the path for sizes of 2^31 blocks and more keeps reading the words in loops.
+// Specialized form (LLMEM_SPECIALIZED, see specialize.hip): this file is compiled again with the
+// compiled tables of one set of architecture tables as constants - when the library is built,
+// for the table sets it ships with, and at run time (specialized_prog.h) for any other.  The
+// loops over parameter groups, classes and terms then have constant bounds and are unrolled;
+// every word, offset and count becomes an immediate and every flag test disappears.  Only the
+// path for sizes of 2^31 blocks and more keeps reading the words in loops.
 #ifndef __HIPCC_RTC__
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -57,7 +58,22 @@ typedef long long int64_t;
 #include "wave.h"
 
 #ifdef LLMEM_SPECIALIZED
-#include "specialized_prog.h"     // SPEC_PROG[] (constants), SPEC_PROG_MEM[] (the same words in memory), SPEC_WAVES
+// The constants of this build, as macros: LLMEM_SPEC_WAVES (waves per SIMD to aim at),
+// LLMEM_SPEC_ARCHS, LLMEM_SPEC_FIRSTS (first word of each of eight architectures) and
+// LLMEM_SPEC_WORDS (the compiled tables).  A build ahead of time names its own file.
+#ifndef LLMEM_SPEC_HEADER
+#define LLMEM_SPEC_HEADER "specialized_prog.h"
+#endif
+#include LLMEM_SPEC_HEADER
+namespace llmem {
+namespace {
+constexpr int SPEC_WAVES = LLMEM_SPEC_WAVES;
+constexpr int SPEC_ARCHS = LLMEM_SPEC_ARCHS;
+constexpr int SPEC_FIRST[8] = {LLMEM_SPEC_FIRSTS};
+__device__ constexpr unsigned SPEC_PROG[] = {LLMEM_SPEC_WORDS};      // every read folds to an immediate
+__constant__ unsigned SPEC_PROG_MEM[] = {LLMEM_SPEC_WORDS};          // the same words in memory, for the loops
+}  // namespace
+}  // namespace llmem
 #define LLMEM_PROG(i) SPEC_PROG[i]
 #define LLMEM_PROG_LOOP(i) SPEC_PROG_MEM[i]
 #define LLMEM_UNROLL_IF(flag) _Pragma("unroll")
@@ -825,17 +841,29 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 
 #ifdef LLMEM_SPECIALIZED
 
-// the flavour the run-time compile was asked for (LLMEM_SPEC_FLAVOUR: 0 m_peak only, 1 with
-// the detail columns, 2 sweep)
+// the flavour this build was asked for (LLMEM_SPEC_FLAVOUR: 0 m_peak only, 1 with the detail
+// columns, 2 sweep); a build ahead of time names its kernel itself (LLMEM_SPEC_KERNEL)
+#ifndef LLMEM_SPEC_KERNEL
 #if LLMEM_SPEC_FLAVOUR == 0
-extern "C" __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
-void llmem_specialized_peaks(const EstimateArgs a) { estimate_batch_body<false, true, false>(a); }
+#define LLMEM_SPEC_KERNEL llmem_specialized_peaks
 #elif LLMEM_SPEC_FLAVOUR == 1
-extern "C" __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
-void llmem_specialized_detail(const EstimateArgs a) { estimate_batch_body<true, true, false>(a); }
+#define LLMEM_SPEC_KERNEL llmem_specialized_detail
 #else
+#define LLMEM_SPEC_KERNEL llmem_specialized_sweep
+#endif
+#endif
 extern "C" __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
-void llmem_specialized_sweep(const EstimateArgs a) { estimate_batch_body<true, true, true>(a); }
+void LLMEM_SPEC_KERNEL(const EstimateArgs a)
+{
+    estimate_batch_body<LLMEM_SPEC_FLAVOUR != 0, true, LLMEM_SPEC_FLAVOUR == 2>(a);
+}
+
+#ifdef LLMEM_SPEC_ENTRY
+// built into the library: the host side reaches the kernel through this function
+extern "C" __attribute__((visibility("hidden"))) const void *LLMEM_SPEC_ENTRY()
+{
+    return reinterpret_cast<const void *>(&LLMEM_SPEC_KERNEL);
+}
 #endif
 
 }  // namespace llmem

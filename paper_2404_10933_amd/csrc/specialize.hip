@@ -1,14 +1,20 @@
-// Specialized form of the lane kernel: estimate_batch.hip compiled at run time
-// (hiprtc) with the compiled tables of one set of architecture tables as
-// constants, loaded as a module and launched like the built-in kernels.
+// Specialized forms of the lane kernel: estimate_batch.hip compiled with the
+// compiled tables of one set of architecture tables as constants.
 //
-// One build per (device, table words, flavour), made on first use (a fraction of a
-// second to a few seconds) and kept until the process ends.  With the environment
-// variable LLMEM_KERNEL_CACHE naming a directory, built code objects are also kept
-// there and loaded from there by later processes (a file per build, verified
-// against the full key and the embedded sources before use).  The sources come from embedded_sources.inc,
-// which the build step writes from the files next to this one, so that the
-// run-time build and the built-in kernels are the same code.
+// Built ahead of time: the build step compiles one kernel per flavour for every
+// table set the library ships with and lists them, with the table words they were
+// made from, in aot_registry.inc; a call whose compiled tables equal such a list
+// word for word launches that kernel like any built-in one (no compiler, no
+// module, nothing allocated).
+//
+// Built at run time (hiprtc): any other tables, when asked for.  One build per
+// (device, table words, flavour), made on first use (a fraction of a second to a
+// few seconds) and kept until the process ends.  With the environment variable
+// LLMEM_KERNEL_CACHE naming a directory, built code objects are also kept there
+// and loaded from there by later processes (a file per build, verified against the
+// full key and the embedded sources before use).  The sources come from
+// embedded_sources.inc, which the build step writes from the files next to this
+// one, so that every form of the kernel is the same code.
 #include <hip/hip_runtime.h>
 #include <hip/hiprtc.h>
 #include <stdint.h>
@@ -17,7 +23,10 @@
 #include <unistd.h>
 #include <string.h>
 
+#include <atomic>
+#include <condition_variable>
 #include <map>
+#include <memory>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -27,8 +36,28 @@
 #include "embedded_sources.inc"   // EMBEDDED_COUNT, EMBEDDED_NAMES[], EMBEDDED_TEXTS[]; entry 0 is estimate_batch.hip
 
 namespace llmem {
+namespace {
+// a kernel built into the library and the compiled tables it was made from
+struct Prebuilt {
+    const char *name;
+    int flavour, n_arch;
+    int first[LLMEM_MAX_ARCH];
+    int n_words;
+    const uint32_t *words;
+    const void *(*entry)();                     // the kernel, as the launch calls take it
+};
+}  // namespace
+}  // namespace llmem
+#ifndef LLMEM_AOT_REGISTRY
+#define LLMEM_AOT_REGISTRY "aot_registry.inc"
+#endif
+#include LLMEM_AOT_REGISTRY       // PREBUILT[], PREBUILT_COUNT (written by the build step; an empty list
+                                  // while the build step is still making the kernels)
+
+namespace llmem {
 
 void set_error_text(const char *text);          // estimate.hip: what llmem_strerror(LLMEM_EHIP) returns
+const char *last_hip_error();
 
 namespace {
 
@@ -59,8 +88,19 @@ struct Key {
     }
 };
 
+// One per key.  The thread that creates it builds the kernel WITHOUT holding g_lock, so that
+// launches of kernels that are already built (other keys) go on meanwhile; threads that want
+// the same key wait for `done`.
+struct Slot {
+    bool done = false;
+    int rc = LLMEM_OK;
+    std::string problem;
+    Built built;
+};
+
 std::mutex g_lock;
-std::map<Key, Built> g_built;                   // never erased: modules stay loaded until the process ends
+std::condition_variable g_built_changed;
+std::map<Key, std::shared_ptr<Slot>> g_built;   // finished builds are never erased: modules stay loaded until the process ends
 
 int fail(const std::string &text)
 {
@@ -78,6 +118,7 @@ size_t words_used(const EstimateArgs &args)
     return n < (size_t)PROG_WORDS ? n : (size_t)PROG_WORDS;
 }
 
+// specialized_prog.h of a run-time build: the constants estimate_batch.hip declares its tables from
 std::string constants_header(const Key &key)
 {
     const std::vector<uint32_t> &words = key.words;
@@ -86,15 +127,13 @@ std::string constants_header(const Key &key)
     for (size_t q = 0; q < words.size(); ++q) {
         snprintf(item, sizeof(item), "0x%08xu,", words[q]);
         list += item;
-        if (q % 8 == 7) list += "\n";
+        if (q % 8 == 7) list += " \\\n";
     }
-    char head[256];
-    snprintf(head, sizeof(head), "#pragma once\nnamespace llmem {\nconstexpr int SPEC_WAVES = %d;\nconstexpr int SPEC_N = %zu;\n"
-             "constexpr int SPEC_ARCHS = %zu;\n", specialized_waves(key.first.size()), words.size(), key.first.size());
-    std::string firsts = "constexpr int SPEC_FIRST[8] = {";
-    for (size_t q = 0; q < 8; ++q) firsts += std::to_string(q < key.first.size() ? key.first[q] : 0) + (q < 7 ? ", " : "};\n");
-    return std::string(head) + firsts + "__device__ constexpr unsigned SPEC_PROG[SPEC_N] = {\n" + list + "};\n"
-           + "__constant__ unsigned SPEC_PROG_MEM[SPEC_N] = {\n" + list + "};\n}\n";
+    std::string firsts;
+    for (size_t q = 0; q < 8; ++q) firsts += std::to_string(q < key.first.size() ? key.first[q] : 0) + (q < 7 ? ", " : "");
+    return "#pragma once\n#define LLMEM_SPEC_WAVES " + std::to_string(specialized_waves(key.first.size()))
+           + "\n#define LLMEM_SPEC_ARCHS " + std::to_string(key.first.size()) + "\n#define LLMEM_SPEC_FIRSTS " + firsts
+           + "\n#define LLMEM_SPEC_WORDS \\\n" + list + "\n";
 }
 
 // ---- code objects kept between processes (LLMEM_KERNEL_CACHE) ---------------------------------
@@ -111,7 +150,7 @@ unsigned long long checksum(const char *data, size_t size)
 
 std::string identity(const Key &key, const char *arch_name)
 {
-    std::string id = std::string("llmem-specialized-2|") + arch_name + "|" + std::to_string(key.flavour) + "|"
+    std::string id = std::string("llmem-specialized-3|") + arch_name + "|" + std::to_string(key.flavour) + "|"
                      + std::to_string(specialized_waves(key.first.size())) + "|";
     for (int f : key.first) id += std::to_string(f) + ",";
     id += "|";
@@ -167,6 +206,27 @@ void cache_write(const std::string &path, const std::string &id, const std::vect
 
 int compile(const Key &key, const char *arch_name, std::vector<char> *code);
 
+// The run-time compiler has crashed the process when started under rocprofv3 (its tool library
+// preloaded): such a process only loads kept code objects.  Returns the variable that gives the
+// profiler away, or null.
+const char *profiler_loaded()
+{
+    const char *tools = getenv("ROCP_TOOL_LIBRARIES");
+    if (tools && tools[0]) return "ROCP_TOOL_LIBRARIES";
+    const char *preload = getenv("LD_PRELOAD");
+    if (preload && strstr(preload, "rocprofiler-sdk-tool")) return "LD_PRELOAD";
+    const char *hsa_tools = getenv("HSA_TOOLS_LIB");
+    if (hsa_tools && strstr(hsa_tools, "rocprof")) return "HSA_TOOLS_LIB";
+    return nullptr;
+}
+
+int refuse_under_profiler(const char *tool)
+{
+    return fail(std::string("the run-time compiler is not started inside a profiled process (") + tool
+                + " names a profiler): run once unprofiled with LLMEM_KERNEL_CACHE naming a directory and profile with "
+                  "the same directory, or use tables the library has a built-in specialization for");
+}
+
 int build(const Key &key, Built *out)
 {
     hipDeviceProp_t prop;
@@ -180,6 +240,11 @@ int build(const Key &key, Built *out)
         // first a kept code object, if there is one; a kept one that does not load is built again
         const bool kept = attempt == 0 && !path.empty() && cache_read(path, id, out->code);
         if (!kept) {
+            if (const char *tool = profiler_loaded()) {
+                delete out->code;
+                out->code = nullptr;
+                return refuse_under_profiler(tool);
+            }
             const int rc = compile(key, prop.gcnArchName, out->code);
             if (rc != LLMEM_OK) { delete out->code; out->code = nullptr; return rc; }
             if (!path.empty()) cache_write(path, id, *out->code);
@@ -239,33 +304,120 @@ int compile(const Key &key, const char *arch_name, std::vector<char> *code)
     return LLMEM_OK;
 }
 
+// the kernel built into the library for exactly these compiled tables and this flavour, or null
+const Prebuilt *find_prebuilt(const EstimateArgs &args, int flavour)
+{
+    const size_t n_words = words_used(args);
+    for (int q = 0; q < PREBUILT_COUNT; ++q) {
+        const Prebuilt &p = PREBUILT[q];
+        if (p.flavour != flavour || p.n_arch != args.n_arch || (size_t)p.n_words != n_words) continue;
+        bool same = true;
+        for (int ar = 0; ar < args.n_arch && same; ++ar) same = p.first[ar] == args.arch[ar].prog_first;
+        if (same && memcmp(p.words, args.prog, n_words * sizeof(uint32_t)) == 0) return &p;
+    }
+    return nullptr;
+}
+
 }  // namespace
 
-int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch, hipStream_t stream)
+bool has_prebuilt(const EstimateArgs &args, int flavour)
+{
+    return args.use_program && flavour >= 0 && flavour <= 2 && find_prebuilt(args, flavour) != nullptr;
+}
+
+namespace {
+
+constexpr int DEVICES_MAX = 64;
+
+int launch_prebuilt(const Prebuilt &p, const EstimateArgs &args, long long n_batch, hipStream_t stream)
+{
+    const size_t lds_bytes = batch_kernel_lds_bytes(args);
+    const void *kernel = p.entry();
+    // resident workgroups per compute unit and compute units, asked once per kernel and device
+    static std::atomic<int> resident_of[DEVICES_MAX][sizeof(PREBUILT) / sizeof(PREBUILT[0])];
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return fail("no current device");
+    const int slot = device >= 0 && device < DEVICES_MAX ? device : 0;
+    int resident = resident_of[slot][&p - PREBUILT].load(std::memory_order_relaxed);
+    if (resident == 0) {
+        int per_cu = 0, cu_count = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 64 * BATCH_WAVES, lds_bytes) != hipSuccess || per_cu < 1)
+            per_cu = 1;
+        if (hipDeviceGetAttribute(&cu_count, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cu_count < 1)
+            cu_count = 256;
+        resident = per_cu * cu_count;
+        resident_of[slot][&p - PREBUILT].store(resident, std::memory_order_relaxed);
+    }
+    long long blocks = (n_batch + BATCH_WAVES - 1) / BATCH_WAVES;
+    if (blocks > (long long)resident * 16) blocks = (long long)resident * 16;   // as for the built-in compiled form
+    EstimateArgs copy = args;
+    void *params[] = {&copy};
+    const hipError_t e = hipLaunchKernel(kernel, dim3((unsigned)blocks), dim3(64 * BATCH_WAVES), params, lds_bytes, stream);
+    if (e != hipSuccess) return fail(std::string("launching the built-in specialized kernel: ") + hipGetErrorString(e));
+    return LLMEM_OK;
+}
+
+}  // namespace
+
+int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch, hipStream_t stream, bool at_run_time)
 {
     if (flavour < 0 || flavour > 2 || !args.use_program || args.n_arch < 1 || args.n_arch > LLMEM_MAX_ARCH)
         return LLMEM_EINVAL_TABLE;
+    if (!at_run_time) {
+        if (const Prebuilt *p = find_prebuilt(args, flavour)) return launch_prebuilt(*p, args, n_batch, stream);
+    }
+    // a profiled process may only load kept code objects: without a place to keep them there is
+    // nothing to try (decided before any device or compiler call)
+    if (const char *tool = profiler_loaded()) {
+        const char *dir = getenv("LLMEM_KERNEL_CACHE");
+        if (!dir || !dir[0]) return refuse_under_profiler(tool);
+    }
     Key key;
     if (hipGetDevice(&key.device) != hipSuccess) return fail("no current device");
     key.flavour = flavour;
     for (int q = 0; q < args.n_arch; ++q) key.first.push_back(args.arch[q].prog_first);
     key.words.assign(args.prog, args.prog + words_used(args));
     const size_t lds_bytes = batch_kernel_lds_bytes(args);
-    Built built;
+    std::shared_ptr<Slot> slot;
+    bool mine = false;
     {
-        std::lock_guard<std::mutex> hold(g_lock);
+        std::unique_lock<std::mutex> hold(g_lock);
         auto at = g_built.find(key);
         if (at == g_built.end()) {
-            const int rc = build(key, &built);
-            if (rc != LLMEM_OK) return rc;
+            slot = std::make_shared<Slot>();
+            g_built.emplace(key, slot);
+            mine = true;
+        } else {
+            slot = at->second;
+            g_built_changed.wait(hold, [&] { return slot->done; });
+        }
+    }
+    if (mine) {
+        // built outside the lock: seconds, during which other kernels are found and launched
+        Built built;
+        int rc = build(key, &built);
+        std::string problem = rc == LLMEM_OK ? std::string() : std::string(llmem::last_hip_error());
+        if (rc == LLMEM_OK) {
             int per_cu = 0;
             if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, built.function, 64 * BATCH_WAVES, lds_bytes)
                     == hipSuccess && per_cu > 0)
                 built.per_cu = per_cu;
-            at = g_built.emplace(key, built).first;
         }
-        built = at->second;
+        {
+            std::lock_guard<std::mutex> hold(g_lock);
+            slot->built = built;
+            slot->rc = rc;
+            slot->problem = problem;
+            slot->done = true;
+            if (rc != LLMEM_OK) g_built.erase(key);                  // a later call tries again
+        }
+        g_built_changed.notify_all();
     }
+    if (slot->rc != LLMEM_OK) {
+        if (!mine) set_error_text(slot->problem.c_str());             // the error text is per thread
+        return slot->rc;
+    }
+    const Built &built = slot->built;
     long long blocks = (n_batch + BATCH_WAVES - 1) / BATCH_WAVES;
     const long long resident = (long long)built.per_cu * built.cu_count * 16;   // as for the built-in compiled form
     if (blocks > resident) blocks = resident;

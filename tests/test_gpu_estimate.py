@@ -20,22 +20,26 @@ def U():
     return gpu_util
 
 
-WAVE, LANE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED = 1, 2, 3, 4, 5       # LLMEM_KERNEL_*
-BOTH = (WAVE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED)
+WAVE, LANE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED, LANE_RUNTIME = 1, 2, 3, 4, 5, 6       # LLMEM_KERNEL_*
+BOTH = (WAVE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED, LANE_RUNTIME)
+BUILT = (LANE, LANE_SPECIALIZED, LANE_RUNTIME)                  # follow from the others
 
 
-def _check(U, cfg, tables, const=CONST, threads=8, expect=None):
+def _check(U, cfg, tables, const=CONST, threads=8, expect=None, prebuilt=None):
     """Every kernel form the tables allow (one wavefront per configuration; one lane per
-    configuration walking all events; the same with the host-compiled tables; the same built at
-    run time with those tables as constants), each forced, plus the library's own choice,
-    against the oracle.  `expect`: forms that must be allowed."""
+    configuration walking all events; the same with the host-compiled tables; the same with those
+    tables as constants, built into the library where it ships the tables, else built at run time;
+    and always built at run time), each forced, plus the library's own choice, against the oracle.
+    `expect`: forms that must be allowed; `prebuilt`: whether the library must hold built-in
+    specializations for these tables."""
     import paper_2404_10933_amd as M
-    allowed = M.llmem_kernel_forms(M.Tables(tables, m_base=const.m_base, cu_p=const.cu_p, align=const.align,
-                                            device=None))["allowed"]
+    forms = M.llmem_kernel_forms(M.Tables(tables, m_base=const.m_base, cu_p=const.cu_p, align=const.align, device=None))
+    allowed = forms["allowed"]
     if expect is not None:
-        assert sorted(k for k in allowed if k not in (LANE, LANE_SPECIALIZED)) \
-            == sorted(k for k in expect if k != LANE_SPECIALIZED), allowed
-        assert (LANE_SPECIALIZED in allowed) == (LANE_COMPILED in allowed)
+        assert sorted(k for k in allowed if k not in BUILT) == sorted(k for k in expect if k not in BUILT), allowed
+    assert (LANE_SPECIALIZED in allowed) == (LANE_COMPILED in allowed) == (LANE_RUNTIME in allowed)
+    if prebuilt is not None:
+        assert forms["prebuilt"] == [prebuilt] * 3, forms
     want_p, want_d = B.estimate(cfg, tables, const, threads=threads)
     for kernel in [0] + allowed:
         got_p, got_d = U.hip_estimate(cfg, tables, const, kernel=kernel)
@@ -43,7 +47,7 @@ def _check(U, cfg, tables, const=CONST, threads=8, expect=None):
         U.assert_same(f"peaks (kernel {kernel})", got_p, want_p)
         got_p2, _ = U.hip_estimate(cfg, tables, const, detail=False, kernel=kernel)
         U.assert_same(f"peaks, no detail (kernel {kernel})", got_p2, want_p)
-    for kernel in (WAVE, LANE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED):
+    for kernel in (WAVE, LANE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED, LANE_RUNTIME):
         if kernel not in allowed:
             with pytest.raises(M.LlmemError) as e:
                 U.hip_estimate(cfg, tables, const, kernel=kernel)
@@ -52,7 +56,7 @@ def _check(U, cfg, tables, const=CONST, threads=8, expect=None):
 
 def test_grid1_all(U):
     cfg = G.grid1()
-    _check(U, cfg, [T.gpt_table()], expect=BOTH)
+    _check(U, cfg, [T.gpt_table()], expect=BOTH, prebuilt=True)
     # and directly against the Python oracle that carries the pins
     rows = np.asarray(A.estimate(cfg, [T.gpt_table()], CONST), dtype=np.int64)
     _, got = U.hip_estimate(cfg, [T.gpt_table()], CONST)
@@ -65,7 +69,7 @@ def test_grid_slices(U, name, n, first):
     """Grids 2 and 3 whole (10^5 and 10^6 configurations, every column of every configuration
     against the oracle), and slices from the far ends of grids 3 and 4."""
     spec = G.GRIDS[name]
-    _check(U, spec["make"](n=n, seed=0, first=first), [T.FAMILIES[spec["family"]]()], expect=BOTH, threads=16)
+    _check(U, spec["make"](n=n, seed=0, first=first), [T.FAMILIES[spec["family"]]()], expect=BOTH, threads=16, prebuilt=True)
 
 
 @pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 127, 128, 129, 1000])
@@ -127,9 +131,9 @@ def test_full_traversal_tables(U, name, n, first):
     spec = G.GRIDS[name]
     make = T.FAMILIES[spec["family"]]
     cfg = spec["make"](n=n, seed=0, first=first)
-    _check(U, cfg, [make(checkpoint=False)], expect=BOTH)
+    _check(U, cfg, [make(checkpoint=False)], expect=BOTH, prebuilt=True)
     cfg["arch_id"] = (np.arange(n) % 2).astype(np.uint8)
-    _check(U, cfg, [make(checkpoint=False), make()], CONST)
+    _check(U, cfg, [make(checkpoint=False), make()], CONST, prebuilt=False)
 
 
 def test_sizes_on_both_sides_of_2_to_31_blocks(U):
@@ -196,8 +200,9 @@ def _full_size_reference():
 
 def test_host_threads_with_their_own_tables_and_streams(U):
     """Four host threads, each with its own tables (so each makes the library build its own
-    specialized kernel), stream and outputs, calling at the same time: the builds are serialized
-    inside the library, the launches are not, every result equals the oracle's."""
+    specialized kernel at run time), stream and outputs, calling at the same time: the builds run
+    side by side (none holds the library's lock while it compiles), every result equals the
+    oracle's; then the same tables again from four threads at once, which wait for one build each."""
     import threading
     rng = np.random.default_rng(61)
     jobs = []
@@ -215,7 +220,7 @@ def test_host_threads_with_their_own_tables_and_streams(U):
             out = []
             for _ in range(3):
                 with torch.cuda.stream(stream):
-                    out.append(U.hip_estimate(cfg, tables, const, stream=stream, kernel=LANE_SPECIALIZED))
+                    out.append(U.hip_estimate(cfg, tables, const, stream=stream, kernel=LANE_RUNTIME))
             results[j] = out
         except Exception as e:                                  # reported by the main thread
             errors.append((j, repr(e)))
@@ -230,12 +235,37 @@ def test_host_threads_with_their_own_tables_and_streams(U):
         for got_p, got_d in results[j]:
             U.assert_same(f"peaks, thread {j}", got_p, want_p)
             U.assert_same(f"detail, thread {j}", got_d, want_d)
+    # one new table set asked for by four threads at the same time: one of them builds, the others wait
+    shared = [T.random_table(rng, 10, 30, "shared", n_sizes=5)]
+    cfg = G.random_configs(np.random.default_rng(80), 64 * 10 + 3, n_arch=1)
+    want_p, want_d = B.estimate(cfg, shared, CONST, threads=8)
+    jobs[:] = [(cfg, shared, CONST, None)] * 4
+    results[:] = [None] * 4
+    threads = [threading.Thread(target=work, args=(j,)) for j in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=200)
+    assert not errors, errors
+    for j in range(4):
+        for got_p, got_d in results[j]:
+            U.assert_same(f"peaks, shared tables, thread {j}", got_p, want_p)
+            U.assert_same(f"detail, shared tables, thread {j}", got_d, want_d)
 
 
-@pytest.mark.parametrize("kernel", (0, LANE_SPECIALIZED))
+def test_profiled_process_runs_everything_but_the_run_time_build(U):
+    """A process with a profiler's tool library named in its environment: asking for a kernel that
+    would have to be built at run time is an error with a message, while the built-in
+    specialization and the interpreting forms run."""
+    from profiled_child import run_profiled_child
+    run_profiled_child(True)
+
+
+@pytest.mark.parametrize("kernel", (0, LANE_COMPILED, LANE_RUNTIME))
 def test_full_size_grid4(U, kernel):
-    """10^7 configurations, in the launch configurations the benchmark times (the kernel built at
-    run time with the tables as constants, and the library's own choice among the built-in forms):
+    """10^7 configurations, in the launch configurations the benchmark times (the library's own
+    choice, which is the specialized kernel built into it for the Llama-style table; the form that
+    reads the compiled tables from its arguments; the specialized kernel built at run time):
     m_peak and all detail columns (including the timeline walk) of every configuration against
     the oracle."""
     import paper_2404_10933_amd as M
@@ -243,6 +273,7 @@ def test_full_size_grid4(U, kernel):
     n = ref["n"]
     dev = M.DeviceConfigs.from_numpy(ref["cfg"])
     tab = M.Tables(ref["tables"], m_base=CONST.m_base, cu_p=CONST.cu_p, align=CONST.align, kernel=kernel)
+    assert M.llmem_kernel_forms(tab)["prebuilt"] == [True, True, True]
     peaks = torch.empty(n, dtype=torch.int64, device="cuda")
     det = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
     M.llmem_estimate_ex(dev, tab, peaks, det)

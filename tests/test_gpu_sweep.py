@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 CONST = T.Constants(m_base=256 << 20)
 CONST0 = T.Constants(m_base=0)
 GIB = 1 << 30
-KERNEL_LANE_EVENTS, KERNEL_LANE_SPECIALIZED = 3, 5          # LLMEM_KERNEL_*
+KERNEL_LANE_EVENTS, KERNEL_LANE_COMPILED, KERNEL_LANE_SPECIALIZED, KERNEL_LANE_RUNTIME = 3, 4, 5, 6     # LLMEM_KERNEL_*
 GRIDS = {1: (G.grid1, "gpt"), 2: (G.grid2, "opt"), 3: (G.grid3, "llama"), 4: (G.grid4, "llama")}
 
 
@@ -81,13 +81,18 @@ def test_events_form_of_the_kernel(U):
 
 @pytest.mark.parametrize("grid_id,n", ((1, 432), (2, 20_000), (4, 30_037)))
 def test_specialized_form_of_the_kernel(U, grid_id, n):
-    """The sweep built at run time with the tables as constants; a second table set in the same
-    process gets its own build."""
+    """The sweep with the tables as constants: the kernel built into the library for the shipped
+    tables, the same built at run time, and the form that reads the compiled tables from its
+    arguments; a table set the library does not ship gets a run-time build of its own."""
     for seed, first, m_total in ((0, 0, 40 * GIB), (7, 123_456_789 if grid_id > 1 else 0, 2 * GIB)):
-        _check(U, grid_id, seed, first, n, m_total, kernel=KERNEL_LANE_SPECIALIZED)
+        for kernel in (KERNEL_LANE_SPECIALIZED, KERNEL_LANE_RUNTIME, KERNEL_LANE_COMPILED):
+            _check(U, grid_id, seed, first, n, m_total, kernel=kernel)
     if grid_id == 4:
-        _check(U, 4, 3, 0, 8_000, 60 * GIB, tables=[T.llama_table(checkpoint=False)], kernel=KERNEL_LANE_SPECIALIZED)
-        # several architectures in one specialization (the grids draw architecture 0 only)
+        for kernel in (KERNEL_LANE_SPECIALIZED, KERNEL_LANE_RUNTIME):
+            _check(U, 4, 3, 0, 8_000, 60 * GIB, tables=[T.llama_table(checkpoint=False)], kernel=kernel)
+        # several architectures in one specialization (the grids draw architecture 0 only): the shipped
+        # set of three, and a pair that is built at run time
+        _check(U, 2, 3, 0, 8_000, 60 * GIB, tables=[T.gpt_table(), T.opt_table(), T.llama_table()], kernel=0)
         _check(U, 4, 3, 0, 8_000, 60 * GIB, tables=[T.llama_table(), T.gpt_table()], kernel=KERNEL_LANE_SPECIALIZED)
 
 
@@ -155,12 +160,13 @@ def test_full_size_grid4(U):
         assert A.config_score2(method, bs, d) == score2
 
 
-@pytest.mark.parametrize("kernel", (0, 5))
+@pytest.mark.parametrize("kernel", (0, 4, 6))
 def test_calls_recorded_in_a_graph_and_replayed(U, kernel):
     """The entry points allocate nothing and do not synchronize (the run-time build aside, done by
     a call before the capture): estimate, decision, sweep reset and sweep recorded into one HIP
     graph, replayed with new inputs in the same buffers and eager work in between; every replay
-    equals the oracle."""
+    equals the oracle.  The library's own choice (the specialization built into it) and the form
+    that reads its tables from the arguments are recorded without any call before the capture."""
     import paper_2404_10933_amd as M
     n, m_total = 64 * 25 + 7, 70 << 30
     tables = [T.llama_table()]
@@ -190,7 +196,8 @@ def test_calls_recorded_in_a_graph_and_replayed(U, kernel):
         return cfg, q, q_tp
 
     load(0)
-    calls()                                               # builds the specialized kernels where asked for
+    if kernel == 6:
+        calls()                                           # builds the specialized kernels
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())

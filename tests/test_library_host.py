@@ -29,14 +29,14 @@ def test_exports_every_declared_symbol(lib):
             "llmem_events_count", "llmem_events_generate", "llmem_config_bytes", "llmem_events_bytes",
             "llmem_strerror", "llmem_abi_version", "llmem_selftest_divide", "llmem_kernel_forms",
             "llmem_estimate_methods", "llmem_decide", "llmem_queries_generate", "llmem_sweep",
-            "llmem_sweep_reset"} <= names
+            "llmem_sweep_reset", "llmem_compiled_tables"} <= names
     for n in names:
         assert hasattr(lib, n), n
 
 
 def test_abi_and_sizes(lib):
     import paper_2404_10933_amd as M
-    assert M.llmem_abi_version() == 3
+    assert M.llmem_abi_version() == 4
     assert M.llmem_config_bytes(10) == 10 * 31 and M.llmem_config_bytes(-1) == 0
     assert M.llmem_events_bytes(2) == 2 * 6 * 3450 * 8
     assert "NULL" in M.llmem_strerror(-1) and "unknown" in M.llmem_strerror(-99)
@@ -170,37 +170,18 @@ def test_embedded_sources_cover_the_kernel_and_its_headers():
         assert f'"{name}"' in text
         for inc in re.findall(r'#include "([^"]+)"', open(path).read()):
             assert os.path.basename(inc) in embedded + ["specialized_prog.h"], (name, inc)
+    # the constants header is included through a macro whose default is the run-time build's file
+    assert '#define LLMEM_SPEC_HEADER "specialized_prog.h"' in open(build.EMBEDDED[0][1]).read()
 
 
 def _compiled_counts(table):
-    """What the host compiler of the tables should arrive at, counted here from the table's own
-    definition: parameter groups (equal size expressions), size classes of the events, and per
-    segment the peak points (an allocation followed by a release or the segment's end) that no
-    other point of the segment dominates, plus the terms of the kept points and net changes."""
-    from workloads import tables as T
-
-    def product(dims):
-        return tuple(sorted(d for d in dims if d != "one"))
-
-    groups = {(p.coef, product(p.dims)) for p in table.params}
-    key = lambda e: (e.coef, product(e.dims), e.elem_bytes, e.times_L, e.scale == "tp_gather", frozenset(e.methods))
-    classes = sorted({key(e) for e in table.events}, key=repr)
-    terms = points = 0
-    for seg in T.SEGMENTS:
-        evs = [e for e in table.events if e.seg == seg]
-        count, seen = {c: 0 for c in classes}, []
-        for j, e in enumerate(evs):
-            count[key(e)] += e.sign
-            if e.sign > 0 and (j + 1 == len(evs) or evs[j + 1].sign < 0):
-                seen.append(tuple(count[c] for c in classes))
-        kept = []
-        for j, v in enumerate(seen):
-            dominated = any(k != j and all(a <= b for a, b in zip(v, w)) and (v != w or k < j) for k, w in enumerate(seen))
-            if not dominated:
-                kept.append(v)
-        points += len(kept)
-        terms += sum(1 for v in kept + [tuple(count[c] for c in classes)] for x in v if x != 0)
-    return dict(param_groups=len(groups), size_classes=len(classes), terms=terms, peak_points=points)
+    """What the host compiler of the tables should arrive at, counted from the table's own
+    definition by the oracle side's census: parameter groups (equal size expressions), size
+    classes of the events, and per segment the peak points (an allocation followed by a release
+    or the segment's end) that no other point of the segment dominates, plus the terms of the
+    kept points and net changes."""
+    from oracle import census
+    return census.lean_counts(table)
 
 
 def test_table_compiler_statistics(lib):
@@ -214,7 +195,7 @@ def test_table_compiler_statistics(lib):
         forms = M.llmem_kernel_forms(M.Tables([t], device=None))
         want = _compiled_counts(t)
         assert {k: forms[k] for k in want} == want, t.name
-        assert 4 in forms["allowed"] and 5 in forms["allowed"]
+        assert {4, 5, 6} <= set(forms["allowed"])
     llama = M.llmem_kernel_forms(M.Tables([T.llama_table()], device=None))
     assert (llama["param_groups"], llama["size_classes"], llama["peak_points"], llama["terms"]) == (5, 20, 33, 125)
     both = M.llmem_kernel_forms(M.Tables([T.gpt_table(), T.llama_table()], device=None))
@@ -223,6 +204,50 @@ def test_table_compiler_statistics(lib):
     many = T.random_table(rng, 5, 400, "many")
     assert _compiled_counts(many)["size_classes"] > 48
     assert M.llmem_kernel_forms(M.Tables([many], device=None))["allowed"] == [1]
+
+
+def test_built_in_specializations_match_the_shipped_tables(lib):
+    """Every table set the build step lists has a built-in specialized kernel for each flavour,
+    found by comparing the compiled words; other tables, and the same tables in another order
+    or with one coefficient changed, have none."""
+    import dataclasses
+    import paper_2404_10933_amd as M
+    from paper_2404_10933_amd import build
+    from workloads import tables as T
+    sets = build.shipped_table_sets()
+    assert {name for name, _ in sets} >= {"gpt", "opt", "llama", "llama_full", "zoo"}
+    for name, tables in sets:
+        for consts in (dict(), dict(m_base=1 << 28, cu_p=1 << 20, align=256)):       # constants are not part of the words
+            forms = M.llmem_kernel_forms(M.Tables(tables, device=None, **consts))
+            assert forms["prebuilt"] == [True, True, True], name
+        words, first = M.llmem_compiled_tables(M.Tables(tables, device=None))
+        assert len(words) == forms["program_words"] and first[0] == 0 and len(first) == 8
+        assert all(first[q] == 0 for q in range(len(tables), 8))
+    rng = np.random.default_rng(9)
+    others = [[T.random_table(rng, 20, 60, "r", n_sizes=7)], [T.llama_table(), T.gpt_table()],
+              [T.opt_table(), T.gpt_table(), T.llama_table()]]
+    llama = T.llama_table()
+    changed = dataclasses.replace(llama, events=(dataclasses.replace(llama.events[0], coef=llama.events[0].coef + 1),)
+                                  + llama.events[1:])
+    others.append([changed])
+    for tables in others:
+        forms = M.llmem_kernel_forms(M.Tables(tables, device=None))
+        assert forms["prebuilt"] == [False, False, False] and 5 in forms["allowed"]
+    # tables that do not admit the compiled form have no words
+    many = T.random_table(rng, 5, 400, "many")
+    with pytest.raises(M.LlmemError) as e:
+        M.llmem_compiled_tables(M.Tables([many], device=None))
+    assert e.value.code == -3
+
+
+def test_run_time_build_refused_under_a_profiler(lib):
+    """With a profiler's tool library named in the environment (and no directory of kept code
+    objects) the library does not start the run-time compiler: a call that would have to build
+    returns LLMEM_EHIP with a message naming LLMEM_KERNEL_CACHE, before any device or compiler call
+    - so this runs without a GPU, on host tensors that are never touched.  In a child process, so
+    that the variable is set before the library loads."""
+    from profiled_child import run_profiled_child
+    run_profiled_child(False)
 
 
 def test_every_entry_point_raises_without_the_library():
@@ -247,7 +272,7 @@ i64 = lambda *shape: torch.zeros(shape, dtype=torch.int64)
 i32 = lambda *shape: torch.zeros(shape, dtype=torch.int32)
 tp = torch.ones(n, dtype=torch.uint8)
 calls = [lambda: M.llmem_abi_version(), lambda: M.llmem_config_bytes(3), lambda: M.llmem_events_bytes(3),
-         lambda: M.llmem_strerror(0), lambda: M.llmem_kernel_forms(tab),
+         lambda: M.llmem_strerror(0), lambda: M.llmem_kernel_forms(tab), lambda: M.llmem_compiled_tables(tab),
          lambda: M.llmem_estimate(cfg, tab, i64(n)), lambda: M.llmem_estimate_ex(cfg, tab, i64(n), i64(M.NDETAIL, n)),
          lambda: M.llmem_estimate_methods(cfg, tp, tab, i64(4, n)),
          lambda: M.llmem_decide(cfg, tp, tab, 1 << 30, i32(n), i32(n), i64(M.NDECIDE, n)),
