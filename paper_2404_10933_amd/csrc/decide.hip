@@ -119,18 +119,28 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
     const int cu_shift = a.cu_shift, align_shift = a.align_shift;
 
     for (long long b = (long long)blockIdx.x * DC_WAVES + wave; b < n_batch; b += (long long)gridDim.x * DC_WAVES) {
-        const long long i = (b << 6) + lane;
-        const bool in_range = i < n;
-        u32 h = 1, ffn = 0, V = 0, P = 0, arch_id = 0, g = 1, cflags = 0, L = 0, n_heads = 1, n_kv = 0, bs = 0,
-            sl = 0, tp = 0;
-        int chunk_k = 0;
-        if (in_range) {
-            h = a.cfg.h[i]; ffn = a.cfg.ffn[i]; V = a.cfg.V[i]; P = a.cfg.P[i];
-            arch_id = a.cfg.arch_id[i]; g = a.cfg.d[i]; cflags = a.cfg.flags[i];
-            L = a.cfg.L[i]; n_heads = a.cfg.n_heads[i]; n_kv = a.cfg.n_kv[i];
-            chunk_k = a.cfg.chunk_k[i]; bs = a.cfg.bs[i]; sl = a.cfg.sl[i];
-            if (a.tp_n) tp = a.tp_n[i];
-        }
+        // The 64 queries of a batch start at a wave-uniform position: every column is read at that
+        // position plus the lane (a 32-bit offset); lanes past the end read the last query again and
+        // are masked afterwards.  The column pointers are read from the argument segment again for
+        // every batch (scalar loads) instead of occupying 30 scalar registers through all of it.
+        const long long first = b << 6, left = n - first;
+        const bool in_range = (long long)lane < left;
+        const u32 last = left < 64 ? (u32)left - 1u : 63u;
+        const u32 lane_at = (u32)lane < last ? (u32)lane : last;
+        const char __attribute__((address_space(4))) *segment =
+            (const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr();
+        asm volatile("" : "+s"(segment));
+#define LLMEM_COLUMN(field) (*(decltype(a.cfg.field) const __attribute__((address_space(4))) *)( \
+        segment + __builtin_offsetof(DecideArgs, cfg) + __builtin_offsetof(llmem_configs, field)))
+        const u32 h = (LLMEM_COLUMN(h) + first)[lane_at], ffn = (LLMEM_COLUMN(ffn) + first)[lane_at], V = (LLMEM_COLUMN(V) + first)[lane_at],
+                  P = (LLMEM_COLUMN(P) + first)[lane_at], arch_id = (LLMEM_COLUMN(arch_id) + first)[lane_at],
+                  g = (LLMEM_COLUMN(d) + first)[lane_at], cflags = (LLMEM_COLUMN(flags) + first)[lane_at],
+                  L = (LLMEM_COLUMN(L) + first)[lane_at], n_heads = (LLMEM_COLUMN(n_heads) + first)[lane_at],
+                  n_kv = (LLMEM_COLUMN(n_kv) + first)[lane_at], bs = (LLMEM_COLUMN(bs) + first)[lane_at],
+                  sl = (LLMEM_COLUMN(sl) + first)[lane_at];
+        const int chunk_k = (LLMEM_COLUMN(chunk_k) + first)[lane_at];
+#undef LLMEM_COLUMN
+        const u32 tp = a.tp_n ? (a.tp_n + first)[lane_at] : 0u;
         u32 err = 0;
         if (arch_id >= (u32)a.n_arch) err |= LLMEM_F_ERR_ARCH;
         if (g == 0) err |= LLMEM_F_ERR_D;
@@ -214,12 +224,8 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
             k_used = k < K_SEARCH_MIN ? K_SEARCH_MIN : k > K_SEARCH_MAX ? K_SEARCH_MAX : k;
         }
         k_used = (k_used < 0 || k_used > K_FIXED_MAX) ? 0 : k_used;          // invalid lanes: any defined shift
-        const u64 cs_mask = (1ull << (k_used + 19)) - 1;
-        const u64 chunked = embed_p + ((other_p + cs_mask) & ~cs_mask);
-        const u64 m_p = d_up(chunked * (B16 + B32), cu_shift);
-        const u64 m_p16 = d_up(chunked * B16, cu_shift);
-        const u64 m_p32 = d_up(chunked * B32, cu_shift);
-        u32 flags = t_max > cs_mask + 1 ? LLMEM_F_CHUNK_INFEASIBLE : 0;
+        const int cs_shift = k_used + 19;                                    // 2^k MiB of fp16 values
+        u32 flags = t_max > (1ull << cs_shift) ? LLMEM_F_CHUNK_INFEASIBLE : 0;
 
         // ---- Sec. 4.1: gradients alias param fp16 unless switched off
         u64 grad_cdp = 0, grad_sharded = 0;
@@ -231,15 +237,52 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
         // ---- batch-independent parts (Sec. 4.2, Sec. 5)
         QueryTerms q;
         const u64 head = lm_p * B16;
-        q.fixed[LLMEM_METHOD_CDP] = (u64)a.m_base + m_p + m_os + head + grad_cdp;
-        q.fixed[LLMEM_METHOD_ZERO3] = (u64)a.m_base + m_p16 + d_up(d_cdiv(m_p32 + m_os, g, div_g), align_shift) + head + grad_sharded;
-        q.fixed[LLMEM_METHOD_TP] = (u64)a.m_base + d_up(d_cdiv(m_p + m_os, g, div_g), align_shift) + head + grad_sharded;
-        // DP+TP: m_peak^dp minus the share of param fp16 that tensor parallelism removes
         const u32 tp1 = tp ? tp : 1u;
-        const u64 removed = d_up(d_cdiv(m_p16 * tp1, g, div_g), align_shift);
-        const u64 removed_other = d_up(d_cdiv(m_p16 * (tp1 - 1), tp1, div_t), align_shift);
-        q.fixed[LLMEM_METHOD_HYBRID] = q.fixed[LLMEM_METHOD_ZERO3] - removed;
-        if (tp > 0 && removed != removed_other) flags |= LLMEM_F_HYBRID_READINGS_DIFFER;
+        // Model states in 32-bit counts of pages and allocator blocks.  A chunk of 2^(k+19) elements is
+        // a whole number of pages at 2, 4 and 6 bytes per element once k + 20 >= log2 cu_p: the chunked
+        // part of m_p, m_p16, m_p32 needs no rounding, the embedding's part is rounded on its own, and a
+        // page is a whole number of blocks, so each shard is one 32-bit division of a block count (the
+        // DP+TP share: of m_p16's blocks times tp_n).  Used by waves whose queries all keep every count
+        // below 2^31 (checked through an upper bound in bytes); the same values as the byte form below.
+        const u64 states_bound = ((other_p + embed_p + (1ull << cs_shift)) * (B16 + B32) + m_os + (4ull << cu_shift)) * tp1;
+        const bool states_ok = cu_shift >= 1 && cs_shift + 1 >= cu_shift && ((other_p | embed_p) >> 48) == 0
+                               && (m_os >> 54) == 0 && (states_bound >> (align_shift + 31)) == 0;
+        if (__builtin_amdgcn_ballot_w64(valid && !states_ok) == 0) {
+            const int half_shift = cu_shift - 1, page_shift = cu_shift - align_shift;
+            const int rel_shift = states_ok ? cs_shift - half_shift : 0;     // lanes that take no part: any defined shift
+            const u64 half_round = (1ull << half_shift) - 1;
+            const u32 chunks = (u32)((other_p + ((1ull << cs_shift) - 1)) >> cs_shift);      // ceil(other_p / cs)
+            const u32 chunk_pages = chunks << rel_shift;                                     // at 2 bytes per element
+            const u32 p16_pages = chunk_pages + (u32)((embed_p + half_round) >> half_shift);
+            const u32 p32_pages = 2u * chunk_pages + (u32)((embed_p * 2 + half_round) >> half_shift);
+            const u32 p_pages = 3u * chunk_pages + (u32)((embed_p * 3 + half_round) >> half_shift);
+            const u32 os_pages = (u32)(m_os >> cu_shift);
+            const u32 p16_blocks = p16_pages << page_shift;
+            const u64 common = (u64)a.m_base + head;
+            const u32 z_shard = d_cdiv32((p32_pages + os_pages) << page_shift, g, div_g);
+            const u32 t_shard = d_cdiv32((p_pages + os_pages) << page_shift, g, div_g);
+            const u32 removed = d_cdiv32(p16_blocks * tp1, g, div_g);
+            const u32 removed_other = d_cdiv32(p16_blocks * (tp1 - 1), tp1, div_t);
+            q.fixed[LLMEM_METHOD_CDP] = common + ((u64)(p_pages + os_pages) << cu_shift) + grad_cdp;
+            q.fixed[LLMEM_METHOD_ZERO3] = common + ((u64)(p16_blocks + z_shard) << align_shift) + grad_sharded;
+            q.fixed[LLMEM_METHOD_TP] = common + ((u64)t_shard << align_shift) + grad_sharded;
+            q.fixed[LLMEM_METHOD_HYBRID] = common + ((u64)(p16_blocks + z_shard - removed) << align_shift) + grad_sharded;
+            if (tp > 0 && removed != removed_other) flags |= LLMEM_F_HYBRID_READINGS_DIFFER;
+        } else {
+            const u64 cs_mask = (1ull << cs_shift) - 1;
+            const u64 chunked = embed_p + ((other_p + cs_mask) & ~cs_mask);
+            const u64 m_p = d_up(chunked * (B16 + B32), cu_shift);
+            const u64 m_p16 = d_up(chunked * B16, cu_shift);
+            const u64 m_p32 = d_up(chunked * B32, cu_shift);
+            q.fixed[LLMEM_METHOD_CDP] = (u64)a.m_base + m_p + m_os + head + grad_cdp;
+            q.fixed[LLMEM_METHOD_ZERO3] = (u64)a.m_base + m_p16 + d_up(d_cdiv(m_p32 + m_os, g, div_g), align_shift) + head + grad_sharded;
+            q.fixed[LLMEM_METHOD_TP] = (u64)a.m_base + d_up(d_cdiv(m_p + m_os, g, div_g), align_shift) + head + grad_sharded;
+            // DP+TP: m_peak^dp minus the share of param fp16 that tensor parallelism removes
+            const u64 removed = d_up(d_cdiv(m_p16 * tp1, g, div_g), align_shift);
+            const u64 removed_other = d_up(d_cdiv(m_p16 * (tp1 - 1), tp1, div_t), align_shift);
+            q.fixed[LLMEM_METHOD_HYBRID] = q.fixed[LLMEM_METHOD_ZERO3] - removed;
+            if (tp > 0 && removed != removed_other) flags |= LLMEM_F_HYBRID_READINGS_DIFFER;
+        }
         const u64 slh = (u64)sl * h;
         q.c_out = ((u64)e_n + L) * slh * B16;
         q.c_logits = (u64)V * Blog * sl;
@@ -254,9 +297,9 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
                 for (int m = 0; m < 4; ++m) {
                     i64 v = peak_at(q, m, bs);
                     if (err || (m == LLMEM_METHOD_HYBRID && tp == 0)) v = -1;
-                    put(&a.out_peaks[(long long)m * n + i], v);
+                    put(&(a.out_peaks + (long long)m * n + first)[(u32)lane], v);
                 }
-                if (a.out_flags) put(&a.out_flags[i], err ? (i64)err : (i64)flags);
+                if (a.out_flags) put(&(a.out_flags + first)[(u32)lane], err ? (i64)err : (i64)flags);
             }
             continue;
         }
@@ -267,9 +310,10 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
         // rounding, which brackets it first:
         //   fixed + bs * growth  <=  m_peak(bs)  <=  fixed + bs * growth + 6 pages
         // (growth: bytes per sample of m_out, the logits, the two shifted copies and 1/t of the TP
-        // buffer; four round-ups to a page plus two in the buffer).  The upper end is safe against
-        // the rounding of the single-precision quotient (two more than its integer part); the
-        // lower end is checked by an estimate of its own and dropped to 0 if it does not fit.
+        // buffer; four round-ups to a page plus two in the buffer).  Both ends are moved out by more
+        // than the rounding of the single-precision quotient can amount to; where that cannot be
+        // shown for the lower end it is checked by an estimate of its own and dropped to 0 if that
+        // does not fit.
         const u32 cap = valid ? bs : 0u;
         u32 best[4], top[4];                                                // the bracket: lower and upper end
 
@@ -298,14 +342,17 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
             return d_cdiv32(b * whole + ceil_pages(b, r), t, div);
         };
 
-        // lower end checked, then the bracket bisected
-        auto search = [&](auto fits) {
+        // lower end checked where the bracket's derivation does not vouch for it (`confirm`, the same
+        // for the whole wave), then the bracket bisected
+        auto search = [&](auto fits, const bool confirm) {
             u32 span = 0;
+            if (confirm) {
 #pragma unroll
-            for (int m = 0; m < 4; ++m) {
-                if (best[m] > 0 && !fits(m, best[m])) best[m] = 0;
-                span |= top[m] - best[m];
+                for (int m = 0; m < 4; ++m)
+                    if (best[m] > 0 && !fits(m, best[m])) best[m] = 0;
             }
+#pragma unroll
+            for (int m = 0; m < 4; ++m) span |= top[m] - best[m];
             for (int s = 32; s >= 1; s >>= 1) span |= (u32)__shfl_xor((int)span, s, 64);
             const int bits = 32 - __builtin_clz(d_uni(span) | 1u);
             for (int bit = bits - 1; bit >= 0; --bit) {                   // best + 2^bit, 2^bit above what is left of the span
@@ -338,23 +385,28 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
                 if (room < 0) {
                     hi = 0;                                               // not even the fixed part fits
                 } else if (growth > 0.0f) {
-                    // single precision: G, 1 / G and the product are each within a few units of the
-                    // last place, the quotient within 10 * 2^-24 of R / G, which is below 0.04 for
-                    // quotients under the cap (at most 65535); the ends move out by 0.25
+                    // Single precision: G, 1 / G and the products are each within a few units of the last
+                    // place; the computed quotient is within 16 * 2^-24 = 1e-6 of R / G relatively.
+                    // Upper end: used for quotients under the cap (at most 65535), where that is below
+                    // 0.07; moved out by 0.25.  Lower end: (R - 6) / G computed as quotient - 6.5 / G - 0.25;
+                    // its error is at most (1e-6 * R + 1e-5) / G, which the extra 0.5 / G covers while
+                    // R < 2^18 pages - then every batch size up to the lower end fits without being
+                    // probed.  A wave with a query of more room confirms its lower ends by a probe.
                     const float inv = __builtin_amdgcn_rcpf(growth);
                     const float upper = (float)room_pages[m] * inv;
                     if (upper < (float)cap) { const u32 u = (u32)(upper + 0.25f); hi = u < cap ? u : cap; }
-                    const float lower = upper - 6.25f * inv - 0.25f;
+                    const float lower = upper - 6.5f * inv - 0.25f;
                     if (lower > 0.0f) lo = lower < (float)hi ? (u32)lower : hi;
                 }
                 best[m] = lo; top[m] = hi;
             }
+            const bool much_room = ((room_pages[0] | room_pages[1] | room_pages[2] | room_pages[3]) >> 18) != 0;
             search([&](int m, u32 b) -> bool {
                 u32 p = plain_pages(b);
                 if (m == LLMEM_METHOD_TP) p += back_pages(b, back_whole_tp, r_back_tp, g, div_g);
                 if (m == LLMEM_METHOD_HYBRID) p += back_pages(b, back_whole_hy, r_back_hy, tp1, div_t);
                 return p <= room_pages[m];
-            });
+            }, __builtin_amdgcn_ballot_w64(valid && much_room) != 0);
         } else {
             // the same bracket in bytes
             const float slope = (float)(q.c_out + q.c_logits + 2 * q.c_shifted);
@@ -376,7 +428,7 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
                 }
                 best[m] = lo; top[m] = hi;
             }
-            search([&](int m, u32 b) -> bool { return peak_at(q, m, b) <= a.m_total; });
+            search([&](int m, u32 b) -> bool { return peak_at(q, m, b) <= a.m_total; }, true);
         }
         if (tp == 0) best[LLMEM_METHOD_HYBRID] = 0;
         // scores (doubled) and the choice
@@ -412,23 +464,21 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
         }
         if (in_range) {
             const bool bad = err != 0;
-            // the index is formed again here (two instructions) rather than kept through the search
-            int lane_again = lane;
-            asm volatile("" : "+v"(lane_again));
-            const long long at = (b << 6) + lane_again;
-            if (a.out_method) put(&a.out_method[at], bad ? -1 : method);
-            if (a.out_bs) put(&a.out_bs[at], bad ? 0 : (int)chosen_bs);
+            // the batch's position is wave-uniform; the lane is a 32-bit offset from it
+            const u32 at = (u32)lane;
+            if (a.out_method) put(&(a.out_method + first)[at], bad ? -1 : method);
+            if (a.out_bs) put(&(a.out_bs + first)[at], bad ? 0 : (int)chosen_bs);
             if (a.out_detail) {
-                long long *o = a.out_detail + at;
-                put(&o[LLMEM_C_METHOD * n], bad ? -1 : method);
-                put(&o[LLMEM_C_BS * n], bad ? 0 : (i64)chosen_bs);
+                long long *o = a.out_detail + first;
+                put(&(o + LLMEM_C_METHOD * n)[at], bad ? -1 : method);
+                put(&(o + LLMEM_C_BS * n)[at], bad ? 0 : (i64)chosen_bs);
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
-                    put(&o[(LLMEM_C_BS_CDP + m) * n], bad ? 0 : (i64)best[m]);
-                    put(&o[(LLMEM_C_SCORE2_CDP + m) * n], bad ? 0 : score2[m]);
+                    put(&(o + (LLMEM_C_BS_CDP + m) * n)[at], bad ? 0 : (i64)best[m]);
+                    put(&(o + (LLMEM_C_SCORE2_CDP + m) * n)[at], bad ? 0 : score2[m]);
                 }
-                put(&o[LLMEM_C_PEAK * n], bad ? 0 : peak);
-                put(&o[LLMEM_C_FLAGS * n], bad ? (i64)err : (i64)flags);
+                put(&(o + LLMEM_C_PEAK * n)[at], bad ? 0 : peak);
+                put(&(o + LLMEM_C_FLAGS * n)[at], bad ? (i64)err : (i64)flags);
             }
         }
     }

@@ -82,6 +82,7 @@ __constant__ unsigned SPEC_PROG_MEM[] = {LLMEM_SPEC_WORDS};          // the same
 // behind this point instead of being hoisted to the start of the batch (registers).
 #define LLMEM_ANCHOR(x) asm volatile("" : "+v"(x))
 #define LLMEM_WAVES_PER_SIMD SPEC_WAVES
+#define LLMEM_TERM_IS_PADDING(word) ((word) == 0u)            // known when compiling: the term vanishes
 #else
 #define LLMEM_PROG(i) a.prog[i]
 #define LLMEM_PROG_LOOP(i) a.prog[i]
@@ -89,6 +90,7 @@ __constant__ unsigned SPEC_PROG_MEM[] = {LLMEM_SPEC_WORDS};          // the same
 #define LLMEM_UNROLL_NARROW
 #define LLMEM_ANCHOR(x)
 #define LLMEM_WAVES_PER_SIMD 5
+#define LLMEM_TERM_IS_PADDING(word) false                     // a wave-uniform test would cost more than the term
 #endif
 
 namespace llmem {
@@ -111,6 +113,14 @@ __device__ __forceinline__ u64 b_div(u64 x, u32 d, u64 mul, u32 shift)
     return d == 1 ? x : (__umul64hi(x, mul) >> shift);
 }
 __device__ __forceinline__ u64 b_cdiv(u64 x, u32 d, u64 mul, u32 shift) { return b_div(x + (d - 1), d, mul, shift); }
+// ceil(x / d) for x + d - 1 < 2^32: the multiply-high of the same 64-bit constant with a 32-bit dividend
+__device__ __forceinline__ u32 b_cdiv32(u32 x, u32 d, u64 mul, u32 shift)
+{
+    const u32 dividend = x + (d - 1);
+    const u64 low = (u64)dividend * (u32)mul;
+    const u64 high = (u64)dividend * (u32)(mul >> 32) + (low >> 32);
+    return d == 1 ? x : (u32)(high >> 32) >> shift;
+}
 __device__ __forceinline__ u64 b_up(u64 x, int shift) { return ((x + ((1ull << shift) - 1)) >> shift) << shift; }
 // x * m (mod 2^64) in three instructions: the 64-bit product of the low half, the low 32 bits of
 // the high half's product (kept as one v_mul_lo_u32, which issues at full rate on gfx950), one add
@@ -120,6 +130,12 @@ __device__ __forceinline__ u64 mul_64x32(u64 x, u32 m)
     u32 hi_part;
     asm("v_mul_lo_u32 %0, %1, %2" : "=v"(hi_part) : "v"((u32)(x >> 32)), "v"(m));
     return ((u64)(hi_part + (u32)(lo >> 32)) << 32) | (u64)(u32)lo;
+}
+// acc + value * factor with value and the wave-uniform factor sign-extended from 32 bits, in one instruction
+__device__ __forceinline__ i64 mad_i64_i32(int value, int factor, i64 acc)
+{
+    asm("v_mad_i64_i32 %0, vcc, %1, %2, %0" : "+v"(acc) : "v"(value), "s"(factor) : "vcc");
+    return acc;
 }
 __device__ __forceinline__ u32 uni(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
 // Results are written once and not read again: streaming stores, which do not keep the lines in
@@ -228,29 +244,54 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 
     // the columns of one configuration as loaded
     struct Raw { u32 h, ffn, V, P, arch_id, method, d, cflags, L, n_heads, n_kv, bs, sl; int chunk_k; };
+    // The 64 configurations of a batch start at a wave-uniform position: every column is read at
+    // that position plus the lane (a 32-bit offset), lanes past the end of the grid read its last
+    // configuration again and are masked afterwards.
     auto fetch = [&](long long batch) -> Raw {
         Raw r = {1, 0, 0, 0, 0, 0, 1, 0, 0, 1, 0, 0, 0, 0};
-        const long long i = (batch << 6) + lane;
+        const long long first = batch << 6;
         if (SWEEP) {
-            if (batch < n_batch && i < n) {
+            const long long i = first + lane;
+            if (i < n) {
                 const DrawnConfig g = draw_config(a.sweep_grid, a.sweep_seed, (u64)(a.sweep_first + i));
                 r.h = g.h; r.ffn = g.ffn; r.V = g.V; r.P = g.P; r.arch_id = g.arch_id; r.method = g.method; r.d = g.d;
                 r.cflags = g.flags; r.L = g.L; r.n_heads = g.n_heads; r.n_kv = g.n_kv; r.chunk_k = g.chunk_k;
                 r.bs = g.bs; r.sl = g.sl;
             }
-        } else if (batch < n_batch && i < n) {
-            r.h = a.cfg.h[i]; r.ffn = a.cfg.ffn[i]; r.V = a.cfg.V[i]; r.P = a.cfg.P[i];
-            r.arch_id = a.cfg.arch_id[i]; r.method = a.cfg.method[i]; r.d = a.cfg.d[i]; r.cflags = a.cfg.flags[i];
-            r.L = a.cfg.L[i]; r.n_heads = a.cfg.n_heads[i]; r.n_kv = a.cfg.n_kv[i];
-            r.chunk_k = a.cfg.chunk_k[i]; r.bs = a.cfg.bs[i]; r.sl = a.cfg.sl[i];
+        } else {
+            const long long left = n - first;
+            const u32 last = left < 64 ? (u32)left - 1u : 63u;
+            const u32 at = (u32)lane < last ? (u32)lane : last;
+#ifdef LLMEM_SPECIALIZED
+            // the fourteen column pointers are read from the argument segment again for every batch
+            // (scalar loads) instead of occupying 28 scalar registers through all of it
+            const char __attribute__((address_space(4))) *segment =
+                (const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr();
+            asm volatile("" : "+s"(segment));
+#define LLMEM_COLUMN(field) (*(decltype(a.cfg.field) const __attribute__((address_space(4))) *)( \
+            segment + __builtin_offsetof(EstimateArgs, cfg) + __builtin_offsetof(llmem_configs, field)))
+            llmem_configs c;
+            c.h = LLMEM_COLUMN(h); c.ffn = LLMEM_COLUMN(ffn); c.V = LLMEM_COLUMN(V); c.P = LLMEM_COLUMN(P);
+            c.arch_id = LLMEM_COLUMN(arch_id); c.method = LLMEM_COLUMN(method); c.d = LLMEM_COLUMN(d);
+            c.flags = LLMEM_COLUMN(flags); c.L = LLMEM_COLUMN(L); c.n_heads = LLMEM_COLUMN(n_heads);
+            c.n_kv = LLMEM_COLUMN(n_kv); c.chunk_k = LLMEM_COLUMN(chunk_k); c.bs = LLMEM_COLUMN(bs); c.sl = LLMEM_COLUMN(sl);
+#undef LLMEM_COLUMN
+#else
+            const llmem_configs &c = a.cfg;
+#endif
+            r.h = (c.h + first)[at]; r.ffn = (c.ffn + first)[at]; r.V = (c.V + first)[at]; r.P = (c.P + first)[at];
+            r.arch_id = (c.arch_id + first)[at]; r.method = (c.method + first)[at]; r.d = (c.d + first)[at];
+            r.cflags = (c.flags + first)[at]; r.L = (c.L + first)[at]; r.n_heads = (c.n_heads + first)[at];
+            r.n_kv = (c.n_kv + first)[at]; r.chunk_k = (c.chunk_k + first)[at]; r.bs = (c.bs + first)[at];
+            r.sl = (c.sl + first)[at];
         }
         return r;
     };
     const long long b_step = (long long)gridDim.x * BB_WAVES;
     long long b = (long long)blockIdx.x * BB_WAVES + wave;
     for (; b < n_batch; b += b_step) {
-        const long long i = (b << 6) + lane;
-        const bool in_range = i < n;
+        const long long i = (b << 6) + lane;                       // only the sweep uses it as a value
+        const bool in_range = (long long)lane < n - (b << 6);
         const Raw now = fetch(b);
         const u32 h = now.h, ffn = now.ffn, V = now.V, P = now.P, arch_id = now.arch_id, method = now.method, d = now.d,
                   cflags = now.cflags, L = now.L, n_heads = now.n_heads, n_kv = now.n_kv, bs = now.bs, sl = now.sl;
@@ -275,8 +316,10 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
         const u64 div_mul = div_mul_of[d & 255u];
         const u32 div_shift = d > 1 ? 31u - (u32)__builtin_clz(d - 1) : 0u;        // ceil(log2 d) - 1
 
-        i64 r_peak = err ? -1 : 0, r_param = 0, r_grad = 0, r_os = 0, r_out = 0, r_lm = 0, r_back = 0, r_k = 0,
-            r_live = 0, r_np = 0, r_tmax = 0, r_flags = err;
+        i64 r_peak = err ? -1 : 0, r_k = 0, r_live = 0, r_np = 0;
+#ifndef LLMEM_SPECIALIZED
+        i64 r_param = 0, r_grad = 0, r_os = 0, r_out = 0, r_lm = 0, r_back = 0, r_tmax = 0, r_flags = err;
+#endif
 
         // The lanes of architecture `ar` (the active ones) estimate their configurations.
         // `words`: where the architecture's compiled tables start, WordsFromArguments or WordsAt<N>.
@@ -362,10 +405,23 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
             const u64 row = (u64)bs_here * V * Blog;
             const u64 m_lm = b_up(row * sl, cu_shift) + 2 * b_up(row * D[LLMEM_DIM_SL_M1], cu_shift) + lm_p * B16;
             u64 m_back = 0;
+#ifdef LLMEM_SPECIALIZED
+            {
+                // ceil(x / (d * cu_p)) = ceil(ceil(x / cu_p) / d); the page count is divided in 32 bits
+                // when that of every lane fits
+                u64 pages = 0;
+                if (method == LLMEM_METHOD_TP) pages = ((u64)L * A * (d - 1) * B16 + ((1ull << cu_shift) - 1)) >> cu_shift;
+                if (__builtin_amdgcn_ballot_w64(((pages + 255) >> 32) != 0) == 0)
+                    m_back = (u64)b_cdiv32((u32)pages, d, div_mul, div_shift) << cu_shift;
+                else
+                    m_back = b_cdiv(pages, d, div_mul, div_shift) << cu_shift;
+            }
+#else
             if (method == LLMEM_METHOD_TP) {
                 const u64 pages = ((u64)L * A * (d - 1) * B16 + ((1ull << cu_shift) - 1)) >> cu_shift;
                 m_back = b_cdiv(pages, d, div_mul, div_shift) << cu_shift;
             }
+#endif
             // ---- Sec. 4.1: gradients alias param fp16 unless switched off -------------------
             const u64 grad_bytes = (embed_p + other_p) * B16;
             const u64 grad_logical = method == LLMEM_METHOD_CDP ? grad_bytes : b_cdiv(grad_bytes, d, div_mul, div_shift);
@@ -375,6 +431,21 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                 grad_extra = method == LLMEM_METHOD_CDP ? g : b_up(b_cdiv(g, d, div_mul, div_shift), align_shift);
             }
 
+#ifdef LLMEM_SPECIALIZED
+            // the columns known by now are stored now, so that they do not occupy registers any longer
+            // (the built-in forms, whose batch is a loop over architectures, store everything at the end:
+            // stores inside that loop cost them more registers than they free)
+            if (DETAIL && !SWEEP) {
+                const u32 at = (u32)lane;
+                long long *o = a.out_detail + (b << 6);                 // wave-uniform; the lane is a 32-bit offset
+                put(&(o + (long long)LLMEM_D_GRAD_GPU * n)[at], (i64)grad_logical);
+                put(&(o + (long long)LLMEM_D_OUT * n)[at], (i64)m_out);
+                put(&(o + (long long)LLMEM_D_LM * n)[at], (i64)m_lm);
+                put(&(o + (long long)LLMEM_D_BACK * n)[at], (i64)m_back);
+                put(&(o + (long long)LLMEM_D_NPARAMS * n)[at], (i64)n_params);
+                put(&(o + (long long)LLMEM_D_TMAX * n)[at], (i64)t_max);
+            }
+#endif
             // ---- chunk size (Sec. 4.1), m_p and the method's peak ----------------------------
             // Every candidate k = 2..10 is estimated; the feasible one with the least padding
             // waste wins, ties to the smaller chunk.  A lane with a given chunk size estimates
@@ -404,48 +475,62 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 #else
             const bool page_form = false;
 #endif
+            // the page form's per-lane constants: also used for the detail columns below
+            const int half_shift = cu_shift - 1, page_shift = cu_shift - align_shift;
+            const u32 fw_half = zero3 ? 2u : 3u;                              // m_p32 or m_p: bytes per element / 2
+            u32 embed_wide_pages = 0, embed_p16_pages = 0, os_blocks = 0;
             if (page_form) {
 #ifdef LLMEM_SPECIALIZED
-                const int half_shift = cu_shift - 1, page_shift = cu_shift - align_shift;
-                const u32 fw_half = zero3 ? 2u : 3u;                          // m_p32 or m_p: bytes per element / 2
+                // every size is a 32-bit count of allocator blocks
                 const u64 half_round = (1ull << half_shift) - 1;
-                const u32 embed_wide_pages = (u32)((embed_p * fw_half + half_round) >> half_shift);
-                const u32 embed_p16_pages = (u32)((embed_p + half_round) >> half_shift);
-                const u32 os_pages = (u32)(m_os >> cu_shift);
-                const u32 back_blocks = (u32)(m_back >> align_shift);
+                embed_wide_pages = (u32)((embed_p * fw_half + half_round) >> half_shift);
+                embed_p16_pages = (u32)((embed_p + half_round) >> half_shift);
+                os_blocks = (u32)(m_os >> align_shift);
                 const u32 need_shift = t_max > 1 ? 64u - (u32)__builtin_clzll(t_max - 1) : 0u;   // least s with t_max <= 2^s
-                u32 best_waste = ~0u;
-#ifdef LLMEM_SPECIALIZED
-#pragma nounroll
-#endif
-                for (int j = 0; j <= K_SEARCH_MAX - K_SEARCH_MIN; ++j) {
-                    if (j > 0 && !any_search) break;
-                    const int k = search ? K_SEARCH_MIN + j : chunk_k;
-                    const int cs_shift = k + 19;                              // 2^k MiB of fp16 values
-                    const u64 cs_mask = (1ull << cs_shift) - 1;
-                    const u64 other_chunked = (other_p + cs_mask) & ~cs_mask; // ceil(other_p / cs) * cs
-                    const u32 chunk_pages = (u32)(other_chunked >> half_shift);            // at 2 bytes per element
-                    const u32 to_shard_pages = chunk_pages * fw_half + embed_wide_pages + os_pages;
-                    const u32 to_shard_blocks = to_shard_pages << page_shift;
-                    // ceil(blocks / d): the multiply-high of the 64-bit constants with a 32-bit dividend
-                    const u32 dividend = to_shard_blocks + (d - 1);
-                    const u64 low = (u64)dividend * (u32)div_mul;
-                    const u64 high = (u64)dividend * (u32)(div_mul >> 32) + (low >> 32);
-                    const u32 shard_blocks = d == 1 ? to_shard_blocks : (u32)(high >> 32) >> div_shift;
-                    u32 state_blocks;
-                    if (method == LLMEM_METHOD_CDP) state_blocks = to_shard_blocks;
-                    else if (zero3) state_blocks = ((chunk_pages + embed_p16_pages) << page_shift) + shard_blocks;
-                    else state_blocks = shard_blocks + back_blocks;
-                    const u64 c_peak = rest + ((u64)state_blocks << align_shift);
-                    const u32 waste = (u32)other_chunked - (u32)other_p;      // below the chunk size: 32 bits hold it
-                    const bool feasible = need_shift <= (u32)cs_shift;
-                    const bool take = search ? ((feasible && waste < best_waste) || (!found && j == K_SEARCH_MAX - K_SEARCH_MIN))
-                                             : j == 0;
-                    if (take) {
-                        m_peak = c_peak; k_used = k;
-                        if (feasible) { best_waste = waste; found = true; }
+                const u32 base_blocks = (embed_wide_pages << page_shift) + os_blocks;            // shared out besides the chunks
+                const bool whole = method == LLMEM_METHOD_CDP || d == 1;                        // nothing is divided
+                const u32 kept_blocks = method == LLMEM_METHOD_CDP ? 0u : zero3 ? embed_p16_pages << page_shift
+                                                                                : (u32)(m_back >> align_shift);
+                const u32 div_low = (u32)div_mul, div_high = (u32)(div_mul >> 32);
+                // the model states of candidate k in blocks, its padding waste and whether the largest tensor fits
+                auto candidate = [&](const int k, u32 &state_blocks, u32 &waste, bool &feasible) {
+                    const int cs_shift = k + 19;                                                 // 2^k MiB of fp16 values
+                    const u32 chunks = (u32)((other_p + ((1ull << cs_shift) - 1)) >> cs_shift);  // ceil(other_p / cs)
+                    const u32 chunk_blocks = chunks << (cs_shift - half_shift + page_shift);     // at 2 bytes per element
+                    const u32 to_shard = chunk_blocks * fw_half + base_blocks;                   // m_p32 (or m_p) + m_os
+                    const u32 dividend = to_shard + (d - 1);
+                    const u64 low = (u64)dividend * div_low;
+                    const u64 high = (u64)dividend * div_high + (low >> 32);
+                    const u32 shard = whole ? to_shard : (u32)(high >> 32) >> div_shift;
+                    state_blocks = shard + kept_blocks + (zero3 ? chunk_blocks : 0u);            // ZeRO-3 keeps m_p16 whole
+                    waste = (chunks << cs_shift) - (u32)other_p;       // below the chunk size: exact modulo 2^32 for k <= 10
+                    feasible = need_shift <= (u32)cs_shift;
+                };
+                u32 best_state = 0, best_waste = ~0u;
+                if (__builtin_amdgcn_ballot_w64(!search) != 0) {
+                    // lanes with a given chunk size estimate that one
+                    u32 state, waste;
+                    bool feasible;
+                    candidate(search ? K_SEARCH_MIN : chunk_k, state, waste, feasible);
+                    best_state = state;
+                }
+                if (any_search) {
+                    // the others: strictly smaller waste among feasible candidates; the last one stands in
+                    // when none is feasible
+#pragma unroll
+                    for (int j = 0; j <= K_SEARCH_MAX - K_SEARCH_MIN; ++j) {
+                        u32 state, waste;
+                        bool feasible;
+                        candidate(K_SEARCH_MIN + j, state, waste, feasible);
+                        const bool better = feasible && waste < best_waste;
+                        const bool take = search && (better || (!found && j == K_SEARCH_MAX - K_SEARCH_MIN));
+                        best_state = take ? state : best_state;
+                        k_used = take ? K_SEARCH_MIN + j : k_used;
+                        best_waste = (search && better) ? waste : best_waste;
+                        found = found || (search && better);
                     }
                 }
+                m_peak = rest + ((u64)best_state << align_shift);
 #endif
             } else {
                 u64 best_waste = ~0ull;
@@ -487,39 +572,45 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
             if (DETAIL) {
                 // m_p, m_p16, m_p32 of the chunk size used (formed again here rather than carried
                 // through the candidates: fewer live registers)
-                const u64 used_mask = (1ull << (k_used + 19)) - 1;
-                const u64 used_chunked = embed_p + ((other_p + used_mask) & ~used_mask);
-                const u64 mp = b_up(used_chunked * (B16 + B32), cu_shift), mp16 = b_up(used_chunked * B16, cu_shift),
-                          mp32 = b_up(used_chunked * B32, cu_shift);
                 u64 param_gpu, os_gpu;
-                if (method == LLMEM_METHOD_CDP) {
-                    param_gpu = mp; os_gpu = m_os;
+                if (page_form) {
+                    // in pages and blocks, as the candidates above: the chunked part is whole pages at
+                    // 2, 4 and 6 bytes per element, the shards are 32-bit divisions
+                    const int used_shift = k_used + 19;
+                    const u32 used_chunks = (u32)((other_p + ((1ull << used_shift) - 1)) >> used_shift);
+                    const u32 chunk_pages = used_chunks << (used_shift - half_shift);            // at 2 bytes per element
+                    const u32 wide_pages = chunk_pages * fw_half + embed_wide_pages;             // m_p32 (ZeRO-3) or m_p
+                    const u64 p_sh = (u64)b_cdiv32(wide_pages << page_shift, d, div_mul, div_shift) << align_shift;
+                    param_gpu = method == LLMEM_METHOD_CDP ? (u64)wide_pages << cu_shift
+                                : zero3 ? ((u64)(chunk_pages + embed_p16_pages) << cu_shift) + p_sh : p_sh;
+                    os_gpu = method == LLMEM_METHOD_CDP ? m_os : (u64)b_cdiv32(os_blocks, d, div_mul, div_shift) << align_shift;
                 } else {
-                    const u64 os_sh = b_up(b_cdiv(m_os, d, div_mul, div_shift), align_shift);
-                    const u64 p_sh = b_up(b_cdiv(method == LLMEM_METHOD_ZERO3 ? mp32 : mp, d, div_mul, div_shift), align_shift);
-                    param_gpu = method == LLMEM_METHOD_ZERO3 ? mp16 + p_sh : p_sh;
-                    os_gpu = os_sh;
+                    const u64 used_mask = (1ull << (k_used + 19)) - 1;
+                    const u64 used_chunked = embed_p + ((other_p + used_mask) & ~used_mask);
+                    const u64 mp = b_up(used_chunked * (B16 + B32), cu_shift), mp16 = b_up(used_chunked * B16, cu_shift),
+                              mp32 = b_up(used_chunked * B32, cu_shift);
+                    if (method == LLMEM_METHOD_CDP) {
+                        param_gpu = mp; os_gpu = m_os;
+                    } else {
+                        const u64 os_sh = b_up(b_cdiv(m_os, d, div_mul, div_shift), align_shift);
+                        const u64 p_sh = b_up(b_cdiv(method == LLMEM_METHOD_ZERO3 ? mp32 : mp, d, div_mul, div_shift), align_shift);
+                        param_gpu = method == LLMEM_METHOD_ZERO3 ? mp16 + p_sh : p_sh;
+                        os_gpu = os_sh;
+                    }
                 }
 
 #ifdef LLMEM_SPECIALIZED
-                // every column but the timeline peak is known: stored now, so that none of them
-                // occupies registers during the timeline
+                // every remaining column but the timeline peak is known: stored now, so that none of
+                // them occupies registers during the timeline
                 if (!SWEEP) {
-                    long long at_i = i;
-                    LLMEM_ANCHOR(at_i);
-                    if (a.out_peaks) put(&a.out_peaks[at_i], (i64)m_peak);
-                    long long *o = a.out_detail + at_i;
-                    put(&o[(long long)LLMEM_D_PEAK * n], (i64)m_peak);
-                    put(&o[(long long)LLMEM_D_PARAM_GPU * n], (i64)param_gpu);
-                    put(&o[(long long)LLMEM_D_GRAD_GPU * n], (i64)grad_logical);
-                    put(&o[(long long)LLMEM_D_OS_GPU * n], (i64)os_gpu);
-                    put(&o[(long long)LLMEM_D_OUT * n], (i64)m_out);
-                    put(&o[(long long)LLMEM_D_LM * n], (i64)m_lm);
-                    put(&o[(long long)LLMEM_D_BACK * n], (i64)m_back);
-                    put(&o[(long long)LLMEM_D_K * n], (i64)k_used);
-                    put(&o[(long long)LLMEM_D_NPARAMS * n], (i64)n_params);
-                    put(&o[(long long)LLMEM_D_TMAX * n], (i64)t_max);
-                    put(&o[(long long)LLMEM_D_FLAGS * n], (i64)flags);
+                    const u32 at = (u32)lane;
+                    if (a.out_peaks) put(&(a.out_peaks + (b << 6))[at], (i64)m_peak);
+                    long long *o = a.out_detail + (b << 6);             // wave-uniform; the lane is a 32-bit offset
+                    put(&(o + (long long)LLMEM_D_PEAK * n)[at], (i64)m_peak);
+                    put(&(o + (long long)LLMEM_D_PARAM_GPU * n)[at], (i64)param_gpu);
+                    put(&(o + (long long)LLMEM_D_OS_GPU * n)[at], (i64)os_gpu);
+                    put(&(o + (long long)LLMEM_D_K * n)[at], (i64)k_used);
+                    put(&(o + (long long)LLMEM_D_FLAGS * n)[at], (i64)flags);
                 }
 #endif
                 // what is resident before the iteration starts (one value instead of five during the timeline)
@@ -639,10 +730,14 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                             for (int g = 0; g < PROG_FETCH; g += PROG_GROUP) {
                                 if (NARROW) {
                                     // signed 32-bit blocks times a signed 16-bit factor: one multiply-add each
-                                    i64 part = 0;
+                                    // (written out: left to itself the compiler replaces the products by the
+                                    // small constant factors of a specialized build with sign extensions, shifts
+                                    // and 64-bit adds, two to three instructions per term)
 #pragma unroll
-                                    for (int q = g; q < g + PROG_GROUP; ++q) part += (i64)v32[q] * (i64)((int)t[q] >> 16);
-                                    acc += part;
+                                    for (int q = g; q < g + PROG_GROUP; ++q) {
+                                        if (LLMEM_TERM_IS_PADDING(t[q])) continue;
+                                        acc = mad_i64_i32(v32[q], (int)t[q] >> 16, acc);
+                                    }
                                 } else {
                                     // the rows hold the byte sizes themselves; the factor is minus the count.
                                     // |count| * value from the low and the high half of the value (each
@@ -682,11 +777,14 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                     if (__builtin_amdgcn_ballot_w64(beyond != 0) == 0) {
                         walk_terms(Narrow());
                     } else {
+                        // the halves of the wave take turns with the same rows (lane l and lane l + 32
+                        // share a slot): the second half's stores stay behind the first half's reads
                         for (u32 half = 0; half < 2; ++half) {
                             if ((u32)(lane >> 5) == half) {
                                 store_classes(Wide());
                                 walk_terms(Wide());
                             }
+                            wave_lds_fence();
                         }
                     }
                 } else {
@@ -724,9 +822,11 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                     close_segment(s, run, top, top != LOWEST);
                 }
                 }
+                r_k = (i64)k_used; r_live = prelude + best; r_np = (i64)n_params;     // the sweep folds these
+#ifndef LLMEM_SPECIALIZED
                 r_param = (i64)param_gpu; r_grad = (i64)grad_logical; r_os = (i64)os_gpu; r_out = (i64)m_out;
-                r_lm = (i64)m_lm; r_back = (i64)m_back; r_k = (i64)k_used; r_live = prelude + best;
-                r_np = (i64)n_params; r_tmax = (i64)t_max; r_flags = (i64)flags;
+                r_lm = (i64)m_lm; r_back = (i64)m_back; r_tmax = (i64)t_max; r_flags = (i64)flags;
+#endif
             }
         };
 #ifdef LLMEM_SPECIALIZED
@@ -785,39 +885,42 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                 }
             }
 #ifdef LLMEM_SPECIALIZED
-        } else if (DETAIL && in_range) {
+        } else if (DETAIL) {
             // valid configurations have stored the other columns already; invalid ones store them all
-            long long *o = a.out_detail + i;
-            if (valid) {
-                put(&o[(long long)LLMEM_D_PEAK_LIVE * n], r_live);
-            } else {
-                if (a.out_peaks) put(&a.out_peaks[i], -1);
+            if (in_range) {
+                const u32 at = (u32)lane;
+                long long *o = a.out_detail + (b << 6);                 // wave-uniform; the lane is a 32-bit offset
+                if (valid) {
+                    put(&(o + (long long)LLMEM_D_PEAK_LIVE * n)[at], r_live);
+                } else {
+                    if (a.out_peaks) put(&(a.out_peaks + (b << 6))[at], -1);
 #pragma unroll
-                for (int c = 0; c < LLMEM_NDETAIL; ++c)
-                    put(&o[(long long)c * n], c == LLMEM_D_PEAK ? -1 : c == LLMEM_D_FLAGS ? (i64)err : 0);
+                    for (int c = 0; c < LLMEM_NDETAIL; ++c)
+                        put(&(o + (long long)c * n)[at], c == LLMEM_D_PEAK ? -1 : c == LLMEM_D_FLAGS ? (i64)err : 0);
+                }
             }
 #endif
         } else if (in_range) {
-            // the index is formed again here (two instructions) rather than kept through the batch
-            int lane_again = lane;
-            asm volatile("" : "+v"(lane_again));
-            const long long at_i = (b << 6) + lane_again;
-            if (a.out_peaks) put(&a.out_peaks[at_i], r_peak);
+            // the batch's position is wave-uniform; the lane is a 32-bit offset from it
+            const u32 at = (u32)lane;
+            if (a.out_peaks) put(&(a.out_peaks + (b << 6))[at], r_peak);
+#ifndef LLMEM_SPECIALIZED
             if (DETAIL) {
-                long long *o = a.out_detail + at_i;
-                put(&o[(long long)LLMEM_D_PEAK * n], r_peak);
-                put(&o[(long long)LLMEM_D_PARAM_GPU * n], r_param);
-                put(&o[(long long)LLMEM_D_GRAD_GPU * n], r_grad);
-                put(&o[(long long)LLMEM_D_OS_GPU * n], r_os);
-                put(&o[(long long)LLMEM_D_OUT * n], r_out);
-                put(&o[(long long)LLMEM_D_LM * n], r_lm);
-                put(&o[(long long)LLMEM_D_BACK * n], r_back);
-                put(&o[(long long)LLMEM_D_K * n], r_k);
-                put(&o[(long long)LLMEM_D_PEAK_LIVE * n], r_live);
-                put(&o[(long long)LLMEM_D_NPARAMS * n], r_np);
-                put(&o[(long long)LLMEM_D_TMAX * n], r_tmax);
-                put(&o[(long long)LLMEM_D_FLAGS * n], r_flags);
+                long long *o = a.out_detail + (b << 6);
+                put(&(o + (long long)LLMEM_D_PEAK * n)[at], r_peak);
+                put(&(o + (long long)LLMEM_D_PARAM_GPU * n)[at], r_param);
+                put(&(o + (long long)LLMEM_D_GRAD_GPU * n)[at], r_grad);
+                put(&(o + (long long)LLMEM_D_OS_GPU * n)[at], r_os);
+                put(&(o + (long long)LLMEM_D_OUT * n)[at], r_out);
+                put(&(o + (long long)LLMEM_D_LM * n)[at], r_lm);
+                put(&(o + (long long)LLMEM_D_BACK * n)[at], r_back);
+                put(&(o + (long long)LLMEM_D_K * n)[at], r_k);
+                put(&(o + (long long)LLMEM_D_PEAK_LIVE * n)[at], r_live);
+                put(&(o + (long long)LLMEM_D_NPARAMS * n)[at], r_np);
+                put(&(o + (long long)LLMEM_D_TMAX * n)[at], r_tmax);
+                put(&(o + (long long)LLMEM_D_FLAGS * n)[at], r_flags);
             }
+#endif
         }
     }
     if (SWEEP) {

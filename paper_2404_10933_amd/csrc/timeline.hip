@@ -97,6 +97,7 @@ __global__ __launch_bounds__(TL_BLOCK) void timeline_kernel(const long long *__r
                 *reinterpret_cast<longlong2 *>(mine + put0 + j * (128 / TL_RUN) * TL_ROW) = make_longlong2(a0, a1);
             }
             request(base + TL_TILE, tile);
+            wave_lds_fence();                         // the tile as all lanes stored it, before any lane reads its run
             const bool narrow = __builtin_amdgcn_ballot_w64(high_bits >= 8u) == 0;   // all |raw| < 2^35
 
             i64 run_s, run_l, top_s, top_l, top_t;    // relative to the run's start; tops >= 0 (the start itself)
@@ -145,6 +146,7 @@ __global__ __launch_bounds__(TL_BLOCK) void timeline_kernel(const long long *__r
             best_t = max64(best_t, start_s + start_l + top_t);
             carry_s += read_lane(incl_s, 63);
             carry_l += read_lane(incl_l, 63);
+            wave_lds_fence();                         // every run has been read before the next tile is stored
         }
         const i64 peak_s = wave_max(best_s), peak_l = wave_max(best_l), peak_t = wave_max(best_t);
         if (lane == 0) {

@@ -16,6 +16,17 @@ typedef unsigned int u32;
 
 __device__ __forceinline__ int lane_id() { return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
 
+// Orders the LDS accesses of this wavefront's lanes among themselves: what any lane wrote before
+// this point is what every lane reads after it, and no read from before it is moved behind a
+// write after it.  A wavefront executes its LDS instructions in order, so this costs no
+// instruction; it keeps the compiler from reordering or merging across the point.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // DPP controls of the GFX9 family
 enum : int {
     DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118,
