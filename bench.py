@@ -49,7 +49,7 @@ PROFILED = {
     "g4_peaks": ("llmem_aot_llama_peaks", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
     "g4_sweep": ("llmem_aot_llama_sweep", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
     "g4_full_traversal": ("llmem_aot_llama_full_detail", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
-    "g4_compiled": ("estimate_batch_kernel<true, true, false>", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
+    "g4_compiled": ("estimate_batch_kernel<true, 1, false>", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
     "g3_detail": ("llmem_aot_llama_detail", 500_000, 2_000_000, 1_000_000, LANE_SOURCES),
     "g2_detail": ("llmem_aot_opt_detail", 50_000, 500_000, 100_000, LANE_SOURCES),
     "g5_lists": ("timeline_kernel", 0, 1 << 62, 100_000, [os.path.join(CSRC, "timeline.hip"), os.path.join(CSRC, "wave.h")]),
@@ -257,9 +257,9 @@ def main():
     assert {k: census[k] for k in ("param_groups", "size_classes", "terms", "peak_points")} \
         == {k: forms[k] for k in ("param_groups", "size_classes", "terms", "peak_points")}
     headline_key = {"auto": "g4_detail", "compiled": "g4_compiled"}.get(args.kernel, "none")
-    kernel_name = {"auto": "llmem_aot_llama_detail" if forms["prebuilt"][1] else "estimate_batch_kernel<true, true, false>",
-                   "compiled": "estimate_batch_kernel<true, true, false>", "runtime": "llmem_specialized_detail",
-                   "wave": "estimate_kernel<true>", "events": "estimate_batch_kernel<true, false, false>"}[args.kernel]
+    kernel_name = {"auto": "llmem_aot_llama_detail" if forms["prebuilt"][1] else "estimate_batch_kernel<true, 1, false>",
+                   "compiled": "estimate_batch_kernel<true, 1, false>", "runtime": "llmem_specialized_detail",
+                   "wave": "estimate_kernel<true>", "events": "estimate_batch_kernel<true, 0, false>"}[args.kernel]
     bytes_per_cfg = M.llmem_config_bytes(1) + 8 + 8 * M.NDETAIL
     roofline = alu_roofline(headline_key, n, kernel_ms, kernel_name, census["lane_ops"])
     roofline["census"]["ops_by_kind"] = census["ops"]
@@ -330,7 +330,7 @@ def main():
             del gdev, gp, gd
 
     if args.forms and args.kernel == "auto":
-        for name, k, key, kname in (("g4_compiled_form", 4, "g4_compiled", "estimate_batch_kernel<true, true, false>"),
+        for name, k, key, kname in (("g4_compiled_form", 4, "g4_compiled", "estimate_batch_kernel<true, 1, false>"),
                                     ("g4_built_at_run_time", 6, "none", "llmem_specialized_detail")):
             ftab = tables_of([table], k)
             t1 = time.perf_counter()
@@ -351,6 +351,31 @@ def main():
                                 "LLMEM_KERNEL_LANE_RUNTIME), first call incl. the build reported"}[k],
                 "n_configs": n, "ms_per_launch": ms, "configs_per_s": n / (ms * 1e-3), "first_call_s": first_call_s,
                 "roofline": alu_roofline(key, n, ms, kname, census["lane_ops"]), "verified_vs_oracle": int(len(idx))}
+
+    if args.forms:
+        # a table with hundreds of distinct event sizes: no form with class slots takes it; the library's choice
+        # (every event evaluated where it stands, one lane per configuration) against one wavefront per configuration
+        wide = T.random_table(np.random.default_rng(11), 64, 700, "many sizes")
+        nw = 1_000_000
+        wcfg = G.random_configs(np.random.default_rng(12), nw, n_arch=1)
+        wdev = M.DeviceConfigs.from_numpy(wcfg)
+        wp = torch.empty(nw, dtype=torch.int64, device="cuda")
+        wd = torch.empty((M.NDETAIL, nw), dtype=torch.int64, device="cuda")
+        ns = 2048
+        want_wp, want_wd = B.estimate(G.slice_configs(wcfg, np.arange(ns)), [wide], const, threads=4)
+        entry = {"workload": "10^6 random configurations with a random table of 64 parameter entries and 700 events in "
+                             f"{C.lean_counts(wide)['size_classes']} distinct sizes, all detail columns",
+                 "n_configs": nw, "allowed_forms": M.llmem_kernel_forms(tables_of([wide]))["allowed"]}
+        for label, k in (("auto_lane_direct", 0), ("wave", 1)):
+            wtab = tables_of([wide], k)
+            wp.fill_(-7)
+            ms = timed_ms(lambda: M.llmem_estimate_ex(wdev, wtab, wp, wd), 5, 1)
+            assert (wp[:ns].cpu().numpy() == want_wp).all() and (wd[:, :ns].cpu().numpy().T == want_wd).all(), label
+            entry[label] = {"ms_per_launch": ms, "configs_per_s": nw / (ms * 1e-3)}
+        entry["speedup_over_wave"] = entry["wave"]["ms_per_launch"] / entry["auto_lane_direct"]["ms_per_launch"]
+        entry["verified_vs_oracle"] = ns
+        extra["many_size_classes"] = entry
+        del wdev, wp, wd
 
     if args.lists > 0:
         nl = args.lists

@@ -173,14 +173,18 @@ typedef struct llmem_tables {
 } llmem_tables;
 
 /* Two kernels compute the same results.  LLMEM_KERNEL_LANE holds one configuration
- * per lane (64 per wavefront) and walks the tables entry by entry; it needs at most
- * 48 distinct size expressions among the events of each architecture.  Its timeline
- * walk has two forms: the host reduces each segment to the peak points that no other
+ * per lane (64 per wavefront) and walks the tables entry by entry.  Its timeline
+ * walk has three forms.  The host reduces each segment to the peak points that no other
  * point dominates and hands them to the kernel in its arguments
- * (LLMEM_KERNEL_LANE_COMPILED, when that fits the argument space), or the kernel
- * walks every event (LLMEM_KERNEL_LANE_EVENTS).  LLMEM_KERNEL_WAVE gives a whole
+ * (LLMEM_KERNEL_LANE_COMPILED, when that fits the argument space); or the kernel groups the
+ * events into size classes, keeps each class's value in LDS and walks every event as an add
+ * or subtract (LLMEM_KERNEL_LANE_EVENTS; at most 120 distinct size expressions among the events
+ * of each architecture, fewer when the LDS of a workgroup does not hold the slots of even one
+ * wavefront); or it evaluates every event's size where it stands (LLMEM_KERNEL_LANE_DIRECT:
+ * any tables, no LDS, slower per event).  LLMEM_KERNEL_WAVE gives a whole
  * wavefront to each configuration with the lanes spread over table entries; it needs
- * the events of all architectures, dealt to lanes, to fit LLMEM_MAX_EVENT_SLOTS.
+ * the events of all architectures, dealt to lanes, to fit LLMEM_MAX_EVENT_SLOTS, and is only
+ * used when asked for (it is several times slower than any lane form).
  * LLMEM_KERNEL_LANE_SPECIALIZED is the compiled form taken one step further: the lane kernel's
  * own source compiled once more with the compiled tables as constants, so that every table word
  * becomes an immediate and every loop over table entries straight-line code.  Results are the
@@ -200,9 +204,8 @@ typedef struct llmem_tables {
  *   HSA_TOOLS_LIB naming a rocprofiler library): without a kept code object such a call is
  *   LLMEM_EHIP; fill LLMEM_KERNEL_CACHE in an unprofiled run first.  A call recorded into a HIP
  *   graph must not be the one that builds.
- * LLMEM_KERNEL_AUTO takes a built-in specialization when one matches, else the first of
- * compiled, events, wave that the tables allow; LLMEM_KERNEL_LANE the same without wave; it
- * never builds at run time.  LLMEM_KERNEL_LANE_SPECIALIZED takes a built-in specialization when
+ * LLMEM_KERNEL_AUTO and LLMEM_KERNEL_LANE take a built-in specialization when one matches, else
+ * the first of compiled, events, direct that the tables allow; they never build at run time.  LLMEM_KERNEL_LANE_SPECIALIZED takes a built-in specialization when
  * one matches and builds at run time otherwise; LLMEM_KERNEL_LANE_RUNTIME always builds at run
  * time.  A forced choice the tables do not allow is LLMEM_EINVAL_TABLE.  llmem_estimate(_ex) and
  * llmem_sweep honour all of these.                                                          */
@@ -213,6 +216,7 @@ typedef struct llmem_tables {
 #define LLMEM_KERNEL_LANE_COMPILED 4
 #define LLMEM_KERNEL_LANE_SPECIALIZED 5
 #define LLMEM_KERNEL_LANE_RUNTIME 6
+#define LLMEM_KERNEL_LANE_DIRECT 7
 
 /* ---- outputs --------------------------------------------------------------- */
 /* Detail columns: out_detail is DEV, LLMEM_NDETAIL columns of n int64 each
@@ -362,7 +366,7 @@ int llmem_queries_generate(uint64_t seed, int64_t first, int64_t n, const llmem_
  * statistics of several index ranges, seeds or devices can share one array or be merged
  * column by column afterwards; llmem_sweep_reset writes the empty statistics (0 everywhere,
  * INT64_MAX in LLMEM_S_MIN_PEAK).  Both are asynchronous on hip_stream; neither allocates.
- * Needs tables that admit a lane form (LLMEM_KERNEL_LANE_*), else LLMEM_EINVAL_TABLE;
+ * Runs a lane form (LLMEM_KERNEL_LANE_*; LLMEM_KERNEL_WAVE is LLMEM_EINVAL_TABLE here);
  * first + n <= 2^40, else LLMEM_EINVAL_ARG.                                               */
 #define LLMEM_SWEEP_GROUPS 48
 enum llmem_sweep_column {
@@ -398,7 +402,7 @@ size_t llmem_config_bytes(int64_t n);
 size_t llmem_events_bytes(int64_t n);
 
 /* Host-only: which kernel forms these tables allow and what they cost.  info[0] = bit mask
- * (bit k set: LLMEM_KERNEL_k is allowed, k = 1..6; LLMEM_FORMS_PREBUILT_*: the library holds a
+ * (bit k set: LLMEM_KERNEL_k is allowed, k = 1..7; LLMEM_FORMS_PREBUILT_*: the library holds a
  * built-in specialization for these tables, for m_peak only / with the detail columns / for
  * llmem_sweep), info[1] = 32-bit words of the compiled
  * tables (of LLMEM_PROGRAM_WORDS available), info[2] = value slots per wavefront in the

@@ -19,7 +19,7 @@ _lib = None
 
 MAX_ARCH = 8
 (KERNEL_AUTO, KERNEL_WAVE, KERNEL_LANE, KERNEL_LANE_EVENTS, KERNEL_LANE_COMPILED, KERNEL_LANE_SPECIALIZED,
- KERNEL_LANE_RUNTIME) = range(7)
+ KERNEL_LANE_RUNTIME, KERNEL_LANE_DIRECT) = range(8)
 PROGRAM_WORDS = 704
 NDETAIL = 12
 DETAIL_COLUMNS = ("m_peak", "param_bytes_gpu", "grad_bytes_gpu", "os_bytes_gpu", "m_out", "m_lm",
@@ -348,7 +348,7 @@ def llmem_events_generate(seed: int, first: int, n: int, offsets: torch.Tensor, 
 def llmem_kernel_forms(tables: "Tables") -> Dict[str, int]:
     info = (ctypes.c_int32 * 8)()
     _check(load_library().llmem_kernel_forms(ctypes.byref(tables.struct), info))
-    return {"allowed": [k for k in range(1, 7) if info[0] >> k & 1],
+    return {"allowed": [k for k in range(1, 8) if info[0] >> k & 1],
             "prebuilt": [bool(info[0] >> (8 + flavour) & 1) for flavour in range(3)],
             "program_words": info[1],
             "compiled_slots": info[2], "event_slots": info[3], "wave_slots": info[4],

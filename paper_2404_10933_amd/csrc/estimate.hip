@@ -623,10 +623,12 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, 
     out->code_count = code;
     if (out->s_slots < 1) out->s_slots = 1;
     if (out->p_slots < 1) out->p_slots = 1;
-    out->use_program = 1;                     // sizes the LDS of the compiled form
-    if (*prog_ok && batch_kernel_lds_bytes(*out) > BATCH_LDS_LIMIT) *prog_ok = false;
+    // each lane form needs its value slots to fit the LDS of a workgroup of at least one wavefront
+    out->use_program = 1;
+    if (*prog_ok && batch_kernel_waves(*out) == 0) *prog_ok = false;
     out->use_program = 0;
-    if (*batch_ok && batch_kernel_lds_bytes(*out) > BATCH_LDS_LIMIT) *batch_ok = false;
+    if (*batch_ok && batch_kernel_waves(*out) == 0) *batch_ok = false;
+    out->waves = BATCH_WAVES;                 // the launch sets it for the form it takes
     *wave_ok = slot <= LLMEM_MAX_EVENT_SLOTS;
     return LLMEM_OK;
 }
@@ -653,22 +655,25 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     const int hint = tables->kernel;
     const int flavour = out_detail ? 1 : 0;
     args.use_program = prog_ok ? 1 : 0;
-    const int lane_form = !prog_ok ? (batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1)
+    const int lane_form = !prog_ok ? (batch_ok ? LLMEM_KERNEL_LANE_EVENTS : LLMEM_KERNEL_LANE_DIRECT)
                           : has_prebuilt(args, flavour) ? LLMEM_KERNEL_LANE_SPECIALIZED : LLMEM_KERNEL_LANE_COMPILED;
     int choice;
     switch (hint) {
-    case LLMEM_KERNEL_AUTO: choice = lane_form >= 0 ? lane_form : wave_ok ? LLMEM_KERNEL_WAVE : -1; break;
+    case LLMEM_KERNEL_AUTO:
     case LLMEM_KERNEL_LANE: choice = lane_form; break;
     case LLMEM_KERNEL_WAVE: choice = wave_ok ? hint : -1; break;
     case LLMEM_KERNEL_LANE_EVENTS: choice = batch_ok ? hint : -1; break;
     case LLMEM_KERNEL_LANE_COMPILED:
     case LLMEM_KERNEL_LANE_SPECIALIZED:
     case LLMEM_KERNEL_LANE_RUNTIME: choice = prog_ok ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_DIRECT: choice = hint; break;
     default: choice = -1;
     }
     if (choice < 0) return LLMEM_EINVAL_TABLE;
     const bool use_batch = choice != LLMEM_KERNEL_WAVE;
-    args.use_program = (choice >= LLMEM_KERNEL_LANE_COMPILED) ? 1 : 0;
+    args.use_program = (choice >= LLMEM_KERNEL_LANE_COMPILED && choice != LLMEM_KERNEL_LANE_DIRECT) ? 1 : 0;
+    args.direct = choice == LLMEM_KERNEL_LANE_DIRECT ? 1 : 0;
+    if (use_batch) args.waves = batch_kernel_waves(args);
     if (n == 0) return LLMEM_OK;
     if (!cfg->arch_id || !cfg->h || !cfg->L || !cfg->n_heads || !cfg->n_kv || !cfg->ffn || !cfg->V
         || !cfg->P || !cfg->bs || !cfg->sl || !cfg->method || !cfg->d || !cfg->chunk_k || !cfg->flags)
@@ -734,7 +739,7 @@ static int launch_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, co
     // the lane forms only; a hint that names one of them is honoured
     const int hint = tables->kernel;
     args.use_program = prog_ok ? 1 : 0;
-    const int lane_form = !prog_ok ? (batch_ok ? LLMEM_KERNEL_LANE_EVENTS : -1)
+    const int lane_form = !prog_ok ? (batch_ok ? LLMEM_KERNEL_LANE_EVENTS : LLMEM_KERNEL_LANE_DIRECT)
                           : has_prebuilt(args, 2) ? LLMEM_KERNEL_LANE_SPECIALIZED : LLMEM_KERNEL_LANE_COMPILED;
     int choice;
     switch (hint) {
@@ -744,11 +749,14 @@ static int launch_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, co
     case LLMEM_KERNEL_LANE_COMPILED:
     case LLMEM_KERNEL_LANE_SPECIALIZED:
     case LLMEM_KERNEL_LANE_RUNTIME: choice = prog_ok ? hint : -1; break;
+    case LLMEM_KERNEL_LANE_DIRECT: choice = hint; break;
     default: choice = -1;
     }
     if (choice < 0) return LLMEM_EINVAL_TABLE;
     if (n == 0) return LLMEM_OK;
-    args.use_program = (choice >= LLMEM_KERNEL_LANE_COMPILED) ? 1 : 0;
+    args.use_program = (choice >= LLMEM_KERNEL_LANE_COMPILED && choice != LLMEM_KERNEL_LANE_DIRECT) ? 1 : 0;
+    args.direct = choice == LLMEM_KERNEL_LANE_DIRECT ? 1 : 0;
+    args.waves = batch_kernel_waves(args);
     args.n = n;
     args.params_dev = reinterpret_cast<const uint4 *>(tables->params_dev);
     args.events_dev = reinterpret_cast<const uint4 *>(tables->events_dev);
@@ -782,7 +790,7 @@ extern "C" int llmem_kernel_forms(const llmem_tables *tables, int32_t info[8])
     if (rc != LLMEM_OK) return rc;
     for (int q = 0; q < 8; ++q) info[q] = 0;
     info[0] = (wave_ok ? 1 << LLMEM_KERNEL_WAVE : 0) | (batch_ok ? 1 << LLMEM_KERNEL_LANE_EVENTS : 0)
-              | (prog_ok ? 1 << LLMEM_KERNEL_LANE_COMPILED : 0) | ((batch_ok || prog_ok) ? 1 << LLMEM_KERNEL_LANE : 0)
+              | (prog_ok ? 1 << LLMEM_KERNEL_LANE_COMPILED : 0) | (1 << LLMEM_KERNEL_LANE) | (1 << LLMEM_KERNEL_LANE_DIRECT)
               | (prog_ok ? (1 << LLMEM_KERNEL_LANE_SPECIALIZED) | (1 << LLMEM_KERNEL_LANE_RUNTIME) : 0);
     if (prog_ok) {
         args.use_program = 1;

@@ -16,16 +16,20 @@
 namespace llmem {
 
 constexpr int K_SEARCH_MIN = 2, K_SEARCH_MAX = 10, K_FIXED_MAX = 16;
+// forms of the lane-per-configuration kernel (see estimate_batch.hip)
+constexpr int FORM_EVENTS = 0, FORM_COMPILED = 1, FORM_DIRECT = 2;
+constexpr int DIRECT_ROWS = 16;                // direct form: LDS rows (256 bytes) per wavefront, one per dimension
 constexpr int B16 = 2, B32 = 4;
 
 // lane-per-configuration kernel: at most CLS_MAX size classes per architecture; class c
 // keeps its value in slot c + 1 of the wave's LDS array, slot 0 holds 0 (padding events).
-// An event code is the slot's byte offset (slot * 512) with two flags in the low bits;
-// codes are fetched CODE_GROUP at a time.
-constexpr int CLS_MAX = 48;
+// An event code is the slot's byte offset (slot * 512, below 2^16) with two flags in the low
+// bits; codes are fetched CODE_GROUP at a time.
+constexpr int CLS_MAX = 120;
 constexpr int CODE_GROUP = 8;
 constexpr unsigned CODE_CHECK = 1, CODE_FREE = 2, CODE_OFFSET_MASK = 0xfe00;
-constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup
+constexpr int BATCH_WAVES = 4;                 // wavefronts per workgroup: this many, or 2 or 1 when the value
+                                               // slots of four wavefronts do not fit the workgroup's LDS
 // lane-per-configuration kernel, compiled form of the tables: the host groups parameter entries
 // with the same size expression, groups events into size classes, reduces the events of every
 // segment to the peak points no other point dominates (class-count vectors compared
@@ -96,6 +100,8 @@ struct EstimateArgs {
     int n_arch, n_param_total, n_slot_total;
     int code_count, max_events, s_slots;
     int p_slots;                     // value slots per wave in the compiled form
+    int waves;                       // wavefronts per workgroup of this launch (4, 2 or 1)
+    int direct;                      // 1 (with use_program 0): every event evaluated where it stands, no size classes
     ArchLayout arch[LLMEM_MAX_ARCH];
     const uint4 *params_dev;
     const uint4 *events_dev;
@@ -141,7 +147,10 @@ int check_tables(const llmem_tables *tables, EstimateArgs *out);
 // the compiled tables above, into `words` (room for max_groups groups).  Returns the number of
 // groups, -1 if there are more than max_groups; *e_n = embedding tables whose outputs are kept.
 int compile_param_groups(const llmem_param_entry *pe, int n_param, uint32_t *words, int max_groups, uint32_t *e_n);
+// dynamic LDS of a lane-kernel launch with a.waves wavefronts per workgroup
 size_t batch_kernel_lds_bytes(const EstimateArgs &a);
+// the most wavefronts per workgroup (4, 2, 1) whose LDS fits, 0 if not even one does; a.use_program picks the form
+int batch_kernel_waves(EstimateArgs a);
 void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream);
 void launch_sweep_kernel(const EstimateArgs &args, long long n_batch, hipStream_t stream);
 void launch_sweep_reset(long long *stats, hipStream_t stream);

@@ -144,23 +144,28 @@ __device__ __forceinline__ void put(long long *p, i64 v) { __builtin_nontemporal
 
 }  // namespace
 
-// COMPILED: the tables come compiled in the kernel arguments (else the kernel reads the entries
-// from memory and walks every event).  SWEEP: the configurations are drawn here instead of loaded,
+// FORM_COMPILED: the tables come compiled in the kernel arguments.  FORM_EVENTS: the kernel reads the
+// entries from memory, groups the events into size classes (values in LDS slots) and walks every
+// event as an add or subtract of its class's value.  FORM_DIRECT: the same walk with every event's
+// size evaluated where it stands - no classes, any number of distinct sizes (LDS holds the
+// dimension vectors of the wave's 64 configurations only).
+// SWEEP: the configurations are drawn here instead of loaded,
 // and their results are folded into statistics per (method, d) instead of stored: LDS atomics per
 // configuration into the workgroup's copy, one global atomic per statistic when the workgroup ends.
-template <bool DETAIL, bool COMPILED, bool SWEEP>
+template <bool DETAIL, int FORM, bool SWEEP>
 __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 {
+    constexpr bool COMPILED = FORM == FORM_COMPILED, DIRECT = FORM == FORM_DIRECT;
     extern __shared__ uint4 lds[];
     // multipliers of the divisions by the partition degree: a lane looks its own d up, from LDS
     // rather than from memory, so that no memory latency stands between a batch's inputs and its work
     __shared__ u64 div_mul_of[256];
-    div_mul_of[threadIdx.x & 255u] = c_div.t[threadIdx.x & 255u].mul;
-    static_assert(BB_BLOCK == 256, "one thread per table entry");
+    const int block = a.waves * 64;                       // threads of this workgroup (a.waves wavefronts)
+    for (int t = threadIdx.x; t < 256; t += block) div_mul_of[t] = c_div.t[t].mul;
     constexpr int SWEEP_WORDS = LLMEM_NSWEEP * LLMEM_SWEEP_GROUPS;
     __shared__ u64 sweep_acc[SWEEP ? SWEEP_WORDS : 1];
     if (SWEEP) {
-        for (int t = threadIdx.x; t < SWEEP_WORDS; t += BB_BLOCK)
+        for (int t = threadIdx.x; t < SWEEP_WORDS; t += block)
             sweep_acc[t] = t / LLMEM_SWEEP_GROUPS == LLMEM_S_MIN_PEAK ? (u64)INT64_MAX : 0ull;
     }
     // LDS: class table | event codes | per-architecture counts | value slots of the waves
@@ -168,25 +173,25 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
     uint4 *cls_tab = lds;                                                       // n_arch * CLS_MAX
     unsigned short *codes = reinterpret_cast<unsigned short *>(lds + a.n_arch * CLS_MAX);
     int *n_class = reinterpret_cast<int *>(codes + a.code_count);                // code_count is a multiple of 8
-    uint4 *dyn = COMPILED ? lds : reinterpret_cast<uint4 *>(n_class + LLMEM_MAX_ARCH);
+    uint4 *dyn = (COMPILED || DIRECT) ? lds : reinterpret_cast<uint4 *>(n_class + LLMEM_MAX_ARCH);
     uint4 *tmp_key = dyn;                                                        // max_events
     unsigned short *tmp_rep = reinterpret_cast<unsigned short *>(tmp_key + a.max_events);
     unsigned short *tmp_cid = tmp_rep + a.max_events;
 
     // ---- set-up: size classes, value slots and event codes of every architecture -----
-    if (DETAIL && !COMPILED) {
-        for (int t = threadIdx.x; t < a.code_count; t += BB_BLOCK) codes[t] = 0;  // padding: slot 0, no check
+    if (DETAIL && FORM == FORM_EVENTS) {
+        for (int t = threadIdx.x; t < a.code_count; t += block) codes[t] = 0;  // padding: slot 0, no check
         for (int ar = 0; ar < a.n_arch; ++ar) {
             const ArchLayout &al = a.arch[ar];
             const int n = al.seg_first[LLMEM_NSEG];
             if (threadIdx.x == 0) n_class[ar] = 0;
-            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {
+            for (int e = threadIdx.x; e < n; e += block) {
                 const uint4 raw = a.events_dev[al.event_first + e];
                 const ClassKey k = make_class_key(raw.x, raw.y, raw.z);
                 tmp_key[e] = make_uint4(k.coef, k.dims, k.meta, raw.z);
             }
             __syncthreads();
-            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {        // first event with the same key
+            for (int e = threadIdx.x; e < n; e += block) {        // first event with the same key
                 const uint4 me = tmp_key[e];
                 int rep = e;
                 for (int j = 0; j < e; ++j) {
@@ -196,7 +201,7 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                 tmp_rep[e] = (unsigned short)rep;
             }
             __syncthreads();
-            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {        // class id = rank of its first event
+            for (int e = threadIdx.x; e < n; e += block) {        // class id = rank of its first event
                 if (tmp_rep[e] != e) continue;
                 int cid = 0;
                 for (int j = 0; j < e; ++j) cid += tmp_rep[j] == j ? 1 : 0;
@@ -205,7 +210,7 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                 atomicMax(&n_class[ar], cid + 1);
             }
             __syncthreads();
-            for (int e = threadIdx.x; e < n; e += BB_BLOCK) {
+            for (int e = threadIdx.x; e < n; e += block) {
                 const u32 z = tmp_key[e].w;
                 const u32 seg = (z >> 8) & 255u, fl = (z >> 16) & 255u;
                 const bool is_free = fl & LLMEM_EV_FREE;
@@ -236,8 +241,9 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
     // of SLOT_ROW bytes holding either 64 values of 32 bits (minus the sizes in allocator blocks, lane
     // l at l * 4) or the 64-bit byte sizes of one half of the wave (lane l at (l % 32) * 8).
     char *vals = reinterpret_cast<char *>(dyn) + (COMPILED ? (size_t)wave * a.p_slots * SLOT_ROW
+                                                  : DIRECT ? (size_t)wave * DIRECT_ROWS * 256    // rows of the dimension vector
                                                            : ((size_t)wave * a.s_slots * 64 + lane) * sizeof(i64));
-    if (DETAIL) {
+    if (DETAIL && !DIRECT) {
         if (COMPILED) *reinterpret_cast<u32 *>(vals + lane * 4) = 0;
         else *reinterpret_cast<i64 *>(vals) = 0;
     }
@@ -287,8 +293,8 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
         }
         return r;
     };
-    const long long b_step = (long long)gridDim.x * BB_WAVES;
-    long long b = (long long)blockIdx.x * BB_WAVES + wave;
+    const long long b_step = (long long)gridDim.x * a.waves;
+    long long b = (long long)blockIdx.x * a.waves + wave;
     for (; b < n_batch; b += b_step) {
         const long long i = (b << 6) + lane;                       // only the sweep uses it as a value
         const bool in_range = (long long)lane < n - (b << 6);
@@ -336,6 +342,19 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                 if (nd > 3) x = mul_64x32(x, D[(desc >> 16) & 15u]);
                 return x;
             };
+            // A table entry names its dimensions by wave-uniform numbers.  Registers cannot be indexed
+            // so; the direct form keeps the dimension vector in LDS as well, one row of 64 lanes per
+            // dimension, and a number selects a row (the other forms index a copy in scratch memory
+            // for the few entries of the parameter table).
+            char *const drow = vals + lane * 4;
+            if (DIRECT) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) *reinterpret_cast<u32 *>(drow + q * 256) = D[q];
+            }
+            auto dim_at = [&](u32 sel) -> u32 {
+                if (DIRECT) return *reinterpret_cast<const u32 *>(drow + sel * 256);
+                return D[sel];
+            };
             // ---- parameter table (Notation table; Sec. 4.2, equation for m_os) ---------
             u64 embed_p = 0, lm_p = 0, other_p = 0, t_max = 0, m_os = 0;
             u32 e_n = 0;
@@ -379,10 +398,10 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                 for (int j = 0; j < n_param; ++j) {
                     const uint4 pe = a.params_dev[param_first + j];           // wave-uniform
                     const u32 cls = pe.z & 255u, role = (pe.z >> 8) & 255u, per_layer = (pe.z >> 16) & 255u;
-                    u64 t_p = (u64)pe.x * D[pe.y & 15u];
-                    t_p *= D[(pe.y >> 8) & 15u];
-                    t_p *= D[(pe.y >> 16) & 15u];
-                    t_p *= D[(pe.y >> 24) & 15u];
+                    u64 t_p = (u64)pe.x * dim_at(pe.y & 15u);
+                    t_p *= dim_at((pe.y >> 8) & 15u);
+                    t_p *= dim_at((pe.y >> 16) & 15u);
+                    t_p *= dim_at((pe.y >> 24) & 15u);
                     const u64 copies = per_layer ? (u64)L : 1ull;
                     const u64 tot = t_p * copies;
                     if (role == LLMEM_ROLE_EMBED_TOK) embed_p += tot;
@@ -787,6 +806,55 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                             wave_lds_fence();
                         }
                     }
+                } else if (DIRECT) {
+                    // ---- timeline (Sec. 2.1 / Sec. 3.1): A, F x L, H, B x L, Z, every event's size evaluated
+                    // where it stands; the live total can only peak right after an allocation
+                    // Events are fetched four at a time (wave-uniform scalar loads, the next four requested
+                    // before these are evaluated; reads stay inside the architecture's entries) and a
+                    // dimension that is LLMEM_DIM_ONE costs nothing (wave-uniform branches).
+                    const int event_first = (int)uni((u32)al.event_first);
+                    const int event_last = event_first + (int)uni((u32)al.seg_first[LLMEM_NSEG]) - 1;
+                    auto fetch_four = [&](int e, uint4 (&four)[4]) {
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) four[q] = a.events_dev[e + q < event_last ? e + q : event_last];
+                    };
+                    auto event_value = [&](u32 coef, u32 dims, u32 z) -> u64 {
+                        u32 dv[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) dv[q] = dim_at((dims >> (8 * q)) & 15u);
+                        u64 x = (u64)coef * (z & 255u);                                   // wave-uniform
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            if (((dims >> (8 * q)) & 15u) != LLMEM_DIM_ONE) {
+                                asm volatile("" ::: "memory");
+                                x = mul_64x32(x, dv[q]);
+                            }
+                        }
+                        const u32 fl = (z >> 16) & 255u, mask = (z >> 24) & 7u;
+                        if (fl & LLMEM_EV_TP_GATHER) x = b_cdiv(x * (u64)(d - 1), d, div_mul, div_shift);
+                        u64 r = b_up(x, align_shift);
+                        if (fl & LLMEM_EV_TIMES_L) r *= (u64)L;
+                        if (mask != 7u) r = ((mask >> method) & 1u) ? r : 0ull;
+                        return r;
+                    };
+                    for (int s = 0; s < LLMEM_NSEG; ++s) {
+                        i64 run = 0, top = LOWEST;
+                        const int e_begin = event_first + (int)uni((u32)al.seg_first[s]);
+                        const int e_end = event_first + (int)uni((u32)al.seg_first[s + 1]);
+                        for (int e = e_begin; e < e_end; ++e) {
+                            const uint4 raw = a.events_dev[e];                  // wave-uniform
+                            const u32 z = uni(raw.z);
+                            const i64 v = (i64)event_value(uni(raw.x), uni(raw.y), z);
+                            if ((z >> 16) & LLMEM_EV_FREE) {
+                                asm volatile("" ::: "memory");
+                                run -= v;
+                            } else {
+                                run += v;
+                                top = run > top ? run : top;
+                            }
+                        }
+                        close_segment(s, run, top, top != LOWEST);
+                    }
                 } else {
                 // ---- size classes of the timeline: rounded bytes into the value slots ----
                 const int nc_raw = (int)uni((u32)n_class[ar]);
@@ -926,7 +994,7 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
     if (SWEEP) {
         // the workgroup's statistics join the caller's: sums add, extremes combine
         __syncthreads();
-        for (int t = threadIdx.x; t < SWEEP_WORDS; t += BB_BLOCK) {
+        for (int t = threadIdx.x; t < SWEEP_WORDS; t += block) {
             const int col = t / LLMEM_SWEEP_GROUPS;
             const u64 v = sweep_acc[t];
             u64 *to = a.sweep_stats + t;
@@ -958,7 +1026,7 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 extern "C" __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
 void LLMEM_SPEC_KERNEL(const EstimateArgs a)
 {
-    estimate_batch_body<LLMEM_SPEC_FLAVOUR != 0, true, LLMEM_SPEC_FLAVOUR == 2>(a);
+    estimate_batch_body<LLMEM_SPEC_FLAVOUR != 0, FORM_COMPILED, LLMEM_SPEC_FLAVOUR == 2>(a);
 }
 
 #ifdef LLMEM_SPEC_ENTRY
@@ -973,11 +1041,11 @@ extern "C" __attribute__((visibility("hidden"))) const void *LLMEM_SPEC_ENTRY()
 
 #else
 
-template <bool DETAIL, bool COMPILED, bool SWEEP>
+template <bool DETAIL, int FORM, bool SWEEP>
 __global__ __launch_bounds__(BB_BLOCK) __attribute__((amdgpu_waves_per_eu(LLMEM_WAVES_PER_SIMD)))
 void estimate_batch_kernel(const EstimateArgs a)
 {
-    estimate_batch_body<DETAIL, COMPILED, SWEEP>(a);
+    estimate_batch_body<DETAIL, FORM, SWEEP>(a);
 }
 
 // empty statistics: 0, and the largest value where a minimum is kept
@@ -995,14 +1063,22 @@ void launch_sweep_reset(long long *stats, hipStream_t stream)
 size_t batch_kernel_lds_bytes(const EstimateArgs &a)
 {
     if (a.use_program)                                                // compiled form: value slots only
-        return ((size_t)SLOT_ROW * (size_t)a.p_slots * BATCH_WAVES + 15) & ~(size_t)15;
-    const size_t values = sizeof(long long) * 64 * (size_t)a.s_slots * BATCH_WAVES;
+        return ((size_t)SLOT_ROW * (size_t)a.p_slots * a.waves + 15) & ~(size_t)15;
+    if (a.direct) return (size_t)DIRECT_ROWS * 256 * a.waves;         // direct form: the dimension vectors of 64 lanes
+    const size_t values = sizeof(long long) * 64 * (size_t)a.s_slots * a.waves;
     size_t fixed = sizeof(uint4) * (size_t)a.n_arch * CLS_MAX;        // class table
     fixed += sizeof(unsigned short) * (size_t)a.code_count;            // event codes
     fixed += sizeof(int) * LLMEM_MAX_ARCH;                             // class counts
     size_t scratch = sizeof(uint4) * (size_t)a.max_events;             // set-up scratch: keys
     scratch += 2 * sizeof(unsigned short) * (size_t)(a.max_events + 1); // representatives, class ids
     return ((fixed + (scratch > values ? scratch : values)) + 15) & ~(size_t)15;
+}
+
+int batch_kernel_waves(EstimateArgs a)
+{
+    for (a.waves = BATCH_WAVES; a.waves >= 1; a.waves /= 2)
+        if (batch_kernel_lds_bytes(a) <= BATCH_LDS_LIMIT) return a.waves;
+    return 0;
 }
 
 static void launch_lane_kernel(const EstimateArgs &args, bool detail, bool sweep, long long n_batch, hipStream_t stream)
@@ -1019,21 +1095,25 @@ static void launch_lane_kernel(const EstimateArgs &args, bool detail, bool sweep
             cu_count = 256;
     }
     typedef void (*Kernel)(const EstimateArgs);
-    const Kernel kernels[3][2] = {{estimate_batch_kernel<false, false, false>, estimate_batch_kernel<false, true, false>},
-                                  {estimate_batch_kernel<true, false, false>, estimate_batch_kernel<true, true, false>},
-                                  {estimate_batch_kernel<true, false, true>, estimate_batch_kernel<true, true, true>}};
-    const Kernel kernel = kernels[sweep ? 2 : detail ? 1 : 0][args.use_program ? 1 : 0];
+    const Kernel kernels[3][3] = {
+        {estimate_batch_kernel<false, FORM_EVENTS, false>, estimate_batch_kernel<false, FORM_COMPILED, false>,
+         estimate_batch_kernel<false, FORM_EVENTS, false>},            // without the timeline the direct form is the events form
+        {estimate_batch_kernel<true, FORM_EVENTS, false>, estimate_batch_kernel<true, FORM_COMPILED, false>,
+         estimate_batch_kernel<true, FORM_DIRECT, false>},
+        {estimate_batch_kernel<true, FORM_EVENTS, true>, estimate_batch_kernel<true, FORM_COMPILED, true>,
+         estimate_batch_kernel<true, FORM_DIRECT, true>}};
+    const Kernel kernel = kernels[sweep ? 2 : detail ? 1 : 0][args.use_program ? FORM_COMPILED : args.direct ? FORM_DIRECT : FORM_EVENTS];
     int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), BB_BLOCK, lds_bytes)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), 64 * args.waves, lds_bytes)
             != hipSuccess || per_cu < 1)
         per_cu = 1;
-    long long blocks = (n_batch + BB_WAVES - 1) / BB_WAVES;
+    long long blocks = (n_batch + args.waves - 1) / args.waves;
     // the compiled form has next to no set-up per workgroup: several times more workgroups than
     // stay resident at once let the dispatcher even out the compute units (measured: 16 is best,
     // also for a sweep, whose workgroups each end with global atomics)
     const long long resident = (long long)per_cu * cu_count * (args.use_program ? 16 : 1);
     if (blocks > resident) blocks = resident;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(BB_BLOCK), lds_bytes, stream, args);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * args.waves), lds_bytes, stream, args);
 }
 
 void launch_batch_kernel(const EstimateArgs &args, bool detail, long long n_batch, hipStream_t stream)

@@ -341,18 +341,18 @@ int launch_prebuilt(const Prebuilt &p, const EstimateArgs &args, long long n_bat
     int resident = resident_of[slot][&p - PREBUILT].load(std::memory_order_relaxed);
     if (resident == 0) {
         int per_cu = 0, cu_count = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 64 * BATCH_WAVES, lds_bytes) != hipSuccess || per_cu < 1)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 64 * args.waves, lds_bytes) != hipSuccess || per_cu < 1)
             per_cu = 1;
         if (hipDeviceGetAttribute(&cu_count, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cu_count < 1)
             cu_count = 256;
         resident = per_cu * cu_count;
         resident_of[slot][&p - PREBUILT].store(resident, std::memory_order_relaxed);
     }
-    long long blocks = (n_batch + BATCH_WAVES - 1) / BATCH_WAVES;
+    long long blocks = (n_batch + args.waves - 1) / args.waves;
     if (blocks > (long long)resident * 16) blocks = (long long)resident * 16;   // as for the built-in compiled form
     EstimateArgs copy = args;
     void *params[] = {&copy};
-    const hipError_t e = hipLaunchKernel(kernel, dim3((unsigned)blocks), dim3(64 * BATCH_WAVES), params, lds_bytes, stream);
+    const hipError_t e = hipLaunchKernel(kernel, dim3((unsigned)blocks), dim3(64 * args.waves), params, lds_bytes, stream);
     if (e != hipSuccess) return fail(std::string("launching the built-in specialized kernel: ") + hipGetErrorString(e));
     return LLMEM_OK;
 }
@@ -399,7 +399,7 @@ int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch,
         std::string problem = rc == LLMEM_OK ? std::string() : std::string(llmem::last_hip_error());
         if (rc == LLMEM_OK) {
             int per_cu = 0;
-            if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, built.function, 64 * BATCH_WAVES, lds_bytes)
+            if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, built.function, 64 * args.waves, lds_bytes)
                     == hipSuccess && per_cu > 0)
                 built.per_cu = per_cu;
         }
@@ -418,12 +418,12 @@ int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch,
         return slot->rc;
     }
     const Built &built = slot->built;
-    long long blocks = (n_batch + BATCH_WAVES - 1) / BATCH_WAVES;
+    long long blocks = (n_batch + args.waves - 1) / args.waves;
     const long long resident = (long long)built.per_cu * built.cu_count * 16;   // as for the built-in compiled form
     if (blocks > resident) blocks = resident;
     EstimateArgs copy = args;
     void *params[] = {&copy};
-    const hipError_t e = hipModuleLaunchKernel(built.function, (unsigned)blocks, 1, 1, 64 * BATCH_WAVES, 1, 1,
+    const hipError_t e = hipModuleLaunchKernel(built.function, (unsigned)blocks, 1, 1, 64 * args.waves, 1, 1,
                                                (unsigned)lds_bytes, stream, params, nullptr);
     if (e != hipSuccess) return fail(std::string("launching the specialized kernel: ") + hipGetErrorString(e));
     return LLMEM_OK;

@@ -20,16 +20,17 @@ def U():
     return gpu_util
 
 
-WAVE, LANE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED, LANE_RUNTIME = 1, 2, 3, 4, 5, 6       # LLMEM_KERNEL_*
-BOTH = (WAVE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED, LANE_RUNTIME)
+WAVE, LANE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED, LANE_RUNTIME, LANE_DIRECT = 1, 2, 3, 4, 5, 6, 7     # LLMEM_KERNEL_*
+BOTH = (WAVE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED, LANE_RUNTIME, LANE_DIRECT)
 BUILT = (LANE, LANE_SPECIALIZED, LANE_RUNTIME)                  # follow from the others
 
 
 def _check(U, cfg, tables, const=CONST, threads=8, expect=None, prebuilt=None):
     """Every kernel form the tables allow (one wavefront per configuration; one lane per
-    configuration walking all events; the same with the host-compiled tables; the same with those
-    tables as constants, built into the library where it ships the tables, else built at run time;
-    and always built at run time), each forced, plus the library's own choice, against the oracle.
+    configuration walking all events through size classes, or evaluating each where it stands; the
+    same with the host-compiled tables; the same with those tables as constants, built into the
+    library where it ships the tables, else built at run time; and always built at run time), each
+    forced, plus the library's own choice, against the oracle.
     `expect`: forms that must be allowed; `prebuilt`: whether the library must hold built-in
     specializations for these tables."""
     import paper_2404_10933_amd as M
@@ -47,7 +48,8 @@ def _check(U, cfg, tables, const=CONST, threads=8, expect=None, prebuilt=None):
         U.assert_same(f"peaks (kernel {kernel})", got_p, want_p)
         got_p2, _ = U.hip_estimate(cfg, tables, const, detail=False, kernel=kernel)
         U.assert_same(f"peaks, no detail (kernel {kernel})", got_p2, want_p)
-    for kernel in (WAVE, LANE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED, LANE_RUNTIME):
+    assert LANE in allowed and LANE_DIRECT in allowed
+    for kernel in (WAVE, LANE_EVENTS, LANE_COMPILED, LANE_SPECIALIZED, LANE_RUNTIME):
         if kernel not in allowed:
             with pytest.raises(M.LlmemError) as e:
                 U.hip_estimate(cfg, tables, const, kernel=kernel)
@@ -84,10 +86,26 @@ def test_random_tables_wild_configs(U):
             T.random_table(rng, 64, 700, "r3"), T.gpt_table(), T.random_table(rng, 1, 1, "one"),
             T.random_table(rng, 30, 1024, "max")]
     cfg = G.random_configs(rng, 64 * 40 + 5, n_arch=len(tabs), wild=True)
-    # more than 48 distinct sizes in one architecture: only the wavefront-per-configuration kernel applies
-    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), expect=(WAVE,))
-    _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512), expect=(WAVE,))
-    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), expect=(WAVE,))
+    # hundreds of distinct sizes in one architecture: no form with class slots applies; the library takes
+    # the lane form that evaluates every event where it stands
+    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), expect=(WAVE, LANE_DIRECT))
+    _check(U, cfg, tabs, T.Constants(m_base=0, cu_p=2 << 20, align=512), expect=(WAVE, LANE_DIRECT))
+    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), expect=(WAVE, LANE_DIRECT))
+
+
+def test_tables_with_many_size_classes(U):
+    """Between 49 and 120 distinct sizes per architecture: the events form keeps a slot per class and
+    launches fewer wavefronts per workgroup so that the slots fit the LDS (two, then one)."""
+    import paper_2404_10933_amd as M
+    rng = np.random.default_rng(17)
+    for n_event, n_sizes, with_slots in ((150, 70, True), (200, 100, True), (400, 120, False)):
+        tabs = [T.random_table(rng, 7, n_event, "wide", n_sizes=n_sizes), T.gpt_table()]
+        forms = M.llmem_kernel_forms(M.Tables(tabs, device=None))
+        assert 48 < forms["event_slots"] - 1 <= 120, forms
+        # the largest of these needs more LDS than one wavefront's workgroup may ask for: direct form
+        assert (LANE_EVENTS in forms["allowed"]) == with_slots, forms
+        cfg = G.random_configs(rng, 64 * 30 + 11, n_arch=2, wild=True)
+        _check(U, cfg, tabs, T.Constants(m_base=77, cu_p=1 << 16, align=512))
 
 
 def test_random_tables_few_sizes(U):
@@ -99,8 +117,8 @@ def test_random_tables_few_sizes(U):
             T.random_table(rng, 30, 600, "r6", n_sizes=7), T.opt_table()]
     cfg = G.random_configs(rng, 64 * 40 + 5, n_arch=len(tabs), wild=True)
     # all eight together do not fit the kernel arguments in compiled form
-    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), expect=(WAVE, LANE_EVENTS))
-    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), expect=(WAVE, LANE_EVENTS))
+    _check(U, cfg, tabs, T.Constants(m_base=1, cu_p=4096, align=512), expect=(WAVE, LANE_EVENTS, LANE_DIRECT))
+    _check(U, cfg, tabs, T.Constants(m_base=12345, cu_p=1 << 16, align=1), expect=(WAVE, LANE_EVENTS, LANE_DIRECT))
     # subsets that do fit: every form
     small = T.random_table(rng, 12, 140, "r8", n_sizes=9)
     for subset in ([tabs[7], tabs[5], tabs[4]], [tabs[1], tabs[4]], [small, tabs[2], tabs[5]]):

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 CONST = T.Constants(m_base=256 << 20)
 CONST0 = T.Constants(m_base=0)
 GIB = 1 << 30
-KERNEL_LANE_EVENTS, KERNEL_LANE_COMPILED, KERNEL_LANE_SPECIALIZED, KERNEL_LANE_RUNTIME = 3, 4, 5, 6     # LLMEM_KERNEL_*
+KERNEL_LANE_EVENTS, KERNEL_LANE_COMPILED, KERNEL_LANE_SPECIALIZED, KERNEL_LANE_RUNTIME, KERNEL_LANE_DIRECT = 3, 4, 5, 6, 7   # LLMEM_KERNEL_*
 GRIDS = {1: (G.grid1, "gpt"), 2: (G.grid2, "opt"), 3: (G.grid3, "llama"), 4: (G.grid4, "llama")}
 
 
@@ -77,6 +77,11 @@ def test_random_grids(U, grid_id, n):
 def test_events_form_of_the_kernel(U):
     _check(U, 4, 0, 0, 5_000, 40 * GIB, kernel=KERNEL_LANE_EVENTS)
     _check(U, 1, 0, 0, 432, 300 << 20, kernel=KERNEL_LANE_EVENTS)
+    # and with every event evaluated where it stands (what tables with very many distinct sizes get)
+    _check(U, 4, 0, 0, 5_000, 40 * GIB, kernel=KERNEL_LANE_DIRECT)
+    _check(U, 1, 0, 0, 432, 300 << 20, kernel=KERNEL_LANE_DIRECT)
+    rng = np.random.default_rng(23)
+    _check(U, 2, 5, 1000, 3_000, 10 * GIB, tables=[T.random_table(rng, 20, 300, "many sizes")], kernel=0)
 
 
 @pytest.mark.parametrize("grid_id,n", ((1, 432), (2, 20_000), (4, 30_037)))

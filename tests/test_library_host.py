@@ -200,10 +200,15 @@ def test_table_compiler_statistics(lib):
     assert (llama["param_groups"], llama["size_classes"], llama["peak_points"], llama["terms"]) == (5, 20, 33, 125)
     both = M.llmem_kernel_forms(M.Tables([T.gpt_table(), T.llama_table()], device=None))
     assert both["param_groups"] == _compiled_counts(T.gpt_table())["param_groups"] + 5
-    # more size classes than the lane kernels take: only the wavefront-per-configuration kernel is left
+    # more size classes than the forms with class slots take: the lane form that evaluates every event
+    # where it stands is left (and is what the library chooses), and the wavefront-per-configuration kernel
     many = T.random_table(rng, 5, 400, "many")
-    assert _compiled_counts(many)["size_classes"] > 48
-    assert M.llmem_kernel_forms(M.Tables([many], device=None))["allowed"] == [1]
+    assert _compiled_counts(many)["size_classes"] > 120
+    assert M.llmem_kernel_forms(M.Tables([many], device=None))["allowed"] == [1, 2, 7]
+    # up to 120 classes the events form takes them, with fewer wavefronts per workgroup
+    some = T.random_table(rng, 5, 100, "some")
+    assert 48 < _compiled_counts(some)["size_classes"] <= 120
+    assert 3 in M.llmem_kernel_forms(M.Tables([some], device=None))["allowed"]
 
 
 def test_built_in_specializations_match_the_shipped_tables(lib):
