@@ -109,7 +109,7 @@ def write_constants(path: str, n_arch: int, words, first) -> None:
     """The constants of one specialized build as macros (what estimate_batch.hip includes)."""
     with open(path, "w") as f:
         f.write("#pragma once\n"
-                f"#define LLMEM_SPEC_WAVES {4 if n_arch == 1 else 3}\n"      # waves per SIMD the build aims at
+                f"#define LLMEM_SPEC_WAVES {5 if n_arch == 1 else 3}\n"      # waves per SIMD the build aims at
                 f"#define LLMEM_SPEC_ARCHS {n_arch}\n"
                 f"#define LLMEM_SPEC_FIRSTS {', '.join(str(v) for v in first)}\n"
                 f"#define LLMEM_SPEC_WORDS \\\n{_word_list(words)}\n")

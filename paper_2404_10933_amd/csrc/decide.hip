@@ -433,9 +433,9 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
         if (tp == 0) best[LLMEM_METHOD_HYBRID] = 0;
         // scores (doubled) and the choice
         const u32 dp_n = tp ? (u32)d_div(g, tp, div_t) : 0u;
-        i64 score2[4];
-        score2[0] = 3ll * best[0] * g; score2[1] = 2ll * best[1] * g; score2[2] = 2ll * best[2];
-        score2[3] = 2ll * best[3] * dp_n;
+        u32 score2[4];                                 // batch sizes are below 2^16 and gpu_n below 2^8: 32 bits hold them
+        score2[0] = 3u * best[0] * g; score2[1] = 2u * best[1] * g; score2[2] = 2u * best[2];
+        score2[3] = 2u * best[3] * dp_n;
         int idx = 0;
 #pragma unroll
         for (int m = 1; m < 4; ++m) idx = score2[m] > score2[idx] ? m : idx;
@@ -463,22 +463,26 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
             if (score2[0] | score2[1] | score2[3]) flags |= LLMEM_F_FALLBACK_READINGS_DIFFER;
         }
         if (in_range) {
+            // An invalid query considers no batch size (its cap is 0): every batch size, score and the
+            // estimate are 0 already and the fallback has been taken; its method and flags are replaced.
             const bool bad = err != 0;
+            const int method_out = bad ? -1 : method;
+            const i64 flags_out = bad ? (i64)err : (i64)flags;
             // the batch's position is wave-uniform; the lane is a 32-bit offset from it
             const u32 at = (u32)lane;
-            if (a.out_method) put(&(a.out_method + first)[at], bad ? -1 : method);
-            if (a.out_bs) put(&(a.out_bs + first)[at], bad ? 0 : (int)chosen_bs);
+            if (a.out_method) put(&(a.out_method + first)[at], method_out);
+            if (a.out_bs) put(&(a.out_bs + first)[at], (int)chosen_bs);
             if (a.out_detail) {
                 long long *o = a.out_detail + first;
-                put(&(o + LLMEM_C_METHOD * n)[at], bad ? -1 : method);
-                put(&(o + LLMEM_C_BS * n)[at], bad ? 0 : (i64)chosen_bs);
+                put(&(o + LLMEM_C_METHOD * n)[at], method_out);
+                put(&(o + LLMEM_C_BS * n)[at], (i64)chosen_bs);
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
-                    put(&(o + (LLMEM_C_BS_CDP + m) * n)[at], bad ? 0 : (i64)best[m]);
-                    put(&(o + (LLMEM_C_SCORE2_CDP + m) * n)[at], bad ? 0 : score2[m]);
+                    put(&(o + (LLMEM_C_BS_CDP + m) * n)[at], (i64)best[m]);
+                    put(&(o + (LLMEM_C_SCORE2_CDP + m) * n)[at], (i64)score2[m]);
                 }
-                put(&(o + LLMEM_C_PEAK * n)[at], bad ? 0 : peak);
-                put(&(o + LLMEM_C_FLAGS * n)[at], bad ? (i64)err : (i64)flags);
+                put(&(o + LLMEM_C_PEAK * n)[at], peak);
+                put(&(o + LLMEM_C_FLAGS * n)[at], flags_out);
             }
         }
     }

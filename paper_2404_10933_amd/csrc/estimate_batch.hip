@@ -67,7 +67,8 @@ typedef long long int64_t;
 #include LLMEM_SPEC_HEADER
 namespace llmem {
 namespace {
-constexpr int SPEC_WAVES = LLMEM_SPEC_WAVES;
+// (the sweep is faster at four waves per SIMD than at five, measured with and without spills)
+constexpr int SPEC_WAVES = (LLMEM_SPEC_FLAVOUR == 2 && LLMEM_SPEC_WAVES > 4) ? 4 : LLMEM_SPEC_WAVES;
 constexpr int SPEC_ARCHS = LLMEM_SPEC_ARCHS;
 constexpr int SPEC_FIRST[8] = {LLMEM_SPEC_FIRSTS};
 __device__ constexpr unsigned SPEC_PROG[] = {LLMEM_SPEC_WORDS};      // every read folds to an immediate
@@ -322,9 +323,9 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
         const u64 div_mul = div_mul_of[d & 255u];
         const u32 div_shift = d > 1 ? 31u - (u32)__builtin_clz(d - 1) : 0u;        // ceil(log2 d) - 1
 
-        i64 r_peak = err ? -1 : 0, r_k = 0, r_live = 0, r_np = 0;
+        i64 r_peak = err ? -1 : 0, r_live = 0;
 #ifndef LLMEM_SPECIALIZED
-        i64 r_param = 0, r_grad = 0, r_os = 0, r_out = 0, r_lm = 0, r_back = 0, r_tmax = 0, r_flags = err;
+        i64 r_param = 0, r_grad = 0, r_os = 0, r_out = 0, r_lm = 0, r_back = 0, r_k = 0, r_np = 0, r_tmax = 0, r_flags = err;
 #endif
 
         // The lanes of architecture `ar` (the active ones) estimate their configurations.
@@ -335,12 +336,23 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
             // size of a compiled expression for this lane's configuration (descriptor: see estimate_args.h)
             auto expression = [&](u32 coef, u32 desc) -> u64 {
                 const u32 nd = desc & 7u;
+#ifdef LLMEM_SPECIALIZED
+                // the dimensions first, the coefficient last: here it is a constant, and a power of two
+                // more often than not - a shift
+                if (nd == 0) return coef;
+                if (nd == 1) return (u64)coef * D[(desc >> 4) & 15u];
+                u64 x = (u64)D[(desc >> 4) & 15u] * D[(desc >> 8) & 15u];
+                if (nd > 2) x = mul_64x32(x, D[(desc >> 12) & 15u]);
+                if (nd > 3) x = mul_64x32(x, D[(desc >> 16) & 15u]);
+                return x * (u64)coef;
+#else
                 u64 x = coef;
                 if (nd > 0) x = (u64)coef * D[(desc >> 4) & 15u];
                 if (nd > 1) x = mul_64x32(x, D[(desc >> 8) & 15u]);
                 if (nd > 2) x = mul_64x32(x, D[(desc >> 12) & 15u]);
                 if (nd > 3) x = mul_64x32(x, D[(desc >> 16) & 15u]);
                 return x;
+#endif
             };
             // A table entry names its dimensions by wave-uniform numbers.  Registers cannot be indexed
             // so; the direct form keeps the dimension vector in LDS as well, one row of 64 lanes per
@@ -587,6 +599,33 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
             }
             const u32 flags = t_max > (1ull << (k_used + 19)) ? LLMEM_F_CHUNK_INFEASIBLE : 0;
             r_peak = (i64)m_peak;
+            if (SWEEP) {
+                // everything but the timeline's peak is known: folded into the group's statistics now (a
+                // group: method and d <= 16), so that it occupies no registers during the timeline
+                if (d - 1u < 16u) {
+                    u64 *at = sweep_acc + (method * 16u + (d - 1u));
+                    auto add = [&](int col, u64 v) {
+                        __hip_atomic_fetch_add(at + col * LLMEM_SWEEP_GROUPS, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    };
+                    auto raise = [&](int col, u64 v) {
+                        __hip_atomic_fetch_max(at + col * LLMEM_SWEEP_GROUPS, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    };
+                    add(LLMEM_S_COUNT, 1);
+                    add(LLMEM_S_K_SUM, (u64)k_used);
+                    raise(LLMEM_S_MAX_PEAK, m_peak);
+                    __hip_atomic_fetch_min(at + LLMEM_S_MIN_PEAK * LLMEM_SWEEP_GROUPS, m_peak, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if ((i64)m_peak <= a.m_total) {
+                        // Sec. 6, Algorithm 1: the batch per step over all GPUs, times 1.5 for conventional
+                        // DP, one batch for a TP group; doubled.  Higher score first, then the lower index.
+                        const u32 score2 = method == LLMEM_METHOD_CDP ? 3u * bs * d : method == LLMEM_METHOD_ZERO3 ? 2u * bs * d : 2u * bs;
+                        const u64 index_mask = (1ull << SWEEP_INDEX_BITS) - 1;
+                        add(LLMEM_S_FIT, 1);
+                        raise(LLMEM_S_MAX_NPARAMS_FIT, n_params);
+                        raise(LLMEM_S_BEST, ((u64)score2 << SWEEP_INDEX_BITS) | (index_mask - (u64)(a.sweep_first + i)));
+                    }
+                }
+            }
 
             if (DETAIL) {
                 // m_p, m_p16, m_p32 of the chunk size used (formed again here rather than carried
@@ -700,8 +739,17 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                                     x = expression(cw[2 * u], desc);
                                 }
                                 raw_before = x;
-                                if (desc & DESC_TP_GATHER) x = b_cdiv(mul_64x32(x, d - 1), d, div_mul, div_shift);
-                                u64 r = (x + ((1ull << align_shift) - 1)) >> align_shift;         // blocks
+                                u64 r;                                                        // blocks
+                                if ((desc & DESC_TP_GATHER) && NARROW) {
+                                    // ceil(ceil(x (d - 1) / d) / block) = ceil(ceil(x (d - 1) / block) / d): the division
+                                    // in 32 bits, on blocks (a count of 2^31 and more sends the wave to the wide walk)
+                                    const u64 scaled = (mul_64x32(x, d - 1) + ((1ull << align_shift) - 1)) >> align_shift;
+                                    beyond |= (u32)(scaled >> 31);
+                                    r = b_cdiv32((u32)scaled, d, div_mul, div_shift);
+                                } else {
+                                    if (desc & DESC_TP_GATHER) x = b_cdiv(mul_64x32(x, d - 1), d, div_mul, div_shift);
+                                    r = (x + ((1ull << align_shift) - 1)) >> align_shift;
+                                }
                                 // the rare descriptor flags are wave-uniform: real branches, no selects
                                 if (desc & DESC_TIMES_L) {
                                     asm volatile("" ::: "memory");
@@ -890,7 +938,10 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                     close_segment(s, run, top, top != LOWEST);
                 }
                 }
-                r_k = (i64)k_used; r_live = prelude + best; r_np = (i64)n_params;     // the sweep folds these
+                r_live = prelude + best;
+#ifndef LLMEM_SPECIALIZED
+                r_k = (i64)k_used; r_np = (i64)n_params;
+#endif
 #ifndef LLMEM_SPECIALIZED
                 r_param = (i64)param_gpu; r_grad = (i64)grad_logical; r_os = (i64)os_gpu; r_out = (i64)m_out;
                 r_lm = (i64)m_lm; r_back = (i64)m_back; r_tmax = (i64)t_max; r_flags = (i64)flags;
@@ -927,31 +978,10 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
         }
 
         if (SWEEP) {
-            // fold this configuration into its group's statistics (a group: method and d <= 16)
-            if (valid && d - 1u < 16u) {
-                u64 *at = sweep_acc + (method * 16u + (d - 1u));
-                auto add = [&](int col, u64 v) {
-                    __hip_atomic_fetch_add(at + col * LLMEM_SWEEP_GROUPS, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                };
-                auto raise = [&](int col, u64 v) {
-                    __hip_atomic_fetch_max(at + col * LLMEM_SWEEP_GROUPS, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                };
-                add(LLMEM_S_COUNT, 1);
-                add(LLMEM_S_K_SUM, (u64)r_k);
-                raise(LLMEM_S_MAX_PEAK, (u64)r_peak);
-                raise(LLMEM_S_MAX_LIVE, (u64)r_live);
-                __hip_atomic_fetch_min(at + LLMEM_S_MIN_PEAK * LLMEM_SWEEP_GROUPS, (u64)r_peak, __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_WORKGROUP);
-                if (r_peak <= a.m_total) {
-                    // Sec. 6, Algorithm 1: the batch per step over all GPUs, times 1.5 for conventional
-                    // DP, one batch for a TP group; doubled.  Higher score first, then the lower index.
-                    const u32 score2 = method == LLMEM_METHOD_CDP ? 3u * bs * d : method == LLMEM_METHOD_ZERO3 ? 2u * bs * d : 2u * bs;
-                    const u64 index_mask = (1ull << SWEEP_INDEX_BITS) - 1;
-                    add(LLMEM_S_FIT, 1);
-                    raise(LLMEM_S_MAX_NPARAMS_FIT, (u64)r_np);
-                    raise(LLMEM_S_BEST, ((u64)score2 << SWEEP_INDEX_BITS) | (index_mask - (u64)(a.sweep_first + i)));
-                }
-            }
+            // the timeline's peak joins the statistics that were folded when the estimate was known
+            if (valid && d - 1u < 16u)
+                __hip_atomic_fetch_max(sweep_acc + (method * 16u + (d - 1u)) + LLMEM_S_MAX_LIVE * LLMEM_SWEEP_GROUPS, (u64)r_live,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 #ifdef LLMEM_SPECIALIZED
         } else if (DETAIL) {
             // valid configurations have stored the other columns already; invalid ones store them all

@@ -61,9 +61,9 @@ const char *last_hip_error();
 
 namespace {
 
-// waves per SIMD the build aims at: four (128 registers, no spills) for one architecture; with
-// several, the code of each sits in a loop over the architectures and needs more registers
-inline int specialized_waves(size_t n_arch) { return n_arch == 1 ? 4 : 3; }
+// waves per SIMD the build aims at: five (96 registers) for one architecture; with several, the
+// code of each sits in a loop over the architectures and needs more registers
+inline int specialized_waves(size_t n_arch) { return n_arch == 1 ? 5 : 3; }
 const char *const FLAVOUR_KERNEL[3] = {"llmem_specialized_peaks", "llmem_specialized_detail", "llmem_specialized_sweep"};
 
 struct Built {
