@@ -43,7 +43,8 @@ CSRC = os.path.join("paper_2404_10933_amd", "csrc")
 LANE_SOURCES = [os.path.join(CSRC, f) for f in ("estimate_batch.hip", "estimate_args.h", "wave.h", "grid_draws.h")] \
     + [os.path.join("include", "llmem.h"), os.path.join("workloads", "tables.py")]
 # key -> (substring of the kernel's name, work-items of a launch over the whole workload: at least, below,
-#         units per launch, sources the kernel is compiled from)
+#         units per launch, sources the kernel is compiled from[, (i, of): the launches that match, in the order
+#         they were made, fall into `of` equal runs and the i-th is this workload's])
 PROFILED = {
     "g4_detail": ("llmem_aot_llama_detail", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
     "g4_peaks": ("llmem_aot_llama_peaks", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
@@ -54,7 +55,8 @@ PROFILED = {
     "g2_detail": ("llmem_aot_opt_detail", 50_000, 500_000, 100_000, LANE_SOURCES),
     "g5_lists": ("timeline_kernel", 0, 1 << 62, 100_000, [os.path.join(CSRC, "timeline.hip"), os.path.join(CSRC, "wave.h")]),
     "g6_decide": ("decide_kernel<true>", 0, 1 << 62, 4_000_000,
-                  [os.path.join(CSRC, "decide.hip"), os.path.join(CSRC, "estimate_args.h"), os.path.join(CSRC, "wave.h")]),
+                  [os.path.join(CSRC, "decide.hip"), os.path.join(CSRC, "estimate_args.h"), os.path.join(CSRC, "wave.h")],
+                  (0, 2)),                  # the second run of launches is the one without the decision columns
 }
 
 
@@ -87,12 +89,15 @@ def import_counters(folder):
     """profiles/counters.json from rocprofv3 --pmc runs of this file under `folder`: sub-folders
     pmc_sq, pmc_fetch, pmc_write (this benchmark) and copy_fetch, copy_write (--calibrate-copy),
     each holding *_counter_collection.csv."""
-    def read(sub, want, lo=0, hi=1 << 62):
+    def read(sub, want, lo=0, hi=1 << 62, part=None):
         agg = collections.defaultdict(list)
         names = [f for f in os.listdir(os.path.join(folder, sub)) if f.endswith("counter_collection.csv")]
-        for r in csv.DictReader(open(os.path.join(folder, sub, names[0]))):
+        rows = sorted(csv.DictReader(open(os.path.join(folder, sub, names[0]))), key=lambda r: int(r["Dispatch_Id"]))
+        for r in rows:
             if want in r["Kernel_Name"] and lo <= int(r["Grid_Size"]) < hi:
                 agg[r["Counter_Name"]].append(float(r["Counter_Value"]))
+        if part is not None:
+            agg = {k: v[len(v) * part[0] // part[1]: len(v) * (part[0] + 1) // part[1]] for k, v in agg.items()}
         return {k: sum(v) / len(v) for k, v in agg.items()}
 
     copy_fetch = read("copy_fetch", "copyBuffer")["FETCH_SIZE"]
@@ -104,10 +109,11 @@ def import_counters(folder):
            "copy_reference": {"fetch_kib_per_gib_copied": copy_fetch, "write_kib_per_gib_copied": copy_write,
                               "fetch_scale": scale_f, "write_scale": scale_w},
            "kernels": {}}
-    for key, (want, lo, hi, units, sources) in PROFILED.items():
-        sq = read("pmc_sq", want, lo, hi)
-        f = read("pmc_fetch", want, lo, hi).get("FETCH_SIZE")
-        w = read("pmc_write", want, lo, hi).get("WRITE_SIZE")
+    for key, (want, lo, hi, units, sources, *rest) in PROFILED.items():
+        part = rest[0] if rest else None
+        sq = read("pmc_sq", want, lo, hi, part)
+        f = read("pmc_fetch", want, lo, hi, part).get("FETCH_SIZE")
+        w = read("pmc_write", want, lo, hi, part).get("WRITE_SIZE")
         if not sq or f is None or w is None:
             print(f"{key}: not in the counter files, left out", file=sys.stderr)
             continue

@@ -535,7 +535,7 @@ int launch(bool decide, const llmem_configs *cfg, const uint8_t *tp_n, int64_t n
     }
     const int64_t n_batch = (n + 63) / 64;
     int64_t blocks = (n_batch + DC_WAVES - 1) / DC_WAVES;
-    const int64_t max_blocks = 256 * 8;                 // 256 CUs, up to 8 resident workgroups each
+    const int64_t max_blocks = 256 * 40;                // 256 CUs; 5 to 160 workgroups per CU measured, 40 to 80 are the fastest
     if (blocks > max_blocks) blocks = max_blocks;
     if (decide)
         hipLaunchKernelGGL(decide_kernel<true>, dim3((unsigned)blocks), dim3(DC_BLOCK), 0, stream, a);
