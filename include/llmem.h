@@ -151,7 +151,10 @@ typedef struct llmem_arch_desc {
 } llmem_arch_desc;
 
 /* HOST struct.  The entry arrays are given twice with identical contents: a HOST
- * copy, validated on every call, and a DEV copy the kernels read.
+ * copy, validated on every call, and a DEV copy the kernels read.  (Each host thread
+ * keeps what the library derived from the last four table sets it was called with and
+ * reuses it when constants, ranges and entries compare equal byte for byte, which makes a
+ * repeated call cost microseconds; the caller may change the contents between calls.)
  * LLMEM_EINVAL_TABLE is returned when: n_arch is outside 1..LLMEM_MAX_ARCH; a
  * range is negative, exceeds the limits above or the array lengths (the slot limit
  * only binds the kernel that uses slots, see LLMEM_KERNEL_*); a selector

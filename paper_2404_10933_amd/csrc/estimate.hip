@@ -633,11 +633,113 @@ static int plan_tables(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, 
     return LLMEM_OK;
 }
 
+// plan_tables costs tens to hundreds of microseconds (the classes and the dominance test of the
+// peak points are quadratic in the events), more than a launch over a small grid.  Its result
+// depends on the contents of the host tables alone, so each host thread keeps the plans of the last
+// few table sets it was called with and takes one over when every byte it was made from is the
+// same: constants, ranges and the entries inside the ranges (a comparison of a few KB).  The
+// tables are still checked in full whenever anything in them differs; a plan that was refused is
+// not kept.  `out` arrives zeroed, as plan_tables expects.
+namespace {
+
+struct PlanKey {
+    int64_t m_base, cu_p, align;
+    int32_t n_arch, n_param_total, n_event_total;
+    llmem_arch_desc arch[LLMEM_MAX_ARCH];
+};
+
+struct KeptPlan {
+    bool used = false;
+    PlanKey key;
+    std::vector<llmem_param_entry> params;      // the entries inside the ranges, architecture by architecture
+    std::vector<llmem_event_entry> events;
+    EstimateArgs args;
+    bool wave_ok, batch_ok, prog_ok;
+    int words, stats[4];
+};
+
+constexpr int KEPT_PLANS = 4;
+
+bool ranges_readable(const llmem_tables *t)
+{
+    if ((!t->params_host || !t->params_dev) && t->n_param_total > 0) return false;
+    if ((!t->events_host || !t->events_dev) && t->n_event_total > 0) return false;
+    if (t->n_arch < 1 || t->n_arch > LLMEM_MAX_ARCH || t->n_param_total < 0 || t->n_event_total < 0) return false;
+    for (int ar = 0; ar < t->n_arch; ++ar) {
+        const llmem_arch_desc &d = t->arch[ar];
+        if (d.param_first < 0 || d.n_param < 0 || d.n_param > LLMEM_MAX_PARAM_ENTRIES
+            || (int64_t)d.param_first + d.n_param > t->n_param_total) return false;
+        if (d.event_first < 0 || d.n_event < 0 || d.n_event > LLMEM_MAX_EVENT_ENTRIES
+            || (int64_t)d.event_first + d.n_event > t->n_event_total) return false;
+    }
+    return true;
+}
+
+bool same_tables(const KeptPlan &k, const PlanKey &key, const llmem_tables *t)
+{
+    if (!k.used || memcmp(&k.key, &key, sizeof(key)) != 0) return false;
+    size_t p = 0, e = 0;
+    for (int ar = 0; ar < t->n_arch; ++ar) {
+        const llmem_arch_desc &d = t->arch[ar];
+        if (d.n_param && memcmp(&k.params[p], t->params_host + d.param_first, sizeof(llmem_param_entry) * d.n_param)) return false;
+        if (d.n_event && memcmp(&k.events[e], t->events_host + d.event_first, sizeof(llmem_event_entry) * d.n_event)) return false;
+        p += d.n_param;
+        e += d.n_event;
+    }
+    return true;
+}
+
+}  // namespace
+
+static int plan_tables_kept(const llmem_tables *t, EstimateArgs *out, bool *wave_ok, bool *batch_ok, bool *prog_ok,
+                            int *prog_words = nullptr, int *prog_stats = nullptr)
+{
+    if (!ranges_readable(t)) return plan_tables(t, out, wave_ok, batch_ok, prog_ok, prog_words, prog_stats);   // reports what is wrong
+    static thread_local KeptPlan kept[KEPT_PLANS];
+    static thread_local int next = 0;
+    PlanKey key;
+    memset(&key, 0, sizeof(key));                           // padding and unused architectures compare equal
+    key.m_base = t->m_base; key.cu_p = t->cu_p; key.align = t->align;
+    key.n_arch = t->n_arch; key.n_param_total = t->n_param_total; key.n_event_total = t->n_event_total;
+    for (int ar = 0; ar < t->n_arch; ++ar) key.arch[ar] = t->arch[ar];
+    for (int q = 0; q < KEPT_PLANS; ++q) {
+        const KeptPlan &k = kept[q];
+        if (!same_tables(k, key, t)) continue;
+        *out = k.args;
+        *wave_ok = k.wave_ok; *batch_ok = k.batch_ok; *prog_ok = k.prog_ok;
+        if (prog_words) *prog_words = k.words;
+        if (prog_stats) for (int i = 0; i < 4; ++i) prog_stats[i] += k.stats[i];
+        return LLMEM_OK;
+    }
+    int words = 0, stats[4] = {0, 0, 0, 0};
+    const int rc = plan_tables(t, out, wave_ok, batch_ok, prog_ok, &words, stats);
+    if (prog_words) *prog_words = words;
+    if (prog_stats) for (int i = 0; i < 4; ++i) prog_stats[i] += stats[i];
+    if (rc != LLMEM_OK) return rc;
+    KeptPlan &k = kept[next];
+    next = (next + 1) % KEPT_PLANS;
+    k.used = false;
+    k.key = key;
+    k.params.clear();
+    k.events.clear();
+    for (int ar = 0; ar < t->n_arch; ++ar) {
+        const llmem_arch_desc &d = t->arch[ar];
+        if (d.n_param) k.params.insert(k.params.end(), t->params_host + d.param_first, t->params_host + d.param_first + d.n_param);
+        if (d.n_event) k.events.insert(k.events.end(), t->events_host + d.event_first, t->events_host + d.event_first + d.n_event);
+    }
+    k.args = *out;
+    k.wave_ok = *wave_ok; k.batch_ok = *batch_ok; k.prog_ok = *prog_ok;
+    k.words = words;
+    for (int i = 0; i < 4; ++i) k.stats[i] = stats[i];
+    k.used = true;
+    return rc;
+}
+
 int check_tables(const llmem_tables *tables, EstimateArgs *out)
 {
     memset(out, 0, sizeof(*out));
     bool wave_ok, batch_ok, prog_ok;
-    return plan_tables(tables, out, &wave_ok, &batch_ok, &prog_ok);
+    return plan_tables_kept(tables, out, &wave_ok, &batch_ok, &prog_ok);
 }
 
 static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tables *tables,
@@ -649,7 +751,7 @@ static int launch_estimate(const llmem_configs *cfg, int64_t n, const llmem_tabl
     EstimateArgs args;
     memset(&args, 0, sizeof(args));
     bool wave_ok, batch_ok, prog_ok;
-    int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok);
+    int rc = plan_tables_kept(tables, &args, &wave_ok, &batch_ok, &prog_ok);
     if (rc != LLMEM_OK) return rc;
     // which kernel (see LLMEM_KERNEL_* in the header)
     const int hint = tables->kernel;
@@ -734,7 +836,7 @@ static int launch_sweep(int grid_id, uint64_t seed, int64_t first, int64_t n, co
     EstimateArgs args;
     memset(&args, 0, sizeof(args));
     bool wave_ok, batch_ok, prog_ok;
-    int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok);
+    int rc = plan_tables_kept(tables, &args, &wave_ok, &batch_ok, &prog_ok);
     if (rc != LLMEM_OK) return rc;
     // the lane forms only; a hint that names one of them is honoured
     const int hint = tables->kernel;
@@ -786,7 +888,7 @@ extern "C" int llmem_kernel_forms(const llmem_tables *tables, int32_t info[8])
     bool wave_ok, batch_ok, prog_ok;
     int words = 0;
     int stats[4] = {0, 0, 0, 0};
-    const int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok, &words, stats);
+    const int rc = plan_tables_kept(tables, &args, &wave_ok, &batch_ok, &prog_ok, &words, stats);
     if (rc != LLMEM_OK) return rc;
     for (int q = 0; q < 8; ++q) info[q] = 0;
     info[0] = (wave_ok ? 1 << LLMEM_KERNEL_WAVE : 0) | (batch_ok ? 1 << LLMEM_KERNEL_LANE_EVENTS : 0)
@@ -814,7 +916,7 @@ extern "C" int llmem_compiled_tables(const llmem_tables *tables, uint32_t *words
     memset(&args, 0, sizeof(args));
     bool wave_ok, batch_ok, prog_ok;
     int n_words = 0;
-    const int rc = plan_tables(tables, &args, &wave_ok, &batch_ok, &prog_ok, &n_words);
+    const int rc = plan_tables_kept(tables, &args, &wave_ok, &batch_ok, &prog_ok, &n_words);
     if (rc != LLMEM_OK) return rc;
     if (!prog_ok) return LLMEM_EINVAL_TABLE;
     if (n_words > max_words) return LLMEM_EINVAL_ARG;

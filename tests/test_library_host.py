@@ -245,6 +245,54 @@ def test_built_in_specializations_match_the_shipped_tables(lib):
     assert e.value.code == -3
 
 
+def test_kept_plans_follow_the_tables_contents(lib):
+    """The library keeps, per host thread, what it made of the last few table sets and reuses it
+    when every byte is the same.  A change anywhere in the host tables must therefore show at the
+    next call: edited in place (same addresses), in the constants, in the ranges, and back again;
+    and more table sets than are kept, taken in turn, must each keep their own answer."""
+    import paper_2404_10933_amd as M
+    from workloads import tables as T
+    tab = M.Tables([T.llama_table()], device=None)
+    first = M.llmem_kernel_forms(tab)
+    assert M.llmem_kernel_forms(tab) == first and first["prebuilt"] == [True, True, True]
+    words, _ = M.llmem_compiled_tables(tab)
+    # one coefficient edited in place: another size class, other words, no built-in kernel any more
+    field = "coef" if "coef" in tab.events_host.dtype.names else tab.events_host.dtype.names[0]
+    old = tab.events_host[field][5]
+    tab.events_host[field][5] = old + 12345
+    changed = M.llmem_kernel_forms(tab)
+    assert changed["prebuilt"] == [False, False, False] and changed["size_classes"] == first["size_classes"] + 1
+    assert M.llmem_compiled_tables(tab)[0] != words
+    tab.events_host[field][5] = old
+    assert M.llmem_kernel_forms(tab) == first and M.llmem_compiled_tables(tab)[0] == words
+    # an invalid entry is reported although the same tables were accepted a call ago
+    dim = tab.events_host["dim"][7].copy()
+    tab.events_host["dim"][7] = 200
+    with pytest.raises(M.LlmemError) as e:
+        M.llmem_kernel_forms(tab)
+    assert e.value.code == -3
+    tab.events_host["dim"][7] = dim
+    assert M.llmem_kernel_forms(tab) == first
+    # constants are part of what is compared
+    tab.struct.cu_p = 3 << 20
+    with pytest.raises(M.LlmemError):
+        M.llmem_kernel_forms(tab)
+    tab.struct.cu_p = 1 << 21
+    # a shorter range of the same array
+    tab.struct.arch[0].n_event -= 1
+    assert M.llmem_kernel_forms(tab) != first
+    tab.struct.arch[0].n_event += 1
+    assert M.llmem_kernel_forms(tab) == first
+    # six table sets in turn, twice
+    rng = np.random.default_rng(21)
+    sets = [M.Tables([T.random_table(rng, 10 + j, 40 + 7 * j, f"t{j}", n_sizes=5 + j)], device=None) for j in range(6)]
+    want = [M.llmem_kernel_forms(t) for t in sets]
+    assert len({w["program_words"] for w in want}) > 3
+    for _ in range(2):
+        for t, w in zip(sets, want):
+            assert M.llmem_kernel_forms(t) == w
+
+
 def test_run_time_build_refused_under_a_profiler(lib):
     """With a profiler's tool library named in the environment (and no directory of kept code
     objects) the library does not start the run-time compiler: a call that would have to build
