@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define LLMEM_ABI_VERSION 4
+#define LLMEM_ABI_VERSION 5
 
 /* ---- error codes --------------------------------------------------------- */
 #define LLMEM_OK            0
@@ -199,9 +199,9 @@ typedef struct llmem_tables {
  *   Built at run time (hiprtc) for any other tables the compiled form admits: the first call with
  *   a given set of tables takes a fraction of a second to a few seconds to build and load the
  *   kernel and allocates host memory for the build and device memory for the loaded code object;
- *   the build is kept, per device, until the process ends, and also between processes when the
- *   environment variable LLMEM_KERNEL_CACHE names a writable directory (one file per build, used
- *   only if its recorded identity matches in full).  A failure of the run-time compiler or loader
+ *   the build is kept, per device, until llmem_kernels_release or the end of the process, and also
+ *   between processes when the environment variable LLMEM_KERNEL_CACHE names a writable directory
+ *   (one file per build, used only if its recorded identity matches in full).  A failure of the run-time compiler or loader
  *   is LLMEM_EHIP with its message in llmem_strerror.  The run-time compiler is not started in a
  *   process that a profiler has been loaded into (ROCP_TOOL_LIBRARIES set, or LD_PRELOAD /
  *   HSA_TOOLS_LIB naming a rocprofiler library): without a kept code object such a call is
@@ -437,6 +437,16 @@ int llmem_compiled_tables(const llmem_tables *method_tables, uint32_t *words, in
  * (0 <= x < 2^63, 1 <= d <= 255; returns 0 for d outside that range).  Lets a host test
  * compare the constants with integer division without a GPU.                              */
 uint64_t llmem_selftest_divide(uint64_t x, uint32_t d);
+
+/* Unloads every kernel that was built at run time (LLMEM_KERNEL_LANE_SPECIALIZED without a
+ * built-in match, LLMEM_KERNEL_LANE_RUNTIME) and frees the host and device memory of its code
+ * object: for a process that goes through many table sets.  Built-in kernels are not
+ * affected.  The caller makes sure that no launch of such a kernel is still pending on any stream
+ * (synchronize first) and that no other thread is inside a call that launches one.  A later call
+ * with the same tables builds again (or loads from LLMEM_KERNEL_CACHE).  Returns the number of
+ * kernels released; 0 - and no device call - when there are none.  A build that another thread
+ * has not finished yet is left alone.                                                        */
+int llmem_kernels_release(void);
 
 const char *llmem_strerror(int code);
 int llmem_abi_version(void);

@@ -122,6 +122,8 @@ def load_library():
     lib.llmem_compiled_tables.argtypes = [ctypes.POINTER(_Tables), ctypes.POINTER(ctypes.c_uint32), ctypes.c_int32,
                                           ctypes.POINTER(ctypes.c_int32)]
     lib.llmem_compiled_tables.restype = ci
+    lib.llmem_kernels_release.argtypes = []
+    lib.llmem_kernels_release.restype = ci
     lib.llmem_selftest_divide.argtypes = [u64, ctypes.c_uint32]
     lib.llmem_selftest_divide.restype = u64
     _lib = lib
@@ -380,3 +382,11 @@ def llmem_strerror(code: int) -> str:
 
 def llmem_abi_version() -> int:
     return int(load_library().llmem_abi_version())
+
+
+def llmem_kernels_release() -> int:
+    """Unloads the kernels built at run time; the caller has synchronized.  Returns how many."""
+    got = int(load_library().llmem_kernels_release())
+    if got < 0:
+        _check(got)
+    return got

@@ -925,6 +925,8 @@ extern "C" int llmem_compiled_tables(const llmem_tables *tables, uint32_t *words
     return n_words;
 }
 
+extern "C" int llmem_kernels_release(void) { return llmem::release_built(); }
+
 extern "C" uint64_t llmem_selftest_divide(uint64_t x, uint32_t d)
 {
     static constexpr llmem::DivMagicTable table = llmem::DivMagicTable();

@@ -143,6 +143,8 @@ __host__ __device__ inline ClassKey make_class_key(uint32_t x, uint32_t y, uint3
 // and per-architecture ranges of `out`; LLMEM_OK or LLMEM_EINVAL_*.
 #ifndef __HIPCC_RTC__
 int check_tables(const llmem_tables *tables, EstimateArgs *out);
+// unloads every kernel built at run time (specialize.hip); returns how many
+int release_built();
 // Parameter entries of one architecture grouped by size expression: four words per group as in
 // the compiled tables above, into `words` (room for max_groups groups).  Returns the number of
 // groups, -1 if there are more than max_groups; *e_n = embedding tables whose outputs are kept.

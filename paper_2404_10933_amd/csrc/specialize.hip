@@ -100,7 +100,7 @@ struct Slot {
 
 std::mutex g_lock;
 std::condition_variable g_built_changed;
-std::map<Key, std::shared_ptr<Slot>> g_built;   // finished builds are never erased: modules stay loaded until the process ends
+std::map<Key, std::shared_ptr<Slot>> g_built;   // finished builds stay (modules loaded) until release_built() or the process ends
 
 int fail(const std::string &text)
 {
@@ -427,6 +427,38 @@ int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch,
                                                (unsigned)lds_bytes, stream, params, nullptr);
     if (e != hipSuccess) return fail(std::string("launching the specialized kernel: ") + hipGetErrorString(e));
     return LLMEM_OK;
+}
+
+// Unloads the modules of all finished run-time builds and frees their code objects; builds that
+// are still running are left alone.  Returns how many kernels were released.
+int release_built()
+{
+    std::vector<std::pair<int, std::shared_ptr<Slot>>> gone;
+    {
+        std::lock_guard<std::mutex> hold(g_lock);
+        for (auto at = g_built.begin(); at != g_built.end();) {
+            if (at->second->done) {
+                gone.emplace_back(at->first.device, at->second);
+                at = g_built.erase(at);
+            } else {
+                ++at;
+            }
+        }
+    }
+    if (gone.empty()) return 0;                                 // nothing built: no device call at all
+    int current = 0, count = 0;
+    const bool restore = hipGetDevice(&current) == hipSuccess;
+    for (auto &entry : gone) {
+        Built &built = entry.second->built;
+        if (entry.second->rc != LLMEM_OK || !built.module) continue;
+        if (hipSetDevice(entry.first) == hipSuccess && hipModuleUnload(built.module) == hipSuccess) ++count;
+        built.module = nullptr;
+        built.function = nullptr;
+        delete built.code;
+        built.code = nullptr;
+    }
+    if (restore) (void)hipSetDevice(current);
+    return count;
 }
 
 }  // namespace llmem

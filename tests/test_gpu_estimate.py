@@ -302,6 +302,33 @@ def test_full_size_grid4(U, kernel):
         U.assert_same(f"detail column {c}, all 10^7", det[c].cpu().numpy(), want_d[:, c])
 
 
+def test_release_of_kernels_built_at_run_time(U):
+    """llmem_kernels_release unloads what was built at run time and nothing else: the count it
+    returns, a second call that finds nothing, the same tables built again with the same results,
+    and the built-in kernels and table-driven forms untouched in between."""
+    import paper_2404_10933_amd as M
+    torch.cuda.synchronize()
+    M.llmem_kernels_release()                                   # whatever earlier tests left
+    base = T.opt_table()
+    table = T.ArchTable("release", base.params, base.events[:-1] + (T.EventEntry("z8", "Z", +1, 131, ("h", "sl"), 2),))
+    cfg = G.grid2(n=5000, seed=4)
+    want_p, want_d = B.estimate(cfg, [table], CONST, threads=8)
+    for round_ in range(2):
+        got_p, got_d = U.hip_estimate(cfg, [table], CONST, kernel=LANE_RUNTIME)          # detail flavour
+        U.assert_same(f"detail, round {round_}", got_d, want_d)
+        got_p, _ = U.hip_estimate(cfg, [table], CONST, kernel=LANE_RUNTIME, detail=False)   # m_peak flavour
+        U.assert_same(f"m_peak, round {round_}", got_p, want_p)
+        torch.cuda.synchronize()
+        assert M.llmem_kernels_release() == 2
+        assert M.llmem_kernels_release() == 0
+        # nothing else went with them
+        other = G.grid4(n=1000, seed=5)
+        U.assert_same("built-in kernel after the release", U.hip_estimate(other, [T.llama_table()], CONST)[1],
+                      B.estimate(other, [T.llama_table()], CONST, threads=8)[1])
+        got_p, got_d = U.hip_estimate(cfg, [table], CONST, kernel=LANE_COMPILED)
+        U.assert_same("compiled form after the release", got_d, want_d)
+
+
 def test_built_kernels_are_kept_between_processes(U, tmp_path):
     """LLMEM_KERNEL_CACHE: a build writes one file; a second process loads it instead of building
     (the file is not rewritten) and computes the same; a file with a foreign identity is ignored."""

@@ -27,7 +27,7 @@ def test_exports_every_declared_symbol(lib):
     names = set(re.findall(r"\b(llmem_[a-z_]+)\s*\(", header))
     assert {"llmem_estimate", "llmem_estimate_ex", "llmem_timeline_peaks", "llmem_grid_generate",
             "llmem_events_count", "llmem_events_generate", "llmem_config_bytes", "llmem_events_bytes",
-            "llmem_strerror", "llmem_abi_version", "llmem_selftest_divide", "llmem_kernel_forms",
+            "llmem_strerror", "llmem_abi_version", "llmem_selftest_divide", "llmem_kernel_forms", "llmem_kernels_release",
             "llmem_estimate_methods", "llmem_decide", "llmem_queries_generate", "llmem_sweep",
             "llmem_sweep_reset", "llmem_compiled_tables"} <= names
     for n in names:
@@ -36,10 +36,17 @@ def test_exports_every_declared_symbol(lib):
 
 def test_abi_and_sizes(lib):
     import paper_2404_10933_amd as M
-    assert M.llmem_abi_version() == 4
+    assert M.llmem_abi_version() == 5
     assert M.llmem_config_bytes(10) == 10 * 31 and M.llmem_config_bytes(-1) == 0
     assert M.llmem_events_bytes(2) == 2 * 6 * 3450 * 8
     assert "NULL" in M.llmem_strerror(-1) and "unknown" in M.llmem_strerror(-99)
+
+
+def test_release_with_nothing_built(lib):
+    """No kernel has been built at run time in a process without a GPU: nothing to release, and
+    no device call is made to find that out."""
+    import paper_2404_10933_amd as M
+    assert M.llmem_kernels_release() == 0 and M.llmem_kernels_release() == 0
 
 
 def test_division_constants_are_exact(lib):
@@ -326,6 +333,7 @@ i32 = lambda *shape: torch.zeros(shape, dtype=torch.int32)
 tp = torch.ones(n, dtype=torch.uint8)
 calls = [lambda: M.llmem_abi_version(), lambda: M.llmem_config_bytes(3), lambda: M.llmem_events_bytes(3),
          lambda: M.llmem_strerror(0), lambda: M.llmem_kernel_forms(tab), lambda: M.llmem_compiled_tables(tab),
+         lambda: M.llmem_kernels_release(),
          lambda: M.llmem_estimate(cfg, tab, i64(n)), lambda: M.llmem_estimate_ex(cfg, tab, i64(n), i64(M.NDETAIL, n)),
          lambda: M.llmem_estimate_methods(cfg, tp, tab, i64(4, n)),
          lambda: M.llmem_decide(cfg, tp, tab, 1 << 30, i32(n), i32(n), i64(M.NDECIDE, n)),
