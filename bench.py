@@ -123,10 +123,38 @@ def import_counters(folder):
             "lds_per_64_units": sq.get("SQ_INSTS_LDS", 0) * 64 / units,
             "valu_per_cu_clock": sq["SQ_INSTS_VALU"] / sq["SQ_BUSY_CU_CYCLES"] if sq.get("SQ_BUSY_CU_CYCLES") else None,
             "fetch_kib": f, "write_kib": w, "traffic_bytes": (f * scale_f + w * scale_w) * 1024}
+    out["calibration"] = read_calibration()
     with open(COUNTERS_FILE, "w") as fh:
         json.dump(out, fh, indent=1, sort_keys=True)
         fh.write("\n")
     print(f"{COUNTERS_FILE}: {sorted(out['kernels'])}")
+
+
+def read_calibration():
+    """What the stand-alone calibration program sustained on the box (profiles/calibrate_*.md): the mean
+    issue rate of the 64-bit integer instructions the kernels are made of, per compute unit and nominal
+    clock, and the best streaming read rate."""
+    path = os.path.join(ROOT, "profiles", "calibrate_gfx950_instruction_rates.md")
+    rates, reads = [], []
+    try:
+        for line in open(path):
+            f = line.split()
+            if f and f[0] in ("v_mad_u64_u32", "v_lshl_add_u64", "v_cmp_gt_i64", "v_cndmask_b32"):
+                rates.append(float(f[-1]))
+            if line.startswith("HBM streaming read"):
+                reads.append(float(f[-2]))
+    except OSError:
+        return None
+    if not rates or not reads:
+        return None
+    return {"valu_per_cu_clock": sum(rates) / len(rates), "hbm_read_gbs": max(reads), "source": os.path.basename(path)}
+
+
+def calibration():
+    try:
+        return json.load(open(COUNTERS_FILE)).get("calibration")
+    except (OSError, ValueError):
+        return None
 
 
 def alu_roofline(key, units, ms, kernel_name, census_ops=None):
@@ -141,6 +169,10 @@ def alu_roofline(key, units, ms, kernel_name, census_ops=None):
     if c is not None:
         out.update(achieved=c["valu_per_unit"] * rate / 1e12, frac=c["valu_per_unit"] * rate / 1e12 / PEAK_LANE_TOPS,
                    traffic=c["traffic_bytes"], valu_per_unit=c["valu_per_unit"])
+        cal = calibration()
+        if cal:         # against what the calibration program sustains for 64-bit integer instructions on the box
+            out["calibrated"] = {"peak": PEAK_LANE_TOPS * cal["valu_per_cu_clock"],
+                                 "frac": out["frac"] / cal["valu_per_cu_clock"]}
     if census_ops is not None:
         out["census"] = {"lane_ops_per_unit": census_ops, "achieved": census_ops * rate / 1e12,
                          "frac": census_ops * rate / 1e12 / PEAK_LANE_TOPS,
@@ -404,6 +436,9 @@ def main():
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": gbs / PEAK_HBM_GBS, "traffic": c["traffic_bytes"] if c else None,
                          "algorithmic_bytes": nbytes, "kernel": "timeline_kernel"}}
+        if calibration():
+            read = calibration()["hbm_read_gbs"]            # the calibration program's best streaming read
+            extra["g5_event_lists"]["roofline"]["calibrated"] = {"peak": read, "frac": gbs / read}
         from workloads import events as E
         ev_c, off_c = E.generate(64, seed=0, first=0)
         wa, wr = B.event_lists_peaks(ev_c, off_c)
