@@ -56,6 +56,68 @@ def _check(U, cfg, tables, const=CONST, threads=8, expect=None, prebuilt=None):
             assert e.value.code == -3
 
 
+def _one(**kw):
+    base = dict(arch_id=0, h=256, L=4, n_heads=4, n_kv=4, ffn=1024, V=8192, P=512, bs=4, sl=256, method=0, d=1,
+                chunk_k=4, flags=G.FLAG_GRAD_ALIAS)
+    base.update(kw)
+    return {k: np.asarray([v]).astype(G.FIELD_DTYPE[k]) for k, v in base.items()}
+
+
+def _rows(*configs):
+    return {k: np.concatenate([c[k] for c in configs]) for k in configs[0]}
+
+
+def test_worked_examples_through_the_hip_path(U, golden):
+    """The hand-worked values of tests/golden directly, not via the oracle, with every kernel
+    form the tables allow: the closed-form example with its gradient and per-GPU columns, both
+    hand-walked timelines, a table without events, and a head declared as an Embedding."""
+    import paper_2404_10933_amd as M
+    g = golden("worked_example_gpt_tiny.txt")
+    c0 = T.Constants(m_base=0)
+    no_alias = 0
+    cfg = _rows(_one(), *[_one(method=1, d=d) for d in (2, 3, 4, 7)], *[_one(method=2, d=d) for d in (2, 3, 4, 7)],
+                _one(chunk_k=2), _one(chunk_k=-1), _one(flags=no_alias),
+                *[_one(method=m, d=d, flags=no_alias) for m in (1, 2) for d in (3, 7)], _one(method=1, d=5, flags=no_alias),
+                _one(method=1, d=5), _one(method=2, d=5))
+    want_peak = [g["peak_cdp"]] + [g[f"peak_zero3_d{d}"] for d in (2, 3, 4, 7)] + [g[f"peak_tp_d{d}"] for d in (2, 3, 4, 7)] \
+        + [g["peak_cdp"] - g["m_p"] + g["m_p_k2"], g["peak_cdp_search"], g["peak_cdp_noalias"],
+           g["peak_zero3_d3_noalias"], g["peak_zero3_d7_noalias"], g["peak_tp_d3_noalias"], g["peak_tp_d7_noalias"],
+           g["peak_zero3_d5_noalias"]]
+    tables = [T.gpt_table()]
+    allowed = M.llmem_kernel_forms(M.Tables(tables, m_base=0, device=None))["allowed"]
+    for kernel in [0] + allowed:
+        p, d = U.hip_estimate(cfg, tables, c0, kernel=kernel)
+        assert p[:len(want_peak)].tolist() == want_peak, kernel
+        assert (d[0, A.D_NPARAMS], d[0, A.D_TMAX], d[0, A.D_PARAM], d[0, A.D_OS], d[0, A.D_OUT], d[0, A.D_LM]) == (
+            g["n_params"], g["t_max"], g["m_p"], g["m_os"], g["m_out"], g["m_lm"]), kernel
+        assert d[5, A.D_BACK] == g["m_back_d2"] and d[10, A.D_K] == g["search_k"]
+        assert d[11, A.D_GRAD] == d[0, A.D_GRAD] == g["grad_logical_cdp"]
+        assert (d[4, A.D_PARAM], d[4, A.D_OS], d[4, A.D_GRAD]) == (g["param_gpu_zero3_d7"], g["os_gpu_d7"], g["grad_logical_d7"])
+        assert (d[8, A.D_PARAM], d[8, A.D_OS], d[8, A.D_GRAD]) == (g["param_gpu_tp_d7"], g["os_gpu_d7"], g["grad_logical_d7"])
+        assert d[12, A.D_GRAD] == d[14, A.D_GRAD] == g["grad_logical_d3"]
+        assert d[17, A.D_OS] == d[18, A.D_OS] == g["os_gpu_d5"]
+    # the hand-walked timelines
+    from test_oracle_pins import _tiny_timeline_table, _second_timeline_table
+    w = golden("worked_timeline_tiny.txt")
+    c5 = T.Constants(m_base=5000)
+    cases = [(_tiny_timeline_table(), _rows(_one(L=3), _one(L=3, method=2, d=4), _one(L=3, method=1, d=4)),
+              [w["peak_live_cdp"], w["peak_live_tp_d4"], w["peak_live_cdp"]]),
+             (_second_timeline_table(), _rows(_one(L=3), _one(L=3, method=2, d=3), _one(L=3, method=2, d=1), _one(L=3, method=1, d=3)),
+              [w["peak_live2_cdp"], w["peak_live2_tp_d3"], w["peak_live2_tp_d1"], w["peak_live2_cdp"]]),
+             (T.ArchTable("none", (), ()), _one(L=3), [w["peak_live_no_events"]])]
+    for table, rows, want in cases:
+        allowed = M.llmem_kernel_forms(M.Tables([table], m_base=5000, device=None))["allowed"]
+        for kernel in [0] + allowed:
+            _, d = U.hip_estimate(rows, [table], c5, kernel=kernel)
+            assert d[:, A.D_LIVE].tolist() == want, (table.name, kernel)
+    # e_n leaves out a head that is declared as an Embedding: m_out is one hidden-state tensor, exactly a page
+    P = T.ParamEntry
+    tied = T.ArchTable("tied", (P("tok", 1, ("V", "h"), "E", "EMBED_TOK", False), P("head", 1, ("V", "h"), "E", "LM_HEAD", False)), ())
+    for kernel in [0] + M.llmem_kernel_forms(M.Tables([tied], m_base=0, device=None))["allowed"]:
+        _, d = U.hip_estimate(_one(L=0, bs=4, sl=512, h=512, V=1000), [tied], c0, kernel=kernel)
+        assert d[0, A.D_OUT] == 2 * 1024 * 1024, kernel
+
+
 def test_grid1_all(U):
     cfg = G.grid1()
     _check(U, cfg, [T.gpt_table()], expect=BOTH, prebuilt=True)

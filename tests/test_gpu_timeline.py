@@ -27,7 +27,8 @@ def test_handwritten_lists(U):
     M2 = 2 * 1024 * 1024
     lists = [[], [1], [-1, 1], [511, 512, 513, -511, -512, -513], [M2 - 513, M2 - 512, M2 - 511, M2, M2 + 1],
              [3_000_000, 100, -3_000_000, 100], [0, 0, 0], [5, -5] * 700, [M2] * 1500 + [-M2] * 1500,
-             list(range(1, 1024)), list(range(1, 1025)), list(range(1, 1026)), list(range(1, 2050)), []]
+             list(range(1, 1024)), list(range(1, 1025)), list(range(1, 1026)), list(range(1, 2050)), [],
+             [-600], [-600, 100], [-3_000_000, 100]]              # nothing live before the first event: peaks of zero
     ev, off = E.from_lists(lists)
     _check(U, ev, off)
     a, r = A.event_lists_peaks(ev, off)                  # the pinned Python oracle agrees too

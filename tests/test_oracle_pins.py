@@ -96,6 +96,19 @@ def _tiny_timeline_table():
     return T.ArchTable("tiny", (), ev)
 
 
+def _second_timeline_table():
+    E = T.EventEntry
+    one = ("one",)
+    tp = frozenset((2,))
+    ev = (
+        E("a", "A", +1, 300, one, 1, T.ALL_METHODS, "none", True),
+        E("f", "F", +1, 600, one, 1), E("f-", "F", -1, 600, one, 1),
+        E("buf", "B", +1, 1537, one, 1, tp, "tp_gather"), E("b", "B", +1, 200, one, 1), E("b-", "B", -1, 200, one, 1),
+        E("a-", "Z", -1, 300, one, 1, T.ALL_METHODS, "none", True), E("buf-", "Z", -1, 1537, one, 1, tp, "tp_gather", True),
+    )
+    return T.ArchTable("second", (), ev)
+
+
 def test_worked_timeline(golden):
     g = golden("worked_timeline_tiny.txt")
     t = _tiny_timeline_table()
@@ -104,6 +117,34 @@ def test_worked_timeline(golden):
     assert est(cfg(L=3, method=2, d=4), t, const, True)[O.D_LIVE] == g["peak_live_tp_d4"]
     # ZeRO-3 does not see the TP-only events
     assert est(cfg(L=3, method=1, d=4), t, const, True)[O.D_LIVE] == g["peak_live_cdp"]
+    # per-block allocation in one event; an all-gather buffer that is no whole number of bytes
+    t2 = _second_timeline_table()
+    assert est(cfg(L=3), t2, const, True)[O.D_LIVE] == g["peak_live2_cdp"]
+    assert est(cfg(L=3, method=2, d=3), t2, const, True)[O.D_LIVE] == g["peak_live2_tp_d3"]
+    assert est(cfg(L=3, method=2, d=1), t2, const, True)[O.D_LIVE] == g["peak_live2_tp_d1"]
+    assert est(cfg(L=3, method=1, d=3), t2, const, True)[O.D_LIVE] == g["peak_live2_cdp"]
+    # no events at all: the resident state is the peak
+    assert est(cfg(L=3), T.ArchTable("none", (), ()), const, True)[O.D_LIVE] == g["peak_live_no_events"]
+
+
+def test_embedding_count_leaves_out_the_head():
+    """e_n of m_out (Sec. 4.2) counts the Embedding operators of the transformer part: a head that
+    is declared as an Embedding-class tensor (a tied copy of the token embedding) is not one.
+    Tiny table: a token embedding and such a head, no blocks: m_out = one hidden-state tensor."""
+    P = T.ParamEntry
+    t = T.ArchTable("tied", (P("tok", 1, ("V", "h"), "E", "EMBED_TOK", False), P("head", 1, ("V", "h"), "E", "LM_HEAD", False)), ())
+    c = cfg(L=0, bs=4, sl=512, h=512, V=1000)
+    assert est(c, t, T.Constants(m_base=0))[O.D_OUT] == 2 * 1024 * 1024          # 4 * 512 * 512 * 2 B = exactly one page
+
+
+def test_event_lists_that_start_with_a_release():
+    """The empty prefix counts (nothing is live before the first event): a list whose running
+    totals never rise above zero has peaks of zero, in both pools."""
+    assert O.event_list_peaks([]) == (0, 0)
+    assert O.event_list_peaks([-600]) == (0, 0)
+    assert O.event_list_peaks([-600, 100]) == (0, 0)
+    # the total never rises above zero, but the small pool on its own reaches one block: one segment reserved
+    assert O.event_list_peaks([-3_000_000, 100]) == (0, 2 * 1024 * 1024)
 
 
 # ---------------------------------------------------------------------------
@@ -511,6 +552,75 @@ def _suite(golden):
     test_model_states_bytes_per_parameter()
     test_output_and_lm_terms_closed_form()
     test_per_tensor_rounding_of_optimizer_states()
+    test_param_count_closed_forms()
+    test_event_list_peaks_against_block_simulation()
+    test_embedding_count_leaves_out_the_head()
+    test_event_lists_that_start_with_a_release()
+
+
+def _wrong_census(t_max_over_all=False, layers_once=False, tied_counted=False, embeddings_all=False):
+    def census(table, D, tied):
+        L = D["L"]
+        embed_p = lm_p = other_p = t_max = e_n = 0
+        for p in table.params:
+            t_p = O.monomial(p.coef, p.dims, D)
+            count = L if (p.per_layer and not layers_once) else 1
+            if p.role == "EMBED_TOK":
+                embed_p += t_p * count
+            elif p.role == "LM_HEAD":
+                lm_p += t_p * count
+            else:
+                other_p += t_p * count
+            if p.role == "OTHER" or t_max_over_all:
+                t_max = max(t_max, t_p)
+            if p.cls == "E" and (p.role != "LM_HEAD" or embeddings_all):
+                e_n += 1
+        n_params = embed_p + other_p + (lm_p if (tied_counted or not tied) else 0)
+        return embed_p, lm_p, other_p, t_max, n_params, e_n
+    return census
+
+
+def _wrong_timeline(backward_once=False, without_resident=False, segment_ends_only=False, forward_last_block_first=False):
+    def peak_of(table, D, method, prelude, align):
+        by_seg = {s: [e for e in table.events if e.seg == s] for s in "AFHBZ"}
+        live = prelude
+        peak = 0 if without_resident else prelude
+        order = ["A"] + ["F"] * D["L"] + ["H"] + ["B"] * (1 if backward_once else D["L"]) + ["Z"]
+        for s in order:
+            for e in by_seg[s]:
+                live += O.event_value(e, D, method, align)
+                if not segment_ends_only:
+                    peak = max(peak, live)
+            if segment_ends_only:
+                peak = max(peak, live)
+        return peak
+    return peak_of
+
+
+def _wrong_event_list(split_inclusive=False, pool_by_raw_size=False, reserved_of_sum=False, reserved_of_total=False,
+                      unrounded=False, without_empty_prefix=False):
+    def peaks(events):
+        small = large = 0
+        top_small = top_large = top = None if without_empty_prefix else 0
+        for raw in events:
+            raw = int(raw)
+            r = abs(raw) if unrounded else O.up(abs(raw), O.EVENT_ALIGN)
+            key = abs(raw) if pool_by_raw_size else r
+            delta = r if raw >= 0 else -r
+            if key < O.EVENT_SPLIT or (split_inclusive and key == O.EVENT_SPLIT):
+                small += delta
+            else:
+                large += delta
+            top_small = small if top_small is None else max(top_small, small)
+            top_large = large if top_large is None else max(top_large, large)
+            top = small + large if top is None else max(top, small + large)
+        top_small, top_large, top = top_small or 0, top_large or 0, top or 0
+        if reserved_of_total:
+            return top, O.up(top, O.EVENT_SEGMENT)
+        if reserved_of_sum:
+            return top, O.up(top_small + top_large, O.EVENT_SEGMENT)
+        return top, O.up(top_small, O.EVENT_SEGMENT) + O.up(top_large, O.EVENT_SEGMENT)
+    return peaks
 
 
 MUTANTS = {
@@ -582,7 +692,31 @@ MUTANTS = {
                            e.sign * O.monomial(e.coef, e.dims, D) * e.elem_bytes * (D["L"] if e.times_L else 1)),
     "method mask ignored": ("event_value", lambda e, D, method, align:
                             e.sign * O.up(O.monomial(e.coef, e.dims, D) * e.elem_bytes, align) * (D["L"] if e.times_L else 1)),
+    "all-gather buffer floored": ("event_value", lambda e, D, method, align: 0 if method not in e.methods else e.sign * O.up(
+        (O.monomial(e.coef, e.dims, D) * e.elem_bytes * (D["d"] - 1) // D["d"]) if e.scale == "tp_gather"
+        else O.monomial(e.coef, e.dims, D) * e.elem_bytes, align) * (D["L"] if e.times_L else 1)),
+    "all-gather buffer whole": ("event_value", lambda e, D, method, align: 0 if method not in e.methods else e.sign * O.up(
+        O.monomial(e.coef, e.dims, D) * e.elem_bytes, align) * (D["L"] if e.times_L else 1)),
+    "per-block events summed before rounding": ("event_value", lambda e, D, method, align: 0 if method not in e.methods else e.sign * O.up(
+        (O.cdiv(O.monomial(e.coef, e.dims, D) * e.elem_bytes * (D["d"] - 1), D["d"]) if e.scale == "tp_gather"
+         else O.monomial(e.coef, e.dims, D) * e.elem_bytes) * (D["L"] if e.times_L else 1), align)),
+    "backward walked once": ("timeline_peak", _wrong_timeline(backward_once=True)),
+    "resident state alone not a peak": ("timeline_peak", _wrong_timeline(without_resident=True)),
+    "peak taken at segment ends": ("timeline_peak", _wrong_timeline(segment_ends_only=True)),
+    "largest tensor over all roles": ("param_census", _wrong_census(t_max_over_all=True)),
+    "per-block tensors counted once": ("param_census", _wrong_census(layers_once=True)),
+    "tied head counted": ("param_census", _wrong_census(tied_counted=True)),
+    "lm_head counted among the embeddings": ("param_census", _wrong_census(embeddings_all=True)),
+    "kv width from the model width": ("dim_vector", lambda c: dict(_REAL_DIM_VECTOR(c), kv_dim=c["n_kv"] * c["h"])),
+    "shifted length not shortened": ("dim_vector", lambda c: dict(_REAL_DIM_VECTOR(c), sl_m1=c["sl"])),
+    "pool split inclusive": ("event_list_peaks", _wrong_event_list(split_inclusive=True)),
+    "pool chosen by raw size": ("event_list_peaks", _wrong_event_list(pool_by_raw_size=True)),
+    "reserved rounds the sum of the pools": ("event_list_peaks", _wrong_event_list(reserved_of_sum=True)),
+    "reserved from the total peak": ("event_list_peaks", _wrong_event_list(reserved_of_total=True)),
+    "list events not rounded": ("event_list_peaks", _wrong_event_list(unrounded=True)),
+    "empty prefix does not count": ("event_list_peaks", _wrong_event_list(without_empty_prefix=True)),
 }
+_REAL_DIM_VECTOR = O.dim_vector
 
 
 @pytest.mark.parametrize("name", sorted(MUTANTS))
