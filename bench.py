@@ -15,7 +15,8 @@ slots the kernel fills: vector instructions per configuration as the hardware
 counters gave them (profiles/counters.json, valid only while the kernel sources
 are the ones that were profiled) times the measured rate, over the nominal issue
 rate.  Next to it, "census": the operations of the method itself in its leanest
-form, counted on the oracle's side from the tables alone, over the same time.
+form, counted on the oracle's side from the tables alone and priced in 64-bit lane
+operations, and how many instructions the kernel issues per such operation.
 
 Prints ONE JSON line.  `--import-counters DIR` (no GPU needed) instead turns the
 rocprofv3 counter files under DIR into profiles/counters.json.
@@ -174,9 +175,12 @@ def alu_roofline(key, units, ms, kernel_name, census_ops=None):
             out["calibrated"] = {"peak": PEAK_LANE_TOPS * cal["valu_per_cu_clock"],
                                  "frac": out["frac"] / cal["valu_per_cu_clock"]}
     if census_ops is not None:
-        out["census"] = {"lane_ops_per_unit": census_ops, "achieved": census_ops * rate / 1e12,
-                         "frac": census_ops * rate / 1e12 / PEAK_LANE_TOPS,
-                         "basis": "operations of the method in its leanest form, counted from the tables by oracle/census.py"}
+        # context, not a fraction of any peak: a kernel that works in 32-bit pages and blocks issues fewer
+        # instructions than the census prices in 64-bit operations
+        out["census"] = {"lane_ops_per_unit": census_ops, "census_ops_per_s": census_ops * rate,
+                         "issued_per_census_op": c["valu_per_unit"] / census_ops if c is not None else None,
+                         "basis": "operations of the method in its leanest form, counted from the tables by "
+                                  "oracle/census.py and priced in 64-bit lane operations"}
     return out
 
 
