@@ -261,6 +261,44 @@ def test_queries_generator(U):
         assert (tp.cpu().numpy() == want_tp).all()
 
 
+def test_outputs_beyond_four_gib(U):
+    """45 000 019 queries generated on the device: the decision columns take 4.3 GB, the last of
+    them beyond 2^32 bytes from the start of the output.  Slices at the start, in the middle and
+    at the ragged end against the oracle; everywhere else the fill value must be gone."""
+    import paper_2404_10933_amd as M
+    n, m_total = 45_000_019, 80 * GIB
+    tables = [T.llama_table()]
+    dev = M.DeviceConfigs.empty(n)
+    tp = torch.empty(n, dtype=torch.uint8, device="cuda")
+    M.llmem_queries_generate(3, 0, n, dev, tp)
+    tab = M.Tables(tables, m_base=CONST.m_base, cu_p=CONST.cu_p, align=CONST.align)
+    method = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    bs = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    det = torch.full((M.NDECIDE, n), -7, dtype=torch.int64, device="cuda")
+    assert det.numel() * 8 > (1 << 32)
+    M.llmem_decide(dev, tp, tab, m_total, method, bs, det)
+    torch.cuda.synchronize()
+    for first, m in ((0, 700), (n // 2 - 300, 700), (n - 723, 723)):
+        cfg, tp_np = G.grid6(n=m, seed=3, first=first)
+        want = B.decide(cfg, tp_np, tables, CONST, m_total, threads=16)
+        U.assert_same(f"decision rows from {first}", det[:, first:first + m].cpu().numpy().T, want)
+        U.assert_same(f"method from {first}", method[first:first + m].cpu().numpy(), want[:, A.C_METHOD])
+        U.assert_same(f"bs from {first}", bs[first:first + m].cpu().numpy(), want[:, A.C_BS])
+    assert int((method == -7).sum().item()) == 0 and int((bs == -7).sum().item()) == 0
+    for c in range(M.NDECIDE):
+        assert int((det[c] == -7).sum().item()) == 0, c
+    # the four estimates at once: 4 columns of 360 MB
+    del det
+    peaks = torch.full((4, n), -7, dtype=torch.int64, device="cuda")
+    M.llmem_estimate_methods(dev, tp, tab, peaks)
+    torch.cuda.synchronize()
+    first, m = n - 723, 723
+    cfg, tp_np = G.grid6(n=m, seed=3, first=first)
+    U.assert_same("estimates of the four methods at the end", peaks[:, first:].cpu().numpy().T,
+                  B.method_peaks(cfg, tp_np, tables, CONST, threads=8)[0])
+    assert int((peaks == -7).sum().item()) == 0
+
+
 def test_full_size_decision_grid(U):
     """4 * 10^6 queries generated on the device, in the launch configuration the benchmark times:
     sampled queries against the oracle; for all of them the properties that define the result."""

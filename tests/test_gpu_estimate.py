@@ -364,6 +364,35 @@ def test_full_size_grid4(U, kernel):
         U.assert_same(f"detail column {c}, all 10^7", det[c].cpu().numpy(), want_d[:, c])
 
 
+def test_outputs_beyond_four_gib(U):
+    """45 000 037 configurations generated on the device: the detail columns take 4.3 GB, so the
+    last of them lie beyond 2^32 bytes from the start of the output (and of a column: 360 MB).
+    The oracle computes slices at the start, in the middle and at the ragged end; everything the
+    kernels wrote elsewhere must at least differ from the fill value."""
+    import paper_2404_10933_amd as M
+    n = 45_000_037
+    dev = M.DeviceConfigs.empty(n)
+    M.llmem_grid_generate(4, 7, 0, n, dev)
+    tables = [T.llama_table()]
+    slices = [(0, 4096), (n // 2 - 1000, 3000), (n - 4101, 4101)]
+    want = [B.estimate(G.grid4(n=m, seed=7, first=first), tables, CONST, threads=8) for first, m in slices]
+    peaks = torch.empty(n, dtype=torch.int64, device="cuda")
+    det = torch.empty((M.NDETAIL, n), dtype=torch.int64, device="cuda")
+    assert det.numel() * 8 > (1 << 32)
+    for kernel in (0, LANE_COMPILED, LANE_EVENTS, LANE_DIRECT):
+        peaks.fill_(-7)
+        det.fill_(-7)
+        tab = M.Tables(tables, m_base=CONST.m_base, cu_p=CONST.cu_p, align=CONST.align, kernel=kernel)
+        M.llmem_estimate_ex(dev, tab, peaks, det)
+        torch.cuda.synchronize()
+        for (first, m), (want_p, want_d) in zip(slices, want):
+            U.assert_same(f"m_peak from {first} (kernel {kernel})", peaks[first:first + m].cpu().numpy(), want_p)
+            U.assert_same(f"detail from {first} (kernel {kernel})", det[:, first:first + m].cpu().numpy().T, want_d)
+        assert int((peaks == -7).sum().item()) == 0 and int((det[M.NDETAIL - 1] == -7).sum().item()) == 0
+        assert int((det[A.D_LIVE] <= 0).sum().item()) == 0                       # every timeline peak was written
+    del det, peaks
+
+
 def test_release_of_kernels_built_at_run_time(U):
     """llmem_kernels_release unloads what was built at run time and nothing else: the count it
     returns, a second call that finds nothing, the same tables built again with the same results,
