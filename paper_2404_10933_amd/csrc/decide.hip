@@ -353,8 +353,15 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
             }
 #pragma unroll
             for (int m = 0; m < 4; ++m) span |= top[m] - best[m];
-            for (int s = 32; s >= 1; s >>= 1) span |= (u32)__shfl_xor((int)span, s, 64);
-            const int bits = 32 - __builtin_clz(d_uni(span) | 1u);
+            // bit length of the widest bracket in the wavefront: brackets are at most 1 wide where the
+            // bracket's derivation holds, which two ballots establish; else bit by bit from the top
+            int bits;
+            if (__builtin_amdgcn_ballot_w64(span > 1u) == 0) {
+                bits = __builtin_amdgcn_ballot_w64(span != 0u) != 0 ? 1 : 0;
+            } else {
+                bits = 32;
+                while (bits > 2 && __builtin_amdgcn_ballot_w64((span >> (bits - 1)) != 0u) == 0) --bits;
+            }
             for (int bit = bits - 1; bit >= 0; --bit) {                   // best + 2^bit, 2^bit above what is left of the span
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
