@@ -66,12 +66,16 @@ __device__ __forceinline__ u32 d_uni(u32 v) { return (u32)__builtin_amdgcn_readf
 // the L2 (with ordinary stores the decision columns cost a quarter of the kernel's time).
 __device__ __forceinline__ void put(long long *p, i64 v) { __builtin_nontemporal_store((long long)v, p); }
 __device__ __forceinline__ void put(int *p, int v) { __builtin_nontemporal_store(v, p); }
-// x * m (mod 2^64): the 64-bit product of the low half plus the low 32 bits of the high half's
-__device__ __forceinline__ u64 d_mul(u64 x, u32 m)
+// acc + x * m (mod 2^64): the low half's 64-bit product added in one instruction, the low 32 bits of
+// the high half's product added to the upper word (three instructions where the plain expression
+// compiles to five)
+__device__ __forceinline__ u64 d_mad(u64 acc, u64 x, u32 m)
 {
-    const u64 lo = (u64)(u32)x * (u64)m;
-    return ((u64)((u32)(x >> 32) * m + (u32)(lo >> 32)) << 32) | (u64)(u32)lo;
+    const u64 low = (u64)(u32)x * (u64)m + acc;
+    const u32 high = (u32)(x >> 32) * m;
+    return low + ((u64)high << 32);
 }
+__device__ __forceinline__ u64 d_mul(u64 x, u32 m) { return d_mad(0ull, x, m); }
 // ceil(x / d) for x + d - 1 < 2^32: the multiply-high of the 64-bit constant with a 32-bit dividend
 __device__ __forceinline__ u32 d_cdiv32(u32 x, u32 d, DivMagic m)
 {
@@ -183,14 +187,15 @@ __global__ __launch_bounds__(DC_BLOCK) void decide_kernel(const DecideArgs a)
                     if (nd > 1) t_p = d_mul(t_p, D[(desc >> 8) & 15u]);
                     if (nd > 2) t_p = d_mul(t_p, D[(desc >> 12) & 15u]);
                     if (nd > 3) t_p = d_mul(t_p, D[(desc >> 16) & 15u]);
-                    if (w2 & 0xffffu) embed_p += t_p * (u64)((w2 & 255u) + ((w2 >> 8) & 255u) * L);
-                    if (w2 >> 16) lm_p += t_p * (u64)(((w2 >> 16) & 255u) + (w2 >> 24) * L);
+                    // (how many tensors: so many once, so many in each of the L blocks)
+                    if (w2 & 0xffffu) embed_p = d_mad(embed_p, t_p, (w2 & 255u) + ((w2 >> 8) & 255u) * L);
+                    if (w2 >> 16) lm_p = d_mad(lm_p, t_p, ((w2 >> 16) & 255u) + (w2 >> 24) * L);
                     if (w3 & 0xffffu) {
-                        other_p += t_p * (u64)((w3 & 255u) + ((w3 >> 8) & 255u) * L);
+                        other_p = d_mad(other_p, t_p, (w3 & 255u) + ((w3 >> 8) & 255u) * L);
                         t_max = t_p > t_max ? t_p : t_max;
                     }
                     if (w3 >> 16)
-                        m_os += d_up(t_p * (u64)(B32 + B32), cu_shift) * (u64)(((w3 >> 16) & 255u) + (w3 >> 24) * L);
+                        m_os = d_mad(m_os, d_up(t_p * (u64)(B32 + B32), cu_shift), ((w3 >> 16) & 255u) + (w3 >> 24) * L);
                 }
                 continue;
             }
