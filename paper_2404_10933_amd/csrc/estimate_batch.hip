@@ -821,7 +821,9 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                                 // a sum ends with this group (wave-uniform): a point competes for the
                                 // segment's maximum, the net change closes the segment
                                 if (t[g] & (PROG_END_POINT | PROG_END_SEGMENT)) {
+#ifndef LLMEM_SPECIALIZED
                                     asm volatile("" ::: "memory");
+#endif
                                     if (t[g] & PROG_END_SEGMENT) {
                                         // the narrow sums are in blocks
                                         const i64 run = NARROW ? (i64)((u64)acc << align_shift) : acc;
