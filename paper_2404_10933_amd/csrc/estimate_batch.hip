@@ -23,6 +23,10 @@
 // they arrive through scalar loads and the set-up above is skipped.  A peak
 // point costs its terms (count * value) instead of every event before it.
 //
+// Direct form (EstimateArgs::direct): for tables with more distinct sizes than class slots fit,
+// every event's size is evaluated where it stands, from the lane's dimension vector kept in
+// wave-private LDS rows.
+//
 // Closed form: Sec. 4.2 (m_p, m_os, m_out, m_lm, m_peak^s) and Sec. 5 (m_peak^dp,
 // m_peak^tp, m_back^tp) of arXiv 2404.10933; chunk size per Sec. 4.1; timeline
 // traversal per Sec. 2.1 / Sec. 3.1.
@@ -822,6 +826,9 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                                 // segment's maximum, the net change closes the segment
                                 if (t[g] & (PROG_END_POINT | PROG_END_SEGMENT)) {
 #ifndef LLMEM_SPECIALIZED
+                                    // (keeps the next sum's reads behind this point: fewer live registers.  A
+                                    // specialized build knows every slot a term names and, left free, reads
+                                    // each class value once for all the sums that use it)
                                     asm volatile("" ::: "memory");
 #endif
                                     if (t[g] & PROG_END_SEGMENT) {

@@ -9,7 +9,7 @@
 //
 // Built at run time (hiprtc): any other tables, when asked for.  One build per
 // (device, table words, flavour), made on first use (a fraction of a second to a
-// few seconds) and kept until the process ends.  With the environment variable
+// few seconds) and kept until release_built() or the end of the process.  With the environment variable
 // LLMEM_KERNEL_CACHE naming a directory, built code objects are also kept there
 // and loaded from there by later processes (a file per build, verified against the
 // full key and the embedded sources before use).  The sources come from
