@@ -201,7 +201,10 @@ typedef struct llmem_tables {
  *   kernel and allocates host memory for the build and device memory for the loaded code object;
  *   the build is kept, per device, until llmem_kernels_release or the end of the process, and also
  *   between processes when the environment variable LLMEM_KERNEL_CACHE names a writable directory
- *   (one file per build, used only if its recorded identity matches in full).  A failure of the run-time compiler or loader
+ *   (one file per build, used only if its recorded identity matches in full).  At most 64 such
+ *   kernels stay loaded per device (LLMEM_KERNELS_KEPT changes the number): a call that has to
+ *   build one more first waits for the device (hipDeviceSynchronize) and unloads the less recently
+ *   used half of those no call is using; a later call with their tables builds them again.  A failure of the run-time compiler or loader
  *   is LLMEM_EHIP with its message in llmem_strerror.  The run-time compiler is not started in a
  *   process that a profiler has been loaded into (ROCP_TOOL_LIBRARIES set, or LD_PRELOAD /
  *   HSA_TOOLS_LIB naming a rocprofiler library): without a kept code object such a call is

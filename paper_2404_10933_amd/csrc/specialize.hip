@@ -23,6 +23,7 @@
 #include <unistd.h>
 #include <string.h>
 
+#include <algorithm>
 #include <atomic>
 #include <condition_variable>
 #include <map>
@@ -96,10 +97,33 @@ struct Slot {
     int rc = LLMEM_OK;
     std::string problem;
     Built built;
+    unsigned long long used = 0;                // g_clock at the last call that looked it up
 };
 
 std::mutex g_lock;
 std::condition_variable g_built_changed;
+unsigned long long g_clock = 0;
+
+// How many kernels built at run time a process keeps loaded per device (LLMEM_KERNELS_KEPT, at
+// least 2): a process that goes through table sets without end does not collect modules without end.
+int kept_limit()
+{
+    static const int limit = [] {
+        const char *text = getenv("LLMEM_KERNELS_KEPT");
+        const int n = text && text[0] ? atoi(text) : 64;
+        return n < 2 ? 2 : n;
+    }();
+    return limit;
+}
+
+void unload(Built &built)
+{
+    if (built.module) (void)hipModuleUnload(built.module);
+    built.module = nullptr;
+    built.function = nullptr;
+    delete built.code;
+    built.code = nullptr;
+}
 std::map<Key, std::shared_ptr<Slot>> g_built;   // finished builds stay (modules loaded) until release_built() or the process ends
 
 int fail(const std::string &text)
@@ -379,18 +403,46 @@ int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch,
     key.words.assign(args.prog, args.prog + words_used(args));
     const size_t lds_bytes = batch_kernel_lds_bytes(args);
     std::shared_ptr<Slot> slot;
+    std::vector<std::shared_ptr<Slot>> evicted;
     bool mine = false;
     {
         std::unique_lock<std::mutex> hold(g_lock);
         auto at = g_built.find(key);
         if (at == g_built.end()) {
+            // room for one more on this device?  Else the less recently used half of the finished
+            // builds that no call is holding leaves the list now and is unloaded below
+            std::vector<std::pair<unsigned long long, const Key *>> idle;
+            int kept = 0;
+            for (auto &entry : g_built) {
+                if (entry.first.device != key.device || !entry.second->done) continue;
+                ++kept;
+                if (entry.second.use_count() == 1) idle.emplace_back(entry.second->used, &entry.first);
+            }
+            if (kept >= kept_limit()) {
+                std::sort(idle.begin(), idle.end());
+                idle.resize(idle.size() < (size_t)(kept + 1) / 2 ? idle.size() : (size_t)(kept + 1) / 2);
+                std::vector<Key> keys;
+                for (auto &entry : idle) keys.push_back(*entry.second);
+                for (const Key &k : keys) {
+                    auto victim = g_built.find(k);
+                    evicted.push_back(victim->second);
+                    g_built.erase(victim);
+                }
+            }
             slot = std::make_shared<Slot>();
+            slot->used = ++g_clock;
             g_built.emplace(key, slot);
             mine = true;
         } else {
             slot = at->second;
+            slot->used = ++g_clock;
             g_built_changed.wait(hold, [&] { return slot->done; });
         }
+    }
+    if (!evicted.empty()) {
+        // launches of the kernels that leave may still be pending: they have ended after this
+        (void)hipDeviceSynchronize();
+        for (auto &gone : evicted) unload(gone->built);
     }
     if (mine) {
         // built outside the lock: seconds, during which other kernels are found and launched
@@ -451,11 +503,7 @@ int release_built()
     for (auto &entry : gone) {
         Built &built = entry.second->built;
         if (entry.second->rc != LLMEM_OK || !built.module) continue;
-        if (hipSetDevice(entry.first) == hipSuccess && hipModuleUnload(built.module) == hipSuccess) ++count;
-        built.module = nullptr;
-        built.function = nullptr;
-        delete built.code;
-        built.code = nullptr;
+        if (hipSetDevice(entry.first) == hipSuccess) { unload(built); ++count; }
     }
     if (restore) (void)hipSetDevice(current);
     return count;

@@ -420,6 +420,39 @@ def test_release_of_kernels_built_at_run_time(U):
         U.assert_same("compiled form after the release", got_d, want_d)
 
 
+def test_kept_run_time_builds_are_bounded(U):
+    """A process keeps a bounded number of kernels built at run time per device (LLMEM_KERNELS_KEPT,
+    read once: a child process with a limit of 4).  Seven table sets in turn, the first one again
+    (its kernel has been unloaded meanwhile and is built again), every result equal to the oracle's,
+    and what is left loaded at the end is within the limit."""
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    child = (
+        "import sys, numpy as np\n"
+        f"sys.path[:0] = [{repr(os.path.dirname(here))}, {repr(here)}]\n"
+        "import torch, gpu_util as U\n"
+        "import paper_2404_10933_amd as M\n"
+        "from oracle import oracle_c as B\n"
+        "from workloads import grids as G, tables as T\n"
+        "const = T.Constants(m_base=256 << 20)\n"
+        "base = T.gpt_table()\n"
+        "tables = [T.ArchTable('t%d' % j, base.params, base.events[:-1] + (T.EventEntry('z', 'Z', +1, 100 + j, ('h', 'ffn'), 2),)) for j in range(7)]\n"
+        "cfg = G.grid2(n=2000, seed=5)\n"
+        "for t in tables + tables[:1]:\n"
+        "    want_p, want_d = B.estimate(cfg, [t], const, threads=8)\n"
+        "    got_p, got_d = U.hip_estimate(cfg, [t], const, kernel=6)\n"
+        "    assert (got_d == want_d).all() and (got_p == want_p).all(), t.name\n"
+        "torch.cuda.synchronize()\n"
+        "left = M.llmem_kernels_release()\n"
+        "assert 1 <= left <= 4, left\n"
+        "print('child ok', left)\n")
+    env = dict(os.environ, LLMEM_KERNELS_KEPT="4")
+    out = subprocess.run([sys.executable, "-c", child], env=env, capture_output=True, text=True, timeout=200)
+    assert out.returncode == 0 and "child ok" in out.stdout, (out.stdout[-500:], out.stderr[-2000:])
+
+
 def test_built_kernels_are_kept_between_processes(U, tmp_path):
     """LLMEM_KERNEL_CACHE: a build writes one file; a second process loads it instead of building
     (the file is not rewritten) and computes the same; a file with a foreign identity is ignored."""
