@@ -35,13 +35,26 @@ JOBS = min(8, os.cpu_count() or 1)
 
 
 def shipped_table_sets():
-    """The table sets the library has built-in specialized kernels for: (name, [tables])."""
+    """The table sets the library has built-in specialized kernels for: (name, [tables]).
+    LLMEM_BUILD_TABLES=package.module:function adds the caller's own: the function returns
+    further (name, [tables]) pairs (names of letters, digits and underscores), so that tables
+    the library does not ship get kernels of the same kind without the run-time compiler."""
     from workloads import tables as T
     sets = []
     for family, make in T.FAMILIES.items():
         sets.append((family, [make()]))
         sets.append((family + "_full", [make(checkpoint=False)]))
     sets.append(("zoo", [T.gpt_table(), T.opt_table(), T.llama_table()]))
+    extra = os.environ.get("LLMEM_BUILD_TABLES", "")
+    if extra:
+        import importlib
+        module, _, function = extra.partition(":")
+        taken = {name for name, _ in sets}
+        for name, tables in getattr(importlib.import_module(module), function)():
+            if not name.replace("_", "").isalnum() or name in taken:
+                raise ValueError(f"LLMEM_BUILD_TABLES: bad or repeated table set name {name!r}")
+            taken.add(name)
+            sets.append((name, list(tables)))
     return sets
 
 

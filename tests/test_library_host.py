@@ -252,6 +252,20 @@ def test_built_in_specializations_match_the_shipped_tables(lib):
     assert e.value.code == -3
 
 
+def test_build_step_takes_further_table_sets(monkeypatch):
+    """LLMEM_BUILD_TABLES names a function whose table sets the build step compiles kernels for
+    beside the shipped ones (checked here up to the list of sets: no compile)."""
+    from paper_2404_10933_amd import build
+    shipped = [name for name, _ in build.shipped_table_sets()]
+    monkeypatch.setenv("LLMEM_BUILD_TABLES", "extra_tables_for_the_build:more")
+    both = build.shipped_table_sets()
+    assert [name for name, _ in both] == shipped + ["mine", "mine_and_gpt"]
+    assert len(both[-1][1]) == 2 and both[-2][1][0].name == "mine"
+    monkeypatch.setenv("LLMEM_BUILD_TABLES", "extra_tables_for_the_build:repeated")
+    with pytest.raises(ValueError):
+        build.shipped_table_sets()
+
+
 def test_kept_plans_follow_the_tables_contents(lib):
     """The library keeps, per host thread, what it made of the last few table sets and reuses it
     when every byte is the same.  A change anywhere in the host tables must therefore show at the
