@@ -307,6 +307,9 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
         const u32 h = now.h, ffn = now.ffn, V = now.V, P = now.P, arch_id = now.arch_id, method = now.method, d = now.d,
                   cflags = now.cflags, L = now.L, n_heads = now.n_heads, n_kv = now.n_kv, bs = now.bs, sl = now.sl;
         const int chunk_k = now.chunk_k;
+        // every column is requested before the first is looked at: left alone, the compiler moves the
+        // loads that only valid configurations need behind the validity test, a second round trip
+        if (!SWEEP) asm volatile("" :: "v"(h), "v"(ffn), "v"(V), "v"(P), "v"(cflags), "v"(L), "v"(n_kv), "v"(bs), "v"(sl));
         u32 err = 0;
         if (arch_id >= (u32)a.n_arch) err |= LLMEM_F_ERR_ARCH;
         if (method > 2) err |= LLMEM_F_ERR_METHOD;
