@@ -34,6 +34,33 @@ def test_exports_every_declared_symbol(lib):
         assert hasattr(lib, n), n
 
 
+def test_header_is_plain_c_and_links(lib, tmp_path):
+    """include/llmem.h compiles as C99 with warnings as errors, and a C program linked against the
+    library calls its host-only entry points (no GPU call is made)."""
+    import subprocess
+    import paper_2404_10933_amd as M
+    src = tmp_path / "use.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <string.h>\n#include "llmem.h"\n'
+        "int main(void) {\n"
+        "    llmem_tables t; llmem_configs c; int32_t info[8];\n"
+        "    memset(&t, 0, sizeof t); memset(&c, 0, sizeof c);\n"
+        "    if (llmem_abi_version() != LLMEM_ABI_VERSION) return 1;\n"
+        "    if (llmem_kernel_forms(&t, info) != LLMEM_EINVAL_TABLE) return 2;      /* no architecture */\n"
+        "    if (llmem_estimate(&c, -1, &t, (int64_t *)0) != LLMEM_EINVAL_NULL) return 3;\n"
+        "    if (llmem_config_bytes(3) != 93 || llmem_kernels_release() != 0) return 4;\n"
+        '    printf("%s\\n", llmem_strerror(LLMEM_EINVAL_N));\n'
+        "    return 0;\n}\n")
+    exe = tmp_path / "use"
+    lib_dir = os.path.dirname(M.library_path())
+    build = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                            str(src), "-o", str(exe), "-L", lib_dir, "-l:libllmem.so", f"-Wl,-rpath,{lib_dir}"],
+                           capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert run.returncode == 0 and run.stdout.strip(), (run.returncode, run.stdout, run.stderr)
+
+
 def test_abi_and_sizes(lib):
     import paper_2404_10933_amd as M
     assert M.llmem_abi_version() == 5
