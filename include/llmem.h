@@ -57,7 +57,10 @@ extern "C" {
 /* ---- configurations (structure of arrays) --------------------------------- */
 /* One fine-tuning configuration = the inputs of the paper's problem statement
  * (Notation table; Algorithm 1 inputs): decoder shape, bs, sl, method, gpu_n (d),
- * chunk size.  Each member is a DEV array of n values.                         */
+ * chunk size.  Each member is a DEV array of n values.  The order of the
+ * configurations never changes a result; it does change the time: 64 consecutive
+ * configurations share a wavefront, which takes the architectures they name one
+ * after the other, so arrays grouped by arch_id run fastest.                   */
 typedef struct llmem_configs {
     uint8_t  *arch_id;   /* index into llmem_tables.arch                                   */
     uint32_t *h;         /* hidden width (o_n)                                             */
