@@ -447,11 +447,12 @@ uint64_t llmem_selftest_divide(uint64_t x, uint32_t d);
 /* Unloads every kernel that was built at run time (LLMEM_KERNEL_LANE_SPECIALIZED without a
  * built-in match, LLMEM_KERNEL_LANE_RUNTIME) and frees the host and device memory of its code
  * object: for a process that goes through many table sets.  Built-in kernels are not
- * affected.  The caller makes sure that no launch of such a kernel is still pending on any stream
- * (synchronize first) and that no other thread is inside a call that launches one.  A later call
- * with the same tables builds again (or loads from LLMEM_KERNEL_CACHE).  Returns the number of
- * kernels released; 0 - and no device call - when there are none.  A build that another thread
- * has not finished yet is left alone.                                                        */
+ * affected.  Every device that has such kernels is synchronized first (launches still pending
+ * there have ended before their code goes), so the call may block and must not be made while a
+ * stream is being captured.  A kernel that a call of another thread holds at that moment (being
+ * built, or found and about to be launched) is left alone.  A later call with the same tables
+ * builds again (or loads from LLMEM_KERNEL_CACHE).  Returns the number of kernels released; 0 -
+ * and no device call - when there are none.                                                  */
 int llmem_kernels_release(void);
 
 const char *llmem_strerror(int code);

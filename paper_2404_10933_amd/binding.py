@@ -385,7 +385,7 @@ def llmem_abi_version() -> int:
 
 
 def llmem_kernels_release() -> int:
-    """Unloads the kernels built at run time; the caller has synchronized.  Returns how many."""
+    """Unloads the kernels built at run time (synchronizes their devices first).  Returns how many."""
     got = int(load_library().llmem_kernels_release())
     if got < 0:
         _check(got)

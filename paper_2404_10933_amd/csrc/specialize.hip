@@ -482,14 +482,17 @@ int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch,
 }
 
 // Unloads the modules of all finished run-time builds and frees their code objects; builds that
-// are still running are left alone.  Returns how many kernels were released.
+// are still running, and kernels that a call of another thread is about to launch, are left
+// alone.  Each device is synchronized before its modules go, so launches that are still
+// pending have ended.  Returns how many kernels were released.
 int release_built()
 {
     std::vector<std::pair<int, std::shared_ptr<Slot>>> gone;
     {
         std::lock_guard<std::mutex> hold(g_lock);
         for (auto at = g_built.begin(); at != g_built.end();) {
-            if (at->second->done) {
+            // use_count 1: only the list holds it, and nobody takes it without g_lock
+            if (at->second->done && at->second.use_count() == 1) {
                 gone.emplace_back(at->first.device, at->second);
                 at = g_built.erase(at);
             } else {
@@ -498,12 +501,18 @@ int release_built()
         }
     }
     if (gone.empty()) return 0;                                 // nothing built: no device call at all
-    int current = 0, count = 0;
+    int current = 0, count = 0, synchronized = -1;
     const bool restore = hipGetDevice(&current) == hipSuccess;
-    for (auto &entry : gone) {
+    for (auto &entry : gone) {                                  // in the order of the keys: device by device
         Built &built = entry.second->built;
         if (entry.second->rc != LLMEM_OK || !built.module) continue;
-        if (hipSetDevice(entry.first) == hipSuccess) { unload(built); ++count; }
+        if (hipSetDevice(entry.first) != hipSuccess) continue;
+        if (synchronized != entry.first) {
+            (void)hipDeviceSynchronize();
+            synchronized = entry.first;
+        }
+        unload(built);
+        ++count;
     }
     if (restore) (void)hipSetDevice(current);
     return count;
