@@ -139,8 +139,19 @@ __device__ __forceinline__ u64 mul_64x32(u64 x, u32 m)
 // acc + value * factor with value and the wave-uniform factor sign-extended from 32 bits, in one instruction
 __device__ __forceinline__ i64 mad_i64_i32(int value, int factor, i64 acc)
 {
-    asm("v_mad_i64_i32 %0, vcc, %1, %2, %0" : "+v"(acc) : "v"(value), "s"(factor) : "vcc");
-    return acc;
+    i64 sum;
+    asm("v_mad_i64_i32 %0, vcc, %1, %2, %3" : "=v"(sum) : "v"(value), "s"(factor), "v"(acc) : "vcc");
+    return sum;
+}
+// The larger of two 64-bit integers, each of them 0 or in [2^59, 2^61]: read as doubles such bit
+// patterns are +0 or positive normal numbers, and doubles of one sign are ordered like their bit
+// patterns, so one v_max_f64 does what takes a compare and two selects on integers (it returns one of
+// its operands unchanged; no NaN, infinity or denormal is among them, so no mode bit matters).
+__device__ __forceinline__ i64 max_of_positive(i64 x, i64 y)
+{
+    i64 larger;
+    asm("v_max_f64 %0, %1, %2" : "=v"(larger) : "v"(x), "v"(y));
+    return larger;
 }
 __device__ __forceinline__ u32 uni(u32 v) { return (u32)__builtin_amdgcn_readfirstlane((int)v); }
 // Results are written once and not read again: streaming stores, which do not keep the lines in
@@ -787,7 +798,15 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
                         const char *row = vals + (NARROW ? lane * 4 : (lane & 31) * 8);
                         int seg = 0;
                         u32 has_point = 0;                                                // wave-uniform, kept scalar
-                        i64 acc = 0, top = LOWEST;
+                        // The narrow sums start at 2^60 instead of 0.  A sum is below 2^53 in magnitude (at most
+                        // 100 values of at most 2^31 blocks, factors below 2^15), so its bit pattern is that
+                        // of a positive double and a point's maximum is one max_of_positive(), against 0
+                        // before the segment's first point.  2^60 is in the high word only: taking it off
+                        // again at the segment's end is one 32-bit add.
+                        constexpr u64 NARROW_ZERO = 1ull << 60;
+                        i64 zero = NARROW ? (i64)NARROW_ZERO : 0;
+                        if (NARROW) asm volatile("" : "+v"(zero));                      // one register pair, not an immediate per sum
+                        i64 acc = zero, top = NARROW ? 0 : LOWEST;
                         const int w_begin = (int)seg_at[0], w_end = (int)seg_at[LLMEM_NSEG];
                         LLMEM_UNROLL_NARROW
                         for (int w = w_begin; w < w_end; w += PROG_FETCH) {
@@ -836,17 +855,23 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 #endif
                                     if (t[g] & PROG_END_SEGMENT) {
                                         // the narrow sums are in blocks
-                                        const i64 run = NARROW ? (i64)((u64)acc << align_shift) : acc;
-                                        const i64 peak = NARROW ? (i64)((u64)top << align_shift) : top;
+                                        const i64 run = NARROW ? (i64)(((u64)acc - NARROW_ZERO) << align_shift) : acc;
+                                        const i64 peak = NARROW ? (i64)(((u64)top - NARROW_ZERO) << align_shift) : top;
                                         close_segment(seg, run, peak, has_point != 0);
                                         ++seg;
-                                        top = LOWEST;
+                                        top = NARROW ? 0 : LOWEST;
                                         has_point = 0;
                                     } else {
-                                        top = acc > top ? acc : top;
+#ifdef LLMEM_SPECIALIZED
+                                        // (a segment's first point needs no comparison, and this build knows which it is)
+                                        if (NARROW) top = has_point ? max_of_positive(acc, top) : acc;
+#else
+                                        if (NARROW) top = max_of_positive(acc, top);
+#endif
+                                        else top = acc > top ? acc : top;
                                         has_point = 1;
                                     }
-                                    acc = 0;
+                                    acc = zero;
                                 }
                             }
                         }
