@@ -184,27 +184,46 @@ def alu_roofline(key, units, ms, kernel_name, census_ops=None):
     return out
 
 
-def timed_ms(fn, reps=10, warm=2):
-    """Mean duration of fn() in ms by HIP events on the current stream, after untimed calls."""
+LEG_MS = {"warm": 60.0, "timed": 200.0}      # set from --leg-warm-ms and --leg-ms
+
+
+def timed_ms(fn, reps=None, warm=None):
+    """Mean duration of fn() in ms by HIP events on the current stream, after untimed calls.  The GPU
+    raises its clock over the first tens of milliseconds of continuous work and drops it again when
+    idle, so every leg warms up by itself: unless given, the untimed calls and the timed calls are as
+    many as fill LEG_MS["warm"] and LEG_MS["timed"] milliseconds (at least 1 and 3).  The counts used
+    are left in timed_ms.last."""
     import torch
-    for _ in range(warm):
-        fn()
+
+    def run(count):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(count):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / count
+
+    fn()
     torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        fn()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / reps
+    if reps is None or warm is None:
+        estimate = max(run(2), 1e-3)
+        warm = min(max(int(LEG_MS["warm"] / estimate), 1), 20000) if warm is None else warm
+        reps = min(max(int(LEG_MS["timed"] / estimate), 3), 50000) if reps is None else reps
+    run(warm)
+    timed_ms.last = (reps, warm)
+    return run(reps)
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=300, help="untimed steps before the timed ones (the GPU reaches its "
+                                                            "clock under load after some 100 launches of 0.3 ms)")
+    ap.add_argument("--leg-ms", type=float, default=200.0, help="timed milliseconds of every other workload (0: three calls)")
+    ap.add_argument("--leg-warm-ms", type=float, default=60.0, help="untimed milliseconds before them (0: one call)")
     ap.add_argument("--n", type=int, default=10_000_000, help="configurations per step (default: the 10^7 grid)")
     ap.add_argument("--lists", type=int, default=100_000, help="event lists of the explicit-timeline grid (0: skip)")
     ap.add_argument("--full-traversal", type=int, default=10_000_000,
@@ -224,6 +243,7 @@ def main():
                     help="only run a plain 1 GiB device copy ten times (reference for the HBM byte counters)")
     ap.add_argument("--import-counters", metavar="DIR", help="write profiles/counters.json from rocprofv3 output (no GPU)")
     args = ap.parse_args()
+    LEG_MS["timed"], LEG_MS["warm"] = args.leg_ms, args.leg_warm_ms
     if args.import_counters:
         import_counters(args.import_counters)
         return
@@ -256,7 +276,7 @@ def main():
     table = T.llama_table()
     n = args.n
     dev = M.DeviceConfigs.empty(n)
-    generators = {"grid4_ms": timed_ms(lambda: M.llmem_grid_generate(4, 0, 0, n, dev), 3, 1), "grid4_configs": n}
+    generators = {"grid4_ms": timed_ms(lambda: M.llmem_grid_generate(4, 0, 0, n, dev)), "grid4_configs": n}
     kernel = {"auto": 0, "wave": 1, "events": 3, "compiled": 4, "runtime": 6}[args.kernel]
 
     def tables_of(tabs, k=0, m_base=const.m_base):
@@ -351,7 +371,7 @@ def main():
             M.llmem_grid_generate(int(name[1]), 0, 0, n_grid, gdev)
             gp = torch.empty(n_grid, dtype=torch.int64, device="cuda")
             gd = torch.empty((M.NDETAIL, n_grid), dtype=torch.int64, device="cuda")
-            ms = timed_ms(lambda: M.llmem_estimate_ex(gdev, gtab, gp, gd), 20, 3)
+            ms = timed_ms(lambda: M.llmem_estimate_ex(gdev, gtab, gp, gd))
             ns = min(n_grid, 4096)
             gcfg = make() if name == "g1" else make(n=ns, seed=0)
             wp, wd = B.estimate(gcfg, [gtab_py], const, threads=4)
@@ -410,7 +430,7 @@ def main():
         for label, k in (("auto_lane_direct", 0), ("wave", 1)):
             wtab = tables_of([wide], k)
             wp.fill_(-7)
-            ms = timed_ms(lambda: M.llmem_estimate_ex(wdev, wtab, wp, wd), 5, 1)
+            ms = timed_ms(lambda: M.llmem_estimate_ex(wdev, wtab, wp, wd))
             assert (wp[:ns].cpu().numpy() == want_wp).all() and (wd[:, :ns].cpu().numpy().T == want_wd).all(), label
             entry[label] = {"ms_per_launch": ms, "configs_per_s": nw / (ms * 1e-3)}
         entry["speedup_over_wave"] = entry["wave"]["ms_per_launch"] / entry["auto_lane_direct"]["ms_per_launch"]
@@ -426,7 +446,7 @@ def main():
         offsets[1:] = torch.cumsum(counts, 0)
         total = int(offsets[-1].item())
         events = torch.empty(total, dtype=torch.int64, device="cuda")
-        generators["event_lists_ms"] = timed_ms(lambda: M.llmem_events_generate(0, 0, nl, offsets, events), 3, 1)
+        generators["event_lists_ms"] = timed_ms(lambda: M.llmem_events_generate(0, 0, nl, offsets, events))
         generators["event_lists"] = nl
         oa = torch.empty(nl, dtype=torch.int64, device="cuda")
         orv = torch.empty(nl, dtype=torch.int64, device="cuda")
@@ -503,14 +523,14 @@ def main():
         del peaks, detail
         qdev = M.DeviceConfigs.empty(nq)
         tp = torch.empty(nq, dtype=torch.uint8, device="cuda")
-        generators["queries_ms"] = timed_ms(lambda: M.llmem_queries_generate(0, 0, nq, qdev, tp), 3, 1)
+        generators["queries_ms"] = timed_ms(lambda: M.llmem_queries_generate(0, 0, nq, qdev, tp))
         generators["queries"] = nq
         qtab = tables_of([table])
         q_method = torch.empty(nq, dtype=torch.int32, device="cuda")
         q_bs = torch.empty(nq, dtype=torch.int32, device="cuda")
         q_det = torch.empty((M.NDECIDE, nq), dtype=torch.int64, device="cuda")
         ms = timed_ms(lambda: M.llmem_decide(qdev, tp, qtab, m_total, q_method, q_bs, q_det))
-        ms_short = timed_ms(lambda: M.llmem_decide(qdev, tp, qtab, m_total, q_method, q_bs, None))
+        ms_short = timed_ms(lambda: M.llmem_decide(qdev, tp, qtab, m_total, q_method, q_bs, None), *timed_ms.last)   # as many launches
         # bracket check + one bisection step (brackets of <= 1 for this grid's models)
         q_census = C.decide_census(table, 2)
         q_bytes = 31 + 1 + 4 + 4 + 8 * M.NDECIDE                       # query columns, tp_n; method, bs, decision columns
@@ -551,6 +571,10 @@ def main():
                                   "host_cores_visible": os.cpu_count()}
     # the seeded inputs are generated on the device before anything is timed; what generating them takes
     result["generators"] = generators
+    result["timing"] = {"headline": f"{args.warmup} untimed steps, then {args.steps} timed ones, one after the other on one stream",
+                        "other_workloads": f"each: untimed launches for {args.leg_warm_ms:g} ms, then timed launches for {args.leg_ms:g} ms",
+                        "why": "the GPU reaches its clock under load only after some tens of milliseconds of continuous work "
+                               "and drops it when idle"}
     print(json.dumps(result))
 
 
