@@ -207,8 +207,8 @@ def timed_ms(fn, reps=None, warm=None):
 
     fn()
     torch.cuda.synchronize()
+    estimate = max(run(2), 1e-3)
     if reps is None or warm is None:
-        estimate = max(run(2), 1e-3)
         warm = min(max(int(LEG_MS["warm"] / estimate), 1), 20000) if warm is None else warm
         reps = min(max(int(LEG_MS["timed"] / estimate), 3), 50000) if reps is None else reps
     run(warm)
@@ -360,7 +360,7 @@ def main():
         extra["g4_peaks_only"] = {
             "workload": "llmem_estimate(configs, n, method_tables, out_peaks): g4, m_peak only (39 B per configuration; "
                         "no timeline walk: peak_live is a detail column)",
-            "n_configs": n, "ms_per_launch": ms, "configs_per_s": n / (ms * 1e-3),
+            "n_configs": n, "ms_per_launch": ms, "timed_launches": timed_ms.last[0], "configs_per_s": n / (ms * 1e-3),
             "hbm_gbs_algorithmic": (M.llmem_config_bytes(1) + 8) * n / (ms * 1e-3) / 1e9,
             "roofline": alu_roofline("g4_peaks", n, ms, "llmem_aot_llama_peaks"), "verified_vs_oracle": int(len(idx))}
         for name, make, family, n_grid in (("g1", G.grid1, "gpt", 432), ("g2", G.grid2, "opt", 100_000),
@@ -384,7 +384,7 @@ def main():
                 "workload": {"g1": "g1: tiny Cartesian grid, GPT-style table, all detail columns (a latency: two workgroups)",
                              "g2": "g2: 10^5 OPT-style configurations, all detail columns",
                              "g3": "g3: 10^6 Llama-style configurations, all detail columns"}[name],
-                "n_configs": n_grid, "ms_per_launch": ms, "configs_per_s": n_grid / (ms * 1e-3),
+                "n_configs": n_grid, "ms_per_launch": ms, "timed_launches": timed_ms.last[0], "configs_per_s": n_grid / (ms * 1e-3),
                 "roofline": alu_roofline(name + "_detail", n_grid, ms, f"llmem_aot_{family}_detail", gcensus["lane_ops"]),
                 "cpu_oracle": {"value": ns / dt, "unit": "configs/s", "cores": 1, "sample": f"first {ns} configurations, {dt:.2f} s"},
                 "verified_vs_oracle": ns}
@@ -410,7 +410,7 @@ def main():
                                 "(what tables without a built-in specialization get from LLMEM_KERNEL_AUTO)",
                              6: "the headline workload with the specialized kernel built at run time (hiprtc; "
                                 "LLMEM_KERNEL_LANE_RUNTIME), first call incl. the build reported"}[k],
-                "n_configs": n, "ms_per_launch": ms, "configs_per_s": n / (ms * 1e-3), "first_call_s": first_call_s,
+                "n_configs": n, "ms_per_launch": ms, "timed_launches": timed_ms.last[0], "configs_per_s": n / (ms * 1e-3), "first_call_s": first_call_s,
                 "roofline": alu_roofline(key, n, ms, kname, census["lane_ops"]), "verified_vs_oracle": int(len(idx))}
 
     if args.forms:
@@ -432,7 +432,7 @@ def main():
             wp.fill_(-7)
             ms = timed_ms(lambda: M.llmem_estimate_ex(wdev, wtab, wp, wd))
             assert (wp[:ns].cpu().numpy() == want_wp).all() and (wd[:, :ns].cpu().numpy().T == want_wd).all(), label
-            entry[label] = {"ms_per_launch": ms, "configs_per_s": nw / (ms * 1e-3)}
+            entry[label] = {"ms_per_launch": ms, "timed_launches": timed_ms.last[0], "configs_per_s": nw / (ms * 1e-3)}
         entry["speedup_over_wave"] = entry["wave"]["ms_per_launch"] / entry["auto_lane_direct"]["ms_per_launch"]
         entry["verified_vs_oracle"] = ns
         extra["many_size_classes"] = entry
@@ -456,7 +456,7 @@ def main():
         c = counters_for("g5_lists", nl)
         extra["g5_event_lists"] = {
             "workload": "g5: explicit allocator event lists (~10^4 events each)", "n_lists": nl,
-            "n_events": total, "ms_per_launch": ms, "lists_per_s": nl / (ms * 1e-3),
+            "n_events": total, "ms_per_launch": ms, "timed_launches": timed_ms.last[0], "lists_per_s": nl / (ms * 1e-3),
             "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": gbs / PEAK_HBM_GBS, "traffic": c["traffic_bytes"] if c else None,
                          "algorithmic_bytes": nbytes, "kernel": "timeline_kernel"}}
@@ -484,7 +484,7 @@ def main():
         extra["g4_full_traversal"] = {
             "workload": "g4 with the Llama table without gradient checkpointing (every saved forward output alive "
                         "until its backward), 64 MiB allocator buffer added to m_base; all detail columns",
-            "n_configs": nf, "ms_per_launch": ms, "configs_per_s": nf / (ms * 1e-3),
+            "n_configs": nf, "ms_per_launch": ms, "timed_launches": timed_ms.last[0], "configs_per_s": nf / (ms * 1e-3),
             "table_events": len(full.events), "table_terms": fforms["terms"], "table_peak_points": fforms["peak_points"],
             "roofline": alu_roofline("g4_full_traversal" if kernel == 0 else "none", nf, ms,
                                      "llmem_aot_llama_full_detail" if kernel == 0 else kernel_name,
@@ -511,7 +511,7 @@ def main():
         extra["g4_streaming_sweep"] = {
             "workload": "g4 drawn in registers, estimated (all of the hot path) and folded into 8 statistics per "
                         "(method, gpu_n) against m_total 64 GiB; nothing per configuration touches HBM; reset + sweep",
-            "n_configs": nsw, "ms_per_launch": ms, "configs_per_s": nsw / (ms * 1e-3),
+            "n_configs": nsw, "ms_per_launch": ms, "timed_launches": timed_ms.last[0], "configs_per_s": nsw / (ms * 1e-3),
             "configs_fitting": int(stats[1].sum().item()),
             "roofline": alu_roofline("g4_sweep" if kernel == 0 else "none", nsw, ms,
                                      "llmem_aot_llama_sweep" if kernel == 0 else "lane kernel, sweep mode",
@@ -547,12 +547,12 @@ def main():
         extra["g6_method_decision"] = {
             "workload": "g6: Algorithm 1 per query (Llama-style model, gpu_n, sl; batch sizes up to 4096; "
                         "m_total 80 GiB), method + bs + all decision columns",
-            "n_queries": nq, "ms_per_launch": ms, "queries_per_s": nq / (ms * 1e-3),
+            "n_queries": nq, "ms_per_launch": ms, "timed_launches": timed_ms.last[0], "queries_per_s": nq / (ms * 1e-3),
             # 136 B per query at 8 TB/s take longer than the census at the vector issue rate: HBM bounds it
             "roofline": {"bound": "hbm", "achieved": q_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                          "frac": q_gbs / PEAK_HBM_GBS, "traffic": c["traffic_bytes"] if c else None,
                          "kernel": "decide_kernel<true>", "algorithmic_bytes_per_query": q_bytes, "alu": alu},
-            "method_and_bs_only": {"workload": "the same queries, out_detail = NULL (40 B per query)", "ms_per_launch": ms_short,
+            "method_and_bs_only": {"workload": "the same queries, out_detail = NULL (40 B per query)", "ms_per_launch": ms_short, "timed_launches": timed_ms.last[0],
                                    "queries_per_s": nq / (ms_short * 1e-3),
                                    "hbm_gbs_algorithmic": 40 * nq / (ms_short * 1e-3) / 1e9},
             "cpu_oracle": {"value": ns / dt, "unit": "queries/s", "cores": 1,
