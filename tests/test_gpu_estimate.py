@@ -253,6 +253,36 @@ def test_sizes_on_both_sides_of_2_to_31_blocks(U):
     _check(U, cfg, [edge], CONST, expect=BOTH)
 
 
+def test_peak_points_with_sums_far_from_zero(U):
+    """Peak points whose sums, counted from the start of their segment, are hundreds of times 2^31
+    allocator blocks above and below zero (the compiled form compares such sums by their bit
+    patterns, moved into the range of positive doubles): wavefronts that take the 32-bit walk, with
+    every large size exactly 2^31 blocks, and wavefronts that take the 64-bit walk."""
+    E = T.EventEntry
+    big = (2, ("V", "V"), 8)                                  # 2^40 bytes = 2^31 blocks at V = 2^18
+    small = (3, ("P",), 4)
+    many = lambda tag, seg, sign, count: tuple(E(f"{tag}{j}", seg, sign, *big) for j in range(count))
+    events = (many("a", "A", +1, 150)
+              + many("f", "F", -1, 100) + (E("fs", "F", +1, *small), E("ft", "F", -1, *small)) + many("g", "F", +1, 100)
+              + many("h", "H", +1, 150) + many("i", "H", -1, 150)
+              + many("b", "B", -1, 90) + (E("bs", "B", +1, *small), E("bt", "B", -1, *small)) + many("c", "B", +1, 91)
+              + (E("bu", "B", -1, *big),) + many("z", "Z", -1, 150))
+    table = T.ArchTable("far", T.gpt_table().params, events)
+    rng = np.random.default_rng(21)
+    n = 64 * 4 + 7
+    cfg = G.random_configs(rng, n, n_arch=1)
+    cfg["L"][:] = rng.integers(0, 9, size=n)
+    cfg["P"][:] = rng.integers(0, 5000, size=n)
+    cfg["V"][:] = 1 << 18
+    cfg["V"][5:128:9] = rng.integers(1, 1 << 18, size=len(cfg["V"][5:128:9]))
+    cfg["V"][64 * 2 + 11] = (1 << 18) + 1                     # this wavefront and the next walk in 64 bits
+    cfg["V"][64 * 3:] = rng.integers(1 << 18, 1 << 19, size=n - 64 * 3)
+    _check(U, cfg, [table], CONST, expect=BOTH)
+    want_p, want_d = B.estimate(cfg, [table], CONST)
+    import paper_2404_10933_amd as M
+    assert int(want_d[:, M.DETAIL_COLUMNS.index("peak_live")].max()) >= 300 << 40      # the sums are of that size
+
+
 def test_determinism_and_stream(U):
     cfg = G.grid3(n=20_000, seed=5)
     for kernel in BOTH:
