@@ -162,6 +162,24 @@ void launch_sweep_reset(long long *stats, hipStream_t stream);
 // tables, flavour and device, kept until the process ends).  flavour: 0 m_peak only, 1 with the
 // detail columns, 2 sweep.  LLMEM_OK, or LLMEM_EHIP with the compiler's or the loader's message
 // as the error text.
+// Workgroups of a lane-kernel launch over n_batch batches of 64 configurations, `waves` wavefronts
+// each striding over the batches.  `resident`: workgroups the device holds at once; `spread`: how
+// many times that number the launch may have (forms with next to no set-up per workgroup take 16:
+// the dispatcher then evens out the compute units; measured 2 to 48).  Every workgroup of a sweep ends with one
+// global atomic per statistic and group (384), which all workgroups aim at the same addresses: they
+// stay few against its own work from six batches per wavefront on (10^7 configurations: 0.40 ms
+// with 16 x resident workgroups, 0.26 ms with 6 x; 10^6: 0.092 ms with one batch per wavefront,
+// 0.038 ms with as many workgroups as are resident).
+inline long long lane_kernel_blocks(long long n_batch, int waves, long long resident, int spread, bool sweep)
+{
+    const long long blocks = (n_batch + waves - 1) / waves;
+    long long cap = resident * spread;
+    if (sweep) {
+        const long long by_work = (n_batch + waves * 6 - 1) / (waves * 6);
+        if (by_work < cap) cap = by_work > resident ? by_work : resident;
+    }
+    return blocks < cap ? blocks : cap;
+}
 bool has_prebuilt(const EstimateArgs &args, int flavour);
 int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch, hipStream_t stream, bool at_run_time);
 #endif

@@ -1174,12 +1174,9 @@ static void launch_lane_kernel(const EstimateArgs &args, bool detail, bool sweep
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(kernel), 64 * args.waves, lds_bytes)
             != hipSuccess || per_cu < 1)
         per_cu = 1;
-    long long blocks = (n_batch + args.waves - 1) / args.waves;
     // the compiled form has next to no set-up per workgroup: several times more workgroups than
-    // stay resident at once let the dispatcher even out the compute units (measured: 16 is best,
-    // also for a sweep, whose workgroups each end with global atomics)
-    const long long resident = (long long)per_cu * cu_count * (args.use_program ? 16 : 1);
-    if (blocks > resident) blocks = resident;
+    // stay resident at once; the others stage their tables per workgroup
+    const long long blocks = lane_kernel_blocks(n_batch, args.waves, (long long)per_cu * cu_count, args.use_program ? 16 : 1, sweep);
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * args.waves), lds_bytes, stream, args);
 }
 

@@ -372,8 +372,7 @@ int launch_prebuilt(const Prebuilt &p, const EstimateArgs &args, long long n_bat
         resident = per_cu * cu_count;
         resident_of[slot][&p - PREBUILT].store(resident, std::memory_order_relaxed);
     }
-    long long blocks = (n_batch + args.waves - 1) / args.waves;
-    if (blocks > (long long)resident * 16) blocks = (long long)resident * 16;   // as for the built-in compiled form
+    const long long blocks = lane_kernel_blocks(n_batch, args.waves, resident, 16, p.flavour == 2);
     EstimateArgs copy = args;
     void *params[] = {&copy};
     const hipError_t e = hipLaunchKernel(kernel, dim3((unsigned)blocks), dim3(64 * args.waves), params, lds_bytes, stream);
@@ -470,9 +469,7 @@ int launch_specialized(const EstimateArgs &args, int flavour, long long n_batch,
         return slot->rc;
     }
     const Built &built = slot->built;
-    long long blocks = (n_batch + args.waves - 1) / args.waves;
-    const long long resident = (long long)built.per_cu * built.cu_count * 16;   // as for the built-in compiled form
-    if (blocks > resident) blocks = resident;
+    const long long blocks = lane_kernel_blocks(n_batch, args.waves, (long long)built.per_cu * built.cu_count, 16, flavour == 2);
     EstimateArgs copy = args;
     void *params[] = {&copy};
     const hipError_t e = hipModuleLaunchKernel(built.function, (unsigned)blocks, 1, 1, 64 * args.waves, 1, 1,
