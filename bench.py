@@ -49,7 +49,7 @@ LANE_SOURCES = [os.path.join(CSRC, f) for f in ("estimate_batch.hip", "estimate_
 PROFILED = {
     "g4_detail": ("llmem_aot_llama_detail", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
     "g4_peaks": ("llmem_aot_llama_peaks", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
-    "g4_sweep": ("llmem_aot_llama_sweep", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
+    "g4_sweep": ("llmem_aot_llama_sweep", 1_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
     "g4_full_traversal": ("llmem_aot_llama_full_detail", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
     "g4_compiled": ("estimate_batch_kernel<true, 1, false>", 2_000_000, 1 << 62, 10_000_000, LANE_SOURCES),
     "g3_detail": ("llmem_aot_llama_detail", 500_000, 2_000_000, 1_000_000, LANE_SOURCES),
@@ -163,9 +163,11 @@ def alu_roofline(key, units, ms, kernel_name, census_ops=None):
     c = counters_for(key, units) if key in PROFILED else None
     rate = units / (ms * 1e-3)
     out = {"bound": "alu", "achieved": None, "peak": PEAK_LANE_TOPS, "unit": "Tlane-op/s", "frac": None,
-           "basis": "vector instructions issued per unit (hardware counter) x units per second; null: no counters "
-                    "for this kernel and workload, or its sources have changed since those in profiles/counters.json "
-                    "were taken",
+           "basis": "vector instructions issued per unit (hardware counter) x units per second, against one 64-lane "
+                    "instruction per compute unit and clock at 2.4 GHz: what 64-bit integer instructions sustain; plain "
+                    "32-bit add/and/mov/xor issue at up to 1.6 per compute unit and clock (calibration program), so a "
+                    "kernel rich in them - the sweep's draws - can pass 1.  null: no counters for this kernel and "
+                    "workload, or its sources have changed since those in profiles/counters.json were taken",
            "traffic": None, "kernel": kernel_name, "kernel_ms": ms}
     if c is not None:
         out.update(achieved=c["valu_per_unit"] * rate / 1e12, frac=c["valu_per_unit"] * rate / 1e12 / PEAK_LANE_TOPS,
