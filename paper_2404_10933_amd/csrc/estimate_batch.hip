@@ -71,8 +71,7 @@ typedef long long int64_t;
 #include LLMEM_SPEC_HEADER
 namespace llmem {
 namespace {
-// (the sweep is faster at four waves per SIMD than at five, measured with and without spills)
-constexpr int SPEC_WAVES = (LLMEM_SPEC_FLAVOUR == 2 && LLMEM_SPEC_WAVES > 4) ? 4 : LLMEM_SPEC_WAVES;
+constexpr int SPEC_WAVES = LLMEM_SPEC_WAVES;
 constexpr int SPEC_ARCHS = LLMEM_SPEC_ARCHS;
 constexpr int SPEC_FIRST[8] = {LLMEM_SPEC_FIRSTS};
 __device__ constexpr unsigned SPEC_PROG[] = {LLMEM_SPEC_WORDS};      // every read folds to an immediate
