@@ -172,11 +172,7 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
 {
     constexpr bool COMPILED = FORM == FORM_COMPILED, DIRECT = FORM == FORM_DIRECT;
     extern __shared__ uint4 lds[];
-    // multipliers of the divisions by the partition degree: a lane looks its own d up, from LDS
-    // rather than from memory, so that no memory latency stands between a batch's inputs and its work
-    __shared__ u64 div_mul_of[256];
     const int block = a.waves * 64;                       // threads of this workgroup (a.waves wavefronts)
-    for (int t = threadIdx.x; t < 256; t += block) div_mul_of[t] = c_div.t[t].mul;
     constexpr int SWEEP_WORDS = LLMEM_NSWEEP * LLMEM_SWEEP_GROUPS;
     __shared__ u64 sweep_acc[SWEEP ? SWEEP_WORDS : 1];
     if (SWEEP) {
@@ -337,7 +333,10 @@ __device__ __forceinline__ void estimate_batch_body(const EstimateArgs &a)
         D[LLMEM_DIM_P] = P; D[LLMEM_DIM_L] = L;
         const u32 Blog = (cflags & LLMEM_CFG_LOGITS_FP32) ? B32 : B16;
         D[LLMEM_DIM_B_LOGITS] = Blog; D[LLMEM_DIM_D] = d; D[DIM_BS_SL] = bs * sl;        // both below 2^16
-        const u64 div_mul = div_mul_of[d & 255u];
+        // multiplier of the divisions by the partition degree: a lane looks its own d up in the table in
+        // constant memory (4 KB, in the caches).  A copy of it in LDS, filled by every workgroup, made no
+        // difference to a batch and cost launches of many short-lived workgroups their set-up.
+        const u64 div_mul = c_div.t[d & 255u].mul;
         const u32 div_shift = d > 1 ? 31u - (u32)__builtin_clz(d - 1) : 0u;        // ceil(log2 d) - 1
 
         i64 r_peak = err ? -1 : 0, r_live = 0;
